@@ -1,0 +1,132 @@
+"""Seeded synthetic inputs for the direct-convolution workloads.
+
+This module only draws numbers and names shapes.  It holds none of the
+method's arithmetic, so both the CPU oracle's tests and the HIP path's tests
+may use it without sharing any code of the computation itself.
+
+Letters follow the C ABI: batch N, channels C, image H x W, K filters of
+F x F.  (The paper writes K for the filter side and F for the filter count;
+see its Fig. 3 caption.)  The paper's own experiments (Sec. 5, Figs. 7 and 8)
+use synthetic tensors parameterised only by size, so these stand in for them
+directly.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+import numpy as np
+
+SEED_BASE = 170510591
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str          # short tag used in reports
+    kind: str          # "single" (one input channel) or "general"
+    N: int
+    C: int
+    H: int
+    W: int
+    K: int
+    F: int
+    in_dist: str       # "u11" = uniform[-1,1], "u01" = uniform[0,1]
+    filt_dist: str     # "u11" or "he" = normal(0, sqrt(2/(C F F)))
+    seed: int
+
+    @property
+    def Ho(self) -> int:
+        return self.H - self.F + 1
+
+    @property
+    def Wo(self) -> int:
+        return self.W - self.F + 1
+
+    @property
+    def out_elems(self) -> int:
+        return self.N * self.K * self.Ho * self.Wo
+
+    @property
+    def flops(self) -> int:
+        return 2 * self.out_elems * self.C * self.F * self.F
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """Input + filters + output, each touched exactly once, 4 bytes each."""
+        return 4 * (self.N * self.C * self.H * self.W
+                    + self.K * self.C * self.F * self.F
+                    + self.out_elems)
+
+    def in_shape(self):
+        return (self.H, self.W) if self.kind == "single" else (self.N, self.C, self.H, self.W)
+
+    def filt_shape(self):
+        return (self.K, self.F, self.F) if self.kind == "single" else (self.K, self.C, self.F, self.F)
+
+    def out_shape(self):
+        return (self.K, self.Ho, self.Wo) if self.kind == "single" else (self.N, self.K, self.Ho, self.Wo)
+
+
+def _mk(name, kind, N, C, H, W, K, F, in_dist, filt_dist, idx):
+    return Workload(name, kind, N, C, H, W, K, F, in_dist, filt_dist, SEED_BASE + idx)
+
+
+# The five benchmark configurations, in the order the baseline lists them,
+# plus the filter-size sweep of the large single-channel case.
+S1 = _mk("S1", "single", 1, 1, 256, 256, 16, 3, "u11", "u11", 0)
+S2 = _mk("S2", "single", 1, 1, 4096, 4096, 64, 5, "u11", "u11", 1)
+G1 = _mk("G1", "general", 64, 3, 224, 224, 64, 11, "u11", "u11", 2)
+G2 = _mk("G2", "general", 32, 64, 56, 56, 64, 3, "u01", "he", 3)
+G3 = _mk("G3", "general", 32, 256, 28, 28, 512, 3, "u01", "he", 4)
+S2_SWEEP = {F: _mk(f"S2_F{F}", "single", 1, 1, 4096, 4096, 64, F, "u11", "u11", 10 + F)
+            for F in (3, 5, 7, 9, 11)}
+
+CONFIGS = {w.name: w for w in (S1, S2, G1, G2, G3)}
+
+
+def _draw(rng: np.random.Generator, dist: str, shape, C: int, F: int) -> np.ndarray:
+    if dist == "u11":
+        a = rng.random(shape, dtype=np.float32) * np.float32(2.0) - np.float32(1.0)
+    elif dist == "u01":
+        a = rng.random(shape, dtype=np.float32)
+    elif dist == "he":
+        sigma = np.float32(np.sqrt(2.0 / (C * F * F)))
+        a = rng.standard_normal(shape, dtype=np.float32) * sigma
+    else:
+        raise ValueError(dist)
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def make_inputs(w: Workload):
+    """Return (input, filters) as contiguous float32 numpy arrays."""
+    rng = np.random.default_rng(w.seed)
+    x = _draw(rng, w.in_dist, w.in_shape(), w.C, w.F)
+    f = _draw(rng, w.filt_dist, w.filt_shape(), w.C, w.F)
+    return x, f
+
+
+def random_case(seed: int, N: int, C: int, H: int, W: int, K: int, F: int,
+                in_dist: str = "u11", filt_dist: str = "u11"):
+    """Inputs for an arbitrary general-layout shape: in[N,C,H,W], filt[K,C,F,F]."""
+    rng = np.random.default_rng(SEED_BASE * 7 + seed)
+    x = _draw(rng, in_dist, (N, C, H, W), C, F)
+    f = _draw(rng, filt_dist, (K, C, F, F), C, F)
+    return x, f
+
+
+def integer_case(seed: int, N: int, C: int, H: int, W: int, K: int, F: int):
+    """Small-integer valued float32 inputs: pixels in [-8, 8], weights in [-4, 4].
+
+    Every product and every partial sum is an integer far below 2**24 for the
+    reduction lengths used here, so any fp32 summation order gives the same
+    bits and results can be compared exactly.
+    """
+    rng = np.random.default_rng(SEED_BASE * 11 + seed)
+    x = rng.integers(-8, 9, size=(N, C, H, W)).astype(np.float32)
+    f = rng.integers(-4, 5, size=(K, C, F, F)).astype(np.float32)
+    return x, f
+
+
+def sample_indices(seed: int, total: int, count: int) -> np.ndarray:
+    """`count` flat output indices in [0, total): the first, the last and seeded random ones."""
+    rng = np.random.default_rng(SEED_BASE * 13 + seed)
+    idx = rng.integers(0, total, size=max(count - 2, 0), dtype=np.int64)
+    return np.unique(np.concatenate([np.array([0, total - 1], dtype=np.int64), idx]))
