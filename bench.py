@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the direct-convolution hot path on one MI355X.
+
+A step is one launch of the single-channel kernel on the large single-channel
+configuration (one 4096x4096 image, 64 filters of 5x5) with all buffers
+resident in HBM.  The same JSON line also carries one entry per remaining
+configuration (the small single-channel case, the filter-size sweep and the
+three general-case shapes), each timed the same way, the roofline figures of
+the dominant kernel, and the CPU oracle timed on a bounded sample.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 (matrix / packed vector), published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-configs", action="store_true")
+    ap.add_argument("--only", default=None,
+                    help="time just this configuration (S1, S2, S2_F3.., G1, G2, G3) as the step")
+    return ap.parse_args()
+
+
+def time_launches(fn, steps, warmup):
+    """Average milliseconds per launch over `steps` launches, by events on the launch stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def make_runner(w):
+    import torch
+    import workloads as wl
+    import paper_1705_10591_amd as dconv
+    x, f = wl.make_inputs(w)
+    xd, fd = torch.from_numpy(x).cuda(), torch.from_numpy(f).cuda()
+    out = torch.empty(w.out_shape(), dtype=torch.float32, device="cuda")
+    if w.kind == "single":
+        return (lambda: dconv.dconv_single_channel(xd, fd, out=out)), (x, f)
+    return (lambda: dconv.dconv_general(xd, fd, out=out)), (x, f)
+
+
+def config_entry(w, ms):
+    gflops = w.flops / (ms * 1e-3) / 1e9
+    gbs = w.algorithmic_bytes / (ms * 1e-3) / 1e9
+    return {"name": w.name, "kernel": "dconv_single_channel" if w.kind == "single" else "dconv_general",
+            "shape": {"N": w.N, "C": w.C, "H": w.H, "W": w.W, "K": w.K, "F": w.F},
+            "ms": round(ms, 5), "gflops": round(gflops, 1),
+            "frac_fp32_peak": round(gflops / 1e3 / FP32_PEAK_TFLOPS, 4),
+            "algorithmic_gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def read_traffic(name):
+    """HBM bytes per launch from the committed counter summary of this kernel/workload, if any."""
+    p = ROOT / "profiles" / f"{name}_hbm_traffic.txt"
+    if not p.exists():
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", p.read_text(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(w, x, f):
+    """The oracle as it stands, on a band of the headline workload, all host cores."""
+    import numpy as np
+    import oracle
+    rows_out = 2048
+    band = np.ascontiguousarray(x[:rows_out + w.F - 1])
+    t0 = time.perf_counter()
+    _, threads = oracle.single_channel(band, f, only32=True)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * w.K * rows_out * w.Wo * w.F * w.F
+    return {"value": round(flops / dt / 1e9, 3), "unit": "GFLOP/s", "cores": int(threads),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"first {rows_out} of {w.Ho} output rows of the same image, all {w.K} filters"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    allw = dict(wl.CONFIGS)
+    allw.update({v.name: v for v in wl.S2_SWEEP.values()})
+    head = allw[args.only] if args.only else wl.S2
+
+    run, (x, f) = make_runner(head)
+    ms, wall_ms = time_launches(run, args.steps, args.warmup)
+    entry = config_entry(head, ms)
+
+    single = head.kind == "single"
+    hbm_bound = single and head.F <= 5
+    if hbm_bound:
+        roof = {"bound": "hbm", "achieved": entry["algorithmic_gbs"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(entry["algorithmic_gbs"] / HBM_PEAK_GBS, 4)}
+    else:
+        roof = {"bound": "mfma", "achieved": round(entry["gflops"] / 1e3, 3), "peak": FP32_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(entry["gflops"] / 1e3 / FP32_PEAK_TFLOPS, 4)}
+    roof["kernel"] = entry["kernel"]
+    roof["kernel_ms"] = round(ms, 5)
+    roof["traffic"] = read_traffic(f"{entry['kernel']}_{head.name}")
+
+    result = {
+        "metric": "GFLOP/s (fp32 direct convolution, per conv shape; % of fp32 peak and HBM GB/s alongside)",
+        "value": entry["gflops"], "unit": "GFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{head.name}: {entry['kernel']} " + json.dumps(entry["shape"]).replace('"', "")},
+        "roofline": roof,
+    }
+    del run
+    torch.cuda.empty_cache()
+
+    if not args.no_extra_configs and not args.only:
+        per = [entry]
+        order = ["S1", "S2_F3", "S2_F7", "S2_F9", "S2_F11", "G1", "G2", "G3"]
+        for name in order:
+            w = allw[name]
+            r, _ = make_runner(w)
+            m, _ = time_launches(r, max(5, min(args.steps, 20)), max(2, min(args.warmup, 3)))
+            per.append(config_entry(w, m))
+            del r
+            torch.cuda.empty_cache()
+        result["per_config"] = per
+        g = {e["name"]: e for e in per}
+        result["roofline_general"] = {
+            "bound": "mfma", "kernel": "dconv_general", "workload": "G3",
+            "achieved": round(g["G3"]["gflops"] / 1e3, 3), "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": g["G3"]["frac_fp32_peak"], "traffic": None}
+
+    if not args.no_cpu_baseline and head.kind == "single":
+        result["cpu_baseline"] = cpu_baseline(head, x, f)
+    elif not args.no_cpu_baseline:
+        import oracle
+        import numpy as np
+        n_img = 1
+        t0 = time.perf_counter()
+        _, _, thr = oracle.general(np.ascontiguousarray(x[:n_img]), f)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(head.flops / head.N * n_img / dt / 1e9, 3),
+                                  "unit": "GFLOP/s", "cores": int(thr), "kind": "oracle",
+                                  "seconds": round(dt, 2), "sample": f"first {n_img} image(s) of the batch"}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

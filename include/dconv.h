@@ -1,0 +1,106 @@
+/*
+ * dconv -- direct (no GEMM lowering, no FFT, no Winograd) fp32 2D convolution
+ * for AMD MI355X (gfx950), after "Optimizing Memory Efficiency for
+ * Convolution Kernels on Kepler GPUs" (Chen, Chen, Chen, Hu, DAC'17).
+ *
+ * C ABI of libdconv.so.  Letters: batch N, channels C, image H x W, K filters
+ * of side F.  (The paper's Fig. 3 caption writes K for the filter side and F
+ * for the number of filters; this header uses the letters above throughout.)
+ *
+ * Common rules for every compute entry point
+ *   - Every data pointer is a DEVICE pointer to dense, row-major fp32 in HBM.
+ *     The caller owns all buffers; the library neither allocates, frees nor
+ *     keeps them.  `out` must not overlap an input.  Base pointers must be
+ *     4-byte aligned (anything hipMalloc or a torch tensor returns is).
+ *   - Semantics: cross-correlation (no filter flip), stride 1, no padding,
+ *     window anchored at the top-left output position:
+ *         Ho = H - F + 1,  Wo = W - F + 1
+ *         out[n][k][y][x] = sum_c sum_i sum_j in[n][c][y+i][x+j] * filt[k][c][i][j]
+ *     Every element of `out` is overwritten (no bias, no scaling, no
+ *     accumulation into old contents).  Arithmetic is fp32 multiply-add with
+ *     fp32 accumulation; the order of additions is unspecified, so results
+ *     agree with an exact sum to within rounding of an fp32 sum of C*F*F
+ *     terms, and are bit-exact whenever all partial sums are exactly
+ *     representable.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it and the call returns without synchronising.
+ *     The launch happens on the device that is current in the calling thread;
+ *     the buffers must live on that device.
+ *   - The return value is a dconv_status; nothing is launched unless
+ *     validation passed.  The library never aborts or throws across the ABI.
+ *   - Calls are thread-safe.
+ */
+#ifndef DCONV_H
+#define DCONV_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dconv_status {
+    DCONV_OK = 0,
+    DCONV_NULL_POINTER = 1,   /* a required pointer argument was NULL            */
+    DCONV_BAD_SHAPE = 2,      /* a dimension <= 0, F > H, F > W, or a size that
+                                 does not fit the kernels' 32-bit indexing       */
+    DCONV_UNSUPPORTED = 3,    /* the requested variant cannot run this shape     */
+    DCONV_LAUNCH_FAILED = 4   /* the HIP runtime reported an error at launch     */
+} dconv_status;
+
+/* Kernel variants accepted by the *_v entry points. */
+enum {
+    DCONV_VARIANT_AUTO = 0,   /* pick by shape (what the plain entry points do)  */
+    DCONV_VARIANT_SIMPLE = 1, /* one thread per output element; any shape        */
+    DCONV_VARIANT_TILED = 2   /* LDS-staged, matrix-core tiled kernel            */
+};
+
+/*
+ * Special case of the paper's Sec. 3 (Algorithm 1): ONE input channel
+ * convolved with K filters.
+ *   img  [H][W]            device, read
+ *   filt [K][F][F]         device, read
+ *   out  [K][H-F+1][W-F+1] device, written
+ * Errors: NULL img/filt/out -> DCONV_NULL_POINTER; H, W, K, F <= 0, F > H or
+ * F > W, or more than 2^31-1 elements in img or in one output plane ->
+ * DCONV_BAD_SHAPE.
+ */
+int dconv_single_channel(const float *img, int H, int W,
+                         const float *filt, int K, int F,
+                         float *out, void *stream);
+
+/*
+ * General case of the paper's Sec. 4 (Algorithm 2, Fig. 3a): C channels,
+ * K filters, with a batch of N independent images sharing the filters (the
+ * batch is this ABI's addition; the paper treats one image).
+ *   in   [N][C][H][W]            device, read
+ *   filt [K][C][F][F]            device, read
+ *   out  [N][K][H-F+1][W-F+1]    device, written
+ * Errors as above; additionally N, C <= 0, or more than 2^31-1 elements in
+ * `in`, in `filt` or in one image's output [K][Ho][Wo], -> DCONV_BAD_SHAPE.
+ */
+int dconv_general(const float *in, int N, int C, int H, int W,
+                  const float *filt, int K, int F,
+                  float *out, void *stream);
+
+/*
+ * The same two operations with the kernel variant chosen by the caller
+ * (DCONV_VARIANT_*), for tests and tuning.  A variant that cannot handle the
+ * shape returns DCONV_UNSUPPORTED without launching anything;
+ * DCONV_VARIANT_SIMPLE accepts every valid shape.
+ */
+int dconv_single_channel_v(const float *img, int H, int W,
+                           const float *filt, int K, int F,
+                           float *out, int variant, void *stream);
+int dconv_general_v(const float *in, int N, int C, int H, int W,
+                    const float *filt, int K, int F,
+                    float *out, int variant, void *stream);
+
+/* Human-readable name of a status code; static storage, never NULL. */
+const char *dconv_status_string(int status);
+
+/* ABI version: major * 1000 + minor. */
+int dconv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCONV_H */

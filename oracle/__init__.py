@@ -93,8 +93,13 @@ def general(x, filt, threads: int = 0, want32: bool = False):
     return (acc, mag, o32, used.value) if want32 else (acc, mag, used.value)
 
 
-def single_channel(img, filt, threads: int = 0):
-    """out[k,y,x] = sum_{i,j} img[y+i,x+j] * filt[k,i,j] in fp64 -> (acc64, mag64, threads)."""
+def single_channel(img, filt, threads: int = 0, only32: bool = False):
+    """out[k,y,x] = sum_{i,j} img[y+i,x+j] * filt[k,i,j] in fp64 -> (acc64, mag64, threads).
+
+    With only32=True the fp64 sums are rounded to float32 and only that array
+    is produced: (out32, threads).  Used to time the oracle on large inputs
+    without the two fp64 result arrays.
+    """
     img, filt = _f32(img), _f32(filt)
     H, W = img.shape
     K, F, F2 = filt.shape
@@ -103,14 +108,21 @@ def single_channel(img, filt, threads: int = 0):
     Ho, Wo = H - F + 1, W - F + 1
     if Ho <= 0 or Wo <= 0:
         raise ValueError("filter larger than image")
-    acc = np.empty((K, Ho, Wo), np.float64)
-    mag = np.empty((K, Ho, Wo), np.float64)
     used = ctypes.c_int(0)
+    if only32:
+        o32 = np.empty((K, Ho, Wo), np.float32)
+        acc = mag = None
+    else:
+        o32 = None
+        acc = np.empty((K, Ho, Wo), np.float64)
+        mag = np.empty((K, Ho, Wo), np.float64)
     rc = _load().dconv_oracle_single_channel(_ptr(img), H, W, _ptr(filt), K, F,
-                                             None, _ptr(acc), _ptr(mag),
+                                             _ptr(o32), _ptr(acc), _ptr(mag),
                                              threads, ctypes.byref(used))
     if rc != 0:
         raise RuntimeError(f"oracle rejected the arguments (code {rc})")
+    if only32:
+        return o32, used.value
     return acc, mag, used.value
 
 

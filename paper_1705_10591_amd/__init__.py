@@ -1,0 +1,128 @@
+"""MI355X-native direct fp32 2D convolution (gfx950): Python binding of libdconv.so.
+
+The functions here only marshal arguments: they take torch CUDA tensors
+(device memory and the current stream come from PyTorch), pass raw device
+pointers and sizes through the C ABI declared in include/dconv.h, and return
+the output tensor.  Every step of the computation runs in the HIP kernels of
+the library.  There is no CPU or PyTorch fallback: if the library has not
+been built, importing the compute functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libdconv.so"
+
+VARIANT_AUTO, VARIANT_SIMPLE, VARIANT_TILED = 0, 1, 2
+STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAUNCH_FAILED = range(5)
+
+EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
+           "dconv_general_v", "dconv_status_string", "dconv_version")
+
+_lib = None
+
+
+class DconvError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"dconv status {status}: {message}")
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdconv.so from the package directory; raise if it was never built."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_1705_10591_amd.build` "
+                "(there is no fallback path)")
+        lib = ctypes.CDLL(str(LIB_PATH))
+        p, i = ctypes.c_void_p, ctypes.c_int
+        lib.dconv_single_channel.argtypes = [p, i, i, p, i, i, p, p]
+        lib.dconv_single_channel_v.argtypes = [p, i, i, p, i, i, p, i, p]
+        lib.dconv_general.argtypes = [p, i, i, i, i, p, i, i, p, p]
+        lib.dconv_general_v.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
+        for name in ("dconv_single_channel", "dconv_single_channel_v",
+                     "dconv_general", "dconv_general_v", "dconv_version"):
+            getattr(lib, name).restype = i
+        lib.dconv_status_string.argtypes = [i]
+        lib.dconv_status_string.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().dconv_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().dconv_version())
+
+
+def _check(t: torch.Tensor, ndim: int, what: str):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32
+            and t.dim() == ndim and t.is_contiguous()):
+        raise TypeError(f"{what} must be a contiguous float32 CUDA tensor with {ndim} dims")
+
+
+def _raise(rc: int):
+    if rc != STATUS_OK:
+        raise DconvError(rc, status_string(rc))
+
+
+def _stream_ptr(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def dconv_single_channel(img: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
+                         variant: int = VARIANT_AUTO) -> torch.Tensor:
+    """out[k,y,x] = sum_{i,j} img[y+i,x+j] * filt[k,i,j]   (one input channel, K filters)."""
+    _check(img, 2, "img")
+    _check(filt, 3, "filt")
+    H, W = img.shape
+    K, F, F2 = filt.shape
+    if F != F2:
+        raise ValueError("filters must be square")
+    if F > H or F > W:
+        _raise(STATUS_BAD_SHAPE)
+    if out is None:
+        out = torch.empty((K, H - F + 1, W - F + 1), dtype=torch.float32, device=img.device)
+    else:
+        _check(out, 3, "out")
+        if tuple(out.shape) != (K, H - F + 1, W - F + 1):
+            raise ValueError("out has the wrong shape")
+    with torch.cuda.device(img.device):
+        rc = load_library().dconv_single_channel_v(
+            img.data_ptr(), H, W, filt.data_ptr(), K, F, out.data_ptr(), int(variant),
+            _stream_ptr(img.device))
+    _raise(rc)
+    return out
+
+
+def dconv_general(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
+                  variant: int = VARIANT_AUTO) -> torch.Tensor:
+    """out[n,k,y,x] = sum_{c,i,j} x[n,c,y+i,x+j] * filt[k,c,i,j]."""
+    _check(x, 4, "in")
+    _check(filt, 4, "filt")
+    N, C, H, W = x.shape
+    K, C2, F, F2 = filt.shape
+    if C2 != C or F != F2:
+        raise ValueError("filter shape does not match the input")
+    if F > H or F > W:
+        _raise(STATUS_BAD_SHAPE)
+    if out is None:
+        out = torch.empty((N, K, H - F + 1, W - F + 1), dtype=torch.float32, device=x.device)
+    else:
+        _check(out, 4, "out")
+        if tuple(out.shape) != (N, K, H - F + 1, W - F + 1):
+            raise ValueError("out has the wrong shape")
+    with torch.cuda.device(x.device):
+        rc = load_library().dconv_general_v(
+            x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), int(variant),
+            _stream_ptr(x.device))
+    _raise(rc)
+    return out

@@ -1,0 +1,100 @@
+// C ABI of libdconv.so: argument validation and kernel dispatch.
+#include "common.h"
+#include "../../include/dconv.h"
+
+using dconv::Shape;
+
+namespace {
+
+constexpr int64_t kMaxElems = 2147483647LL;
+
+int validate(const void* in, const void* filt, const void* out,
+             int N, int C, int H, int W, int K, int F, Shape* s)
+{
+    if (!in || !filt || !out) return DCONV_NULL_POINTER;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || F <= 0) return DCONV_BAD_SHAPE;
+    if (F > H || F > W) return DCONV_BAD_SHAPE;
+    const int Ho = H - F + 1, Wo = W - F + 1;
+    // sizes are checked in floating point first so the int64 products below cannot overflow
+    const double in_elems = (double)N * C * H * W;
+    const double filt_elems = (double)K * C * F * F;
+    const double img_out = (double)K * Ho * Wo;
+    if (in_elems > (double)kMaxElems || filt_elems > (double)kMaxElems ||
+        img_out > (double)kMaxElems || (double)N * img_out > 9.0e18)
+        return DCONV_BAD_SHAPE;
+    *s = Shape{N, C, H, W, K, F, Ho, Wo};
+    return DCONV_OK;
+}
+
+int dispatch(bool single, const float* in, const float* filt, float* out,
+             const Shape& s, int variant, void* stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const bool tiled_ok = single ? dconv::single_tiled_supports(s)
+                                 : dconv::general_tiled_supports(s);
+    switch (variant) {
+    case DCONV_VARIANT_AUTO:
+        if (tiled_ok)
+            return single ? dconv::launch_single_tiled(in, filt, out, s, st)
+                          : dconv::launch_general_tiled(in, filt, out, s, st);
+        return dconv::launch_simple(in, filt, out, s, st);
+    case DCONV_VARIANT_SIMPLE:
+        return dconv::launch_simple(in, filt, out, s, st);
+    case DCONV_VARIANT_TILED:
+        if (!tiled_ok) return DCONV_UNSUPPORTED;
+        return single ? dconv::launch_single_tiled(in, filt, out, s, st)
+                      : dconv::launch_general_tiled(in, filt, out, s, st);
+    default:
+        return DCONV_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int dconv_single_channel_v(const float* img, int H, int W, const float* filt, int K, int F,
+                           float* out, int variant, void* stream)
+{
+    Shape s;
+    const int rc = validate(img, filt, out, 1, 1, H, W, K, F, &s);
+    if (rc != DCONV_OK) return rc;
+    return dispatch(true, img, filt, out, s, variant, stream);
+}
+
+int dconv_general_v(const float* in, int N, int C, int H, int W, const float* filt, int K, int F,
+                    float* out, int variant, void* stream)
+{
+    Shape s;
+    const int rc = validate(in, filt, out, N, C, H, W, K, F, &s);
+    if (rc != DCONV_OK) return rc;
+    return dispatch(false, in, filt, out, s, variant, stream);
+}
+
+int dconv_single_channel(const float* img, int H, int W, const float* filt, int K, int F,
+                         float* out, void* stream)
+{
+    return dconv_single_channel_v(img, H, W, filt, K, F, out, DCONV_VARIANT_AUTO, stream);
+}
+
+int dconv_general(const float* in, int N, int C, int H, int W, const float* filt, int K, int F,
+                  float* out, void* stream)
+{
+    return dconv_general_v(in, N, C, H, W, filt, K, F, out, DCONV_VARIANT_AUTO, stream);
+}
+
+const char* dconv_status_string(int status)
+{
+    switch (status) {
+    case DCONV_OK: return "ok";
+    case DCONV_NULL_POINTER: return "null pointer argument";
+    case DCONV_BAD_SHAPE: return "bad shape";
+    case DCONV_UNSUPPORTED: return "variant does not support this shape";
+    case DCONV_LAUNCH_FAILED: return "kernel launch failed";
+    default: return "unknown status";
+    }
+}
+
+int dconv_version(void) { return 1000; }
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Shared declarations of the dconv HIP sources (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dconv {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kThreads = 256;        // four waves per workgroup: one per SIMD of a CU
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// D(32x32) += A(32x2) * B(2x32) on the matrix cores, fp32 in, fp32 accumulate.
+// Operand layout for lane l of the wave:
+//   a  = A[l % 32][l / 32]          (row of D, reduction index l / 32)
+//   b  = B[l / 32][l % 32]          (reduction index l / 32, column of D)
+//   acc[r] = D[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32]
+__device__ __forceinline__ v16f mfma_32x32x2(float a, float b, v16f acc) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+}
+
+// Row of D held in accumulator register r by a lane of half h = lane / 32.
+__device__ __forceinline__ constexpr int mfma_row(int r, int h) {
+    return 8 * (r / 4) + 4 * h + (r % 4);
+}
+
+struct LaunchResult {
+    int status;      // dconv_status
+};
+
+// Shape of one problem, general layout (the single-channel case has N = C = 1).
+struct Shape {
+    int N, C, H, W, K, F, Ho, Wo;
+};
+
+// Host-side launchers, one per translation unit.  Each returns a dconv_status.
+int launch_simple(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st);
+int launch_single_tiled(const float* img, const float* filt, float* out, const Shape& s,
+                        hipStream_t st);
+int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
+                         hipStream_t st);
+bool single_tiled_supports(const Shape& s);
+bool general_tiled_supports(const Shape& s);
+
+}  // namespace dconv

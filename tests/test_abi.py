@@ -1,0 +1,83 @@
+"""CPU-side checks of the C ABI: the library loads, exports what the header
+declares, and validates arguments before touching the GPU."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+import paper_1705_10591_amd as dconv
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def _declared_functions():
+    text = (ROOT / "include" / "dconv.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dconv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert _declared_functions() == sorted(dconv.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = dconv.load_library()
+    for name in _declared_functions():
+        assert hasattr(lib, name), f"libdconv.so does not export {name}"
+
+
+def test_version_and_status_strings():
+    assert dconv.version() >= 1000
+    seen = {dconv.status_string(s) for s in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert dconv.status_string(12345)
+
+
+FAKE = ctypes.c_void_p(0x1000)   # never dereferenced: every call below fails validation
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_null_pointers_are_rejected(variant):
+    lib = dconv.load_library()
+    assert lib.dconv_single_channel_v(None, 8, 8, FAKE, 2, 3, FAKE, variant, None) == dconv.STATUS_NULL_POINTER
+    assert lib.dconv_single_channel_v(FAKE, 8, 8, None, 2, 3, FAKE, variant, None) == dconv.STATUS_NULL_POINTER
+    assert lib.dconv_single_channel_v(FAKE, 8, 8, FAKE, 2, 3, None, variant, None) == dconv.STATUS_NULL_POINTER
+    assert lib.dconv_general_v(None, 1, 2, 8, 8, FAKE, 2, 3, FAKE, variant, None) == dconv.STATUS_NULL_POINTER
+    assert lib.dconv_general(FAKE, 1, 2, 8, 8, FAKE, 2, 3, None, None) == dconv.STATUS_NULL_POINTER
+    assert lib.dconv_single_channel(FAKE, 8, 8, None, 2, 3, FAKE, None) == dconv.STATUS_NULL_POINTER
+
+
+@pytest.mark.parametrize("dims", [
+    (0, 1, 8, 8, 1, 3), (1, 0, 8, 8, 1, 3), (1, 1, 0, 8, 1, 3), (1, 1, 8, 0, 1, 3),
+    (1, 1, 8, 8, 0, 3), (1, 1, 8, 8, 1, 0), (1, 1, 8, 8, 1, -3), (-1, 1, 8, 8, 1, 3),
+    (1, 1, 4, 8, 1, 5),            # filter taller than the image
+    (1, 1, 8, 4, 1, 5),            # filter wider than the image
+    (64, 1024, 1024, 1024, 1, 3),  # input beyond 2^31-1 elements
+    (1, 1, 40000, 40000, 4, 3),    # one image's output beyond 2^31-1 elements
+    (1, 30000, 64, 64, 30000, 3),  # filter bank beyond 2^31-1 elements
+])
+def test_bad_shapes_are_rejected(dims):
+    N, C, H, W, K, F = dims
+    lib = dconv.load_library()
+    assert lib.dconv_general(FAKE, N, C, H, W, FAKE, K, F, FAKE, None) == dconv.STATUS_BAD_SHAPE
+    if N == 1 and C == 1:
+        assert lib.dconv_single_channel(FAKE, H, W, FAKE, K, F, FAKE, None) == dconv.STATUS_BAD_SHAPE
+
+
+def test_unknown_variant_and_unsupported_tiled_shape():
+    lib = dconv.load_library()
+    assert lib.dconv_general_v(FAKE, 1, 1, 8, 8, FAKE, 1, 3, FAKE, 99, None) == dconv.STATUS_UNSUPPORTED
+    # filter side above the largest compiled tiled kernel
+    assert lib.dconv_general_v(FAKE, 1, 1, 32, 32, FAKE, 1, 13, FAKE, dconv.VARIANT_TILED, None) \
+        == dconv.STATUS_UNSUPPORTED
+    assert lib.dconv_single_channel_v(FAKE, 32, 32, FAKE, 1, 13, FAKE, dconv.VARIANT_TILED, None) \
+        == dconv.STATUS_UNSUPPORTED
+
+
+def test_python_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        dconv.dconv_general(torch.zeros(1, 1, 4, 4), torch.zeros(1, 1, 3, 3))
+    with pytest.raises(TypeError):
+        dconv.dconv_single_channel(torch.zeros(4, 4), torch.zeros(1, 3, 3))

@@ -1,0 +1,276 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bar: integer-valued cases bit-exact; floating point within
+|gpu - exact| <= 1e-5 * sum|x*w| per output element, where `exact` is the
+oracle's fp64 sum.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_1705_10591_amd as dconv
+from helpers import assert_within_bound
+
+pytestmark = pytest.mark.gpu
+
+SIMPLE, TILED, AUTO = dconv.VARIANT_SIMPLE, dconv.VARIANT_TILED, dconv.VARIANT_AUTO
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def run_general(x, f, variant):
+    print(f"general N,C,H,W={x.shape} K,F={f.shape[0]},{f.shape[-1]} variant={variant}", flush=True)
+    out = dconv.dconv_general(dev(x), dev(f), variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def run_single(img, f, variant):
+    print(f"single H,W={img.shape} K,F={f.shape[0]},{f.shape[-1]} variant={variant}", flush=True)
+    out = dconv.dconv_single_channel(dev(img), dev(f), variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+# (N, C, H, W, K, F): several tiles, ragged tails, strips, image-boundary crossings
+GENERAL_SHAPES = [
+    (2, 3, 20, 23, 5, 3),
+    (1, 8, 30, 30, 70, 3),       # more than 64 filters: the wide filter tile
+    (3, 16, 28, 28, 130, 3),     # pixel blocks wrap over rows and images
+    (2, 4, 40, 150, 33, 5),      # output wider than one column strip
+    (1, 2, 12, 300, 8, 2),
+    (2, 3, 37, 41, 64, 11),
+    (1, 1, 9, 9, 1, 1),
+    (2, 5, 16, 16, 3, 4),
+    (1, 7, 20, 20, 9, 7),
+    (5, 6, 8, 8, 4, 3),          # tiny images: one pixel block spans several images
+    (3, 2, 5, 5, 4, 5),          # filter as large as the image: 1x1 output
+    (1, 3, 14, 14, 2, 9),
+    (1, 2, 13, 12, 3, 10),
+    (2, 2, 11, 10, 2, 6),
+    (1, 2, 12, 11, 2, 8),
+    (7, 24, 9, 35, 96, 3),
+    (1, 64, 20, 20, 64, 1),      # 1x1 filters: no spatial reuse at all
+]
+
+
+@pytest.mark.parametrize("variant", [SIMPLE, TILED], ids=["simple", "tiled"])
+@pytest.mark.parametrize("shape", GENERAL_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_general_small_shapes(shape, variant):
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(100 + F, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    got = run_general(x, f, variant)
+    assert_within_bound(got, acc, mag, f"general {shape}")
+
+
+# (H, W, K, F)
+SINGLE_SHAPES = [
+    (40, 300, 5, 3),
+    (33, 31, 70, 5),
+    (20, 20, 1, 1),
+    (64, 600, 130, 7),
+    (30, 40, 3, 11),
+    (17, 17, 2, 2),
+    (50, 50, 33, 9),
+    (21, 260, 16, 4),
+    (19, 22, 8, 6),
+    (25, 140, 40, 8),
+    (15, 15, 3, 10),
+    (9, 9, 2, 9),               # 1x1 output
+    (100, 515, 64, 5),          # three tiles across, ragged last one
+]
+
+
+@pytest.mark.parametrize("variant", [SIMPLE, TILED], ids=["simple", "tiled"])
+@pytest.mark.parametrize("shape", SINGLE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_single_channel_small_shapes(shape, variant):
+    H, W, K, F = shape
+    x, f = wl.random_case(200 + F, 1, 1, H, W, K, F)
+    img, flt = x[0, 0], f[:, 0]
+    acc, mag, _ = oracle.single_channel(img, flt)
+    got = run_single(img, flt, variant)
+    assert_within_bound(got, acc, mag, f"single {shape}")
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 28, 28, 70, 3), (1, 3, 30, 140, 64, 11), (3, 6, 12, 12, 9, 5)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_general_integer_inputs_are_bit_exact(shape):
+    N, C, H, W, K, F = shape
+    x, f = wl.integer_case(1, N, C, H, W, K, F)
+    _, _, o32, _ = oracle.general(x, f, want32=True)
+    for variant in (SIMPLE, TILED):
+        np.testing.assert_array_equal(run_general(x, f, variant), o32)
+
+
+@pytest.mark.parametrize("shape", [(60, 300, 40, 3), (40, 41, 64, 5), (30, 270, 7, 11)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_single_channel_integer_inputs_are_bit_exact(shape):
+    H, W, K, F = shape
+    x, f = wl.integer_case(2, 1, 1, H, W, K, F)
+    _, _, o32, _ = oracle.general(x, f, want32=True)
+    for variant in (SIMPLE, TILED):
+        np.testing.assert_array_equal(run_single(x[0, 0], f[:, 0], variant), o32[0])
+
+
+def test_filter_side_without_a_tiled_kernel_falls_back():
+    x, f = wl.random_case(3, 1, 2, 20, 20, 3, 13)
+    acc, mag, _ = oracle.general(x, f)
+    assert_within_bound(run_general(x, f, AUTO), acc, mag, "F=13 auto")
+    with pytest.raises(dconv.DconvError) as e:
+        run_general(x, f, TILED)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
+    acc, mag, _ = oracle.single_channel(x[0, 0], f[:, 0])
+    assert_within_bound(run_single(x[0, 0], f[:, 0], AUTO), acc, mag, "F=13 single auto")
+
+
+def test_single_channel_agrees_with_general_on_one_image_one_channel():
+    x, f = wl.random_case(4, 1, 1, 70, 290, 48, 5)
+    acc, mag, _ = oracle.general(x, f)
+    a = run_single(x[0, 0], f[:, 0], AUTO)
+    b = run_general(x, f, AUTO)
+    assert_within_bound(a, acc[0], mag[0], "single")
+    assert_within_bound(b, acc, mag, "general")
+
+
+def test_output_guard_bands_stay_untouched_and_every_element_is_written():
+    N, C, H, W, K, F = 2, 8, 28, 28, 40, 3
+    x, f = wl.random_case(5, N, C, H, W, K, F)
+    n_out = N * K * (H - F + 1) * (W - F + 1)
+    pad = 4096
+    buf = torch.full((n_out + 2 * pad,), float("nan"), device="cuda")
+    out = buf[pad:pad + n_out].view(N, K, H - F + 1, W - F + 1)
+    for variant in (SIMPLE, TILED):
+        buf.fill_(float("nan"))
+        dconv.dconv_general(dev(x), dev(f), out=out, variant=variant)
+        torch.cuda.synchronize()
+        assert torch.isnan(buf[:pad]).all() and torch.isnan(buf[pad + n_out:]).all()
+        assert torch.isfinite(out).all()
+    Hs, Ws, Ks, Fs = 45, 300, 20, 5
+    xs, fs = wl.random_case(6, 1, 1, Hs, Ws, Ks, Fs)
+    n_out = Ks * (Hs - Fs + 1) * (Ws - Fs + 1)
+    buf = torch.full((n_out + 2 * pad,), float("nan"), device="cuda")
+    out = buf[pad:pad + n_out].view(Ks, Hs - Fs + 1, Ws - Fs + 1)
+    for variant in (SIMPLE, TILED):
+        buf.fill_(float("nan"))
+        dconv.dconv_single_channel(dev(xs[0, 0]), dev(fs[:, 0]), out=out, variant=variant)
+        torch.cuda.synchronize()
+        assert torch.isnan(buf[:pad]).all() and torch.isnan(buf[pad + n_out:]).all()
+        assert torch.isfinite(out).all()
+
+
+def test_runs_on_a_side_stream_and_is_repeatable():
+    x, f = wl.random_case(7, 2, 8, 30, 30, 64, 3)
+    acc, mag, _ = oracle.general(x, f)
+    xd, fd = dev(x), dev(f)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        a = dconv.dconv_general(xd, fd)
+        b = dconv.dconv_general(xd, fd)
+    s.synchronize()
+    assert torch.equal(a, b)
+    assert_within_bound(a.cpu().numpy(), acc, mag, "side stream")
+
+
+def test_python_binding_reports_bad_shapes():
+    with pytest.raises(dconv.DconvError) as e:
+        dconv.dconv_general(torch.zeros(1, 1, 4, 4, device="cuda"), torch.zeros(1, 1, 5, 5, device="cuda"))
+    assert e.value.status == dconv.STATUS_BAD_SHAPE
+
+
+# ---- the benchmark configurations at full size -------------------------------------------
+
+def _sampled_check(w, out_dev, x, f, count, what):
+    idx = wl.sample_indices(w.seed, w.out_elems, count)
+    got = out_dev.reshape(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    x4 = x.reshape(w.N, w.C, w.H, w.W)
+    f4 = f.reshape(w.K, w.C, w.F, w.F)
+    acc, mag = oracle.general_at(x4, f4, idx)
+    return assert_within_bound(got, acc, mag, what)
+
+
+def test_config_S1_whole_output():
+    w = wl.S1
+    img, f = wl.make_inputs(w)
+    acc, mag, _ = oracle.single_channel(img, f)
+    for variant in (AUTO, SIMPLE):
+        assert_within_bound(run_single(img, f, variant), acc, mag, f"S1 variant {variant}")
+
+
+@pytest.mark.parametrize("F", [5, 3, 7, 9, 11])
+def test_config_S2_sampled_outputs(F):
+    w = wl.S2_SWEEP[F] if F != 5 else wl.S2
+    img, f = wl.make_inputs(w)
+    print(f"S2 F={F}", flush=True)
+    out = dconv.dconv_single_channel(dev(img), dev(f))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    _sampled_check(w, out, img, f, 40000, f"S2 F={F}")
+    # rows and columns at tile seams and at the far edges, whole
+    ys = [0, 15, 16, 17, w.Ho - 1]
+    for k in (0, w.K - 1):
+        for y in ys:
+            idx = (k * w.Ho + y) * w.Wo + np.arange(w.Wo, dtype=np.int64)
+            got = out.reshape(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+            acc, mag = oracle.general_at(img.reshape(1, 1, w.H, w.W), f.reshape(w.K, 1, F, F), idx)
+            assert_within_bound(got, acc, mag, f"S2 F={F} row {y} of map {k}")
+    del out
+
+
+def test_config_S2_delta_filters_reproduce_the_shifted_image_exactly():
+    w = wl.S2
+    img, _ = wl.make_inputs(w)
+    f = np.zeros(w.filt_shape(), np.float32)
+    taps = [(k % w.F, (k // w.F) % w.F) for k in range(w.K)]
+    for k, (a, b) in enumerate(taps):
+        f[k, a, b] = 1.0
+    imgd = dev(img)
+    out = dconv.dconv_single_channel(imgd, dev(f))
+    torch.cuda.synchronize()
+    for k, (a, b) in enumerate(taps):
+        assert torch.equal(out[k], imgd[a:a + w.Ho, b:b + w.Wo]), f"map {k} tap {(a, b)}"
+
+
+def test_config_G1_sampled_outputs():
+    w = wl.G1
+    x, f = wl.make_inputs(w)
+    print("G1", flush=True)
+    out = dconv.dconv_general(dev(x), dev(f))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    _sampled_check(w, out, x, f, 60000, "G1")
+
+
+def test_config_G2_whole_output():
+    w = wl.G2
+    x, f = wl.make_inputs(w)
+    acc, mag, _ = oracle.general(x, f)
+    assert_within_bound(run_general(x, f, AUTO), acc, mag, "G2")
+
+
+def test_config_G3_sampled_outputs_and_one_image_whole():
+    w = wl.G3
+    x, f = wl.make_inputs(w)
+    print("G3", flush=True)
+    out = dconv.dconv_general(dev(x), dev(f))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    _sampled_check(w, out, x, f, 100000, "G3")
+    acc, mag, _ = oracle.general(x[-1:], f[:64])
+    assert_within_bound(out[-1, :64].cpu().numpy(), acc[0], mag[0], "G3 last image, 64 maps")
+
+
+def test_config_G3_integer_inputs_bit_exact_on_samples():
+    w = wl.G3
+    x, f = wl.integer_case(9, w.N, w.C, w.H, w.W, w.K, w.F)
+    out = dconv.dconv_general(dev(x), dev(f))
+    torch.cuda.synchronize()
+    idx = wl.sample_indices(99, w.out_elems, 50000)
+    got = out.reshape(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    acc, _ = oracle.general_at(x, f, idx)
+    np.testing.assert_array_equal(got.astype(np.float64), acc)
