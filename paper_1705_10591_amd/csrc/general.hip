@@ -61,7 +61,8 @@ general_tiled_kernel(GenParams p)
     float* shImg = lds + TP * LDK;            // [CSH][RS][LS] image block, then one zero word
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: lets wave-level math run on the scalar unit
     const int h = lane >> 5, l32 = lane & 31;
     const int wm = wave / WN, wn = wave % WN;
 

@@ -21,8 +21,19 @@
 // Instead of the rolling one-row prefetch, the whole tile is staged up front:
 // several workgroups share a CU, so one group's loads overlap the others'
 // arithmetic and stores.
+#include <stdlib.h>
 #include "common.h"
 #include "../../include/dconv.h"
+
+#ifdef DCONV_DBG_TIMING
+__device__ unsigned long long dconv_dbg_t[4 * 65536];
+extern "C" int dconv_dbg_read(unsigned long long* host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(dconv_dbg_t), sizeof(unsigned long long) * n);
+}
+#define DBG_T(slot) do { if (lane == 0 && blockIdx.x < 4096) dconv_dbg_t[(blockIdx.x * 4 + wave) * 4 + (slot)] = wall_clock64(); } while (0)
+#else
+#define DBG_T(slot) do {} while (0)
+#endif
 
 namespace dconv {
 
@@ -32,44 +43,70 @@ struct SingleParams {
     float* out;
     int H, W, K, Ho, Wo;
     int tiles_x, tiles_y;
+    int fgroups;     // filter groups (of 32*fbw filters); work items = tiles * fgroups
+    int per_xcd;     // work items per XCD (the chip has 8), see the mapping in the kernel
     int fbw;         // 32-filter blocks handled by one workgroup: 1, 2 or 4
+    int colsplit;    // 1: the four waves share a filter block and a row and split its passes
 };
 
-// TW: tile width in pixels (multiple of 128), TR: tile rows, PAD: extra words per LDS row.
-template <int F, int TW, int TR, int PAD>
-__global__ void __launch_bounds__(kThreads)
+// Write-back.  The output is the whole cost of this case and HBM only runs at
+// full rate when whole, aligned 128-byte lines are stored; but rows of Wo
+// floats start at arbitrary 4-byte offsets and every output plane has its own
+// offset.  So a wave does not store its accumulators directly.  It computes
+// 32 more columns than it writes (NBW + 1 blocks of 32 pixels per pass), parks
+// 8 filters at a time in a private LDS strip, each filter row shifted by its
+// own misalignment s_k in [0,31], and then streams out, per filter, the window
+// of 32*NBW pixels that begins on a line boundary of the global address, 16
+// bytes per lane.  Successive passes along a row use the same shift, so their
+// windows tile the row exactly; only the first s_k pixels and the clipped end
+// of each row are written piecemeal (the "edge" path below).
+
+// TW: nominal tile width in pixels, TR: tile rows, NBW: 32-pixel blocks written per pass,
+// PAD: extra words per LDS row, WPE: waves per SIMD the register budget is cut for.
+template <int F, int TW, int TR, int NBW, int PAD, int WPE, bool PIPE>
+__global__ void __launch_bounds__(kThreads, WPE)
 single_tiled_kernel(SingleParams p)
 {
     constexpr int FF = F * F;
     constexpr int TP = FF + (FF & 1);
     constexpr int S = TP / 2;                   // matrix-core steps per 32x32 block
-    constexpr int LS = TW + F - 1 + PAD;        // LDS row stride
+    constexpr int LS = TW + 32 + F - 1 + PAD;   // LDS row stride of the image tile
     constexpr int ROWS = TR + F - 1;            // staged image rows; one more row of zeros follows
-    constexpr int NB = 4;                       // 32-pixel blocks per wave pass: 128 pixels
-    constexpr int CHUNKS = TW / (32 * NB);
+    constexpr int NB = NBW + 1;                 // blocks computed per pass
+    constexpr int PASS = 32 * NBW;              // pixels written per pass
+    constexpr int CHUNKS = TW / PASS;
+    constexpr int SW = 32 * NB + 32;            // row stride of the write-back strip
+    constexpr int LPR = PASS / 4;               // lanes that cover one filter's window, 16 B each
+    constexpr int RPI = kWave / LPR;            // filter rows stored per instruction
+    constexpr int ITS = 8 / RPI;                // store instructions per group of 8 filters
+    constexpr int IMG_WORDS = ((ROWS + 1) * LS + 3) & ~3;
+    static_assert(TW % PASS == 0 && (NBW == 4 || NBW == 8), "tile shape");
 
-    __shared__ float sh[(ROWS + 1) * LS];
+    __shared__ __attribute__((aligned(16))) float sh[IMG_WORDS + 4 * 8 * SW];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: lets wave-level math run on the scalar unit
     const int h = lane >> 5, l32 = lane & 31;
+    float* stg = sh + IMG_WORDS + wave * (8 * SW);
 
-    const int tx = blockIdx.x % p.tiles_x;
-    const int ty = blockIdx.x / p.tiles_x;
+    // Workgroups are handed to the 8 XCDs round-robin by their linear id.  Give each XCD one
+    // contiguous range of work items (a band of the image), walked along x, so that its L2
+    // sees neighbouring tiles and every XCD gets the same mix of edge and interior tiles.
+    const int item = (blockIdx.x % 8) * p.per_xcd + blockIdx.x / 8;
+    const int ntiles = p.tiles_x * p.tiles_y;
+    if (item >= ntiles * p.fgroups) return;                // uniform: before any barrier
+    const int fgroup = item / ntiles, tile = item - fgroup * ntiles;
+    const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
     const int x0 = tx * TW, y0 = ty * TR;
-    const int fb = blockIdx.y * p.fbw + wave % p.fbw;     // this wave's 32-filter block
-    const int sub = wave / p.fbw, nsub = 4 / p.fbw;       // its share of the tile rows
+    const int fb = fgroup * p.fbw + wave % p.fbw;          // this wave's 32-filter block
+    // Which (row, pass) pairs this wave takes.  Either the waves of a filter block
+    // interleave the tile rows, or (colsplit) all four waves walk the rows together and
+    // interleave the passes of each row, so that the workgroup writes into few pages at a time.
+    const int row_start = p.colsplit ? 0 : wave / p.fbw, row_step = p.colsplit ? 1 : 4 / p.fbw;
+    const int ch_start = p.colsplit ? wave : 0, ch_step = p.colsplit ? 4 : 1;
 
-    // ---- stage the tile (zeros outside the image), coalesced along rows --------------
-    const int cols = min(TW + F - 1, p.W - x0);
-    for (int r = 0; r < ROWS; ++r) {
-        const int gy = y0 + r;
-        const float* src = p.img + (int64_t)gy * p.W + x0;
-        for (int c = tid; c < LS; c += kThreads)
-            sh[r * LS + c] = (gy < p.H && c < cols) ? src[c] : 0.f;
-    }
-    for (int c = tid; c < LS; c += kThreads) sh[ROWS * LS + c] = 0.f;
-
+    DBG_T(0);
     // ---- this wave's filter operands: a[s] = filt[k][tap 2s + h], zero beyond K / F*F --
     float a[S];
     {
@@ -80,61 +117,197 @@ single_tiled_kernel(SingleParams p)
             a[s] = (k < p.K && t < FF) ? p.filt[(int64_t)k * FF + t] : 0.f;
         }
     }
-    __syncthreads();
-
-    const int64_t plane = (int64_t)p.Ho * p.Wo;
-    const int rows_here = min(TR, p.Ho - y0);
-    const int dY = h * (LS - (F - 1));          // second tap of a pair sits on the next row
-
-    for (int r = sub; r < rows_here; r += nsub) {
-#pragma unroll 1
-        for (int ch = 0; ch < CHUNKS; ++ch) {
-            const int xc = ch * (32 * NB);                 // first column of this pass, in tile
-            if (x0 + xc >= p.Wo) break;
-            const int base = r * LS + xc + l32;
-            v16f acc[NB];
+    // ---- stage the tile (zeros outside the image), coalesced along rows --------------
+    {
+        const int cols = min(LS, p.W - x0);
+        const int rows_ok = min(ROWS, p.H - y0);
+        const float* src = p.img + (int64_t)y0 * p.W + x0;
+        constexpr int TOTAL = (ROWS + 1) * LS;
+        // all loads are issued before the first LDS store: one trip to HBM, not one per batch
+        constexpr int UN = (TOTAL + kThreads - 1) / kThreads;
+        float v[UN];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+        for (int u = 0; u < UN; ++u) {
+            const int e = tid + u * kThreads;
+            const int r = e / LS, c = e - r * LS;
+            v[u] = (e < TOTAL && r < rows_ok && c < cols) ? src[(int64_t)r * p.W + c] : 0.f;
+        }
 #pragma unroll
-                for (int q = 0; q < 16; ++q) acc[nb][q] = 0.f;
-
-#pragma unroll
-            for (int s = 0; s < S; ++s) {
-                const int t0 = 2 * s, t1 = 2 * s + 1;
-                const int i = t0 / F, j = t0 % F;
-                float b[NB];
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    int addr;
-                    if (t1 >= FF)            // pad tap: the zero row (any column of it)
-                        addr = h ? (ROWS * LS + l32) : base + i * LS + j + nb * 32;
-                    else if (t1 / F != i) addr = base + dY + i * LS + j + nb * 32;
-                    else                  addr = base + h + i * LS + j + nb * 32;
-                    b[nb] = sh[addr];
-                }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma_32x32x2(a[s], b[nb], acc[nb]);
-            }
-
-            // 32 lanes write 32 consecutive pixels of one output plane
-            const int y = y0 + r;
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int k = fb * 32 + mfma_row(q, h);
-                float* dst = p.out + k * plane + (int64_t)y * p.Wo + x0 + xc + l32;
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int x = x0 + xc + nb * 32 + l32;
-                    if (k < p.K && x < p.Wo) __builtin_nontemporal_store(acc[nb][q], dst + nb * 32);
-                }
-            }
+        for (int u = 0; u < UN; ++u) {
+            const int e = tid + u * kThreads;
+            if (e < TOTAL) sh[e] = v[u];
         }
     }
+
+    __syncthreads();
+    DBG_T(1);
+
+    const int64_t plane = (int64_t)p.Ho * p.Wo;
+    const int pm = (int)(plane & 31);
+    const int a0 = (int)(((uintptr_t)p.out >> 2) & 31);   // misalignment of the buffer itself
+    const int rows_here = min(TR, p.Ho - y0);
+    const int dY = h * (LS - (F - 1));          // second tap of a pair sits on the next row
+    const int kb = fb * 32;
+    const bool full_block = kb + 32 <= p.K;
+    const int rrow = lane / LPR, c4 = lane % LPR;          // read phase: strip row and 16 B column
+    const int rdofs = rrow * SW + 32 + 4 * c4;
+    // The shift of filter k in output row y is s = -(k*pm + c0(y)) mod 32.  k*pm is split into
+    // a per-lane part (one register) and a wave-uniform part per accumulator register / store.
+    const int wl = 4 * h * SW + 32 + l32;                  // strip word of (q % 4 == 0, block 0, s = 0)
+    const int tw_lane = (kb + 4 * h) * pm;
+    const unsigned gl = (unsigned)(rrow * (int)plane + 4 * c4);
+    const int tr_lane = (kb + rrow) * pm;
+
+    // ---- the write-back of one pass, cut into UNITS small pieces ---------------------------
+    // Per group g of eight filters: 4 pieces that park one accumulator register of every block
+    // in the strip, ITS pieces that read one 16 B column back, ITS pieces that store it.
+    constexpr int UPG = 4 + 2 * ITS;
+    constexpr int UNITS = 4 * UPG;
+    struct Pending {           // the pass whose results still sit in registers
+        int tw, tr;            // per-lane shift seeds of its output row
+        float* orow;           // out[kb][y][X], wave-uniform
+        int X;                 // first output column of the pass
+        bool edge;             // first or last pass of a row, or a partly filled filter block
+    };
+    v4f held[ITS];
+    auto wb_unit = [&](int u, const v16f (&A)[NB], const Pending& pd) {
+        const int g = u / UPG, j = u % UPG;
+        if (j < 4) {
+            const int q = 4 * g + j;
+            const int sk = (-(pd.tw + (8 * g + j) * pm)) & 31;
+            float* dst = stg + (wl - sk) + j * SW;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) dst[nb * 32] = A[nb][q];
+        } else if (j < 4 + ITS) {
+            const int it = j - 4;
+            held[it] = *reinterpret_cast<const v4f*>(stg + rdofs + it * RPI * SW);
+        } else {
+            const int it = j - 4 - ITS;
+            const int sk = (-(pd.tr + (8 * g + it * RPI) * pm)) & 31;
+            float* ub = pd.orow + (8 * g + it * RPI) * plane;     // out[kb + 8g + it*RPI][y][X]
+            float* dst = ub + (gl + (unsigned)sk);                // this lane's four pixels
+            if (!pd.edge) {
+                *reinterpret_cast<v4f*>(dst) = held[it];
+            } else if (kb + 8 * g + it * RPI + rrow < p.K) {
+                // Same window, clipped to the row; whole 16 B pieces wherever they fit.
+                const int px = pd.X + sk + 4 * c4;
+                if (px + 3 < p.Wo) {
+                    *reinterpret_cast<v4f*>(dst) = held[it];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (px + e < p.Wo) dst[e] = held[it][e];
+                }
+                // First pass of a row: the sk pixels before the first line boundary.
+#ifndef DCONV_DBG_NOHEAD
+                if (pd.X == 0 && c4 < 8) {
+                    const float* row = stg + (it * RPI + rrow) * SW + 32 - sk;
+                    float* head = ub + rrow * plane;              // out[k][y][0]
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int hx = 4 * c4 + e;
+                        if (hx < sk && hx < p.Wo) head[hx] = row[hx];
+                    }
+                }
+#endif
+            }
+        }
+    };
+
+    // ---- one pass: the matrix-core steps for AN, with the write-back of the pending pass
+    // (accumulators AP) slotted between them so that LDS, stores and MFMA overlap in one wave.
+    auto compute = [&](v16f (&AN)[NB], const v16f (&AP)[NB], bool have_pending, const Pending& pd,
+                       int base) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) AN[nb][q] = 0.f;
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const int t0 = 2 * s, t1 = 2 * s + 1;
+            const int i = t0 / F, j = t0 % F;
+            float b[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                int addr;
+                if (t1 >= FF)            // pad tap: the zero row (any column of it)
+                    addr = h ? (ROWS * LS + l32) : base + i * LS + j + nb * 32;
+                else if (t1 / F != i) addr = base + dY + i * LS + j + nb * 32;
+                else                  addr = base + h + i * LS + j + nb * 32;
+                b[nb] = sh[addr];
+            }
+            if (have_pending) {
+#pragma unroll
+                for (int u = (s * UNITS) / S; u < ((s + 1) * UNITS) / S; ++u) wb_unit(u, AP, pd);
+            }
+#ifndef DCONV_DBG_NOMFMA
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) AN[nb] = mfma_32x32x2(a[s], b[nb], AN[nb]);
+#else
+            if (s == 0) for (int nb = 0; nb < NB; ++nb) for (int q = 0; q < 16; ++q) AN[nb][q] = a[0] + b[nb];
+#endif
+        }
+    };
+    auto flush = [&](const v16f (&AP)[NB], const Pending& pd) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) wb_unit(u, AP, pd);
+    };
+
+    // ---- the passes of this wave, two per trip so that the accumulator sets alternate -------
+    const int ch_eff = min(CHUNKS, (p.Wo - x0 + PASS - 1) / PASS);       // passes per row here
+    const int ch_mine = (ch_eff - ch_start + ch_step - 1) / ch_step;      // ... taken by this wave
+    const int rows_mine = rows_here > row_start ? (rows_here - row_start + row_step - 1) / row_step : 0;
+    const int npass = rows_mine * max(ch_mine, 0);
+
+    v16f acc0[NB], acc1[NB];
+    Pending pd{0, 0, nullptr, 0, false};
+    bool pend0 = false, pend1 = false;     // acc0 / acc1 hold an interior pass not yet written
+    int ri = 0, ci = 0;                    // row and chunk counters of the next pass
+
+    // one pass: fills AN; meanwhile writes back AP if it is pending; then either leaves AN
+    // pending (interior) or writes it at once (edge)
+    auto one_pass = [&](v16f (&AN)[NB], const v16f (&AP)[NB], bool& pendN, bool& pendP) {
+        const int r = row_start + ri * row_step;
+        const int ch = ch_start + ci * ch_step;
+        if (++ci == ch_mine) { ci = 0; ++ri; }
+        const int y = y0 + r;
+        const int64_t rowoff = (int64_t)y * p.Wo;
+        // alignment (in floats, mod 32) of out[k][y][X] is (k*pm + c0) mod 32 for every pass
+        // of a row, because passes start at multiples of 32
+        const int c0 = (int)((rowoff + x0 + a0) & 31);
+        const int tw = tw_lane + c0, tr = tr_lane + c0;
+        const int xc = ch * PASS;                      // first column of this pass, in tile
+        const int X = x0 + xc;                         // ... and in the output row
+        const int base = r * LS + xc + l32;
+        const bool interior = X > 0 && X + 32 + PASS <= p.Wo && full_block;
+        compute(AN, AP, pendP, pd, base);
+        pendP = false;
+        pd.tw = tw; pd.tr = tr;
+        pd.orow = p.out + kb * plane + rowoff + X;
+        pd.X = X;
+        pd.edge = !interior;
+        if (PIPE) pendN = true;
+        else flush(AN, pd);
+    };
+    if (PIPE) {
+#pragma unroll 1
+        for (int q = 0; q < npass; q += 2) {
+            one_pass(acc0, acc1, pend0, pend1);
+            if (q + 1 < npass) one_pass(acc1, acc0, pend1, pend0);
+        }
+    } else {
+#pragma unroll 1
+        for (int q = 0; q < npass; ++q) one_pass(acc0, acc0, pend0, pend1);
+    }
+    DBG_T(2);
+    if (pend0) flush(acc0, pd);
+    if (pend1) flush(acc1, pd);
+    DBG_T(3);
 }
 
 namespace {
 
-template <int F, int TW, int TR, int PAD>
+template <int F, int TW, int TR, int NBW, int PAD, int WPE, bool PIPE>
 int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
     SingleParams p;
@@ -144,25 +317,47 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     p.tiles_y = (s.Ho + TR - 1) / TR;
     const int fblocks = (s.K + 31) / 32;
     p.fbw = fblocks >= 4 ? 4 : fblocks >= 2 ? 2 : 1;
-    const int64_t gx = (int64_t)p.tiles_x * p.tiles_y;
-    const int gy = (fblocks + p.fbw - 1) / p.fbw;
-    if (gx > 2147483647LL || gy > 65535) return DCONV_UNSUPPORTED;
-    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, PAD>), dim3((unsigned)gx, (unsigned)gy),
-                       dim3(kThreads), 0, st, p);
+    p.colsplit = 0;
+    static const int mode = [] { const char* e = getenv("DCONV_SINGLE_MODE"); return e ? atoi(e) : 0; }();
+    if (mode == 1) { p.fbw = 1; p.colsplit = 1; }
+    if (mode == 2) { p.fbw = 1; }
+    if (mode == 3) { p.fbw = fblocks >= 2 ? 2 : 1; }
+    p.fgroups = (fblocks + p.fbw - 1) / p.fbw;
+    const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups;
+    if (items > 2000000000LL) return DCONV_UNSUPPORTED;
+    p.per_xcd = (int)((items + 7) / 8);
+    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, PAD, WPE, PIPE>),
+                       dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
+// Tile configurations compiled for every filter side.  Index 0 is the default; the others
+// can be selected with the environment variable DCONV_SINGLE_CFG for tuning runs.
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
-    return launch_cfg<F, 256, 16, 0>(img, filt, out, s, st);
+    static const int forced = [] {
+        const char* e = getenv("DCONV_SINGLE_CFG");
+        return e ? atoi(e) : -1;
+    }();
+    switch (forced) {
+    case 1: return launch_cfg<F, 512, 8, 4, 0, 2, true>(img, filt, out, s, st);
+    case 2: return launch_cfg<F, 1024, 8, 4, 0, 2, true>(img, filt, out, s, st);
+    case 3: return launch_cfg<F, 256, 16, 4, 0, 3, false>(img, filt, out, s, st);
+    case 4: return launch_cfg<F, 512, 8, 4, 0, 3, false>(img, filt, out, s, st);
+    case 5: return launch_cfg<F, 512, 4, 4, 0, 3, false>(img, filt, out, s, st);
+    case 6: return launch_cfg<F, 256, 8, 4, 0, 4, false>(img, filt, out, s, st);
+    default: return launch_cfg<F, 256, 16, 4, 0, 2, true>(img, filt, out, s, st);
+    }
 }
 
 }  // namespace
 
 bool single_tiled_supports(const Shape& s)
 {
-    return s.N == 1 && s.C == 1 && s.F >= 1 && s.F <= 11;
+    // lane offsets of the write-back are 32-bit: one output plane plus a row must fit
+    return s.N == 1 && s.C == 1 && s.F >= 1 && s.F <= 11 &&
+           (int64_t)s.Ho * s.Wo < (1LL << 29);
 }
 
 int launch_single_tiled(const float* img, const float* filt, float* out, const Shape& s,
