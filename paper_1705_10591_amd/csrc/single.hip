@@ -21,19 +21,27 @@
 // Instead of the rolling one-row prefetch, the whole tile is staged up front:
 // several workgroups share a CU, so one group's loads overlap the others'
 // arithmetic and stores.
+//
+// Write-back.  The output is the whole cost of this case, and HBM only runs
+// at full rate when whole, aligned 128-byte lines are stored: a line written
+// in two pieces by different workgroups costs many times a whole one.  But
+// rows of Wo floats start at arbitrary 4-byte offsets and every output plane
+// has its own offset.  So a wave does not store its accumulators directly.
+// It computes 32 more columns than it writes (NBW + 1 blocks of 32 pixels per
+// pass), parks 8 filters at a time in a private LDS strip, each filter row
+// shifted by its own misalignment s_k in [0,31], and then streams out, per
+// filter, the window of 32*NBW pixels that begins on a line boundary of the
+// global address, 16 bytes per lane.  Successive passes along a row use the
+// same shift, so their windows tile the row exactly.  Rows follow each other
+// without a gap in memory, so the line that holds the end of row y also holds
+// the first pixels of row y+1: on wide images the last pass of a row computes
+// those pixels too (its lanes beyond Wo wrap to the next row, whose first
+// columns are staged beside the tile) and stores the shared line whole.  Only
+// the very first and last line of a plane, and narrow images, are written
+// piecemeal.
 #include <stdlib.h>
 #include "common.h"
 #include "../../include/dconv.h"
-
-#ifdef DCONV_DBG_TIMING
-__device__ unsigned long long dconv_dbg_t[4 * 65536];
-extern "C" int dconv_dbg_read(unsigned long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(dconv_dbg_t), sizeof(unsigned long long) * n);
-}
-#define DBG_T(slot) do { if (lane == 0 && blockIdx.x < 4096) dconv_dbg_t[(blockIdx.x * 4 + wave) * 4 + (slot)] = wall_clock64(); } while (0)
-#else
-#define DBG_T(slot) do {} while (0)
-#endif
 
 namespace dconv {
 
@@ -43,34 +51,28 @@ struct SingleParams {
     float* out;
     int H, W, K, Ho, Wo;
     int tiles_x, tiles_y;
+    int fbw;         // 32-filter blocks handled by one workgroup: 1, 2 or 4
     int fgroups;     // filter groups (of 32*fbw filters); work items = tiles * fgroups
     int per_xcd;     // work items per XCD (the chip has 8), see the mapping in the kernel
-    int fbw;         // 32-filter blocks handled by one workgroup: 1, 2 or 4
-    int colsplit;    // 1: the four waves share a filter block and a row and split its passes
+    int wrap;        // 1: row ends are completed with the head of the next row (wide images)
 };
 
-// Write-back.  The output is the whole cost of this case and HBM only runs at
-// full rate when whole, aligned 128-byte lines are stored; but rows of Wo
-// floats start at arbitrary 4-byte offsets and every output plane has its own
-// offset.  So a wave does not store its accumulators directly.  It computes
-// 32 more columns than it writes (NBW + 1 blocks of 32 pixels per pass), parks
-// 8 filters at a time in a private LDS strip, each filter row shifted by its
-// own misalignment s_k in [0,31], and then streams out, per filter, the window
-// of 32*NBW pixels that begins on a line boundary of the global address, 16
-// bytes per lane.  Successive passes along a row use the same shift, so their
-// windows tile the row exactly; only the first s_k pixels and the clipped end
-// of each row are written piecemeal (the "edge" path below).
+// Kinds of pass, by how its windows may be stored.
+enum : int { kPlain = 0, kTail = 1, kEdge = 2 };
 
 // TW: nominal tile width in pixels, TR: tile rows, NBW: 32-pixel blocks written per pass,
-// PAD: extra words per LDS row, WPE: waves per SIMD the register budget is cut for.
-template <int F, int TW, int TR, int NBW, int PAD, int WPE, bool PIPE>
+// WPE: waves per SIMD the register budget is cut for, PIPE: overlap the write-back of a pass
+// with the matrix-core steps of the next one inside each wave, NT: nontemporal stores.
+template <int F, int TW, int TR, int NBW, int WPE, bool PIPE, bool NT>
 __global__ void __launch_bounds__(kThreads, WPE)
 single_tiled_kernel(SingleParams p)
 {
     constexpr int FF = F * F;
     constexpr int TP = FF + (FF & 1);
     constexpr int S = TP / 2;                   // matrix-core steps per 32x32 block
-    constexpr int LS = TW + 32 + F - 1 + PAD;   // LDS row stride of the image tile
+    constexpr int PC0 = TW + 32 + F - 1;        // first column of the next-row patch
+    constexpr int PW = 32 + F - 1;              // its width: the head of the next row
+    constexpr int LS = PC0 + PW;                // LDS row stride of the image tile
     constexpr int ROWS = TR + F - 1;            // staged image rows; one more row of zeros follows
     constexpr int NB = NBW + 1;                 // blocks computed per pass
     constexpr int PASS = 32 * NBW;              // pixels written per pass
@@ -79,14 +81,16 @@ single_tiled_kernel(SingleParams p)
     constexpr int LPR = PASS / 4;               // lanes that cover one filter's window, 16 B each
     constexpr int RPI = kWave / LPR;            // filter rows stored per instruction
     constexpr int ITS = 8 / RPI;                // store instructions per group of 8 filters
-    constexpr int IMG_WORDS = ((ROWS + 1) * LS + 3) & ~3;
+    constexpr int TOTAL = (ROWS + 1) * LS;
+    constexpr int IMG_WORDS = (TOTAL + 3) & ~3;
     static_assert(TW % PASS == 0 && (NBW == 4 || NBW == 8), "tile shape");
 
     __shared__ __attribute__((aligned(16))) float sh[IMG_WORDS + 4 * 8 * SW];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: lets wave-level math run on the scalar unit
+    // uniform: lets wave-level index math run on the scalar unit
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, l32 = lane & 31;
     float* stg = sh + IMG_WORDS + wave * (8 * SW);
 
@@ -100,13 +104,9 @@ single_tiled_kernel(SingleParams p)
     const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
     const int x0 = tx * TW, y0 = ty * TR;
     const int fb = fgroup * p.fbw + wave % p.fbw;          // this wave's 32-filter block
-    // Which (row, pass) pairs this wave takes.  Either the waves of a filter block
-    // interleave the tile rows, or (colsplit) all four waves walk the rows together and
-    // interleave the passes of each row, so that the workgroup writes into few pages at a time.
-    const int row_start = p.colsplit ? 0 : wave / p.fbw, row_step = p.colsplit ? 1 : 4 / p.fbw;
-    const int ch_start = p.colsplit ? wave : 0, ch_step = p.colsplit ? 4 : 1;
+    const int row_start = wave / p.fbw, row_step = 4 / p.fbw;   // its share of the tile rows
+    const bool wrap_tile = p.wrap && tx == p.tiles_x - 1;
 
-    DBG_T(0);
     // ---- this wave's filter operands: a[s] = filt[k][tap 2s + h], zero beyond K / F*F --
     float a[S];
     {
@@ -117,12 +117,15 @@ single_tiled_kernel(SingleParams p)
             a[s] = (k < p.K && t < FF) ? p.filt[(int64_t)k * FF + t] : 0.f;
         }
     }
-    // ---- stage the tile (zeros outside the image), coalesced along rows --------------
+    // ---- stage the tile (zeros outside the image), coalesced along rows.  LDS row r holds
+    // image row y0+r in columns [0, PC0) and, in the last tile column of a wide image, the
+    // first PW pixels of image row y0+r+1 in columns [PC0, LS).
     {
-        const int cols = min(LS, p.W - x0);
+        const int cols = min(PC0, p.W - x0);
         const int rows_ok = min(ROWS, p.H - y0);
+        const int prow_ok = wrap_tile ? min(ROWS, p.H - y0 - 1) : 0;
         const float* src = p.img + (int64_t)y0 * p.W + x0;
-        constexpr int TOTAL = (ROWS + 1) * LS;
+        const float* psrc = p.img + (int64_t)(y0 + 1) * p.W - PC0;
         // all loads are issued before the first LDS store: one trip to HBM, not one per batch
         constexpr int UN = (TOTAL + kThreads - 1) / kThreads;
         float v[UN];
@@ -130,7 +133,12 @@ single_tiled_kernel(SingleParams p)
         for (int u = 0; u < UN; ++u) {
             const int e = tid + u * kThreads;
             const int r = e / LS, c = e - r * LS;
-            v[u] = (e < TOTAL && r < rows_ok && c < cols) ? src[(int64_t)r * p.W + c] : 0.f;
+            float val = 0.f;
+            if (e < TOTAL) {
+                if (c < PC0) { if (r < rows_ok && c < cols) val = src[(int64_t)r * p.W + c]; }
+                else if (r < prow_ok) val = psrc[(int64_t)r * p.W + c];
+            }
+            v[u] = val;
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -138,9 +146,7 @@ single_tiled_kernel(SingleParams p)
             if (e < TOTAL) sh[e] = v[u];
         }
     }
-
     __syncthreads();
-    DBG_T(1);
 
     const int64_t plane = (int64_t)p.Ho * p.Wo;
     const int pm = (int)(plane & 31);
@@ -164,12 +170,17 @@ single_tiled_kernel(SingleParams p)
     constexpr int UPG = 4 + 2 * ITS;
     constexpr int UNITS = 4 * UPG;
     struct Pending {           // the pass whose results still sit in registers
-        int tw, tr;            // per-lane shift seeds of its output row
+        int tw, tr, trn;       // per-lane shift seeds of its output row and of the next row
         float* orow;           // out[kb][y][X], wave-uniform
         int X;                 // first output column of the pass
-        bool edge;             // first or last pass of a row, or a partly filled filter block
+        int kind;              // kPlain, kTail or kEdge
+        bool head;             // kEdge only: also write the pixels before the first boundary
     };
     v4f held[ITS];
+    auto store4 = [&](float* dst, const v4f& v) {
+        if (NT) __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(dst));
+        else *reinterpret_cast<v4f*>(dst) = v;
+    };
     auto wb_unit = [&](int u, const v16f (&A)[NB], const Pending& pd) {
         const int g = u / UPG, j = u % UPG;
         if (j < 4) {
@@ -183,33 +194,38 @@ single_tiled_kernel(SingleParams p)
             held[it] = *reinterpret_cast<const v4f*>(stg + rdofs + it * RPI * SW);
         } else {
             const int it = j - 4 - ITS;
-            const int sk = (-(pd.tr + (8 * g + it * RPI) * pm)) & 31;
+            const int kofs = (8 * g + it * RPI) * pm;
+            const int sk = (-(pd.tr + kofs)) & 31;
             float* ub = pd.orow + (8 * g + it * RPI) * plane;     // out[kb + 8g + it*RPI][y][X]
             float* dst = ub + (gl + (unsigned)sk);                // this lane's four pixels
-            if (!pd.edge) {
-                *reinterpret_cast<v4f*>(dst) = held[it];
+            const int px = pd.X + sk + 4 * c4;
+            if (pd.kind == kPlain) {
+                store4(dst, held[it]);
+            } else if (pd.kind == kTail) {
+                // The window runs over the end of the row into the head of the next one; it
+                // stops at the first line boundary of the next row, where that row's own
+                // passes begin.  Both limits are multiples of 16 B away from px.
+                const int skn = (-(pd.trn + kofs)) & 31;
+                if (px < p.Wo + skn) store4(dst, held[it]);
             } else if (kb + 8 * g + it * RPI + rrow < p.K) {
                 // Same window, clipped to the row; whole 16 B pieces wherever they fit.
-                const int px = pd.X + sk + 4 * c4;
                 if (px + 3 < p.Wo) {
-                    *reinterpret_cast<v4f*>(dst) = held[it];
+                    store4(dst, held[it]);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (px + e < p.Wo) dst[e] = held[it][e];
                 }
-                // First pass of a row: the sk pixels before the first line boundary.
-#ifndef DCONV_DBG_NOHEAD
-                if (pd.X == 0 && c4 < 8) {
+                // The sk pixels before the first line boundary of the row.
+                if (pd.head && c4 < 8) {
                     const float* row = stg + (it * RPI + rrow) * SW + 32 - sk;
-                    float* head = ub + rrow * plane;              // out[k][y][0]
+                    float* hd = ub + rrow * plane - pd.X;         // out[k][y][0]
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int hx = 4 * c4 + e;
-                        if (hx < sk && hx < p.Wo) head[hx] = row[hx];
+                        if (hx < sk && hx < p.Wo) hd[hx] = row[hx];
                     }
                 }
-#endif
             }
         }
     };
@@ -217,7 +233,7 @@ single_tiled_kernel(SingleParams p)
     // ---- one pass: the matrix-core steps for AN, with the write-back of the pending pass
     // (accumulators AP) slotted between them so that LDS, stores and MFMA overlap in one wave.
     auto compute = [&](v16f (&AN)[NB], const v16f (&AP)[NB], bool have_pending, const Pending& pd,
-                       int base) {
+                       const int (&base)[NB]) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -231,21 +247,17 @@ single_tiled_kernel(SingleParams p)
             for (int nb = 0; nb < NB; ++nb) {
                 int addr;
                 if (t1 >= FF)            // pad tap: the zero row (any column of it)
-                    addr = h ? (ROWS * LS + l32) : base + i * LS + j + nb * 32;
-                else if (t1 / F != i) addr = base + dY + i * LS + j + nb * 32;
-                else                  addr = base + h + i * LS + j + nb * 32;
+                    addr = h ? (ROWS * LS + l32) : base[nb] + i * LS + j;
+                else if (t1 / F != i) addr = base[nb] + dY + i * LS + j;
+                else                  addr = base[nb] + h + i * LS + j;
                 b[nb] = sh[addr];
             }
             if (have_pending) {
 #pragma unroll
                 for (int u = (s * UNITS) / S; u < ((s + 1) * UNITS) / S; ++u) wb_unit(u, AP, pd);
             }
-#ifndef DCONV_DBG_NOMFMA
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) AN[nb] = mfma_32x32x2(a[s], b[nb], AN[nb]);
-#else
-            if (s == 0) for (int nb = 0; nb < NB; ++nb) for (int q = 0; q < 16; ++q) AN[nb][q] = a[0] + b[nb];
-#endif
         }
     };
     auto flush = [&](const v16f (&AP)[NB], const Pending& pd) {
@@ -254,38 +266,47 @@ single_tiled_kernel(SingleParams p)
     };
 
     // ---- the passes of this wave, two per trip so that the accumulator sets alternate -------
-    const int ch_eff = min(CHUNKS, (p.Wo - x0 + PASS - 1) / PASS);       // passes per row here
-    const int ch_mine = (ch_eff - ch_start + ch_step - 1) / ch_step;      // ... taken by this wave
+    const int ch_mine = min(CHUNKS, (p.Wo - x0 + PASS - 1) / PASS);      // passes per row here
     const int rows_mine = rows_here > row_start ? (rows_here - row_start + row_step - 1) / row_step : 0;
-    const int npass = rows_mine * max(ch_mine, 0);
+    const int npass = rows_mine * ch_mine;
 
     v16f acc0[NB], acc1[NB];
-    Pending pd{0, 0, nullptr, 0, false};
-    bool pend0 = false, pend1 = false;     // acc0 / acc1 hold an interior pass not yet written
+    Pending pd{0, 0, 0, nullptr, 0, kPlain, false};
+    bool pend0 = false, pend1 = false;     // acc0 / acc1 hold a pass not yet written
     int ri = 0, ci = 0;                    // row and chunk counters of the next pass
 
-    // one pass: fills AN; meanwhile writes back AP if it is pending; then either leaves AN
-    // pending (interior) or writes it at once (edge)
+    // one pass: fills AN; meanwhile writes back AP if it is pending; then leaves AN pending
+    // (or writes it at once when not pipelining)
     auto one_pass = [&](v16f (&AN)[NB], const v16f (&AP)[NB], bool& pendN, bool& pendP) {
         const int r = row_start + ri * row_step;
-        const int ch = ch_start + ci * ch_step;
+        const int ch = ci;
         if (++ci == ch_mine) { ci = 0; ++ri; }
         const int y = y0 + r;
         const int64_t rowoff = (int64_t)y * p.Wo;
         // alignment (in floats, mod 32) of out[k][y][X] is (k*pm + c0) mod 32 for every pass
         // of a row, because passes start at multiples of 32
-        const int c0 = (int)((rowoff + x0 + a0) & 31);
-        const int tw = tw_lane + c0, tr = tr_lane + c0;
-        const int xc = ch * PASS;                      // first column of this pass, in tile
-        const int X = x0 + xc;                         // ... and in the output row
-        const int base = r * LS + xc + l32;
-        const bool interior = X > 0 && X + 32 + PASS <= p.Wo && full_block;
+        const int c0 = (int)((rowoff + a0) & 31);
+        const int c0n = (int)((rowoff + p.Wo + a0) & 31);
+        const int X = x0 + ch * PASS;                  // first output column of this pass
+        int base[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int x = X + nb * 32 + l32;
+            // lanes beyond the row end compute the head of the next row from the patch
+            base[nb] = r * LS + ((wrap_tile && x >= p.Wo) ? PC0 + min(x - p.Wo, 31) : x - x0);
+        }
+        const bool reaches_end = X + 32 + PASS > p.Wo;                // a window may cross Wo
+        const bool needs_head = X == 0 && (y == 0 || !p.wrap || !full_block);
+        int kind = kPlain;
+        if (!full_block || needs_head) kind = kEdge;
+        else if (reaches_end) kind = (p.wrap && y < p.Ho - 1) ? kTail : kEdge;
         compute(AN, AP, pendP, pd, base);
         pendP = false;
-        pd.tw = tw; pd.tr = tr;
+        pd.tw = tw_lane + c0; pd.tr = tr_lane + c0; pd.trn = tr_lane + c0n;
         pd.orow = p.out + kb * plane + rowoff + X;
         pd.X = X;
-        pd.edge = !interior;
+        pd.kind = kind;
+        pd.head = needs_head;
         if (PIPE) pendN = true;
         else flush(AN, pd);
     };
@@ -299,15 +320,13 @@ single_tiled_kernel(SingleParams p)
 #pragma unroll 1
         for (int q = 0; q < npass; ++q) one_pass(acc0, acc0, pend0, pend1);
     }
-    DBG_T(2);
     if (pend0) flush(acc0, pd);
     if (pend1) flush(acc1, pd);
-    DBG_T(3);
 }
 
 namespace {
 
-template <int F, int TW, int TR, int NBW, int PAD, int WPE, bool PIPE>
+template <int F, int TW, int TR, int NBW, int WPE, bool PIPE, bool NT>
 int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
     SingleParams p;
@@ -317,16 +336,16 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     p.tiles_y = (s.Ho + TR - 1) / TR;
     const int fblocks = (s.K + 31) / 32;
     p.fbw = fblocks >= 4 ? 4 : fblocks >= 2 ? 2 : 1;
-    p.colsplit = 0;
-    static const int mode = [] { const char* e = getenv("DCONV_SINGLE_MODE"); return e ? atoi(e) : 0; }();
-    if (mode == 1) { p.fbw = 1; p.colsplit = 1; }
-    if (mode == 2) { p.fbw = 1; }
-    if (mode == 3) { p.fbw = fblocks >= 2 ? 2 : 1; }
     p.fgroups = (fblocks + p.fbw - 1) / p.fbw;
+    // Completing row ends with the next row's head needs a pass to span at most one row end,
+    // and every pass that reaches the row end to lie in the last tile column.
+    p.wrap = (s.Wo >= 2 * (32 * NBW + 32) && (p.tiles_x - 1) * TW + 32 <= s.Wo) ? 1 : 0;
+    static const int nowrap = [] { const char* e = getenv("DCONV_SINGLE_NOWRAP"); return e ? atoi(e) : 0; }();
+    if (nowrap) p.wrap = 0;
     const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups;
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
-    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, PAD, WPE, PIPE>),
+    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE, PIPE, NT>),
                        dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
@@ -341,13 +360,9 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         return e ? atoi(e) : -1;
     }();
     switch (forced) {
-    case 1: return launch_cfg<F, 512, 8, 4, 0, 2, true>(img, filt, out, s, st);
-    case 2: return launch_cfg<F, 1024, 8, 4, 0, 2, true>(img, filt, out, s, st);
-    case 3: return launch_cfg<F, 256, 16, 4, 0, 3, false>(img, filt, out, s, st);
-    case 4: return launch_cfg<F, 512, 8, 4, 0, 3, false>(img, filt, out, s, st);
-    case 5: return launch_cfg<F, 512, 4, 4, 0, 3, false>(img, filt, out, s, st);
-    case 6: return launch_cfg<F, 256, 8, 4, 0, 4, false>(img, filt, out, s, st);
-    default: return launch_cfg<F, 256, 16, 4, 0, 2, true>(img, filt, out, s, st);
+    case 1: return launch_cfg<F, 256, 16, 4, 3, false, true>(img, filt, out, s, st);
+    case 2: return launch_cfg<F, 512, 8, 4, 3, false, true>(img, filt, out, s, st);
+    default: return launch_cfg<F, 512, 4, 4, 3, false, true>(img, filt, out, s, st);
     }
 }
 

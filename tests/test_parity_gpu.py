@@ -83,6 +83,11 @@ SINGLE_SHAPES = [
     (15, 15, 3, 10),
     (9, 9, 2, 9),               # 1x1 output
     (100, 515, 64, 5),          # three tiles across, ragged last one
+    (40, 1030, 33, 3),          # last tile column only a few pixels wide
+    (24, 700, 64, 5),           # row ends completed with the head of the next row
+    (10, 2100, 32, 7),
+    (35, 1200, 96, 3),
+    (9, 1300, 70, 1),
 ]
 
 
