@@ -35,6 +35,7 @@ struct GenParams {
     int tiles_max;   // pixel tiles per strip (upper bound; surplus workgroups exit)
     int LS;          // LDS row stride of the image block: bw + F - 1
     int RS;          // LDS row slots per channel
+    int vec4;        // filter rows can be fetched 16 B at a time
 };
 
 // Reduction index t of a chunk <-> (channel in chunk, filter row, filter column).
@@ -43,7 +44,7 @@ template <int F> __device__ __forceinline__ constexpr int tap_i(int t) { return 
 template <int F> __device__ __forceinline__ constexpr int tap_j(int t) { return t % F; }
 
 template <int F, int CSH, int MW, int NW, int WM, int WN, int IMAX>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, 2)
 general_tiled_kernel(GenParams p)
 {
     static_assert(WM * WN * kWave == kThreads, "four waves per workgroup");
@@ -54,7 +55,6 @@ general_tiled_kernel(GenParams p)
     constexpr int TP = T + (T & 1);           // padded to a whole number of pairs
     constexpr int S = TP / 2;                 // matrix-core steps per chunk
     constexpr int LDK = MT + 1;               // odd row stride: transposing writes hit 32 banks
-    constexpr int WPT = (MT * T + kThreads - 1) / kThreads;
 
     extern __shared__ float lds[];
     float* shFlt = lds;                       // [TP][LDK]   filter block, reduction-major
@@ -124,19 +124,35 @@ general_tiled_kernel(GenParams p)
     const int HW = p.H * p.W;
     const int CFF = p.C * FF;
 
-    float ireg[IMAX], wreg[WPT];
+    // Filter block: TPF threads share one filter; each brings in a contiguous run of EPT of
+    // its T reduction indices per chunk (16 B at a time when the layout allows) and scatters
+    // it down a column of the transposed LDS block.  All per-element offsets are immediates.
+    constexpr int TPF = kThreads / MT;
+    constexpr int EPT = (T + TPF - 1) / TPF;
+    const int wkl = tid / TPF, we0 = (tid % TPF) * EPT;
+    const bool wk_ok = k0 + wkl < p.K;
+    const float* wsrc = p.filt + (int64_t)(wk_ok ? k0 + wkl : 0) * CFF + we0;
+    float* wdst = shFlt + we0 * LDK + wkl;
+
+    float ireg[IMAX], wreg[EPT];
     auto fetch = [&](int c0) {
         const float* ip = p.in + (int64_t)c0 * HW;
 #pragma unroll
         for (int it = 0; it < IMAX; ++it)
             ireg[it] = ig[it] >= 0 ? ip[ig[it]] : 0.f;
-        const float* fp = p.filt + (int64_t)c0 * FF;
+        const float* fp = wsrc + (int64_t)c0 * FF;
+        if (EPT % 4 == 0 && p.vec4) {
 #pragma unroll
-        for (int it = 0; it < WPT; ++it) {
-            const int f = tid + it * kThreads;
-            const int kl = f / T, e = f - kl * T;
-            const bool ok = f < MT * T && k0 + kl < p.K;
-            wreg[it] = ok ? fp[(int64_t)(k0 + kl) * CFF + e] : 0.f;
+            for (int it = 0; it < EPT / 4; ++it) {
+                const v4f v = (wk_ok && we0 + 4 * it < T) ? *reinterpret_cast<const v4f*>(fp + 4 * it)
+                                                          : (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) wreg[4 * it + u] = v[u];
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < EPT; ++it)
+                wreg[it] = (wk_ok && we0 + it < T) ? fp[it] : 0.f;
         }
     };
     auto commit = [&]() {
@@ -144,11 +160,8 @@ general_tiled_kernel(GenParams p)
         for (int it = 0; it < IMAX; ++it)
             if (ig[it] != -2) shImg[tid + it * kThreads] = ireg[it];
 #pragma unroll
-        for (int it = 0; it < WPT; ++it) {
-            const int f = tid + it * kThreads;
-            const int kl = f / T, e = f - kl * T;
-            if (f < MT * T) shFlt[e * LDK + kl] = wreg[it];
-        }
+        for (int it = 0; it < EPT; ++it)
+            if (we0 + it < T) wdst[it * LDK] = wreg[it];
     };
 
     if (tid == 0) shImg[zero_word] = 0.f;
@@ -171,6 +184,9 @@ general_tiled_kernel(GenParams p)
     for (int c0 = 0; c0 < p.C; c0 += CSH) {
         const bool more = c0 + CSH < p.C;
         if (more) fetch(c0 + CSH);
+        // keep the tap addresses from being expanded into one register each outside the loop
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt) asm volatile("" : "+v"(base[nt]));
 
 #pragma unroll
         for (int s = 0; s < S; ++s) {
@@ -272,8 +288,10 @@ int try_launch(const float* in, const float* filt, float* out, const Shape& s, h
             return DCONV_LAUNCH_FAILED;
         attr_set = true;
     }
+    const int vec4 = ((int64_t)s.C * F * F) % 4 == 0 && (CSH * F * F) % 4 == 0 &&
+                     ((uintptr_t)filt & 15) == 0;
     GenParams p{in, filt, out, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo,
-                pl.bw, pl.tiles_max, pl.LS, pl.RS};
+                pl.bw, pl.tiles_max, pl.LS, pl.RS, vec4};
     hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads),
                        (size_t)lds_bytes, st, p);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
