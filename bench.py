@@ -34,6 +34,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-configs", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy a few times, so that a "
+                         "counter run can scale FETCH_SIZE / WRITE_SIZE by a transfer of known size")
     ap.add_argument("--only", default=None,
                     help="time just this configuration (S1, S2, S2_F3.., G1, G2, G3) as the step")
     return ap.parse_args()
@@ -92,7 +95,7 @@ def cpu_baseline(w, x, f):
     """The oracle as it stands, on a band of the headline workload, all host cores."""
     import numpy as np
     import oracle
-    rows_out = 2048
+    rows_out = w.Ho
     band = np.ascontiguousarray(x[:rows_out + w.F - 1])
     t0 = time.perf_counter()
     _, threads = oracle.single_channel(band, f, only32=True)
@@ -100,7 +103,7 @@ def cpu_baseline(w, x, f):
     flops = 2.0 * w.K * rows_out * w.Wo * w.F * w.F
     return {"value": round(flops / dt / 1e9, 3), "unit": "GFLOP/s", "cores": int(threads),
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"first {rows_out} of {w.Ho} output rows of the same image, all {w.K} filters"}
+            "sample": f"{rows_out} of {w.Ho} output rows of the same image, all {w.K} filters"}
 
 
 def main():
@@ -145,6 +148,16 @@ def main():
     }
     del run
     torch.cuda.empty_cache()
+
+    if args.copy_calibration:
+        n = 1 << 28                                   # 2^28 floats = 1 GiB read + 1 GiB written
+        a = torch.ones(n, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
 
     if not args.no_extra_configs and not args.only:
         per = [entry]
