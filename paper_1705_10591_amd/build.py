@@ -36,7 +36,7 @@ def _compile(src: str) -> Path:
 def build(verbose: bool = False) -> Path:
     """Compile every HIP source and link libdconv.so; always recompiles."""
     BUILD.mkdir(exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = PKG / f"libdconv.tmp{os.getpid()}.so"
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]
