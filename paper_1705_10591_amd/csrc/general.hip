@@ -183,17 +183,19 @@ general_tiled_kernel(GenParams p)
 
     for (int c0 = 0; c0 < p.C; c0 += CSH) {
         const bool more = c0 + CSH < p.C;
+#if DCONV_GEN_EXP != 1 && DCONV_GEN_EXP != 2
         if (more) fetch(c0 + CSH);
+#endif
         // keep the tap addresses from being expanded into one register each outside the loop
 #pragma unroll
         for (int nt = 0; nt < NW; ++nt) asm volatile("" : "+v"(base[nt]));
 
-#pragma unroll
-        for (int s = 0; s < S; ++s) {
+        // Operands of step s+1 are requested from LDS before the matrix-core instructions
+        // of step s are issued, so a wave never waits for LDS with the matrix pipe idle.
+        auto load_ops = [&](int s, float (&a)[MW], float (&b)[NW]) {
             const int t0 = 2 * s, t1 = 2 * s + 1;
             const int c = tap_c<F>(t0), i = tap_i<F>(t0), j = tap_j<F>(t0);
             const int rowoff = c * PL + i * LS;
-            float a[MW], b[NW];
 #pragma unroll
             for (int nt = 0; nt < NW; ++nt) {
                 int addr;
@@ -207,16 +209,28 @@ general_tiled_kernel(GenParams p)
 #pragma unroll
             for (int mt = 0; mt < MW; ++mt)
                 a[mt] = shFlt[wbase + t0 * LDK + mt * 32];
+        };
+        float a0[MW], b0[NW], a1[MW], b1[NW];
+        load_ops(0, a0, b0);
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            float (&a)[MW] = (s & 1) ? a1 : a0;
+            float (&b)[NW] = (s & 1) ? b1 : b0;
+            if (s + 1 < S) load_ops(s + 1, (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mt = 0; mt < MW; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < NW; ++nt)
                     acc[mt][nt] = mfma_32x32x2(a[mt], b[nt], acc[mt][nt]);
+            __builtin_amdgcn_sched_barrier(0);
         }
 
+#if DCONV_GEN_EXP != 1 && DCONV_GEN_EXP != 2
         __syncthreads();
         if (more) commit();
         __syncthreads();
+#endif
     }
 
     // ---- write back: 32 lanes hold 32 consecutive pixels of one output map -----------
@@ -228,7 +242,11 @@ general_tiled_kernel(GenParams p)
             const int k = k0 + (wm * MW + mt) * 32 + mfma_row(r, h);
 #pragma unroll
             for (int nt = 0; nt < NW; ++nt)
+#if DCONV_GEN_EXP == 2 || DCONV_GEN_EXP == 3
+                if (valid[nt] && k < p.K && acc[mt][nt][r] == 1234567.f) p.out[obase[nt] + k * plane] = acc[mt][nt][r];
+#else
                 if (valid[nt] && k < p.K) p.out[obase[nt] + k * plane] = acc[mt][nt][r];
+#endif
         }
     }
 }

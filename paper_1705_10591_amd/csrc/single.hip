@@ -40,6 +40,7 @@
 // the very first and last line of a plane, and narrow images, are written
 // piecemeal.
 #include <stdlib.h>
+#include <type_traits>
 #include "common.h"
 #include "../../include/dconv.h"
 
@@ -232,10 +233,15 @@ single_tiled_kernel(SingleParams p)
 
     // ---- one pass: the matrix-core steps for AN, with the write-back of the pending pass
     // (accumulators AP) slotted between them so that LDS, stores and MFMA overlap in one wave.
-    auto compute = [&](v16f (&AN)[NB], const v16f (&AP)[NB], bool have_pending, const Pending& pd,
-                       const int (&base)[NB]) {
+    // Block 0 of a pass covers the same 32 pixels as block NB-1 of the pass before it on the
+    // same row; when CARRY is set those sums are taken over instead of being formed again.
+    auto compute = [&](auto carry_tag, v16f (&AN)[NB], const v16f (&AP)[NB], bool have_pending,
+                       const Pending& pd, const int (&base)[NB]) {
+        constexpr bool CARRY = decltype(carry_tag)::value;
+        constexpr int NB0 = CARRY ? 1 : 0;
+        if (CARRY) AN[0] = PIPE ? AP[NB - 1] : AN[NB - 1];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int nb = NB0; nb < NB; ++nb)
 #pragma unroll
             for (int q = 0; q < 16; ++q) AN[nb][q] = 0.f;
 #pragma unroll
@@ -244,7 +250,7 @@ single_tiled_kernel(SingleParams p)
             const int i = t0 / F, j = t0 % F;
             float b[NB];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
+            for (int nb = NB0; nb < NB; ++nb) {
                 int addr;
                 if (t1 >= FF)            // pad tap: the zero row (any column of it)
                     addr = h ? (ROWS * LS + l32) : base[nb] + i * LS + j;
@@ -257,7 +263,7 @@ single_tiled_kernel(SingleParams p)
                 for (int u = (s * UNITS) / S; u < ((s + 1) * UNITS) / S; ++u) wb_unit(u, AP, pd);
             }
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) AN[nb] = mfma_32x32x2(a[s], b[nb], AN[nb]);
+            for (int nb = NB0; nb < NB; ++nb) AN[nb] = mfma_32x32x2(a[s], b[nb], AN[nb]);
         }
     };
     auto flush = [&](const v16f (&AP)[NB], const Pending& pd) {
@@ -300,7 +306,9 @@ single_tiled_kernel(SingleParams p)
         int kind = kPlain;
         if (!full_block || needs_head) kind = kEdge;
         else if (reaches_end) kind = (p.wrap && y < p.Ho - 1) ? kTail : kEdge;
-        compute(AN, AP, pendP, pd, base);
+        // every pass but the first of a row continues the previous pass of this wave
+        if (ch > 0) compute(std::true_type{}, AN, AP, pendP, pd, base);
+        else compute(std::false_type{}, AN, AP, pendP, pd, base);
         pendP = false;
         pd.tw = tw_lane + c0; pd.tr = tr_lane + c0; pd.trn = tr_lane + c0n;
         pd.orow = p.out + kb * plane + rowoff + X;
