@@ -50,7 +50,12 @@ typedef enum dconv_status {
 enum {
     DCONV_VARIANT_AUTO = 0,   /* pick by shape (what the plain entry points do)  */
     DCONV_VARIANT_SIMPLE = 1, /* one thread per output element; any shape        */
-    DCONV_VARIANT_TILED = 2   /* LDS-staged, matrix-core tiled kernel            */
+    DCONV_VARIANT_TILED = 2,  /* LDS-staged, matrix-core tiled kernel, tile
+                                 configuration picked by shape                   */
+    DCONV_VARIANT_TILED_CFG0 = 0x100
+                              /* DCONV_VARIANT_TILED_CFG0 + i: the tiled kernel
+                                 with tile configuration i forced, 0 <= i <
+                                 dconv_tile_config_count(); for tests and tuners */
 };
 
 /*
@@ -93,6 +98,16 @@ int dconv_single_channel_v(const float *img, int H, int W,
 int dconv_general_v(const float *in, int N, int C, int H, int W,
                     const float *filt, int K, int F,
                     float *out, int variant, void *stream);
+
+/*
+ * Number of tile configurations compiled into the tiled kernel of the
+ * single-channel case (single_channel != 0) or of the general case
+ * (single_channel == 0).  The paper picks its tile sizes by exploring the
+ * design space per device (Sec. 5, Table 1); this is the hook for doing the
+ * same here: time DCONV_VARIANT_TILED_CFG0 + i for every i.  A configuration
+ * that cannot hold a given shape returns DCONV_UNSUPPORTED without launching.
+ */
+int dconv_tile_config_count(int single_channel);
 
 /* Human-readable name of a status code; static storage, never NULL. */
 const char *dconv_status_string(int status);

@@ -18,10 +18,12 @@ _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libdconv.so"
 
 VARIANT_AUTO, VARIANT_SIMPLE, VARIANT_TILED = 0, 1, 2
+VARIANT_TILED_CFG0 = 0x100     # + i: tiled kernel with tile configuration i forced
 STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAUNCH_FAILED = range(5)
 
 EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
-           "dconv_general_v", "dconv_status_string", "dconv_version")
+           "dconv_general_v", "dconv_status_string", "dconv_version",
+           "dconv_tile_config_count")
 
 _lib = None
 
@@ -49,6 +51,8 @@ def load_library() -> ctypes.CDLL:
         for name in ("dconv_single_channel", "dconv_single_channel_v",
                      "dconv_general", "dconv_general_v", "dconv_version"):
             getattr(lib, name).restype = i
+        lib.dconv_tile_config_count.argtypes = [i]
+        lib.dconv_tile_config_count.restype = i
         lib.dconv_status_string.argtypes = [i]
         lib.dconv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -57,6 +61,11 @@ def load_library() -> ctypes.CDLL:
 
 def status_string(status: int) -> str:
     return load_library().dconv_status_string(int(status)).decode()
+
+
+def tile_config_count(single_channel: bool) -> int:
+    """Number of tile configurations of the tiled kernel (see VARIANT_TILED_CFG0)."""
+    return int(load_library().dconv_tile_config_count(1 if single_channel else 0))
 
 
 def version() -> int:

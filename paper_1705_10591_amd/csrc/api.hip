@@ -32,21 +32,24 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
     hipStream_t st = (hipStream_t)stream;
     const bool tiled_ok = single ? dconv::single_tiled_supports(s)
                                  : dconv::general_tiled_supports(s);
+    auto tiled = [&](int cfg) {
+        return single ? dconv::launch_single_tiled(in, filt, out, s, st, cfg)
+                      : dconv::launch_general_tiled(in, filt, out, s, st, cfg);
+    };
     switch (variant) {
     case DCONV_VARIANT_AUTO:
-        if (tiled_ok)
-            return single ? dconv::launch_single_tiled(in, filt, out, s, st)
-                          : dconv::launch_general_tiled(in, filt, out, s, st);
-        return dconv::launch_simple(in, filt, out, s, st);
+        return tiled_ok ? tiled(-1) : dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_SIMPLE:
         return dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_TILED:
-        if (!tiled_ok) return DCONV_UNSUPPORTED;
-        return single ? dconv::launch_single_tiled(in, filt, out, s, st)
-                      : dconv::launch_general_tiled(in, filt, out, s, st);
+        return tiled_ok ? tiled(-1) : DCONV_UNSUPPORTED;
     default:
-        return DCONV_UNSUPPORTED;
+        break;
     }
+    const int ncfg = single ? dconv::single_tile_configs() : dconv::general_tile_configs();
+    if (variant >= DCONV_VARIANT_TILED_CFG0 && variant < DCONV_VARIANT_TILED_CFG0 + ncfg)
+        return tiled_ok ? tiled(variant - DCONV_VARIANT_TILED_CFG0) : DCONV_UNSUPPORTED;
+    return DCONV_UNSUPPORTED;
 }
 
 }  // namespace
@@ -95,6 +98,11 @@ const char* dconv_status_string(int status)
     }
 }
 
-int dconv_version(void) { return 1000; }
+int dconv_tile_config_count(int single_channel)
+{
+    return single_channel ? dconv::single_tile_configs() : dconv::general_tile_configs();
+}
+
+int dconv_version(void) { return 1001; }
 
 }  // extern "C"

@@ -36,10 +36,13 @@ struct Shape {
 
 // Host-side launchers, one per translation unit.  Each returns a dconv_status.
 int launch_simple(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st);
+// cfg selects one of the compiled tile configurations; cfg < 0 lets the shape decide.
 int launch_single_tiled(const float* img, const float* filt, float* out, const Shape& s,
-                        hipStream_t st);
+                        hipStream_t st, int cfg);
 int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
-                         hipStream_t st);
+                         hipStream_t st, int cfg);
+int single_tile_configs();
+int general_tile_configs();
 bool single_tiled_supports(const Shape& s);
 bool general_tiled_supports(const Shape& s);
 

@@ -368,9 +368,12 @@ bool general_tiled_supports(const Shape& s)
     return launch_any(nullptr, nullptr, nullptr, s, nullptr, true) == DCONV_OK;
 }
 
+int general_tile_configs() { return 1; }
+
 int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
-                         hipStream_t st)
+                         hipStream_t st, int cfg)
 {
+    if (cfg > 0) return DCONV_UNSUPPORTED;
     return launch_any(in, filt, out, s, st, false);
 }
 

@@ -39,7 +39,6 @@
 // columns are staged beside the tile) and stores the shared line whole.  Only
 // the very first and last line of a plane, and narrow images, are written
 // piecemeal.
-#include <stdlib.h>
 #include <type_traits>
 #include "common.h"
 #include "../../include/dconv.h"
@@ -348,8 +347,6 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     // Completing row ends with the next row's head needs a pass to span at most one row end,
     // and every pass that reaches the row end to lie in the last tile column.
     p.wrap = (s.Wo >= 2 * (32 * NBW + 32) && (p.tiles_x - 1) * TW + 32 <= s.Wo) ? 1 : 0;
-    static const int nowrap = [] { const char* e = getenv("DCONV_SINGLE_NOWRAP"); return e ? atoi(e) : 0; }();
-    if (nowrap) p.wrap = 0;
     const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups;
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
@@ -358,18 +355,32 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
-// Tile configurations compiled for every filter side.  Index 0 is the default; the others
-// can be selected with the environment variable DCONV_SINGLE_CFG for tuning runs.
+// Tile configurations compiled for every filter side, and the rule that picks one.  Measured
+// on 4096 x 4096 images with 64 filters: the output stream bounds the time up to 5x5 and wide
+// tiles (fewer first-of-row passes, which cannot take over a block) win; from 7x7 on the matrix
+// cores bound it and, for the largest filters, taller tiles (fewer halo rows staged per output
+// row) win.  Small images get small tiles so that the launch still covers the chip.
+constexpr int kSingleConfigs = 4;
+
 template <int F>
-int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
+int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
+             int cfg)
 {
-    static const int forced = [] {
-        const char* e = getenv("DCONV_SINGLE_CFG");
-        return e ? atoi(e) : -1;
-    }();
-    switch (forced) {
-    case 1: return launch_cfg<F, 256, 16, 4, 3, false, true>(img, filt, out, s, st);
+    if (cfg >= kSingleConfigs) return DCONV_UNSUPPORTED;
+    if (cfg < 0) {
+        const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4;
+        auto items = [&](int tw, int tr) {
+            return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
+        };
+        if (items(512, 4) < 1024) cfg = 3;
+        else if (F >= 8) cfg = 2;
+        else if (F >= 5 && s.Wo >= 2048) cfg = 1;
+        else cfg = 0;
+    }
+    switch (cfg) {
+    case 1: return launch_cfg<F, 1024, 4, 4, 2, false, true>(img, filt, out, s, st);
     case 2: return launch_cfg<F, 512, 8, 4, 3, false, true>(img, filt, out, s, st);
+    case 3: return launch_cfg<F, 256, 2, 4, 3, false, true>(img, filt, out, s, st);
     default: return launch_cfg<F, 512, 4, 4, 3, false, true>(img, filt, out, s, st);
     }
 }
@@ -383,21 +394,23 @@ bool single_tiled_supports(const Shape& s)
            (int64_t)s.Ho * s.Wo < (1LL << 29);
 }
 
+int single_tile_configs() { return kSingleConfigs; }
+
 int launch_single_tiled(const float* img, const float* filt, float* out, const Shape& s,
-                        hipStream_t st)
+                        hipStream_t st, int cfg)
 {
     switch (s.F) {
-    case 1: return launch_F<1>(img, filt, out, s, st);
-    case 2: return launch_F<2>(img, filt, out, s, st);
-    case 3: return launch_F<3>(img, filt, out, s, st);
-    case 4: return launch_F<4>(img, filt, out, s, st);
-    case 5: return launch_F<5>(img, filt, out, s, st);
-    case 6: return launch_F<6>(img, filt, out, s, st);
-    case 7: return launch_F<7>(img, filt, out, s, st);
-    case 8: return launch_F<8>(img, filt, out, s, st);
-    case 9: return launch_F<9>(img, filt, out, s, st);
-    case 10: return launch_F<10>(img, filt, out, s, st);
-    case 11: return launch_F<11>(img, filt, out, s, st);
+    case 1: return launch_F<1>(img, filt, out, s, st, cfg);
+    case 2: return launch_F<2>(img, filt, out, s, st, cfg);
+    case 3: return launch_F<3>(img, filt, out, s, st, cfg);
+    case 4: return launch_F<4>(img, filt, out, s, st, cfg);
+    case 5: return launch_F<5>(img, filt, out, s, st, cfg);
+    case 6: return launch_F<6>(img, filt, out, s, st, cfg);
+    case 7: return launch_F<7>(img, filt, out, s, st, cfg);
+    case 8: return launch_F<8>(img, filt, out, s, st, cfg);
+    case 9: return launch_F<9>(img, filt, out, s, st, cfg);
+    case 10: return launch_F<10>(img, filt, out, s, st, cfg);
+    case 11: return launch_F<11>(img, filt, out, s, st, cfg);
     default: return DCONV_UNSUPPORTED;
     }
 }

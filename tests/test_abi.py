@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert dconv.version() >= 1000
+    assert dconv.version() >= 1001
     seen = {dconv.status_string(s) for s in range(5)}
     assert len(seen) == 5 and all(seen)
     assert dconv.status_string(12345)
@@ -73,6 +73,20 @@ def test_unknown_variant_and_unsupported_tiled_shape():
         == dconv.STATUS_UNSUPPORTED
     assert lib.dconv_single_channel_v(FAKE, 32, 32, FAKE, 1, 13, FAKE, dconv.VARIANT_TILED, None) \
         == dconv.STATUS_UNSUPPORTED
+
+
+def test_tile_configuration_variants_are_bounded():
+    lib = dconv.load_library()
+    for single in (0, 1):
+        n = dconv.tile_config_count(bool(single))
+        assert n >= 1
+        beyond = dconv.VARIANT_TILED_CFG0 + n
+        if single:
+            assert lib.dconv_single_channel_v(FAKE, 32, 32, FAKE, 1, 3, FAKE, beyond, None) \
+                == dconv.STATUS_UNSUPPORTED
+        else:
+            assert lib.dconv_general_v(FAKE, 1, 1, 32, 32, FAKE, 1, 3, FAKE, beyond, None) \
+                == dconv.STATUS_UNSUPPORTED
 
 
 def test_python_binding_refuses_cpu_tensors():

@@ -102,6 +102,29 @@ def test_single_channel_small_shapes(shape, variant):
     assert_within_bound(got, acc, mag, f"single {shape}")
 
 
+def _tile_variants(single):
+    """Every compiled tile configuration of the tiled kernel, forced."""
+    return [dconv.VARIANT_TILED_CFG0 + i for i in range(dconv.tile_config_count(single))]
+
+
+# shapes that exercise wide tiles, tall tiles, carried blocks and row ends in every configuration
+SINGLE_CFG_SHAPES = [(33, 31, 70, 5), (24, 700, 64, 5), (21, 2300, 40, 3), (40, 1290, 33, 7),
+                     (19, 1100, 96, 9), (12, 12, 3, 11), (70, 530, 130, 4)]
+
+
+@pytest.mark.parametrize("shape", SINGLE_CFG_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_single_channel_every_tile_configuration(shape):
+    H, W, K, F = shape
+    x, f = wl.random_case(300 + F, 1, 1, H, W, K, F)
+    img, flt = x[0, 0], f[:, 0]
+    acc, mag, _ = oracle.single_channel(img, flt)
+    xi, fi = wl.integer_case(30 + F, 1, 1, H, W, K, F)
+    _, _, o32, _ = oracle.general(xi, fi, want32=True)
+    for variant in _tile_variants(True):
+        assert_within_bound(run_single(img, flt, variant), acc, mag, f"single {shape} variant {variant}")
+        np.testing.assert_array_equal(run_single(xi[0, 0], fi[:, 0], variant), o32[0])
+
+
 @pytest.mark.parametrize("shape", [(2, 8, 28, 28, 70, 3), (1, 3, 30, 140, 64, 11), (3, 6, 12, 12, 9, 5)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_general_integer_inputs_are_bit_exact(shape):
