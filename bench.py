@@ -30,8 +30,8 @@ FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 (matrix / packed vector), published
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-configs", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -42,11 +42,20 @@ def parse_args():
     return ap.parse_args()
 
 
-def time_launches(fn, steps, warmup):
-    """Average milliseconds per launch over `steps` launches, by events on the launch stream."""
+def time_launches(fn, steps, warmup, warm_ms=0.0):
+    """Average milliseconds per launch over `steps` launches, by events on the launch stream.
+
+    `warmup` untimed launches come first; with `warm_ms` > 0 untimed launches continue until
+    that much time has passed, so that short kernels are also timed at the clocks the chip
+    settles at under load and not during its ramp from idle."""
     import torch
-    for _ in range(warmup):
+    t_start = time.perf_counter()
+    done = 0
+    while done < warmup or (time.perf_counter() - t_start) * 1e3 < warm_ms:
         fn()
+        done += 1
+        if done % 8 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
@@ -165,7 +174,7 @@ def main():
         for name in order:
             w = allw[name]
             r, _ = make_runner(w)
-            m, _ = time_launches(r, max(5, min(args.steps, 20)), max(2, min(args.warmup, 3)))
+            m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
             per.append(config_entry(w, m))
             del r
             torch.cuda.empty_cache()

@@ -109,6 +109,20 @@ int dconv_general_v(const float *in, int N, int C, int H, int W,
  */
 int dconv_tile_config_count(int single_channel);
 
+/*
+ * dconv_general keeps one device workspace per (device, stream) it has been
+ * called on: when the tiles of a shape do not spread evenly over the chip, a
+ * tile is summed over channels by several workgroups and their partial sums
+ * meet there (at most 2 * tile * workgroups floats, 64 MiB for the largest
+ * tile on a 256-CU chip, plus one int per workgroup).  It is allocated with
+ * hipMalloc on the first call that needs it and grown when a later call needs
+ * more; no other entry point allocates.  Calls on one stream share it safely
+ * (they run in order); calls on different streams use different workspaces.
+ * This function frees all of them; the caller must make sure that no
+ * dconv_general launch is still running.  Always returns DCONV_OK.
+ */
+int dconv_release_workspace(void);
+
 /* Human-readable name of a status code; static storage, never NULL. */
 const char *dconv_status_string(int status);
 

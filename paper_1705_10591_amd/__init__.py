@@ -23,7 +23,7 @@ STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAU
 
 EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
            "dconv_general_v", "dconv_status_string", "dconv_version",
-           "dconv_tile_config_count")
+           "dconv_tile_config_count", "dconv_release_workspace")
 
 _lib = None
 
@@ -49,7 +49,8 @@ def load_library() -> ctypes.CDLL:
         lib.dconv_general.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_v.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
         for name in ("dconv_single_channel", "dconv_single_channel_v",
-                     "dconv_general", "dconv_general_v", "dconv_version"):
+                     "dconv_general", "dconv_general_v", "dconv_version",
+                     "dconv_release_workspace"):
             getattr(lib, name).restype = i
         lib.dconv_tile_config_count.argtypes = [i]
         lib.dconv_tile_config_count.restype = i
@@ -66,6 +67,12 @@ def status_string(status: int) -> str:
 def tile_config_count(single_channel: bool) -> int:
     """Number of tile configurations of the tiled kernel (see VARIANT_TILED_CFG0)."""
     return int(load_library().dconv_tile_config_count(1 if single_channel else 0))
+
+
+def release_workspace() -> None:
+    """Free the device workspaces dconv_general keeps per (device, stream)."""
+    torch.cuda.synchronize()
+    load_library().dconv_release_workspace()
 
 
 def version() -> int:

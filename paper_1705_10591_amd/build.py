@@ -11,7 +11,10 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libdconv.so"
 BUILD = PKG / "_build"
-SOURCES = ["api.hip", "simple.hip", "single.hip", "general.hip"]
+# (source, extra flags, object name); the general-case kernel is compiled once per filter side
+SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", [], "single"),
+           ("general.hip", [], "general")] + \
+          [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 12)]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed fp32 VALU forms are switched off for all device code (the host pass
@@ -24,9 +27,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
-def _compile(src: str) -> Path:
-    obj = BUILD / (src + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
+def _compile(item) -> Path:
+    src, extra, name = item
+    obj = BUILD / (name + ".o")
+    cmd = [HIPCC, *FLAGS, *extra, "-c", str(CSRC / src), "-o", str(obj)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stderr[-4000:]}")
@@ -36,7 +40,7 @@ def _compile(src: str) -> Path:
 def build(verbose: bool = False) -> Path:
     """Compile every HIP source and link libdconv.so; always recompiles."""
     BUILD.mkdir(exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = PKG / f"libdconv.tmp{os.getpid()}.so"
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]

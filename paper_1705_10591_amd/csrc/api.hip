@@ -103,6 +103,12 @@ int dconv_tile_config_count(int single_channel)
     return single_channel ? dconv::single_tile_configs() : dconv::general_tile_configs();
 }
 
-int dconv_version(void) { return 1001; }
+int dconv_release_workspace(void)
+{
+    dconv::release_general_workspaces();
+    return DCONV_OK;
+}
+
+int dconv_version(void) { return 1002; }
 
 }  // extern "C"

@@ -45,5 +45,6 @@ int single_tile_configs();
 int general_tile_configs();
 bool single_tiled_supports(const Shape& s);
 bool general_tiled_supports(const Shape& s);
+void release_general_workspaces();
 
 }  // namespace dconv

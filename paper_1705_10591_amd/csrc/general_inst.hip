@@ -1,0 +1,81 @@
+// Instantiations of the general-case kernel for ONE filter side (DCONV_F, given on the
+// compiler command line), so that the filter sides compile in parallel.
+//
+// Channel chunk per filter side: 16-36 reduction indices per chunk for small filters (short
+// enough that three chunks of a 128-filter tile fit in LDS with two workgroups per CU), one
+// channel per chunk from 5x5 on.  A chunk that does not divide the channel
+// count is padded with zeros in LDS, so the smaller chunk is only there for inputs with
+// very few channels.
+#include "general_kernel.h"
+
+#ifndef DCONV_F
+#error "compile with -DDCONV_F=<filter side>"
+#endif
+
+namespace dconv {
+
+namespace {
+
+constexpr int F = DCONV_F;
+constexpr int kChunkBig = F == 1 ? 16 : F == 2 ? 8 : F == 3 ? 4 : F == 4 ? 2 : 1;
+constexpr int kChunkSmall = F == 1 ? 4 : F == 2 ? 2 : 1;
+// filter rows per chunk: whole filters up to 5x5, groups of rows above (see GenGeom)
+constexpr int kRowGroup = F <= 5 ? F : F == 6 ? 3 : F == 9 ? 3 : F == 10 ? 5 : 4;
+// image words a thread stages per chunk: small filters have small halos
+constexpr int kImaxF = (F >= 2 && F <= 4) ? 8 : 16;
+
+// Three LDS slots when three chunks with the largest image block fit twice on a CU (or at
+// least once, for chunks with enough steps); two otherwise.
+template <int CSH, int MT>
+constexpr int nbuf_for()
+{
+    constexpr int RG = CSH == 1 ? kRowGroup : F, NG = (F + RG - 1) / RG, RGL = F - (NG - 1) * RG;
+    constexpr int T = CSH * RG * F, TP = T + (T & 1), S = (CSH * RGL * F + 1) / 2;
+    constexpr long slot = 4L * ((long)TP * (MT + 1) + kImaxF * kThreads + 8);
+    return (S >= 4 && 3 * slot <= kGenLdsLimit) ? 3 : 2;
+}
+
+template <int CSH, bool VEC>
+int launch_tile(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
+                int tile_cfg, const GenSched& sched, bool dry)
+{
+    // tile 0: 128 filters x 128 pixels; tile 1: 64 filters x 128 pixels (light on registers:
+    // three workgroups per CU); tile 2: 64 filters x 256 pixels (every wave holds all 64
+    // filters, so that it issues four matrix-core instructions per pair of operands loaded,
+    // like tile 0)
+    constexpr int RG = CSH == 1 ? kRowGroup : F;
+    if (tile_cfg == 0)
+        return gen_try_launch<F, CSH, RG, 2, 2, 2, 2, kImaxF, VEC, nbuf_for<CSH, 128>(), 2>(in, filt, out, s, st, sched, dry);
+    if (tile_cfg == 2)
+        return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 2>(in, filt, out, s, st, sched, dry);
+    return gen_try_launch<F, CSH, RG, 1, 2, 2, 2, kImaxF, VEC, nbuf_for<CSH, 64>(), 3>(in, filt, out, s, st, sched, dry);
+}
+
+template <int CSH>
+int launch_chunk(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
+                 int tile_cfg, const GenSched& sched, bool dry)
+{
+    // 16-byte filter loads need every run of a chunk to start on a 16-byte boundary
+    constexpr bool can_vec = (CSH * F * F) % 4 == 0 && (CSH > 1 || kRowGroup == F);
+    if (can_vec && ((int64_t)s.C * F * F) % 4 == 0 && s.C % CSH == 0 && (dry || ((uintptr_t)filt & 15) == 0))
+        return launch_tile<CSH, can_vec>(in, filt, out, s, st, tile_cfg, sched, dry);
+    return launch_tile<CSH, false>(in, filt, out, s, st, tile_cfg, sched, dry);
+}
+
+}  // namespace
+
+template <>
+int gen_launch_for_F<DCONV_F>(const float* in, const float* filt, float* out, const Shape& s,
+                              hipStream_t st, int tile_cfg, const GenSched& sched, bool dry)
+{
+    // the chunk that wastes the least on zero padding; the bigger one on a tie
+    auto padded = [&](int csh) { return (s.C + csh - 1) / csh * csh; };
+    int rc = DCONV_UNSUPPORTED;
+    if (kChunkBig != kChunkSmall && padded(kChunkBig) <= padded(kChunkSmall)) {
+        rc = launch_chunk<kChunkBig>(in, filt, out, s, st, tile_cfg, sched, dry);
+        if (rc != DCONV_UNSUPPORTED) return rc;
+    }
+    return launch_chunk<kChunkSmall>(in, filt, out, s, st, tile_cfg, sched, dry);
+}
+
+}  // namespace dconv

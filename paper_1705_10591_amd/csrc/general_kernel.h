@@ -1,0 +1,693 @@
+// General-case direct convolution (paper Sec. 4, Algorithm 2) for gfx950: the kernel.
+//
+// What is kept from the paper's scheme: a workgroup owns a block of filters
+// times a block of output pixels; channels are consumed in chunks of CSH;
+// each chunk's image block (with its halo) goes to LDS untransposed and the
+// matching filter block goes to LDS transposed, with a padded row stride, so
+// that both are read conflict-free; the next chunks are prefetched from HBM
+// into registers while the current one is consumed; the image block is read
+// at shifted addresses for the F*F taps instead of being unrolled in memory,
+// so an input pixel is fetched once per tile and reused F*F*K times on chip.
+//
+// What differs (CDNA4 instead of Kepler):
+//  * The multiply-accumulate runs on the matrix cores.  One
+//    v_mfma_f32_32x32x2_f32 forms a 32-filter x 32-pixel block of partial
+//    sums for two reduction indices at once; it is the only route to the
+//    chip's fp32 peak, and it makes the per-lane register tile of the paper
+//    (F_T x W_T) a per-wave tile of MW x NW such blocks.  The two reduction
+//    indices of one instruction are two consecutive entries of the flattened
+//    (channel, filter row, filter column) list of the chunk, so the image
+//    operand of lane l is the LDS word of pixel (l % 32) at the tap chosen
+//    by (l / 32).
+//  * Output pixels are numbered along (image, row, column) of a column
+//    strip, so a 32-pixel block may wrap over rows and images and no lanes
+//    are wasted on narrow maps (Wo = 26, 54).
+//  * LDS holds NBUF chunks (3 where they fit).  While chunk u is consumed,
+//    chunk u+1 moves from registers to the next LDS slot and chunk u+2 is
+//    requested from HBM: every staging register is written to LDS and
+//    re-loaded in the same breath, one or two registers per matrix-core
+//    step, so each load has a whole chunk period to arrive, the demand on
+//    L2 is even, and there is no phase in which a workgroup only copies.
+//    With three slots the one barrier per chunk sits two steps before the
+//    chunk's end and the first operands of the next chunk are requested
+//    across it, so the matrix pipe does not drain between chunks.
+//  * The launch is persistent: a fixed number of workgroups (what fits on
+//    the chip at once) each walk a contiguous range of (tile, chunk) units.
+//    Prefetching runs across tile boundaries.  When the number of tiles does
+//    not divide evenly over the chip, the range boundaries fall inside tiles:
+//    a tile is then summed over channels by two or more workgroups, each of
+//    which leaves its partial sums in a workspace and counts itself in; the
+//    one that arrives last adds the partial sums in a fixed order and writes
+//    the tile.  Nobody waits for anybody, so every workgroup always exits, and
+//    the result does not depend on the order of arrival.
+#pragma once
+#include "common.h"
+#include "../../include/dconv.h"
+
+namespace dconv {
+
+// Division of a non-negative int below 2^31 by a fixed positive divisor d, as one multiply-high
+// and a shift: with l = ceil(log2 d) and m = ceil(2^(31+l) / d) < 2^32, floor(n / d) equals
+// (n * m) >> (31 + l).  d = 1 is flagged by m = 0.  The setup of a tile divides a dozen times.
+struct FastDiv {
+    uint32_t m;
+    int sh;          // l - 1
+    int d;
+};
+inline FastDiv make_fastdiv(int d)
+{
+    FastDiv f{0u, 0, d};
+    if (d <= 1) return f;
+    int l = 0;
+    while ((1LL << l) < d) ++l;
+    f.m = (uint32_t)(((1ULL << (31 + l)) + (uint64_t)d - 1) / (uint64_t)d);
+    f.sh = l - 1;
+    return f;
+}
+__device__ __forceinline__ int fdiv(int n, FastDiv f) {
+    return f.m ? (int)(__umulhi((uint32_t)n, f.m) >> f.sh) : n;
+}
+
+struct GenParams {
+    const float* in;
+    const float* filt;
+    float* out;
+    float* part;     // workspace: partial tiles, [workgroup][2][MT * NT]
+    int* cnt;        // workspace: arrivals per split tile, indexed by its first workgroup; all 0
+    int N, C, H, W, K, Ho, Wo;
+    int bw;          // width of a column strip of the output (the last strip may be narrower)
+    int nstrips;
+    int LS;          // LDS row stride of the image block: bw + F - 1
+    int RS;          // LDS row slots per channel
+    int pt_full;     // pixel tiles in a full-width strip
+    int KB;          // filter tiles
+    int nch;         // channel chunks per tile
+    int tiles;       // all tiles: ((nstrips - 1) * pt_full + pt_last) * KB
+    int G;           // workgroups launched
+    int split;       // 1: ranges are cut in units (tiles may be shared), 0: in whole tiles
+    FastDiv d_strip; // by pt_full * KB
+    FastDiv d_kb;    // by KB
+    FastDiv d_wsf;   // by bw, the width of a full strip
+    FastDiv d_wsl;   // by the width of the last strip
+    FastDiv d_ho;    // by Ho
+    FastDiv d_h;     // by H
+    FastDiv d_nch;   // by nch
+};
+
+// Reduction index t of a chunk <-> (channel in chunk, filter row within the chunk's row group,
+// filter column).  A chunk holds RG of the F filter rows of CSH channels.
+template <int F, int RG> __device__ __forceinline__ constexpr int tap_c(int t) { return t / (RG * F); }
+template <int F, int RG> __device__ __forceinline__ constexpr int tap_i(int t) { return (t % (RG * F)) / F; }
+template <int F, int RG> __device__ __forceinline__ constexpr int tap_j(int t) { return t % F; }
+
+// First unit of workgroup j's range and the workgroup that owns unit v, for U units cut
+// evenly over G workgroups: range(j) = [j*U/G, (j+1)*U/G).
+__device__ __forceinline__ int range_start(int j, int U, int G) {
+    return (int)(((int64_t)j * U) / G);
+}
+__device__ __forceinline__ int unit_owner(int v, int U, int G) {
+    return (int)((((int64_t)v + 1) * G - 1) / U);
+}
+
+// Compile-time geometry of one instantiation, shared by the kernel and its launcher.
+//   RG:   filter rows per chunk; RG < F (large filters, one channel per chunk) cuts a channel
+//         into row groups so that the filter block of a chunk stays small; the last group
+//         may have fewer rows, its chunk then ends after fewer steps
+//   IMAX: image words a thread stages per chunk, at most
+//   VEC:  filter runs are fetched 16 B at a time (needs 16 B alignment of every run)
+//   NBUF: chunks held in LDS
+//   OCC:  workgroups per CU the register budget is cut for
+template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, bool VEC, int NBUF, int OCC>
+struct GenGeom {
+    static_assert(RG >= 1 && RG <= F && (RG == F || CSH == 1), "row groups need one channel per chunk");
+    static_assert(!VEC || RG == F, "16-byte filter loads only with whole channels");
+    static constexpr int NG = (F + RG - 1) / RG;     // row groups per channel
+    static constexpr int RGL = F - (NG - 1) * RG;    // filter rows in the last group
+    static constexpr int MT = 32 * MW * WM;          // filters per tile
+    static constexpr int NT = 32 * NW * WN;          // output pixels per tile
+    static constexpr int FF = F * F;
+    static constexpr int T = CSH * RG * F;           // reduction indices per chunk
+    static constexpr int TP = T + (T & 1);           // padded to a whole number of pairs
+    static constexpr int S = TP / 2;                 // matrix-core steps per chunk
+    static constexpr int TL = CSH * RGL * F;         // the same for the chunk of a last row group
+    static constexpr int SL = (TL + 1) / 2;
+    static constexpr int LDK = MT + 1;               // odd row stride: transposing writes hit 32 banks
+    static constexpr int TPF = kThreads / MT;        // threads that share one filter when staging
+    static constexpr int EPT0 = (T + TPF - 1) / TPF;
+    static constexpr int EPT = VEC ? (EPT0 + 3) / 4 * 4 : EPT0;   // reduction indices per thread
+    static constexpr int NFI = VEC ? EPT / 4 : EPT;  // filter loads per thread per chunk
+    static constexpr int NI = IMAX + NFI;            // staging items per thread per chunk
+    static_assert(NBUF == 2 || (NBUF == 3 && SL >= 4), "three LDS slots need at least four steps");
+    // steps that carry staging items (every chunk has them); with three slots the barrier sits
+    // two steps before the chunk's end
+    static constexpr int NS = NBUF == 3 ? SL - 2 : SL;
+    static constexpr int IPS = (NI + NS - 1) / NS;   // items per step
+};
+
+template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, bool VEC, int NBUF, int OCC>
+__global__ void __launch_bounds__(kThreads, OCC)
+general_tiled_kernel(GenParams p)
+{
+    static_assert(WM * WN * kWave == kThreads, "four waves per workgroup");
+    using Gm = GenGeom<F, CSH, RG, MW, NW, WM, WN, IMAX, VEC, NBUF, OCC>;
+    constexpr int NG = Gm::NG, RGL = Gm::RGL, TL = Gm::TL, SL = Gm::SL;
+    constexpr int MT = Gm::MT, NT = Gm::NT, FF = Gm::FF, T = Gm::T, TP = Gm::TP, S = Gm::S;
+    constexpr int LDK = Gm::LDK, TPF = Gm::TPF, EPT = Gm::EPT, NFI = Gm::NFI, NI = Gm::NI;
+    constexpr int NS = Gm::NS, IPS = Gm::IPS;
+
+    extern __shared__ float lds[];
+    __shared__ int s_old;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: index math on the scalar unit
+    const int h = lane >> 5, l32 = lane & 31;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int LS = p.LS, PL = p.RS * p.LS;
+    const int img_words = CSH * PL;
+    // one LDS slot: filter block [TP][LDK], image block [CSH][RS][LS], a zero word, a trash word
+    const int zero_word = TP * LDK + img_words;
+    const int trash_word = zero_word + 1;
+    const int BUF = (TP * LDK + img_words + 2 + 3) & ~3;
+
+    // Workgroups are handed to the 8 XCDs round-robin by their id; give each XCD one contiguous
+    // stretch of the unit list so that neighbouring tiles share its L2.
+    const int G = p.G;
+    const int j = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8)
+                               : (int)blockIdx.x;
+    const int nch = p.nch;
+    const int U = p.split ? p.tiles * nch : p.tiles;
+    const int unit_scale = p.split ? 1 : nch;
+    const int u0 = range_start(j, U, G) * unit_scale;
+    const int u1 = range_start(j + 1, U, G) * unit_scale;
+    if (u0 >= u1) return;                                   // uniform: before any barrier
+
+    const int HW = p.H * p.W;
+    const int64_t plane = (int64_t)p.Ho * p.Wo;
+    const int CFF = p.C * FF;
+    const int per_strip = p.pt_full * p.KB;
+
+    // ---- the staging side ------------------------------------------------------------------------
+    // HBM addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit byte offset
+    // per lane; the host has checked that the offsets of one tile fit.  Every load is issued
+    // unconditionally: a lane with nothing to bring reads the base address itself and its
+    // value is replaced by zero on the way to LDS.  The state of the unit being requested
+    // (suffix _f) and of the unit on its way from registers to LDS (suffix _c) is kept apart,
+    // because the two may belong to different tiles.
+    uint32_t ig[IMAX];       // image: byte offset from in[n_first][c0][0][0]
+    uint32_t imask_f = 0, imask_c = 0;          // bit it: item it carries an image word
+    const int wkl = tid / TPF, we0 = (tid % TPF) * EPT;
+    const uint32_t wofs = (uint32_t)(wkl * CFF + we0) * 4u;   // filter: byte offset from filt[k0][c0][0][0]
+    const char* ibase = (const char*)p.in;      // in[n_first][0][0][0] of the tile being requested
+    const char* wbase_g = (const char*)p.filt;  // filt[k0][0][0][0] of the tile being requested
+    const char* ip_f = ibase;                   // the same, at the chunk being requested
+    const char* fp_f = wbase_g;
+    bool wok_f = false, wok_c = false;          // this thread's filter exists
+    int cleft_f = CSH, cleft_c = CSH;           // channels really present in the chunk
+    int tlim_f = T, tlim_c = T;                 // reduction indices really present in the chunk
+    auto setup_fetch = [&](int tile) __attribute__((always_inline)) {
+        const int strip = min(fdiv(tile, p.d_strip), p.nstrips - 1);
+        const int rem = tile - strip * per_strip;
+        const int ptile = fdiv(rem, p.d_kb), kb = rem - ptile * p.KB;
+        const int x0 = strip * p.bw;
+        const int ws = min(p.bw, p.Wo - x0);
+        const bool last_strip = strip == p.nstrips - 1;
+        const FastDiv d_ws{last_strip ? p.d_wsl.m : p.d_wsf.m, last_strip ? p.d_wsl.sh : p.d_wsf.sh, ws};
+        const int total_p = p.N * p.Ho * ws;
+        const int p0 = ptile * NT;
+        // input rows are numbered n*H + y over the batch; the tile touches rows G0 .. G0+nslots-1
+        const int Q0 = fdiv(p0, d_ws);
+        const int n_first = fdiv(Q0, p.d_ho);
+        const int y_first = Q0 - n_first * p.Ho;
+        const int G0 = n_first * p.H + y_first;
+        const int Ql = fdiv(min(p0 + NT, total_p) - 1, d_ws);
+        const int nl = fdiv(Ql, p.d_ho);
+        const int nslots = nl * p.H + (Ql - nl * p.Ho) - G0 + F;
+        uint32_t mask = 0;
+#pragma unroll
+        for (int it = 0; it < IMAX; ++it) {
+            const int e = tid + it * kThreads;
+            uint32_t g = 0;
+            if (e < img_words) {
+                const int cc = e / PL, r2 = e - cc * PL;
+                const int slot = r2 / LS, col = r2 - slot * LS;
+                const int dn = fdiv(y_first + slot, p.d_h);          // images past the first one
+                const int yy = y_first + slot - dn * p.H;
+                if (slot < nslots && n_first + dn < p.N && x0 + col < p.W) {
+                    g = (uint32_t)(((dn * p.C + cc) * p.H + yy) * p.W + x0 + col) * 4u;
+                    mask |= 1u << it;
+                }
+            }
+            ig[it] = g;
+        }
+        imask_f = mask;
+        const int k0 = kb * MT;
+        wok_f = k0 + wkl < p.K;
+        ibase = (const char*)(p.in + (int64_t)n_first * p.C * HW);
+        wbase_g = (const char*)(p.filt + (int64_t)k0 * CFF);
+    };
+    auto set_chunk = [&](int chunk) __attribute__((always_inline)) {
+        const int cidx = chunk / NG, g = chunk - cidx * NG;
+        const int c0 = cidx * CSH;
+        cleft_f = min(CSH, p.C - c0);
+        tlim_f = cleft_f * ((g == NG - 1 ? RGL : RG) * F);
+        ip_f = ibase + (int64_t)c0 * HW * 4;
+        fp_f = wbase_g + ((int64_t)c0 * FF + g * (RG * F)) * 4;
+    };
+
+    float ireg[IMAX];
+    float wreg[EPT];
+    // Staging item w < IMAX is an image word, item IMAX + q a filter load (one word, or four).
+    auto fetch_item = [&](int w) __attribute__((always_inline)) {
+        if (w < IMAX) {
+            ireg[w] = *reinterpret_cast<const float*>(ip_f + ig[w]);
+        } else if (VEC) {
+            const int q = w - IMAX;
+            const uint32_t o = (wok_f && we0 + 4 * q < T) ? wofs : 0u;
+            const v4f v = reinterpret_cast<const v4f*>(fp_f + o)[(wok_f && we0 + 4 * q < T) ? q : 0];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) wreg[4 * q + e] = v[e];
+        } else {
+            const int q = w - IMAX;
+            const bool ok = wok_f && we0 + q < tlim_f;
+            wreg[q] = reinterpret_cast<const float*>(fp_f + (ok ? wofs : 0u))[ok ? q : 0];
+        }
+    };
+    auto commit_item = [&](int w, float* slot) __attribute__((always_inline)) {
+        if (w < IMAX) {
+            const int e = tid + w * kThreads;
+            const bool live = ((imask_c >> w) & 1u) && e < cleft_c * PL;
+            slot[e < img_words ? TP * LDK + e : trash_word] = live ? ireg[w] : 0.f;
+        } else if (VEC) {
+            const int q = w - IMAX;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int t = we0 + 4 * q + e;
+                slot[t < T ? t * LDK + wkl : trash_word] = wok_c ? wreg[4 * q + e] : 0.f;
+            }
+        } else {
+            const int q = w - IMAX;
+            const int t = we0 + q;
+            slot[t < T ? t * LDK + wkl : trash_word] =
+                (wok_c && t < tlim_c) ? wreg[q] : 0.f;
+        }
+    };
+
+    // ---- the compute side: where this lane's pixels sit in LDS and in the output --------------
+    int base[NW];            // LDS word (within a slot) of tap (0,0,0) of the lane's pixel
+    uint32_t oofs[NW];       // byte offset of out[n][k0 + 32*wm*MW + 4*h][y][x] from out[n_first][k0][0][0]
+    bool valid[NW];
+    int kleft = 0;           // filters from k0 + 32*wm*MW + 4*h to K
+    float* obase_t = p.out;  // out[n_first][k0][0][0]
+    auto setup_compute = [&](int tile) __attribute__((always_inline)) {
+        const int strip = min(fdiv(tile, p.d_strip), p.nstrips - 1);
+        const int rem = tile - strip * per_strip;
+        const int ptile = fdiv(rem, p.d_kb), kb = rem - ptile * p.KB;
+        const int x0 = strip * p.bw;
+        const int ws = min(p.bw, p.Wo - x0);
+        const bool last_strip = strip == p.nstrips - 1;
+        const FastDiv d_ws{last_strip ? p.d_wsl.m : p.d_wsf.m, last_strip ? p.d_wsl.sh : p.d_wsf.sh, ws};
+        const int total_p = p.N * p.Ho * ws;
+        const int p0 = ptile * NT;
+        const int Q0 = fdiv(p0, d_ws);
+        const int n_first = fdiv(Q0, p.d_ho);
+        const int G0 = n_first * p.H + (Q0 - n_first * p.Ho);
+        const int k0 = kb * MT;
+        kleft = p.K - k0 - 32 * wm * MW - 4 * h;
+        obase_t = p.out + ((int64_t)n_first * p.K + k0) * plane;
+        const int kplane = p.K * (int)plane;                  // one image of the output: fits, checked
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt) {
+            const int pp = p0 + (wn * NW + nt) * 32 + l32;
+            valid[nt] = pp < total_p;
+            const int pc = valid[nt] ? pp : total_p - 1;
+            const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
+            const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
+            base[nt] = TP * LDK + (n * p.H + y - G0) * LS + xl;
+            oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
+                                  y * p.Wo + x0 + xl) * 4u;
+        }
+    };
+    // Offsets of the second tap of a pair relative to the first, by kind of pair.
+    const int dX = h;                                         // next column, same row
+    const int dY = h * (LS - (F - 1));                        // first column of the next row
+    const int dZ = h * (PL - (RG - 1) * LS - (F - 1));        // first tap of the next channel
+    const int wbase = h * LDK + wm * (MW * 32) + l32;
+    // operands of step s of the chunk in `slot`; bb: the lane's pixels at the chunk's first row;
+    // shortg: the chunk is a last row group with fewer rows (its odd tap count is padded here)
+    auto load_ops = [&](int s, const float* slot, const int (&bb)[NW], bool shortg, float (&a)[MW],
+                        float (&b)[NW]) __attribute__((always_inline)) {
+        const int t0 = 2 * s, t1 = 2 * s + 1;
+        const int c = tap_c<F, RG>(t0), i = tap_i<F, RG>(t0), jj = tap_j<F, RG>(t0);
+        const int rowoff = c * PL + i * LS;
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt) {
+            int addr;
+            if (t1 >= T)                                              // pad: second tap reads 0
+                addr = h ? zero_word : bb[nt] + rowoff + jj;
+            else if (tap_c<F, RG>(t1) != c) addr = bb[nt] + dZ + rowoff + jj;
+            else if (tap_i<F, RG>(t1) != i) addr = bb[nt] + dY + rowoff + jj;
+            else                            addr = bb[nt] + dX + rowoff + jj;
+            if (TL != T && (TL & 1) && t1 == TL) addr = (shortg && h) ? zero_word : addr;
+            b[nt] = slot[addr];
+        }
+#pragma unroll
+        for (int mt = 0; mt < MW; ++mt)
+            a[mt] = slot[wbase + t0 * LDK + mt * 32];
+    };
+
+    v16f acc[MW][NW];
+    auto zero_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NW; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
+    };
+    // 32 lanes hold 32 consecutive pixels of one output map
+    auto store_out = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int mt = 0; mt < MW; ++mt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kk = mt * 32 + mfma_row(r, 0);          // filter, from this lane's first one
+                char* ob = (char*)(obase_t + kk * plane);          // uniform
+#pragma unroll
+                for (int nt = 0; nt < NW; ++nt)
+                    if (valid[nt] && kk < kleft)
+                        *reinterpret_cast<float*>(ob + oofs[nt]) = acc[mt][nt][r];
+            }
+        }
+    };
+    // A partial tile in the workspace: per wave, per block, per accumulator register, one word
+    // per lane, so that every store and load is 256 B contiguous per wave.  The words are
+    // written and read with device-scope accesses, which pass through the per-XCD L2 to the
+    // memory side where all XCDs meet; no cache has to be flushed or invalidated as a whole.
+    auto part_ptr = [&](int wg, int which) __attribute__((always_inline)) {
+        char* b = (char*)(p.part + ((int64_t)(2 * wg + which)) * (MT * NT) +
+                          wave * (MW * NW * 16 * kWave));              // uniform
+        return reinterpret_cast<float*>(b + (uint32_t)lane * 4u);
+    };
+    // The tile whose chunks [.., last] this workgroup has just summed is complete if the
+    // workgroup also summed its first chunk; otherwise it is shared with its neighbours.
+    auto finish_tile = [&](int tile, bool whole) __attribute__((always_inline)) {
+        if (whole) { store_out(); return; }
+        const int t0u = tile * nch;
+        const int first = unit_owner(t0u, U, G), last = unit_owner(t0u + nch - 1, U, G);
+        const int m = last - first + 1;
+        float* mine = part_ptr(j, u0 >= t0u ? 0 : 1);
+#pragma unroll
+        for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NW; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __hip_atomic_store(mine + ((mt * NW + nt) * 16 + r) * kWave, acc[mt][nt][r],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // every store of this workgroup has been acknowledged ...
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (tid == 0)                        // ... before its arrival is counted
+            s_old = __hip_atomic_fetch_add(&p.cnt[first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int old = s_old;
+        if (old != m - 1) return;            // somebody else arrives later and writes the tile
+        if (tid == 0)                        // ready for the next launch
+            __hip_atomic_store(&p.cnt[first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // Sum in the order of the workgroups, whoever does it.  With two parts the sum of this
+        // workgroup's registers and the other part is that sum already (addition commutes).
+        if (m > 2) zero_acc();
+        for (int i = first; i <= last; ++i) {
+            if (m == 2 && i == j) continue;
+            const float* src = part_ptr(i, range_start(i, U, G) >= t0u ? 0 : 1);
+#pragma unroll
+            for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NW; ++nt) {
+                    float v[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        v[r] = __hip_atomic_load(src + ((mt * NW + nt) * 16 + r) * kWave,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mt][nt][r] += v[r];
+                    __builtin_amdgcn_sched_barrier(0);   // one block's loads in flight at a time
+                }
+        }
+        store_out();
+    };
+
+    // ---- prologue: constant LDS words, first unit into slot 0, second unit into registers ------
+    for (int b = 0; b < NBUF; ++b) {
+        if (tid == 0) lds[b * BUF + zero_word] = 0.f;
+        if (TP != T)                         // the padding reduction index carries zero weights
+            for (int k = tid; k < MT; k += kThreads) lds[b * BUF + T * LDK + k] = 0.f;
+    }
+    int ftile = fdiv(u0, p.d_nch), fchunk = u0 - ftile * nch;   // the unit being requested
+    const int ftile_first = ftile;
+    setup_fetch(ftile);
+    set_chunk(fchunk);
+#pragma unroll
+    for (int w = 0; w < NI; ++w) fetch_item(w);
+    imask_c = imask_f; wok_c = wok_f; cleft_c = cleft_f; tlim_c = tlim_f;
+#pragma unroll
+    for (int w = 0; w < NI; ++w) commit_item(w, lds);
+    auto advance_fetch = [&]() __attribute__((always_inline)) {
+        if (++fchunk == nch) { fchunk = 0; ++ftile; setup_fetch(ftile); }
+        set_chunk(fchunk);
+    };
+    if (u0 + 1 < u1) advance_fetch();
+#pragma unroll
+    for (int w = 0; w < NI; ++w) fetch_item(w);           // unit u0+1 (or u0 again: never used)
+    int tile = ftile_first, chunk = u0 - tile * nch;       // the unit being consumed
+    bool from_first = chunk == 0;                          // this workgroup summed the tile's chunk 0
+    setup_compute(tile);
+    zero_acc();
+    __syncthreads();
+
+    // the lane's pixels in the image block, at the first filter row of the chunk's row group
+    int bb[NW];
+    auto is_short = [&](int ch) __attribute__((always_inline)) { return TL != T && ch % NG == NG - 1; };
+    auto set_bb = [&](int ch) __attribute__((always_inline)) {
+        const int i0LS = (ch % NG) * (RG * LS);
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt) bb[nt] = base[nt] + i0LS;
+    };
+    float a0[MW], b0[NW], a1[MW], b1[NW];
+    set_bb(chunk);
+    load_ops(0, lds, bb, is_short(chunk), a0, b0);
+    int bi = 0;                                            // LDS slot of the unit being consumed
+
+    // ---- main loop: one (tile, chunk) unit per trip --------------------------------------------
+    for (int u = u0; u < u1; ++u) {
+        const int bn = bi + 1 == NBUF ? 0 : bi + 1;
+        const float* cur = lds + bi * BUF;
+        float* nxt = lds + bn * BUF;
+        const bool has1 = u + 1 < u1, has2 = u + 2 < u1;
+        const bool tile_ends = chunk == nch - 1 || !has1;
+        // the unit in the registers moves to LDS during this trip; the next one is requested
+        imask_c = imask_f; wok_c = wok_f; cleft_c = cleft_f; tlim_c = tlim_f;
+        if (has2) advance_fetch();
+        const bool shortg = is_short(chunk);         // this chunk ends after SL steps
+        // keep the tap addresses from being expanded into one register each outside the loop
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt) asm volatile("" : "+v"(bb[nt]));
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (s >= SL && shortg) continue;                 // uniform; compiled away when SL == S
+            float (&a)[MW] = (s & 1) ? a1 : a0;
+            float (&b)[NW] = (s & 1) ? b1 : b0;
+            const bool last_step = s == S - 1 || (s == SL - 1 && shortg);
+            // Operands of step s+1 are requested from LDS before the matrix-core instructions
+            // of step s are issued, so a wave never waits for LDS with the matrix pipe idle.
+            if (!last_step) load_ops(s + 1, cur, bb, shortg, (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
+            else if (NBUF == 3 && !tile_ends) {
+                set_bb(chunk + 1);
+                load_ops(0, nxt, bb, is_short(chunk + 1), (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
+            }
+            if (s < NS) {
+#pragma unroll
+                for (int q = 0; q < IPS; ++q)
+                    if (s * IPS + q < NI) {
+                        commit_item(s * IPS + q, nxt);
+                        fetch_item(s * IPS + q);
+                    }
+            }
+            // unit u+1 is complete in LDS two steps before the chunk's end
+            if (NBUF == 3 && (s == S - 2 || s == SL - 2) && (s == S - 2) != shortg) __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NW; ++nt)
+                    acc[mt][nt] = mfma_32x32x2(a[mt], b[nt], acc[mt][nt]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (NBUF == 2) __syncthreads();      // unit u+1 is in LDS; everyone is done with unit u
+
+        if (tile_ends) {
+            finish_tile(tile, from_first && chunk == nch - 1);
+            if (has1) {
+                ++tile; chunk = 0; from_first = true;
+                setup_compute(tile);
+                zero_acc();
+                set_bb(0);
+                load_ops(0, nxt, bb, is_short(0), a0, b0);
+            }
+        } else {
+            ++chunk;
+            if (NBUF == 2) { set_bb(chunk); load_ops(0, nxt, bb, is_short(chunk), a0, b0); }
+            else if (((shortg ? SL : S) & 1) != 0) {   // the operands requested across the chunk end
+#pragma unroll
+                for (int mt = 0; mt < MW; ++mt) a0[mt] = a1[mt];
+#pragma unroll
+                for (int nt = 0; nt < NW; ++nt) b0[nt] = b1[nt];
+            }
+        }
+        bi = bn;
+    }
+}
+
+// ---- host side: one instantiation -------------------------------------------------------------
+
+struct GenPlan {
+    int bw, nstrips, LS, RS, pt_full, pt_last;
+    bool ok;
+};
+
+// Column strips and LDS image-block geometry for tiles of NT pixels: the widest strips (at
+// most 128 columns) whose image block of CSH channels a workgroup can stage with `imax`
+// words per thread.
+inline GenPlan make_gen_plan(const Shape& s, int NT, int CSH, int imax)
+{
+    GenPlan pl{};
+    for (int nstrips = (s.Wo + 127) / 128; nstrips <= s.Wo; ++nstrips) {
+        pl.bw = (s.Wo + nstrips - 1) / nstrips;
+        pl.nstrips = (s.Wo + pl.bw - 1) / pl.bw;
+        pl.LS = pl.bw + s.F - 1;
+        // A run of NT consecutive strip pixels touches at most this many output rows, taken
+        // over every strip width from the narrowest (the last strip) to bw ...
+        const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
+        const int rows = NT >= 2 ? (NT - 2) / wmin + 2 : 1;
+        // ... and crosses at most this many image boundaries, each adding F-1 input rows.
+        const int cross = rows >= 2 ? (rows - 2) / s.Ho + 1 : 0;
+        pl.RS = rows + (s.F - 1) * (cross + 1);
+        pl.pt_full = (int)(((int64_t)s.N * s.Ho * pl.bw + NT - 1) / NT);
+        pl.pt_last = (int)(((int64_t)s.N * s.Ho * wmin + NT - 1) / NT);
+        if ((int64_t)CSH * pl.RS * pl.LS <= (int64_t)imax * kThreads) { pl.ok = true; return pl; }
+    }
+    pl.ok = false;
+    return pl;
+}
+
+// How a launch cuts the work; filled in by the dispatcher.
+struct GenSched {
+    int mode;          // 0: decide by shape, 1: whole tiles only, 2: cut inside tiles
+    int force_G;       // > 0: this many workgroups (tests), 0: what the chip holds
+};
+
+// Workspace of one (device, stream): grown on demand by the dispatcher.
+struct GenWorkspace {
+    float* part;
+    int* cnt;
+};
+// Returns a workspace with room for `part_floats` floats of partial sums and `ncnt` counters,
+// or nullptr members on allocation failure.
+GenWorkspace gen_workspace(hipStream_t st, size_t part_floats, size_t ncnt);
+
+constexpr int kGenLdsLimit = 160 * 1024 - 256;     // dynamic LDS; the rest is for the static word
+
+template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, bool VEC, int NBUF, int OCC>
+int gen_try_launch(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
+                   const GenSched& sched, bool dry)
+{
+    using Gm = GenGeom<F, CSH, RG, MW, NW, WM, WN, IMAX, VEC, NBUF, OCC>;
+    constexpr int MT = Gm::MT, NT = Gm::NT, TP = Gm::TP, LDK = Gm::LDK;
+    const GenPlan pl = make_gen_plan(s, NT, CSH, IMAX);
+    if (!pl.ok) return DCONV_UNSUPPORTED;
+    const int64_t img_words = (int64_t)CSH * pl.RS * pl.LS;
+    const int64_t buf_words = ((int64_t)TP * LDK + img_words + 2 + 3) & ~3LL;
+    const int64_t lds_bytes = NBUF * 4 * buf_words;
+    if (lds_bytes > kGenLdsLimit) return DCONV_UNSUPPORTED;
+    const int KB = (s.K + MT - 1) / MT;
+    const int nch = (s.C + CSH - 1) / CSH * Gm::NG;
+    const int64_t tiles = ((int64_t)(pl.nstrips - 1) * pl.pt_full + pl.pt_last) * KB;
+    if (tiles * nch > 2147483647LL || (int64_t)s.N * s.Ho * s.Wo > 2147483647LL)
+        return DCONV_UNSUPPORTED;
+    // Lanes address HBM with 32-bit byte offsets from per-tile bases: everything one tile can
+    // reach from its first image must lie within 4 GiB.
+    {
+        const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
+        const int64_t span = NT / ((int64_t)s.Ho * wmin) + 2;        // images a tile can touch
+        const int64_t plane = (int64_t)s.Ho * s.Wo;
+        const int64_t lim = 1LL << 30;                                // floats
+        if (span * s.C * s.H * s.W >= lim || span * s.K * plane + (MT + 1) * plane >= lim ||
+            (int64_t)MT * s.C * F * F >= lim)
+            return DCONV_UNSUPPORTED;
+    }
+    if (dry) return DCONV_OK;
+    // 16-byte filter loads: the dispatcher only picks VEC when every run is aligned
+    if (VEC && (((int64_t)s.C * F * F) % 4 != 0 || s.C % CSH != 0 || ((uintptr_t)filt & 15) != 0))
+        return DCONV_UNSUPPORTED;
+
+    auto kern = general_tiled_kernel<F, CSH, RG, MW, NW, WM, WN, IMAX, VEC, NBUF, OCC>;
+    // Workgroups the chip holds at once for this LDS size (at most OCC per CU are used): cached
+    // per instantiation for the last LDS size seen.  A race between threads can only pair the
+    // count with another shape's LDS size, which changes the grid size and nothing else:
+    // no workgroup ever waits for another one.
+    static bool attr_set = false;
+    static int64_t cached_lds = -1;
+    static int cached_chip = 0;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kGenLdsLimit) != hipSuccess)
+            return DCONV_LAUNCH_FAILED;
+        attr_set = true;
+    }
+    if (cached_lds != lds_bytes) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, kThreads,
+                                                         (size_t)lds_bytes) != hipSuccess ||
+            cus <= 0 || per_cu <= 0)
+            return DCONV_LAUNCH_FAILED;
+        cached_chip = cus * (per_cu > OCC ? OCC : per_cu);
+        cached_lds = lds_bytes;
+    }
+    const int chip = cached_chip;
+
+    // Whole tiles when they spread evenly enough, otherwise cut inside tiles.
+    int G, split;
+    if (sched.mode == 1) split = 0;
+    else if (sched.mode == 2) split = 1;
+    else {
+        const int64_t rounds = (tiles + chip - 1) / chip;
+        split = (nch >= 2 && tiles < 8LL * chip && (double)tiles < 0.93 * (double)(rounds * chip)) ? 1 : 0;
+    }
+    const int64_t U = split ? tiles * nch : tiles;
+    G = sched.force_G > 0 ? sched.force_G : chip;
+    if (G > U) G = (int)U;
+
+    GenWorkspace ws{nullptr, nullptr};
+    if (split) {
+        ws = gen_workspace(st, (size_t)G * 2 * MT * NT, (size_t)G);
+        if (!ws.part || !ws.cnt) return DCONV_LAUNCH_FAILED;
+    }
+    GenParams p{in, filt, out, ws.part, ws.cnt, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo,
+                pl.bw, pl.nstrips, pl.LS, pl.RS, pl.pt_full, KB, nch, (int)tiles, G, split,
+                make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
+                make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho), make_fastdiv(s.H),
+                make_fastdiv(nch)};
+    hipLaunchKernelGGL(kern, dim3((unsigned)G), dim3(kThreads), (size_t)lds_bytes, st, p);
+    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+}
+
+// Implemented once per filter side, each in its own translation unit.
+template <int F>
+int gen_launch_for_F(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
+                     int tile_cfg, const GenSched& sched, bool dry);
+
+}  // namespace dconv

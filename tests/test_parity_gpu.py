@@ -125,6 +125,29 @@ def test_single_channel_every_tile_configuration(shape):
         np.testing.assert_array_equal(run_single(xi[0, 0], fi[:, 0], variant), o32[0])
 
 
+# shapes for every tile shape x schedule of the general kernel: channel counts that leave one,
+# several and many chunks per tile (tiles shared by 2, by 3 and more workgroups, and whole),
+# a channel count the chunk does not divide, more than 128 filters, several column strips
+GENERAL_CFG_SHAPES = [(3, 16, 28, 28, 130, 3), (2, 3, 20, 23, 5, 3), (2, 37, 14, 14, 70, 3),
+                      (1, 64, 20, 20, 64, 1), (2, 4, 40, 150, 33, 5), (2, 3, 37, 41, 64, 11),
+                      (9, 24, 9, 35, 96, 3), (1, 7, 20, 20, 9, 7), (2, 19, 16, 16, 200, 2)]
+
+
+@pytest.mark.parametrize("shape", GENERAL_CFG_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_general_every_tile_configuration(shape):
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(400 + F, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    xi, fi = wl.integer_case(40 + F, N, C, H, W, K, F)
+    _, _, o32, _ = oracle.general(xi, fi, want32=True)
+    for variant in _tile_variants(False):
+        got = run_general(x, f, variant)
+        assert_within_bound(got, acc, mag, f"general {shape} variant {variant}")
+        # the sum over channels of a shared tile is taken in a fixed order: same bits every time
+        np.testing.assert_array_equal(run_general(x, f, variant), got)
+        np.testing.assert_array_equal(run_general(xi, fi, variant), o32)
+
+
 @pytest.mark.parametrize("shape", [(2, 8, 28, 28, 70, 3), (1, 3, 30, 140, 64, 11), (3, 6, 12, 12, 9, 5)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_general_integer_inputs_are_bit_exact(shape):
