@@ -131,7 +131,7 @@ def main():
     head = allw[args.only] if args.only else wl.S2
 
     run, (x, f) = make_runner(head)
-    ms, wall_ms = time_launches(run, args.steps, args.warmup)
+    ms, wall_ms = time_launches(run, args.steps, args.warmup, warm_ms=60.0)
     entry = config_entry(head, ms)
 
     single = head.kind == "single"
@@ -183,7 +183,7 @@ def main():
         result["roofline_general"] = {
             "bound": "mfma", "kernel": "dconv_general", "workload": "G3",
             "achieved": round(g["G3"]["gflops"] / 1e3, 3), "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": g["G3"]["frac_fp32_peak"], "traffic": None}
+            "frac": g["G3"]["frac_fp32_peak"], "traffic": read_traffic("dconv_general_G3")}
 
     if not args.no_cpu_baseline and head.kind == "single":
         result["cpu_baseline"] = cpu_baseline(head, x, f)
