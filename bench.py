@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy a few times, so that a "
                          "counter run can scale FETCH_SIZE / WRITE_SIZE by a transfer of known size")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="also time the other corners the paper sweeps (1x1 filters, one filter, "
+                         "5x5 and 7x7 general layers, 32x32 images): entries under 'paper_sweep'")
     ap.add_argument("--only", default=None,
                     help="time just this configuration (S1, S2, S2_F3.., G1, G2, G3) as the step")
     return ap.parse_args()
@@ -128,6 +131,7 @@ def main():
 
     allw = dict(wl.CONFIGS)
     allw.update({v.name: v for v in wl.S2_SWEEP.values()})
+    allw.update(wl.PAPER_SWEEP)
     head = allw[args.only] if args.only else wl.S2
 
     run, (x, f) = make_runner(head)
@@ -184,6 +188,16 @@ def main():
             "bound": "mfma", "kernel": "dconv_general", "workload": "G3",
             "achieved": round(g["G3"]["gflops"] / 1e3, 3), "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": g["G3"]["frac_fp32_peak"], "traffic": read_traffic("dconv_general_G3")}
+
+    if args.paper_sweep:
+        sweep = []
+        for name, w in wl.PAPER_SWEEP.items():
+            r, _ = make_runner(w)
+            m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
+            sweep.append(config_entry(w, m))
+            del r
+            torch.cuda.empty_cache()
+        result["paper_sweep"] = sweep
 
     if not args.no_cpu_baseline and head.kind == "single":
         result["cpu_baseline"] = cpu_baseline(head, x, f)

@@ -325,3 +325,28 @@ def test_config_G3_integer_inputs_bit_exact_on_samples():
     got = out.reshape(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
     acc, _ = oracle.general_at(x, f, idx)
     np.testing.assert_array_equal(got.astype(np.float64), acc)
+
+
+# ---- the paper's other swept corners and the tile search ---------------------------------
+
+@pytest.mark.parametrize("name", list(wl.PAPER_SWEEP))
+def test_paper_sweep_shapes_sampled(name):
+    w = wl.PAPER_SWEEP[name]
+    x, f = wl.make_inputs(w)
+    print(name, flush=True)
+    if w.kind == "single":
+        out = dconv.dconv_single_channel(dev(x), dev(f))
+    else:
+        out = dconv.dconv_general(dev(x), dev(f))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    _sampled_check(w, out, x, f, 30000, name)
+
+
+def test_tile_search_reports_every_configuration():
+    from paper_1705_10591_amd import tune
+    rows = tune.tune("general", (2, 8, 28, 28, 70, 3), steps=2)
+    assert len(rows) == 1 + dconv.tile_config_count(False)
+    assert all(ms is None or ms > 0 for _, ms in rows) and rows[0][1] is not None
+    rows = tune.tune("single", (64, 600, 40, 5), steps=2)
+    assert len(rows) == 1 + dconv.tile_config_count(True)

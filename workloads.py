@@ -81,6 +81,23 @@ S2_SWEEP = {F: _mk(f"S2_F{F}", "single", 1, 1, 4096, 4096, 64, F, "u11", "u11", 
 
 CONFIGS = {w.name: w for w in (S1, S2, G1, G2, G3)}
 
+# The other corners the paper sweeps (Sec. 5: Fig. 7 for the special case with 1x1, 3x3 and 5x5
+# filters, a single filter being its stated weak spot; Fig. 8 / Table 1 for the general case
+# with 3x3, 5x5 and 7x7 filters, 32 x 32 images being the one place where it lost).  The
+# figures themselves did not survive, so sizes are chosen here: the image and batch sizes of
+# the benchmark configurations with the paper's filter sides and corner cases.
+PAPER_SWEEP = {w.name: w for w in (
+    _mk("A_F1", "single", 1, 1, 4096, 4096, 64, 1, "u11", "u11", 30),     # no data sharing at all
+    _mk("A_K1_F3", "single", 1, 1, 4096, 4096, 1, 3, "u11", "u11", 31),   # one filter
+    _mk("A_K1_F5", "single", 1, 1, 4096, 4096, 1, 5, "u11", "u11", 32),
+    _mk("A_K16_F3", "single", 1, 1, 2048, 2048, 16, 3, "u11", "u11", 33),
+    _mk("B_F5", "general", 32, 64, 56, 56, 64, 5, "u01", "he", 34),
+    _mk("B_F7", "general", 32, 64, 56, 56, 64, 7, "u01", "he", 35),
+    _mk("B_32_F3", "general", 128, 64, 32, 32, 128, 3, "u01", "he", 36),  # very small images
+    _mk("B_32_F5", "general", 128, 64, 32, 32, 128, 5, "u01", "he", 37),
+    _mk("B_32_F7", "general", 128, 64, 32, 32, 128, 7, "u01", "he", 38),
+)}
+
 
 def _draw(rng: np.random.Generator, dist: str, shape, C: int, F: int) -> np.ndarray:
     if dist == "u11":
