@@ -3,9 +3,8 @@
 //
 // Channel chunk per filter side: 16-36 reduction indices per chunk for small filters (short
 // enough that three chunks of a 128-filter tile fit in LDS with two workgroups per CU), one
-// channel per chunk from 5x5 on.  A chunk that does not divide the channel
-// count is padded with zeros in LDS, so the smaller chunk is only there for inputs with
-// very few channels.
+// channel per chunk from 5x5 on.  The chunk has to divide the channel count; smaller chunks
+// (down to one channel) are there for the counts it does not.
 #include "general_kernel.h"
 
 #ifndef DCONV_F
@@ -68,14 +67,18 @@ template <>
 int gen_launch_for_F<DCONV_F>(const float* in, const float* filt, float* out, const Shape& s,
                               hipStream_t st, int tile_cfg, const GenSched& sched, bool dry)
 {
-    // the chunk that wastes the least on zero padding; the bigger one on a tie
-    auto padded = [&](int csh) { return (s.C + csh - 1) / csh * csh; };
+    // the largest compiled chunk that divides the channel count (one channel always does)
     int rc = DCONV_UNSUPPORTED;
-    if (kChunkBig != kChunkSmall && padded(kChunkBig) <= padded(kChunkSmall)) {
+    if (s.C % kChunkBig == 0) {
         rc = launch_chunk<kChunkBig>(in, filt, out, s, st, tile_cfg, sched, dry);
         if (rc != DCONV_UNSUPPORTED) return rc;
     }
-    return launch_chunk<kChunkSmall>(in, filt, out, s, st, tile_cfg, sched, dry);
+    if (kChunkSmall != kChunkBig && s.C % kChunkSmall == 0) {
+        rc = launch_chunk<kChunkSmall>(in, filt, out, s, st, tile_cfg, sched, dry);
+        if (rc != DCONV_UNSUPPORTED) return rc;
+    }
+    if (kChunkSmall != 1) rc = launch_chunk<1>(in, filt, out, s, st, tile_cfg, sched, dry);
+    return rc;
 }
 
 }  // namespace dconv

@@ -189,22 +189,25 @@ general_tiled_kernel(GenParams p)
     const int per_strip = p.pt_full * p.KB;
 
     // ---- the staging side ------------------------------------------------------------------------
-    // HBM addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit byte offset
-    // per lane; the host has checked that the offsets of one tile fit.  Every load is issued
-    // unconditionally: a lane with nothing to bring reads the base address itself and its
-    // value is replaced by zero on the way to LDS.  The state of the unit being requested
+    // HBM is read through buffer descriptors: a wave-uniform base and extent (scalar registers)
+    // plus a 32-bit byte offset per lane, range-checked by the hardware.  A lane with nothing
+    // to bring uses an offset beyond the extent and receives zero, so every load is issued
+    // unconditionally and its value goes to LDS as it is: no compare or select on the vector
+    // ALU, whose every instruction takes time from the matrix cores.  The host has checked
+    // that the offsets of one tile stay below 2 GiB.  The state of the unit being requested
     // (suffix _f) and of the unit on its way from registers to LDS (suffix _c) is kept apart,
     // because the two may belong to different tiles.
-    uint32_t ig[IMAX];       // image: byte offset from in[n_first][c0][0][0]
-    uint32_t imask_f = 0, imask_c = 0;          // bit it: item it carries an image word
+    constexpr uint32_t kNowhere = 0xC0000000u;  // beyond every extent (extents are at most 2^31)
+    constexpr int kRsrcFlags = 0x00020000;      // raw buffer of 32-bit words
+    uint32_t ig[IMAX];       // image: byte offset from in[n_first][c0][0][0], or kNowhere
     const int wkl = tid / TPF, we0 = (tid % TPF) * EPT;
     const uint32_t wofs = (uint32_t)(wkl * CFF + we0) * 4u;   // filter: byte offset from filt[k0][c0][0][0]
     const char* ibase = (const char*)p.in;      // in[n_first][0][0][0] of the tile being requested
-    const char* wbase_g = (const char*)p.filt;  // filt[k0][0][0][0] of the tile being requested
-    const char* ip_f = ibase;                   // the same, at the chunk being requested
-    const char* fp_f = wbase_g;
-    bool wok_f = false, wok_c = false;          // this thread's filter exists
-    int cleft_f = CSH, cleft_c = CSH;           // channels really present in the chunk
+    int64_t ileft = 0;                          // bytes from there to the end of the input
+    int64_t wfirst = 0;                         // first filter word of the tile being requested
+    const int64_t in_bytes = (int64_t)p.N * p.C * HW * 4, filt_words = (int64_t)p.K * CFF;
+    __amdgpu_buffer_rsrc_t irs = __builtin_amdgcn_make_buffer_rsrc((void*)p.in, 0, 0, kRsrcFlags);
+    __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)p.filt, 0, 0, kRsrcFlags);
     int tlim_f = T, tlim_c = T;                 // reduction indices really present in the chunk
     auto setup_fetch = [&](int tile) __attribute__((always_inline)) {
         const int strip = min(fdiv(tile, p.d_strip), p.nstrips - 1);
@@ -224,73 +227,75 @@ general_tiled_kernel(GenParams p)
         const int Ql = fdiv(min(p0 + NT, total_p) - 1, d_ws);
         const int nl = fdiv(Ql, p.d_ho);
         const int nslots = nl * p.H + (Ql - nl * p.Ho) - G0 + F;
-        uint32_t mask = 0;
 #pragma unroll
         for (int it = 0; it < IMAX; ++it) {
             const int e = tid + it * kThreads;
-            uint32_t g = 0;
+            uint32_t g = kNowhere;
             if (e < img_words) {
                 const int cc = e / PL, r2 = e - cc * PL;
                 const int slot = r2 / LS, col = r2 - slot * LS;
                 const int dn = fdiv(y_first + slot, p.d_h);          // images past the first one
                 const int yy = y_first + slot - dn * p.H;
-                if (slot < nslots && n_first + dn < p.N && x0 + col < p.W) {
+                if (slot < nslots && n_first + dn < p.N && x0 + col < p.W)
                     g = (uint32_t)(((dn * p.C + cc) * p.H + yy) * p.W + x0 + col) * 4u;
-                    mask |= 1u << it;
-                }
             }
             ig[it] = g;
         }
-        imask_f = mask;
-        const int k0 = kb * MT;
-        wok_f = k0 + wkl < p.K;
-        ibase = (const char*)(p.in + (int64_t)n_first * p.C * HW);
-        wbase_g = (const char*)(p.filt + (int64_t)k0 * CFF);
+        const int64_t ifirst = (int64_t)n_first * p.C * HW * 4;
+        ibase = (const char*)p.in + ifirst;
+        ileft = in_bytes - ifirst;
+        wfirst = (int64_t)kb * MT * CFF;
     };
     auto set_chunk = [&](int chunk) __attribute__((always_inline)) {
         const int cidx = chunk / NG, g = chunk - cidx * NG;
         const int c0 = cidx * CSH;
-        cleft_f = min(CSH, p.C - c0);
-        tlim_f = cleft_f * ((g == NG - 1 ? RGL : RG) * F);
-        ip_f = ibase + (int64_t)c0 * HW * 4;
-        fp_f = wbase_g + ((int64_t)c0 * FF + g * (RG * F)) * 4;
+        tlim_f = CSH * ((g == NG - 1 ? RGL : RG) * F);
+        const int64_t ioff = (int64_t)c0 * HW * 4;
+        const int64_t ibytes = ileft - ioff;
+        irs = __builtin_amdgcn_make_buffer_rsrc((void*)(ibase + ioff), 0,
+                                                (int)min(ibytes, (int64_t)0x7FFFFFFF), kRsrcFlags);
+        const int64_t w0 = wfirst + (int64_t)c0 * FF + g * (RG * F);
+        const int64_t wbytes = (filt_words - w0) * 4;
+        wrs = __builtin_amdgcn_make_buffer_rsrc((void*)(p.filt + w0), 0,
+                                                (int)min(wbytes, (int64_t)0x7FFFFFFF), kRsrcFlags);
     };
 
     float ireg[IMAX];
     float wreg[EPT];
     // Staging item w < IMAX is an image word, item IMAX + q a filter load (one word, or four).
+    // A thread whose filter lies beyond K has offsets beyond the end of the filter bank.
     auto fetch_item = [&](int w) __attribute__((always_inline)) {
         if (w < IMAX) {
-            ireg[w] = *reinterpret_cast<const float*>(ip_f + ig[w]);
+            ireg[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(irs, ig[w], 0, 0));
         } else if (VEC) {
             const int q = w - IMAX;
-            const uint32_t o = (wok_f && we0 + 4 * q < T) ? wofs : 0u;
-            const v4f v = reinterpret_cast<const v4f*>(fp_f + o)[(wok_f && we0 + 4 * q < T) ? q : 0];
+            // (the whole 16 bytes are reinterpreted at once: converting the builtin's result
+            // element by element through another vector type drops all but the first word)
+            const v4f v = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs + 16u * q, 0, 0));
 #pragma unroll
             for (int e = 0; e < 4; ++e) wreg[4 * q + e] = v[e];
         } else {
             const int q = w - IMAX;
-            const bool ok = wok_f && we0 + q < tlim_f;
-            wreg[q] = reinterpret_cast<const float*>(fp_f + (ok ? wofs : 0u))[ok ? q : 0];
+            wreg[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrs, wofs + 4u * q, 0, 0));
         }
     };
     auto commit_item = [&](int w, float* slot) __attribute__((always_inline)) {
         if (w < IMAX) {
             const int e = tid + w * kThreads;
-            const bool live = ((imask_c >> w) & 1u) && e < cleft_c * PL;
-            slot[e < img_words ? TP * LDK + e : trash_word] = live ? ireg[w] : 0.f;
+            slot[e < img_words ? TP * LDK + e : trash_word] = ireg[w];
         } else if (VEC) {
             const int q = w - IMAX;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int t = we0 + 4 * q + e;
-                slot[t < T ? t * LDK + wkl : trash_word] = wok_c ? wreg[4 * q + e] : 0.f;
+                slot[t < T ? t * LDK + wkl : trash_word] = wreg[4 * q + e];
             }
         } else {
             const int q = w - IMAX;
             const int t = we0 + q;
-            slot[t < T ? t * LDK + wkl : trash_word] =
-                (wok_c && t < tlim_c) ? wreg[q] : 0.f;
+            // only the chunk of a shorter last row group has reduction indices to blank out
+            const float v = (TL != T && t >= tlim_c) ? 0.f : wreg[q];
+            slot[t < T ? t * LDK + wkl : trash_word] = v;
         }
     };
 
@@ -451,7 +456,7 @@ general_tiled_kernel(GenParams p)
     set_chunk(fchunk);
 #pragma unroll
     for (int w = 0; w < NI; ++w) fetch_item(w);
-    imask_c = imask_f; wok_c = wok_f; cleft_c = cleft_f; tlim_c = tlim_f;
+    tlim_c = tlim_f;
 #pragma unroll
     for (int w = 0; w < NI; ++w) commit_item(w, lds);
     auto advance_fetch = [&]() __attribute__((always_inline)) {
@@ -488,7 +493,7 @@ general_tiled_kernel(GenParams p)
         const bool has1 = u + 1 < u1, has2 = u + 2 < u1;
         const bool tile_ends = chunk == nch - 1 || !has1;
         // the unit in the registers moves to LDS during this trip; the next one is requested
-        imask_c = imask_f; wok_c = wok_f; cleft_c = cleft_f; tlim_c = tlim_f;
+        tlim_c = tlim_f;
         if (has2) advance_fetch();
         const bool shortg = is_short(chunk);         // this chunk ends after SL steps
         // keep the tap addresses from being expanded into one register each outside the loop
@@ -612,17 +617,18 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     const int64_t lds_bytes = NBUF * 4 * buf_words;
     if (lds_bytes > kGenLdsLimit) return DCONV_UNSUPPORTED;
     const int KB = (s.K + MT - 1) / MT;
-    const int nch = (s.C + CSH - 1) / CSH * Gm::NG;
+    if (s.C % CSH != 0) return DCONV_UNSUPPORTED;
+    const int nch = s.C / CSH * Gm::NG;
     const int64_t tiles = ((int64_t)(pl.nstrips - 1) * pl.pt_full + pl.pt_last) * KB;
     if (tiles * nch > 2147483647LL || (int64_t)s.N * s.Ho * s.Wo > 2147483647LL)
         return DCONV_UNSUPPORTED;
     // Lanes address HBM with 32-bit byte offsets from per-tile bases: everything one tile can
-    // reach from its first image must lie within 4 GiB.
+    // reach from its first image must lie within 2 GiB.
     {
         const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
         const int64_t span = NT / ((int64_t)s.Ho * wmin) + 2;        // images a tile can touch
         const int64_t plane = (int64_t)s.Ho * s.Wo;
-        const int64_t lim = 1LL << 30;                                // floats
+        const int64_t lim = 1LL << 29;                                // floats: 2 GiB
         if (span * s.C * s.H * s.W >= lim || span * s.K * plane + (MT + 1) * plane >= lim ||
             (int64_t)MT * s.C * F * F >= lim)
             return DCONV_UNSUPPORTED;
