@@ -243,11 +243,12 @@ single_tiled_kernel(SingleParams p)
         for (int nb = NB0; nb < NB; ++nb)
 #pragma unroll
             for (int q = 0; q < 16; ++q) AN[nb][q] = 0.f;
-#pragma unroll
-        for (int s = 0; s < S; ++s) {
+        // pixel operands of step s; those of step s+1 are requested before the matrix-core
+        // instructions of step s are issued, so the wave does not wait for LDS with the
+        // matrix pipe idle
+        auto load_b = [&](int s, float (&b)[NB]) {
             const int t0 = 2 * s, t1 = 2 * s + 1;
             const int i = t0 / F, j = t0 % F;
-            float b[NB];
 #pragma unroll
             for (int nb = NB0; nb < NB; ++nb) {
                 int addr;
@@ -257,12 +258,21 @@ single_tiled_kernel(SingleParams p)
                 else                  addr = base[nb] + h + i * LS + j;
                 b[nb] = sh[addr];
             }
+        };
+        float b0[NB], b1[NB];
+        load_b(0, b0);
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            float (&b)[NB] = (s & 1) ? b1 : b0;
+            if (s + 1 < S) load_b(s + 1, (s & 1) ? b0 : b1);
             if (have_pending) {
 #pragma unroll
                 for (int u = (s * UNITS) / S; u < ((s + 1) * UNITS) / S; ++u) wb_unit(u, AP, pd);
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int nb = NB0; nb < NB; ++nb) AN[nb] = mfma_32x32x2(a[s], b[nb], AN[nb]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     auto flush = [&](const v16f (&AP)[NB], const Pending& pd) {
