@@ -350,3 +350,49 @@ def test_tile_search_reports_every_configuration():
     assert all(ms is None or ms > 0 for _, ms in rows) and rows[0][1] is not None
     rows = tune.tune("single", (64, 600, 40, 5), steps=2)
     assert len(rows) == 1 + dconv.tile_config_count(True)
+
+
+def _random_shapes(seed, count):
+    """Seeded small shapes over the whole parameter range of the tiled kernels."""
+    rng = np.random.default_rng(wl.SEED_BASE * 17 + seed)
+    shapes = []
+    while len(shapes) < count:
+        F = int(rng.integers(1, 12))
+        H = int(rng.integers(F, F + 40))
+        W = int(rng.integers(F, F + (300 if len(shapes) % 5 == 0 else 60)))
+        N = int(rng.integers(1, 5))
+        C = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 17, 32]))
+        K = int(rng.choice([1, 2, 7, 16, 33, 64, 65, 130, 200]))
+        if N * C * H * W * K * F * F > 3e8:
+            continue
+        shapes.append((N, C, H, W, K, F))
+    return shapes
+
+
+def test_general_random_shapes_every_schedule():
+    shapes = _random_shapes(1, 36)
+    ncfg = dconv.tile_config_count(False)
+    for idx, shape in enumerate(shapes):
+        N, C, H, W, K, F = shape
+        x, f = wl.random_case(500 + idx, N, C, H, W, K, F)
+        acc, mag, _ = oracle.general(x, f)
+        for variant in (AUTO, dconv.VARIANT_TILED_CFG0 + idx % ncfg, dconv.VARIANT_TILED_CFG0 + (idx * 5 + 3) % ncfg):
+            try:
+                got = run_general(x, f, variant)
+            except dconv.DconvError as e:     # a forced configuration may not hold the shape
+                assert e.status == dconv.STATUS_UNSUPPORTED and variant != AUTO
+                continue
+            assert_within_bound(got, acc, mag, f"general {shape} variant {variant}")
+
+
+def test_single_channel_random_shapes_every_configuration():
+    shapes = _random_shapes(2, 30)
+    ncfg = dconv.tile_config_count(True)
+    for idx, (N, C, H, W, K, F) in enumerate(shapes):
+        W = W * 4 if idx % 3 == 0 else W          # some images wide enough for whole-line row ends
+        x, f = wl.random_case(600 + idx, 1, 1, H, W, K, F)
+        img, flt = x[0, 0], f[:, 0]
+        acc, mag, _ = oracle.single_channel(img, flt)
+        for variant in (AUTO, dconv.VARIANT_TILED_CFG0 + idx % ncfg):
+            assert_within_bound(run_single(img, flt, variant), acc, mag,
+                                f"single {(H, W, K, F)} variant {variant}")
