@@ -99,14 +99,17 @@ int launch_any(const float* in, const float* filt, float* out, const Shape& s, h
 // Tile shape by problem shape (measured on the chip, see the tuning notes of the build):
 // more than 64 filters: the 128 x 128 tile (each image operand feeds two filter blocks of a
 // wave).  Up to 64 filters: the 64 x 256 tile (every wave holds all filters: the same four
-// matrix-core instructions per operand pair) when there are enough such tiles to keep every
-// workgroup busy for several tiles; otherwise the 64 x 128 tile, which is light enough on
-// registers for three workgroups per CU and so covers small problems in one round.
+// matrix-core instructions per operand pair) when the work divides finely enough over the chip
+// with it; otherwise the 64 x 128 tile, which is light enough on registers for three
+// workgroups per CU and so covers small problems in one round.
 int shape_for(const Shape& s)
 {
     if (s.K > 64) return 0;
+    // enough wide tiles for several per workgroup, or enough chunks per tile that sharing
+    // tiles between workgroups balances the chip without costing much
     const int64_t wide_tiles = ((int64_t)s.N * s.Ho * s.Wo + 255) / 256;
-    return wide_tiles >= 1024 ? 2 : 1;
+    const int64_t chunks = ((int64_t)s.C * s.F * s.F + 35) / 36;
+    return (wide_tiles >= 1024 || wide_tiles * chunks >= 12000) ? 2 : 1;
 }
 
 }  // namespace

@@ -38,16 +38,17 @@ template <int CSH, bool VEC>
 int launch_tile(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                 int tile_cfg, const GenSched& sched, bool dry)
 {
-    // tile 0: 128 filters x 128 pixels; tile 1: 64 filters x 128 pixels (light on registers:
-    // three workgroups per CU); tile 2: 64 filters x 256 pixels (every wave holds all 64
-    // filters, so that it issues four matrix-core instructions per pair of operands loaded,
+    // tile 0: 128 filters x 128 pixels, 2 x 2 waves of 2 x 2 blocks; tile 1: 64 filters x 128
+    // pixels, four waves side by side, each with all 64 filters of 32 pixels (light on
+    // registers: three workgroups per CU); tile 2: 64 filters x 256 pixels, four waves side by
+    // side with 2 x 2 blocks each (four matrix-core instructions per pair of operand loads,
     // like tile 0)
     constexpr int RG = CSH == 1 ? kRowGroup : F;
     if (tile_cfg == 0)
         return gen_try_launch<F, CSH, RG, 2, 2, 2, 2, kImaxF, VEC, nbuf_for<CSH, 128>(), 2>(in, filt, out, s, st, sched, dry);
     if (tile_cfg == 2)
         return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 2>(in, filt, out, s, st, sched, dry);
-    return gen_try_launch<F, CSH, RG, 1, 2, 2, 2, kImaxF, VEC, nbuf_for<CSH, 64>(), 3>(in, filt, out, s, st, sched, dry);
+    return gen_try_launch<F, CSH, RG, 2, 1, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 3>(in, filt, out, s, st, sched, dry);
 }
 
 template <int CSH>
