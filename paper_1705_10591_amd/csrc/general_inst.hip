@@ -30,7 +30,7 @@ constexpr int nbuf_for()
 {
     constexpr int RG = CSH == 1 ? kRowGroup : F, NG = (F + RG - 1) / RG, RGL = F - (NG - 1) * RG;
     constexpr int T = CSH * RG * F, TP = T + (T & 1), S = (CSH * RGL * F + 1) / 2;
-    constexpr long slot = 4L * ((long)TP * (MT + 1) + kImaxF * kThreads + 8);
+    constexpr long slot = 4L * ((long)(TP + 16) * (MT + 1) + kImaxF * kThreads + 8);   // rows: see TROWS
     return (S >= 4 && 3 * slot <= kGenLdsLimit) ? 3 : 2;
 }
 

@@ -136,6 +136,9 @@ struct GenGeom {
     static constexpr int EPT0 = (T + TPF - 1) / TPF;
     static constexpr int EPT = VEC ? (EPT0 + 3) / 4 * 4 : EPT0;   // reduction indices per thread
     static constexpr int NFI = VEC ? EPT / 4 : EPT;  // filter loads per thread per chunk
+    // rows of the filter block in LDS: with 16-byte loads every thread's run is written whole
+    // (rows beyond TP are never read), so the write addresses need no test
+    static constexpr int TROWS = (VEC && TPF * EPT > TP) ? TPF * EPT : TP;
     static constexpr int NI = IMAX + NFI;            // staging items per thread per chunk
     static_assert(NBUF == 2 || (NBUF == 3 && SL >= 4), "three LDS slots need at least four steps");
     // steps that carry staging items (every chunk has them); with three slots the barrier sits
@@ -153,7 +156,7 @@ general_tiled_kernel(GenParams p)
     constexpr int NG = Gm::NG, RGL = Gm::RGL, TL = Gm::TL, SL = Gm::SL;
     constexpr int MT = Gm::MT, NT = Gm::NT, FF = Gm::FF, T = Gm::T, TP = Gm::TP, S = Gm::S;
     constexpr int LDK = Gm::LDK, TPF = Gm::TPF, EPT = Gm::EPT, NFI = Gm::NFI, NI = Gm::NI;
-    constexpr int NS = Gm::NS, IPS = Gm::IPS;
+    constexpr int NS = Gm::NS, IPS = Gm::IPS, TROWS = Gm::TROWS;
 
     extern __shared__ float lds[];
     __shared__ int s_old;
@@ -167,9 +170,9 @@ general_tiled_kernel(GenParams p)
     const int LS = p.LS, PL = p.RS * p.LS;
     const int img_words = CSH * PL;
     // one LDS slot: filter block [TP][LDK], image block [CSH][RS][LS], a zero word, a trash word
-    const int zero_word = TP * LDK + img_words;
+    const int zero_word = TROWS * LDK + img_words;
     const int trash_word = zero_word + 1;
-    const int BUF = (TP * LDK + img_words + 2 + 3) & ~3;
+    const int BUF = (TROWS * LDK + img_words + 2 + 3) & ~3;
 
     // Workgroups are handed to the 8 XCDs round-robin by their id; give each XCD one contiguous
     // stretch of the unit list so that neighbouring tiles share its L2.
@@ -262,6 +265,9 @@ general_tiled_kernel(GenParams p)
 
     float ireg[IMAX];
     float wreg[EPT];
+    int wrow[4];             // LDS word of this thread's filter run, one base per word of a 16-byte load
+#pragma unroll
+    for (int e = 0; e < 4; ++e) wrow[e] = we0 * LDK + wkl + e * LDK;
     // Staging item w < IMAX is an image word, item IMAX + q a filter load (one word, or four).
     // A thread whose filter lies beyond K has offsets beyond the end of the filter bank.
     auto fetch_item = [&](int w) __attribute__((always_inline)) {
@@ -282,13 +288,14 @@ general_tiled_kernel(GenParams p)
     auto commit_item = [&](int w, float* slot) __attribute__((always_inline)) {
         if (w < IMAX) {
             const int e = tid + w * kThreads;
-            slot[e < img_words ? TP * LDK + e : trash_word] = ireg[w];
+            slot[e < img_words ? TROWS * LDK + e : trash_word] = ireg[w];
         } else if (VEC) {
             const int q = w - IMAX;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int t = we0 + 4 * q + e;
-                slot[t < T ? t * LDK + wkl : trash_word] = wreg[4 * q + e];
+                if (TROWS >= TPF * EPT) slot[wrow[e] + 4 * q * LDK] = wreg[4 * q + e];
+                else slot[t < T ? t * LDK + wkl : trash_word] = wreg[4 * q + e];
             }
         } else {
             const int q = w - IMAX;
@@ -329,7 +336,7 @@ general_tiled_kernel(GenParams p)
             const int pc = valid[nt] ? pp : total_p - 1;
             const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
             const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
-            base[nt] = TP * LDK + (n * p.H + y - G0) * LS + xl;
+            base[nt] = TROWS * LDK + (n * p.H + y - G0) * LS + xl;
             oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
                                   y * p.Wo + x0 + xl) * 4u;
         }
@@ -338,7 +345,13 @@ general_tiled_kernel(GenParams p)
     const int dX = h;                                         // next column, same row
     const int dY = h * (LS - (F - 1));                        // first column of the next row
     const int dZ = h * (PL - (RG - 1) * LS - (F - 1));        // first tap of the next channel
-    const int wbase = h * LDK + wm * (MW * 32) + l32;
+    // One LDS base per filter block of the wave and (below) per word of a 16-byte filter run,
+    // each made opaque to the compiler once per chunk: reads and writes that share a base get
+    // paired into two-address LDS instructions whose short offset fields then need a vector
+    // add per pair; with a base of their own they keep full-range immediate offsets.
+    int wb[MW];
+#pragma unroll
+    for (int mt = 0; mt < MW; ++mt) wb[mt] = h * LDK + wm * (MW * 32) + l32 + mt * 32;
     // operands of step s of the chunk in `slot`; bb: the lane's pixels at the chunk's first row;
     // shortg: the chunk is a last row group with fewer rows (its odd tap count is padded here)
     auto load_ops = [&](int s, const float* slot, const int (&bb)[NW], bool shortg, float (&a)[MW],
@@ -359,7 +372,7 @@ general_tiled_kernel(GenParams p)
         }
 #pragma unroll
         for (int mt = 0; mt < MW; ++mt)
-            a[mt] = slot[wbase + t0 * LDK + mt * 32];
+            a[mt] = slot[wb[mt] + t0 * LDK];
     };
 
     v16f acc[MW][NW];
@@ -500,6 +513,12 @@ general_tiled_kernel(GenParams p)
 #pragma unroll
         for (int nt = 0; nt < NW; ++nt) asm volatile("" : "+v"(bb[nt]));
 #pragma unroll
+        for (int mt = 0; mt < MW; ++mt) asm volatile("" : "+v"(wb[mt]));
+        if (VEC) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(wrow[e]));
+        }
+#pragma unroll
         for (int s = 0; s < S; ++s) {
             if (s >= SL && shortg) continue;                 // uniform; compiled away when SL == S
             float (&a)[MW] = (s & 1) ? a1 : a0;
@@ -613,7 +632,7 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     const GenPlan pl = make_gen_plan(s, NT, CSH, IMAX);
     if (!pl.ok) return DCONV_UNSUPPORTED;
     const int64_t img_words = (int64_t)CSH * pl.RS * pl.LS;
-    const int64_t buf_words = ((int64_t)TP * LDK + img_words + 2 + 3) & ~3LL;
+    const int64_t buf_words = ((int64_t)Gm::TROWS * LDK + img_words + 2 + 3) & ~3LL;
     const int64_t lds_bytes = NBUF * 4 * buf_words;
     if (lds_bytes > kGenLdsLimit) return DCONV_UNSUPPORTED;
     const int KB = (s.K + MT - 1) / MT;
