@@ -186,9 +186,12 @@ single_tiled_kernel(SingleParams p)
         if (j < 4) {
             const int q = 4 * g + j;
             const int sk = (-(pd.tw + (8 * g + j) * pm)) & 31;
-            float* dst = stg + (wl - sk) + j * SW;
+            // the strip word as one opaque register: the stores then pair up with offsets of
+            // 0..4 blocks and need no further address arithmetic on the vector ALU
+            int word = (int)(stg - sh) + (wl - sk) + j * SW;
+            asm volatile("" : "+v"(word));
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) dst[nb * 32] = A[nb][q];
+            for (int nb = 0; nb < NB; ++nb) sh[word + nb * 32] = A[nb][q];
         } else if (j < 4 + ITS) {
             const int it = j - 4;
             held[it] = *reinterpret_cast<const v4f*>(stg + rdofs + it * RPI * SW);
