@@ -52,6 +52,11 @@ enum {
     DCONV_VARIANT_SIMPLE = 1, /* one thread per output element; any shape        */
     DCONV_VARIANT_TILED = 2,  /* LDS-staged, matrix-core tiled kernel, tile
                                  configuration picked by shape                   */
+    DCONV_VARIANT_FEW_FILTERS = 3,
+                              /* single-channel case only, F <= 7: vector-ALU
+                                 kernel with a sliding register window (the
+                                 paper's Algorithm 1 as it stands); what AUTO
+                                 picks for up to 8 filters on large images       */
     DCONV_VARIANT_TILED_CFG0 = 0x100
                               /* DCONV_VARIANT_TILED_CFG0 + i: the tiled kernel
                                  with tile configuration i forced, 0 <= i <

@@ -17,7 +17,7 @@ import torch
 _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libdconv.so"
 
-VARIANT_AUTO, VARIANT_SIMPLE, VARIANT_TILED = 0, 1, 2
+VARIANT_AUTO, VARIANT_SIMPLE, VARIANT_TILED, VARIANT_FEW_FILTERS = 0, 1, 2, 3
 VARIANT_TILED_CFG0 = 0x100     # + i: tiled kernel with tile configuration i forced
 STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAUNCH_FAILED = range(5)
 

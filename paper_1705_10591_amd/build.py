@@ -12,7 +12,7 @@ CSRC = PKG / "csrc"
 LIB = PKG / "libdconv.so"
 BUILD = PKG / "_build"
 # (source, extra flags, object name); the general-case kernel is compiled once per filter side
-SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", [], "single"),
+SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", [], "single"), ("single_fewfilters.hip", [], "single_fewfilters"),
            ("general.hip", [], "general")] + \
           [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 12)]
 

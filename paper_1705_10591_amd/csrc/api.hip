@@ -38,7 +38,11 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
     };
     switch (variant) {
     case DCONV_VARIANT_AUTO:
+        if (single && dconv::single_few_preferred(s)) return dconv::launch_single_few(in, filt, out, s, st);
         return tiled_ok ? tiled(-1) : dconv::launch_simple(in, filt, out, s, st);
+    case DCONV_VARIANT_FEW_FILTERS:
+        if (!single || !dconv::single_few_supports(s)) return DCONV_UNSUPPORTED;
+        return dconv::launch_single_few(in, filt, out, s, st);
     case DCONV_VARIANT_SIMPLE:
         return dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_TILED:
@@ -109,6 +113,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1002; }
+int dconv_version(void) { return 1003; }
 
 }  // extern "C"

@@ -43,6 +43,9 @@ int launch_general_tiled(const float* in, const float* filt, float* out, const S
                          hipStream_t st, int cfg);
 int single_tile_configs();
 int general_tile_configs();
+int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st);
+bool single_few_supports(const Shape& s);      // the few-filters kernel can run the shape
+bool single_few_preferred(const Shape& s);     // ... and is the better choice for it
 bool single_tiled_supports(const Shape& s);
 bool general_tiled_supports(const Shape& s);
 void release_general_workspaces();

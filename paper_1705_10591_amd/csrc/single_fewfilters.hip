@@ -1,0 +1,189 @@
+// Special-case direct convolution for VERY FEW filters (paper Sec. 3, Algorithm 1), gfx950.
+//
+// With a handful of filters the single-channel case is pure communication: the
+// matrix-core kernel of single.hip would fill a 32-filter block with one or two
+// filters.  This kernel is the paper's scheme taken almost literally, on the
+// vector ALU:
+//  * the image is cut into tiles, a workgroup stages its tile plus the F-1 halo
+//    columns and rows right and below in LDS, so every pixel is read from HBM
+//    once (halo aside);
+//  * a lane owns four consecutive output columns and sweeps a band of rows
+//    downwards with a window of F image rows in registers: every step reads ONE
+//    new image row segment from LDS (16 bytes per lane and instruction) and
+//    reuses the other F-1 rows, which is the paper's sliding register window;
+//  * the filters are wave-uniform: a group of KB filters sits in scalar
+//    registers (the counterpart of the constant-cache broadcast), so each
+//    multiply-add takes its weight from a scalar operand and its pixel from the
+//    window;
+//  * the four outputs of a lane are stored as 16 bytes, a wave writes 1 KiB of
+//    consecutive pixels per filter and row.
+// What differs: no rolling one-row prefetch from global memory (several
+// workgroups share a CU and overlap each other's loads); the window does not
+// shift, the row loop is unrolled so that the ring index is a compile-time
+// constant; filter groups are the outer loop, so a group's weights are fetched
+// once per wave and tile.
+#include <type_traits>
+#include "common.h"
+#include "../../include/dconv.h"
+
+namespace dconv {
+
+namespace {
+
+struct FewParams {
+    const float* img;
+    const float* filt;
+    float* out;
+    int H, W, K, Ho, Wo;
+    int tiles_x;
+};
+
+constexpr int kFewTW = 256;          // tile width: 64 lanes x 4 columns
+constexpr int kFewRPW = 8;           // output rows per wave
+constexpr int kFewTR = 4 * kFewRPW;  // tile rows: four waves, one band each
+
+// filters held in scalar registers at a time: at most 64 weights
+constexpr int few_kb(int F) { return F * F <= 16 ? 4 : F * F <= 32 ? 2 : 1; }
+
+template <int F>
+__global__ void __launch_bounds__(kThreads)
+single_few_kernel(FewParams p)
+{
+    constexpr int FF = F * F;
+    constexpr int KB = few_kb(F);
+    constexpr int WIN = 4 + F - 1;                 // window columns of a lane
+    constexpr int NV = (WIN + 3) / 4;              // 16-byte LDS reads per window row
+    constexpr int LS = kFewTW + 4 * NV - 4;        // LDS row stride: the last lane's reads stay in the row
+    constexpr int ROWS = kFewTR + F - 1;
+    static_assert(LS % 4 == 0, "16-byte aligned rows");
+
+    __shared__ __attribute__((aligned(16))) float sh[ROWS * LS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ty = blockIdx.x / p.tiles_x, tx = blockIdx.x - ty * p.tiles_x;
+    const int x0 = tx * kFewTW, y0 = ty * kFewTR;
+
+    // ---- stage the tile (zeros outside the image), coalesced along rows -------------------
+    {
+        const int cols = min(LS, p.W - x0);
+        const int rows = min(ROWS, p.H - y0);
+        const float* src = p.img + (int64_t)y0 * p.W + x0;
+        for (int e = tid; e < ROWS * LS; e += kThreads) {
+            const int r = e / LS, c = e - r * LS;
+            sh[e] = (r < rows && c < cols) ? src[(int64_t)r * p.W + c] : 0.f;
+        }
+    }
+    __syncthreads();
+
+    const int r0 = wave * kFewRPW;                 // first output row of this wave's band
+    const int xo = x0 + 4 * lane;                  // first output column of this lane
+    if (y0 + r0 >= p.Ho) return;                   // uniform per wave; no barrier follows
+    const int64_t plane = (int64_t)p.Ho * p.Wo;
+    const float* wrow = sh + 4 * lane;
+
+    // window row of image row (r0 + rr) lives in win[(rr) % F]
+    auto load_row = [&](int rr, float (&w)[4 * NV]) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const v4f q = *reinterpret_cast<const v4f*>(wrow + (r0 + rr) * LS + 4 * v);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[4 * v + e] = q[e];
+        }
+    };
+
+    for (int k0 = 0; k0 < p.K; k0 += KB) {         // filter groups: uniform loop
+        // the group's weights, wave-uniform and kept in scalar registers
+        float wgt[KB][FF];
+#pragma unroll
+        for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+            for (int t = 0; t < FF; ++t)
+                wgt[kk][t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(
+                    int, (k0 + kk < p.K) ? p.filt[(int64_t)(k0 + kk) * FF + t] : 0.f)));
+
+        float win[F][4 * NV];
+#pragma unroll
+        for (int i = 0; i < F - 1; ++i) load_row(i, win[i]);
+#pragma unroll
+        for (int rr = 0; rr < kFewRPW; ++rr) {
+            load_row(rr + F - 1, win[(rr + F - 1) % F]);
+            float acc[KB][4];
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[kk][e] = 0.f;
+#pragma unroll
+            for (int i = 0; i < F; ++i)
+#pragma unroll
+                for (int j = 0; j < F; ++j)
+#pragma unroll
+                    for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            acc[kk][e] = __builtin_fmaf(win[(rr + i) % F][j + e], wgt[kk][i * F + j], acc[kk][e]);
+            const int y = y0 + r0 + rr;
+            if (y < p.Ho) {
+#pragma unroll
+                for (int kk = 0; kk < KB; ++kk) {
+                    if (k0 + kk >= p.K) break;
+                    float* dst = p.out + (int64_t)(k0 + kk) * plane + (int64_t)y * p.Wo + xo;
+                    // 16 bytes at once where they fit (rows start at any 4-byte offset: the store
+                    // is declared 4-byte aligned), single words at the row end
+                    typedef float v4f_a4 __attribute__((ext_vector_type(4), aligned(4)));
+                    if (xo + 3 < p.Wo) {
+                        *reinterpret_cast<v4f_a4*>(dst) = (v4f_a4){acc[kk][0], acc[kk][1], acc[kk][2], acc[kk][3]};
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (xo + e < p.Wo) dst[e] = acc[kk][e];
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int F>
+int launch_few_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
+{
+    FewParams p{img, filt, out, s.H, s.W, s.K, s.Ho, s.Wo, (s.Wo + kFewTW - 1) / kFewTW};
+    const int64_t tiles = (int64_t)p.tiles_x * ((s.Ho + kFewTR - 1) / kFewTR);
+    if (tiles > 2147483647LL) return DCONV_UNSUPPORTED;
+    hipLaunchKernelGGL(single_few_kernel<F>, dim3((unsigned)tiles), dim3(kThreads), 0, st, p);
+    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+}
+
+}  // namespace
+
+// Filter sides with a window that fits the register file comfortably; any filter count (the
+// groups are looped over), though it only pays for few.
+bool single_few_supports(const Shape& s)
+{
+    return s.N == 1 && s.C == 1 && s.F >= 1 && s.F <= 7;
+}
+
+// Worth it: few enough filters that a 32-filter matrix-core block would be mostly empty, and
+// enough tiles to cover the chip.
+bool single_few_preferred(const Shape& s)
+{
+    const int64_t tiles = (int64_t)((s.Wo + kFewTW - 1) / kFewTW) * ((s.Ho + kFewTR - 1) / kFewTR);
+    return single_few_supports(s) && s.K <= 8 && tiles >= 512;
+}
+
+int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
+{
+    switch (s.F) {
+    case 1: return launch_few_F<1>(img, filt, out, s, st);
+    case 2: return launch_few_F<2>(img, filt, out, s, st);
+    case 3: return launch_few_F<3>(img, filt, out, s, st);
+    case 4: return launch_few_F<4>(img, filt, out, s, st);
+    case 5: return launch_few_F<5>(img, filt, out, s, st);
+    case 6: return launch_few_F<6>(img, filt, out, s, st);
+    case 7: return launch_few_F<7>(img, filt, out, s, st);
+    default: return DCONV_UNSUPPORTED;
+    }
+}
+
+}  // namespace dconv

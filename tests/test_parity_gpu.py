@@ -396,3 +396,45 @@ def test_single_channel_random_shapes_every_configuration():
         for variant in (AUTO, dconv.VARIANT_TILED_CFG0 + idx % ncfg):
             assert_within_bound(run_single(img, flt, variant), acc, mag,
                                 f"single {(H, W, K, F)} variant {variant}")
+
+
+# ---- the few-filters kernel of the single-channel case ----------------------------------
+
+FEW = dconv.VARIANT_FEW_FILTERS
+# (H, W, K, F): one and several filter groups, ragged tiles in both directions, row ends at
+# every alignment, filter sides 1..7, a filter as large as the image
+FEW_SHAPES = [(40, 300, 1, 3), (33, 31, 5, 5), (20, 20, 1, 1), (70, 600, 9, 7), (17, 17, 2, 2),
+              (65, 515, 3, 4), (50, 263, 8, 6), (7, 7, 3, 7), (130, 258, 2, 5), (36, 1030, 4, 3)]
+
+
+@pytest.mark.parametrize("shape", FEW_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_single_channel_few_filters_kernel(shape):
+    H, W, K, F = shape
+    x, f = wl.random_case(700 + F, 1, 1, H, W, K, F)
+    img, flt = x[0, 0], f[:, 0]
+    acc, mag, _ = oracle.single_channel(img, flt)
+    assert_within_bound(run_single(img, flt, FEW), acc, mag, f"few-filters {shape}")
+    xi, fi = wl.integer_case(70 + F, 1, 1, H, W, K, F)
+    _, _, o32, _ = oracle.general(xi, fi, want32=True)
+    np.testing.assert_array_equal(run_single(xi[0, 0], fi[:, 0], FEW), o32[0])
+
+
+def test_few_filters_kernel_guard_bands_and_limits():
+    Hs, Ws, Ks, Fs = 45, 300, 3, 5
+    xs, fs = wl.random_case(8, 1, 1, Hs, Ws, Ks, Fs)
+    n_out = Ks * (Hs - Fs + 1) * (Ws - Fs + 1)
+    pad = 4096
+    buf = torch.full((n_out + 2 * pad,), float("nan"), device="cuda")
+    out = buf[pad:pad + n_out].view(Ks, Hs - Fs + 1, Ws - Fs + 1)
+    dconv.dconv_single_channel(dev(xs[0, 0]), dev(fs[:, 0]), out=out, variant=FEW)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:pad]).all() and torch.isnan(buf[pad + n_out:]).all()
+    assert torch.isfinite(out).all()
+    # filter sides above 7 and the general case are not its business
+    x, f = wl.random_case(9, 1, 1, 20, 20, 2, 9)
+    with pytest.raises(dconv.DconvError) as e:
+        run_single(x[0, 0], f[:, 0], FEW)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
+    with pytest.raises(dconv.DconvError) as e:
+        run_general(x, f, FEW)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
