@@ -75,6 +75,9 @@ int dconv_general_v(const float* in, int N, int C, int H, int W, const float* fi
     Shape s;
     const int rc = validate(in, filt, out, N, C, H, W, K, F, &s);
     if (rc != DCONV_OK) return rc;
+    // one image with one channel is the special case, layouts included
+    if (N == 1 && C == 1 && variant == DCONV_VARIANT_AUTO)
+        return dispatch(true, in, filt, out, s, variant, stream);
     return dispatch(false, in, filt, out, s, variant, stream);
 }
 

@@ -71,11 +71,11 @@ void release_general_workspaces()
 namespace {
 
 // Tile configurations offered through the ABI: tile shape x schedule.
-//   shape    0: 128 filters x 128 pixels, 1: 64 filters x 128 pixels, 2: 64 filters x 256 pixels
+//   shape    0: 128 filters x 128 pixels, 1: 64 x 128, 2: 64 x 256, 3: 32 x 256
 //   schedule 0: by shape, 1: whole tiles only, 2: tiles cut over channels wherever the even
 //            split of the work falls, 3: the same on a grid of 7 workgroups (so that small
 //            test shapes exercise every way a tile can be shared)
-constexpr int kShapes = 3, kSchedules = 4;
+constexpr int kShapes = 4, kSchedules = 4;
 
 int launch_any(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                int tile_cfg, const GenSched& sched, bool dry)
@@ -101,10 +101,12 @@ int launch_any(const float* in, const float* filt, float* out, const Shape& s, h
 // wave).  Up to 64 filters: the 64 x 256 tile (every wave holds all filters: the same four
 // matrix-core instructions per operand pair) when the work divides finely enough over the chip
 // with it; otherwise the 64 x 128 tile, which is light enough on registers for three
-// workgroups per CU and so covers small problems in one round.
+// workgroups per CU and so covers small problems in one round.  Up to 32 filters: the 32 x 256
+// tile, so that half of every filter block is not padding.
 int shape_for(const Shape& s)
 {
     if (s.K > 64) return 0;
+    if (s.K <= 32) return 3;
     // enough wide tiles for several per workgroup, or enough chunks per tile that sharing
     // tiles between workgroups balances the chip without costing much
     const int64_t wide_tiles = ((int64_t)s.N * s.Ho * s.Wo + 255) / 256;

@@ -17,7 +17,7 @@ namespace {
 
 constexpr int F = DCONV_F;
 constexpr int kChunkBig = F == 1 ? 16 : F == 2 ? 8 : F == 3 ? 4 : F == 4 ? 2 : 1;
-constexpr int kChunkSmall = F == 1 ? 4 : F == 2 ? 2 : 1;
+constexpr int kChunkSmall = F == 1 ? 4 : F == 2 ? 2 : F == 3 ? 3 : 1;   // 3: RGB inputs
 // filter rows per chunk: whole filters up to 5x5, groups of rows above (see GenGeom)
 constexpr int kRowGroup = F <= 5 ? F : F == 6 ? 3 : F == 9 ? 3 : F == 10 ? 5 : 4;
 // image words a thread stages per chunk: small filters have small halos
@@ -42,12 +42,14 @@ int launch_tile(const float* in, const float* filt, float* out, const Shape& s, 
     // pixels, four waves side by side, each with all 64 filters of 32 pixels (light on
     // registers: three workgroups per CU); tile 2: 64 filters x 256 pixels, four waves side by
     // side with 2 x 2 blocks each (four matrix-core instructions per pair of operand loads,
-    // like tile 0)
+    // like tile 0); tile 3: 32 filters x 256 pixels, four waves side by side with 1 x 2 blocks
     constexpr int RG = CSH == 1 ? kRowGroup : F;
     if (tile_cfg == 0)
         return gen_try_launch<F, CSH, RG, 2, 2, 2, 2, kImaxF, VEC, nbuf_for<CSH, 128>(), 2>(in, filt, out, s, st, sched, dry);
     if (tile_cfg == 2)
         return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 2>(in, filt, out, s, st, sched, dry);
+    if (tile_cfg == 3)
+        return gen_try_launch<F, CSH, RG, 1, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 32>(), 3>(in, filt, out, s, st, sched, dry);
     return gen_try_launch<F, CSH, RG, 2, 1, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 3>(in, filt, out, s, st, sched, dry);
 }
 

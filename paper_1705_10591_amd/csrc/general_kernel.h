@@ -695,6 +695,9 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     const int64_t U = split ? tiles * nch : tiles;
     G = sched.force_G > 0 ? sched.force_G : chip;
     if (G > U) G = (int)U;
+    // The workgroup that completes a shared tile adds all its parts by itself: keep the parts
+    // per tile few (at most about eight) when there are far fewer tiles than workgroups.
+    if (split && sched.force_G <= 0 && sched.mode == 0 && (int64_t)G > 8 * tiles) G = (int)(8 * tiles);
 
     GenWorkspace ws{nullptr, nullptr};
     if (split) {
