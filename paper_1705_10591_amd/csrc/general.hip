@@ -71,11 +71,11 @@ void release_general_workspaces()
 namespace {
 
 // Tile configurations offered through the ABI: tile shape x schedule.
-//   shape    0: 128 filters x 128 pixels, 1: 64 x 128, 2: 64 x 256, 3: 32 x 256
+//   shape    0: 64 filters x 128 pixels, 1: 64 x 256, 2: 32 x 256
 //   schedule 0: by shape, 1: whole tiles only, 2: tiles cut over channels wherever the even
 //            split of the work falls, 3: the same on a grid of 7 workgroups (so that small
 //            test shapes exercise every way a tile can be shared)
-constexpr int kShapes = 4, kSchedules = 4;
+constexpr int kShapes = 3, kSchedules = 4;
 
 int launch_any(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                int tile_cfg, const GenSched& sched, bool dry)
@@ -96,22 +96,22 @@ int launch_any(const float* in, const float* filt, float* out, const Shape& s, h
     }
 }
 
-// Tile shape by problem shape (measured on the chip, see the tuning notes of the build):
-// more than 64 filters: the 128 x 128 tile (each image operand feeds two filter blocks of a
-// wave).  Up to 64 filters: the 64 x 256 tile (every wave holds all filters: the same four
-// matrix-core instructions per operand pair) when the work divides finely enough over the chip
-// with it; otherwise the 64 x 128 tile, which is light enough on registers for three
-// workgroups per CU and so covers small problems in one round.  Up to 32 filters: the 32 x 256
-// tile, so that half of every filter block is not padding.
+// Tile shape by problem shape, from the tile search (paper_1705_10591_amd.tune) over twenty
+// layer shapes.  Up to 32 filters: the 32 x 256 tile, so that half of every filter block is not
+// padding.  Up to 64 filters: 64 x 256 when the work divides finely enough over the chip with it
+// (many tiles, or so many chunks per tile that sharing tiles is cheap), else 32 x 256, which
+// doubles the number of tiles.  More filters: 64 x 256 on large maps, 64 x 128 (three workgroups
+// per CU) on small ones.
 int shape_for(const Shape& s)
 {
-    if (s.K > 64) return 0;
-    if (s.K <= 32) return 3;
-    // enough wide tiles for several per workgroup, or enough chunks per tile that sharing
-    // tiles between workgroups balances the chip without costing much
-    const int64_t wide_tiles = ((int64_t)s.N * s.Ho * s.Wo + 255) / 256;
-    const int64_t chunks = ((int64_t)s.C * s.F * s.F + 35) / 36;
-    return (wide_tiles >= 1024 || wide_tiles * chunks >= 12000) ? 2 : 1;
+    const int64_t px = (int64_t)s.N * s.Ho * s.Wo;
+    if (s.K <= 32) return 2;
+    if (s.K <= 64) {
+        const int64_t wide_tiles = (px + 255) / 256;
+        const int64_t chunks = ((int64_t)s.C * s.F * s.F + 35) / 36;
+        return (wide_tiles >= 1024 || wide_tiles * chunks >= 12000) ? 1 : 2;
+    }
+    return px >= 16384 ? 1 : 0;
 }
 
 }  // namespace
@@ -122,7 +122,7 @@ bool general_tiled_supports(const Shape& s)
 {
     const GenSched sched{0, 0};
     return launch_any(nullptr, nullptr, nullptr, s, nullptr, shape_for(s), sched, true) == DCONV_OK ||
-           launch_any(nullptr, nullptr, nullptr, s, nullptr, 1, sched, true) == DCONV_OK;
+           launch_any(nullptr, nullptr, nullptr, s, nullptr, 0, sched, true) == DCONV_OK;
 }
 
 int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
@@ -133,7 +133,7 @@ int launch_general_tiled(const float* in, const float* filt, float* out, const S
         const GenSched sched{0, 0};
         int rc = launch_any(in, filt, out, s, st, shape_for(s), sched, false);
         if (rc == DCONV_UNSUPPORTED)
-            rc = launch_any(in, filt, out, s, st, 1, sched, false);
+            rc = launch_any(in, filt, out, s, st, 0, sched, false);
         return rc;
     }
     const int schedule = cfg / kShapes;

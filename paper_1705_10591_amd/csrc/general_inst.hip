@@ -2,7 +2,7 @@
 // compiler command line), so that the filter sides compile in parallel.
 //
 // Channel chunk per filter side: 16-36 reduction indices per chunk for small filters (short
-// enough that three chunks of a 128-filter tile fit in LDS with two workgroups per CU), one
+// enough that three chunks of a tile fit in LDS with two or three workgroups per CU), one
 // channel per chunk from 5x5 on.  The chunk has to divide the channel count; smaller chunks
 // (down to one channel) are there for the counts it does not.
 #include "general_kernel.h"
@@ -38,17 +38,16 @@ template <int CSH, bool VEC>
 int launch_tile(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                 int tile_cfg, const GenSched& sched, bool dry)
 {
-    // tile 0: 128 filters x 128 pixels, 2 x 2 waves of 2 x 2 blocks; tile 1: 64 filters x 128
-    // pixels, four waves side by side, each with all 64 filters of 32 pixels (light on
-    // registers: three workgroups per CU); tile 2: 64 filters x 256 pixels, four waves side by
-    // side with 2 x 2 blocks each (four matrix-core instructions per pair of operand loads,
-    // like tile 0); tile 3: 32 filters x 256 pixels, four waves side by side with 1 x 2 blocks
+    // Four waves side by side in every tile, each with all the filters of its pixels.
+    // tile 0: 64 filters x 128 pixels, 2 x 1 blocks per wave (light on registers: three
+    // workgroups per CU); tile 1: 64 filters x 256 pixels, 2 x 2 blocks per wave (four
+    // matrix-core instructions per pair of operand loads); tile 2: 32 filters x 256 pixels,
+    // 1 x 2 blocks per wave.  (A 128 x 128 tile of 2 x 2 waves was never the fastest of the
+    // four on any of twenty layer shapes and is no longer compiled.)
     constexpr int RG = CSH == 1 ? kRowGroup : F;
-    if (tile_cfg == 0)
-        return gen_try_launch<F, CSH, RG, 2, 2, 2, 2, kImaxF, VEC, nbuf_for<CSH, 128>(), 2>(in, filt, out, s, st, sched, dry);
-    if (tile_cfg == 2)
+    if (tile_cfg == 1)
         return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 2>(in, filt, out, s, st, sched, dry);
-    if (tile_cfg == 3)
+    if (tile_cfg == 2)
         return gen_try_launch<F, CSH, RG, 1, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 32>(), 3>(in, filt, out, s, st, sched, dry);
     return gen_try_launch<F, CSH, RG, 2, 1, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 3>(in, filt, out, s, st, sched, dry);
 }

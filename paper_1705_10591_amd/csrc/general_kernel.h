@@ -689,8 +689,13 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     if (sched.mode == 1) split = 0;
     else if (sched.mode == 2) split = 1;
     else {
+        // ... when a last round would leave much of the chip idle and a tile is long enough
+        // (about 60 us with the workgroups of a CU sharing its matrix cores) for the saving to
+        // outweigh the cost of meeting in the workspace (measured: some 25 us per launch)
         const int64_t rounds = (tiles + chip - 1) / chip;
-        split = (nch >= 2 && tiles < 8LL * chip && (double)tiles < 0.93 * (double)(rounds * chip)) ? 1 : 0;
+        const double tile_us = (double)nch * Gm::S * (MW * NW) * 64.0 * OCC / 2400.0;
+        split = (nch >= 2 && tile_us >= 60.0 && tiles < 8LL * chip &&
+                 (double)tiles < 0.93 * (double)(rounds * chip)) ? 1 : 0;
     }
     const int64_t U = split ? tiles * nch : tiles;
     G = sched.force_G > 0 ? sched.force_G : chip;

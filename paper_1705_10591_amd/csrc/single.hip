@@ -385,10 +385,18 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         auto items = [&](int tw, int tr) {
             return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
         };
-        if (items(512, 4) < 1024) cfg = 3;
-        else if (F >= 8) cfg = 2;
-        else if (F >= 5 && s.Wo >= 2048) cfg = 1;
-        else cfg = 0;
+        // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
+        if (F <= 4) {
+            cfg = items(512, 4) < 1280 ? 3 : 0;
+        } else if (items(512, 4) < 384) {
+            cfg = 3;
+        } else if (F >= 8) {
+            cfg = items(512, 8) >= 512 ? 2 : 0;
+        } else if (s.Wo >= 3072) {
+            cfg = 1;
+        } else {
+            cfg = items(512, 8) >= 256 ? 2 : 0;
+        }
     }
     switch (cfg) {
     case 1: return launch_cfg<F, 1024, 4, 4, 2, false, true>(img, filt, out, s, st);
