@@ -9,6 +9,7 @@ that the rules can be checked or re-derived on another chip.
 
     python -m paper_1705_10591_amd.tune single H W K F
     python -m paper_1705_10591_amd.tune general N C H W K F
+    python -m paper_1705_10591_amd.tune table single|general     (the shapes the rules were set on)
 """
 from __future__ import annotations
 
@@ -67,7 +68,43 @@ def tune(kind: str, dims, steps: int = 20):
     return rows
 
 
+# The shapes the library's rules were derived from: (H, W, K, F) and (N, C, H, W, K, F).
+TABLE_SINGLE = [(4096, 4096, 64, 5), (4096, 4096, 64, 3), (4096, 4096, 64, 7), (4096, 4096, 64, 11),
+                (2048, 2048, 64, 5), (2048, 2048, 64, 9), (1024, 1024, 64, 5), (1024, 1024, 64, 9),
+                (1024, 1024, 64, 3), (512, 512, 64, 3), (1080, 1920, 32, 3), (1080, 1920, 64, 7),
+                (256, 256, 16, 3), (1536, 1536, 128, 3), (3000, 3000, 64, 5), (2048, 2048, 256, 5),
+                (720, 1280, 96, 5)]
+TABLE_GENERAL = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (64, 3, 224, 224, 64, 11),
+                 (32, 128, 56, 56, 128, 3), (32, 256, 14, 14, 256, 3), (16, 64, 112, 112, 128, 3),
+                 (64, 32, 32, 32, 32, 3), (32, 96, 27, 27, 256, 5), (16, 64, 224, 224, 64, 3),
+                 (64, 128, 28, 28, 128, 3), (16, 512, 14, 14, 512, 3), (32, 192, 13, 13, 384, 3),
+                 (8, 3, 224, 224, 32, 3), (32, 16, 64, 64, 32, 5), (128, 64, 32, 32, 128, 3),
+                 (32, 64, 56, 56, 64, 5), (32, 64, 56, 56, 64, 7), (32, 64, 56, 56, 256, 3),
+                 (8, 128, 112, 112, 128, 3), (64, 512, 7, 7, 512, 3)]
+
+
+def table(kind: str) -> None:
+    """One line per shape: the library's choice and every configuration, in microseconds."""
+    shapes = TABLE_SINGLE if kind == "single" else TABLE_GENERAL
+    n = dconv.tile_config_count(kind == "single")
+    print(f"# {kind}: microseconds per launch; columns: library choice, configurations 0..{n - 1} "
+          "(n/a = cannot hold the shape), fastest configuration, library / fastest")
+    for sh in shapes:
+        rows = tune(kind, sh)
+        lib, cfgs = rows[0][1], [ms for _, ms in rows[1:]]
+        best = min(ms for ms in cfgs if ms is not None)
+        cells = " ".join("    n/a" if ms is None else f"{ms * 1e3:7.1f}" for ms in cfgs)
+        print(f"{'x'.join(map(str, sh)):24s} {lib * 1e3:7.1f} | {cells} | {cfgs.index(best):2d} {lib / best:5.2f}",
+              flush=True)
+
+
 def main(argv):
+    if len(argv) == 2 and argv[0] == "table" and argv[1] in ("single", "general"):
+        if not torch.cuda.is_available():
+            print("tune needs a GPU", file=sys.stderr)
+            return 2
+        table(argv[1])
+        return 0
     if len(argv) < 2 or argv[0] not in ("single", "general") or \
             len(argv) - 1 != (4 if argv[0] == "single" else 6):
         print(__doc__)

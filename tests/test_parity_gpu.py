@@ -438,3 +438,33 @@ def test_few_filters_kernel_guard_bands_and_limits():
     with pytest.raises(dconv.DconvError) as e:
         run_general(x, f, FEW)
     assert e.value.status == dconv.STATUS_UNSUPPORTED
+
+
+def test_shared_tiles_on_two_streams_at_once_and_workspace_release():
+    """Each stream has its own workspace: launches that overlap in time must not mix parts."""
+    shapes = [(3, 16, 28, 28, 130, 3), (2, 37, 14, 14, 70, 3)]
+    split = dconv.VARIANT_TILED_CFG0 + 2 * 3 + 1      # shared tiles, 64 x 256 tile
+    cases = []
+    for i, (N, C, H, W, K, F) in enumerate(shapes):
+        x, f = wl.random_case(800 + i, N, C, H, W, K, F)
+        acc, mag, _ = oracle.general(x, f)
+        cases.append((dev(x), dev(f), acc, mag))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[], []]
+    for rep in range(6):
+        for si, s in enumerate(streams):
+            with torch.cuda.stream(s):
+                xd, fd, _, _ = cases[si]
+                outs[si].append(dconv.dconv_general(xd, fd, variant=split))
+    torch.cuda.synchronize()
+    for si in range(2):
+        _, _, acc, mag = cases[si]
+        for o in outs[si]:
+            assert_within_bound(o.cpu().numpy(), acc, mag, f"stream {si}")
+            assert torch.equal(o, outs[si][0])
+    dconv.release_workspace()
+    xd, fd, acc, mag = cases[0]
+    again = dconv.dconv_general(xd, fd, variant=split)
+    torch.cuda.synchronize()
+    assert torch.equal(again, outs[0][0])
