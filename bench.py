@@ -118,6 +118,55 @@ def cpu_baseline(w, x, f):
             "sample": f"{rows_out} of {w.Ho} output rows of the same image, all {w.K} filters"}
 
 
+def oracle_sample(w, x, f, threads=0, budget_gflop=40.0):
+    """Time the oracle on a bounded part of a configuration (a band of rows of the single image,
+    or the first images of the batch), on `threads` host threads (0 = all)."""
+    import numpy as np
+    import oracle
+    if w.kind == "single":
+        per_row = 2.0 * w.K * w.Wo * w.F * w.F
+        rows = int(max(1, min(w.Ho, budget_gflop * 1e9 // per_row)))
+        band = np.ascontiguousarray(x[:rows + w.F - 1])
+        t0 = time.perf_counter()
+        _, used = oracle.single_channel(band, f, threads=threads, only32=True)
+        dt = time.perf_counter() - t0
+        flops, what = per_row * rows, f"{rows} of {w.Ho} output rows"
+    else:
+        per_img = w.flops / w.N
+        n = int(max(1, min(w.N, budget_gflop * 1e9 // per_img)))
+        t0 = time.perf_counter()
+        _, _, used = oracle.general(np.ascontiguousarray(x[:n]), f, threads=threads)
+        dt = time.perf_counter() - t0
+        flops, what = per_img * n, f"{n} of {w.N} images"
+    return {"gflops": round(flops / dt / 1e9, 2), "threads": int(used), "seconds": round(dt, 3),
+            "sample": what}
+
+
+def rotating_buffers_ms(w, steps):
+    """Per-launch time of a small configuration with every launch on its own set of buffers
+    (more than 512 MB in all), so that neither inputs nor outputs are served from a cache."""
+    import torch
+    import workloads as wl
+    import paper_1705_10591_amd as dconv
+    x, f = wl.make_inputs(w)
+    per_set = 4 * (x.size + f.size + w.out_elems)
+    nsets = int(600e6 // per_set) + 1
+    xs = [torch.from_numpy(x).cuda() for _ in range(nsets)]
+    fs = [torch.from_numpy(f).cuda() for _ in range(nsets)]
+    outs = [torch.empty(w.out_shape(), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    state = {"i": 0}
+
+    def run():
+        i = state["i"]
+        state["i"] = (i + 1) % nsets
+        if w.kind == "single":
+            dconv.dconv_single_channel(xs[i], fs[i], out=outs[i])
+        else:
+            dconv.dconv_general(xs[i], fs[i], out=outs[i])
+    ms, _ = time_launches(run, max(steps, 2 * nsets), nsets, warm_ms=60.0)
+    return ms, nsets
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -177,11 +226,24 @@ def main():
         order = ["S1", "S2_F3", "S2_F7", "S2_F9", "S2_F11", "G1", "G2", "G3"]
         for name in order:
             w = allw[name]
-            r, _ = make_runner(w)
+            r, (xw, fw) = make_runner(w)
             m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
-            per.append(config_entry(w, m))
+            e = config_entry(w, m)
             del r
             torch.cuda.empty_cache()
+            if name == "S1":
+                # 4 MB of output fit the caches: also time it with every launch on fresh buffers
+                e["ms_rotating_buffers"], e["rotating_sets"] = (lambda t: (round(t[0], 5), t[1]))(
+                    rotating_buffers_ms(w, max(5, min(args.steps, 50))))
+            if not args.no_cpu_baseline:
+                # the oracle on a bounded part of the same configuration, all host threads
+                # (one thread too for the two smallest), and what the whole would take over the GPU
+                o = oracle_sample(w, xw, fw)
+                e["oracle"] = o
+                e["oracle_over_gpu_time"] = round((w.flops / (o["gflops"] * 1e9)) / (m * 1e-3), 1)
+                if name in ("S1", "G2"):
+                    e["oracle_one_thread"] = oracle_sample(w, xw, fw, threads=1, budget_gflop=2.0)
+            per.append(e)
         result["per_config"] = per
         g = {e["name"]: e for e in per}
         result["roofline_general"] = {
