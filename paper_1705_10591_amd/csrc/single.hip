@@ -61,9 +61,8 @@ struct SingleParams {
 enum : int { kPlain = 0, kTail = 1, kEdge = 2 };
 
 // TW: nominal tile width in pixels, TR: tile rows, NBW: 32-pixel blocks written per pass,
-// WPE: waves per SIMD the register budget is cut for, PIPE: overlap the write-back of a pass
-// with the matrix-core steps of the next one inside each wave, NT: nontemporal stores.
-template <int F, int TW, int TR, int NBW, int WPE, bool PIPE, bool NT>
+// WPE: waves per SIMD the register budget is cut for.
+template <int F, int TW, int TR, int NBW, int WPE>
 __global__ void __launch_bounds__(kThreads, WPE)
 single_tiled_kernel(SingleParams p)
 {
@@ -164,88 +163,88 @@ single_tiled_kernel(SingleParams p)
     const unsigned gl = (unsigned)(rrow * (int)plane + 4 * c4);
     const int tr_lane = (kb + rrow) * pm;
 
-    // ---- the write-back of one pass, cut into UNITS small pieces ---------------------------
-    // Per group g of eight filters: 4 pieces that park one accumulator register of every block
-    // in the strip, ITS pieces that read one 16 B column back, ITS pieces that store it.
-    constexpr int UPG = 4 + 2 * ITS;
-    constexpr int UNITS = 4 * UPG;
-    struct Pending {           // the pass whose results still sit in registers
-        int tw, tr, trn;       // per-lane shift seeds of its output row and of the next row
+    // ---- the write-back of one pass ---------------------------------------------------------
+    // Per group g of eight filters: park one accumulator register of every block in the strip
+    // (4 pieces), read 16 B columns back (ITS pieces), store them (ITS pieces).  The stores are
+    // nontemporal: the output is written once and not read again.
+    struct PassOut {
+        int tw, tr, trn;       // per-lane shift seeds of the pass's output row and of the next row
         float* orow;           // out[kb][y][X], wave-uniform
         int X;                 // first output column of the pass
         int kind;              // kPlain, kTail or kEdge
         bool head;             // kEdge only: also write the pixels before the first boundary
     };
-    v4f held[ITS];
     auto store4 = [&](float* dst, const v4f& v) {
-        if (NT) __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(dst));
-        else *reinterpret_cast<v4f*>(dst) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(dst));
     };
-    auto wb_unit = [&](int u, const v16f (&A)[NB], const Pending& pd) {
-        const int g = u / UPG, j = u % UPG;
-        if (j < 4) {
-            const int q = 4 * g + j;
-            const int sk = (-(pd.tw + (8 * g + j) * pm)) & 31;
-            // the strip word as one opaque register: the stores then pair up with offsets of
-            // 0..4 blocks and need no further address arithmetic on the vector ALU
-            int word = (int)(stg - sh) + (wl - sk) + j * SW;
-            asm volatile("" : "+v"(word));
+    auto write_back = [&](const v16f (&A)[NB], const PassOut& pd) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) sh[word + nb * 32] = A[nb][q];
-        } else if (j < 4 + ITS) {
-            const int it = j - 4;
-            held[it] = *reinterpret_cast<const v4f*>(stg + rdofs + it * RPI * SW);
-        } else {
-            const int it = j - 4 - ITS;
-            const int kofs = (8 * g + it * RPI) * pm;
-            const int sk = (-(pd.tr + kofs)) & 31;
-            float* ub = pd.orow + (8 * g + it * RPI) * plane;     // out[kb + 8g + it*RPI][y][X]
-            float* dst = ub + (gl + (unsigned)sk);                // this lane's four pixels
-            const int px = pd.X + sk + 4 * c4;
-            if (pd.kind == kPlain) {
-                store4(dst, held[it]);
-            } else if (pd.kind == kTail) {
-                // The window runs over the end of the row into the head of the next one; it
-                // stops at the first line boundary of the next row, where that row's own
-                // passes begin.  Both limits are multiples of 16 B away from px.
-                const int skn = (-(pd.trn + kofs)) & 31;
-                if (px < p.Wo + skn) store4(dst, held[it]);
-            } else if (kb + 8 * g + it * RPI + rrow < p.K) {
-                // Same window, clipped to the row; whole 16 B pieces wherever they fit.
-                if (px + 3 < p.Wo) {
+        for (int g = 0; g < 4; ++g) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int q = 4 * g + j;
+                const int sk = (-(pd.tw + (8 * g + j) * pm)) & 31;
+                // the strip word as one opaque register: the stores then pair up with offsets of
+                // 0..4 blocks and need no further address arithmetic on the vector ALU
+                int word = (int)(stg - sh) + (wl - sk) + j * SW;
+                asm volatile("" : "+v"(word));
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) sh[word + nb * 32] = A[nb][q];
+            }
+            v4f held[ITS];
+#pragma unroll
+            for (int it = 0; it < ITS; ++it)
+                held[it] = *reinterpret_cast<const v4f*>(stg + rdofs + it * RPI * SW);
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {
+                const int kofs = (8 * g + it * RPI) * pm;
+                const int sk = (-(pd.tr + kofs)) & 31;
+                float* ub = pd.orow + (8 * g + it * RPI) * plane;     // out[kb + 8g + it*RPI][y][X]
+                float* dst = ub + (gl + (unsigned)sk);                // this lane's four pixels
+                const int px = pd.X + sk + 4 * c4;
+                if (pd.kind == kPlain) {
                     store4(dst, held[it]);
-                } else {
+                } else if (pd.kind == kTail) {
+                    // The window runs over the end of the row into the head of the next one; it
+                    // stops at the first line boundary of the next row, where that row's own
+                    // passes begin.  Both limits are multiples of 16 B away from px.
+                    const int skn = (-(pd.trn + kofs)) & 31;
+                    if (px < p.Wo + skn) store4(dst, held[it]);
+                } else if (kb + 8 * g + it * RPI + rrow < p.K) {
+                    // Same window, clipped to the row; whole 16 B pieces wherever they fit.
+                    if (px + 3 < p.Wo) {
+                        store4(dst, held[it]);
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (px + e < p.Wo) dst[e] = held[it][e];
-                }
-                // The sk pixels before the first line boundary of the row.
-                if (pd.head && c4 < 8) {
-                    const float* row = stg + (it * RPI + rrow) * SW + 32 - sk;
-                    float* hd = ub + rrow * plane - pd.X;         // out[k][y][0]
+                        for (int e = 0; e < 4; ++e)
+                            if (px + e < p.Wo) dst[e] = held[it][e];
+                    }
+                    // The sk pixels before the first line boundary of the row.
+                    if (pd.head && c4 < 8) {
+                        const float* row = stg + (it * RPI + rrow) * SW + 32 - sk;
+                        float* hd = ub + rrow * plane - pd.X;         // out[k][y][0]
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int hx = 4 * c4 + e;
-                        if (hx < sk && hx < p.Wo) hd[hx] = row[hx];
+                        for (int e = 0; e < 4; ++e) {
+                            const int hx = 4 * c4 + e;
+                            if (hx < sk && hx < p.Wo) hd[hx] = row[hx];
+                        }
                     }
                 }
             }
         }
     };
 
-    // ---- one pass: the matrix-core steps for AN, with the write-back of the pending pass
-    // (accumulators AP) slotted between them so that LDS, stores and MFMA overlap in one wave.
+    // ---- the matrix-core steps of one pass ---------------------------------------------------
     // Block 0 of a pass covers the same 32 pixels as block NB-1 of the pass before it on the
     // same row; when CARRY is set those sums are taken over instead of being formed again.
-    auto compute = [&](auto carry_tag, v16f (&AN)[NB], const v16f (&AP)[NB], bool have_pending,
-                       const Pending& pd, const int (&base)[NB]) {
+    auto compute = [&](auto carry_tag, v16f (&A)[NB], const int (&base)[NB]) {
         constexpr bool CARRY = decltype(carry_tag)::value;
         constexpr int NB0 = CARRY ? 1 : 0;
-        if (CARRY) AN[0] = PIPE ? AP[NB - 1] : AN[NB - 1];
+        if (CARRY) A[0] = A[NB - 1];
 #pragma unroll
         for (int nb = NB0; nb < NB; ++nb)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) AN[nb][q] = 0.f;
+            for (int q = 0; q < 16; ++q) A[nb][q] = 0.f;
         // pixel operands of step s; those of step s+1 are requested before the matrix-core
         // instructions of step s are issued, so the wave does not wait for LDS with the
         // matrix pipe idle
@@ -268,34 +267,22 @@ single_tiled_kernel(SingleParams p)
         for (int s = 0; s < S; ++s) {
             float (&b)[NB] = (s & 1) ? b1 : b0;
             if (s + 1 < S) load_b(s + 1, (s & 1) ? b0 : b1);
-            if (have_pending) {
-#pragma unroll
-                for (int u = (s * UNITS) / S; u < ((s + 1) * UNITS) / S; ++u) wb_unit(u, AP, pd);
-            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nb = NB0; nb < NB; ++nb) AN[nb] = mfma_32x32x2(a[s], b[nb], AN[nb]);
+            for (int nb = NB0; nb < NB; ++nb) A[nb] = mfma_32x32x2(a[s], b[nb], A[nb]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    auto flush = [&](const v16f (&AP)[NB], const Pending& pd) {
-#pragma unroll
-        for (int u = 0; u < UNITS; ++u) wb_unit(u, AP, pd);
-    };
 
-    // ---- the passes of this wave, two per trip so that the accumulator sets alternate -------
+    // ---- the passes of this wave: along each of its rows, then on to its next row ------------
     const int ch_mine = min(CHUNKS, (p.Wo - x0 + PASS - 1) / PASS);      // passes per row here
     const int rows_mine = rows_here > row_start ? (rows_here - row_start + row_step - 1) / row_step : 0;
     const int npass = rows_mine * ch_mine;
 
-    v16f acc0[NB], acc1[NB];
-    Pending pd{0, 0, 0, nullptr, 0, kPlain, false};
-    bool pend0 = false, pend1 = false;     // acc0 / acc1 hold a pass not yet written
+    v16f acc[NB];
     int ri = 0, ci = 0;                    // row and chunk counters of the next pass
-
-    // one pass: fills AN; meanwhile writes back AP if it is pending; then leaves AN pending
-    // (or writes it at once when not pipelining)
-    auto one_pass = [&](v16f (&AN)[NB], const v16f (&AP)[NB], bool& pendN, bool& pendP) {
+#pragma unroll 1
+    for (int q = 0; q < npass; ++q) {
         const int r = row_start + ri * row_step;
         const int ch = ci;
         if (++ci == ch_mine) { ci = 0; ++ri; }
@@ -319,34 +306,17 @@ single_tiled_kernel(SingleParams p)
         if (!full_block || needs_head) kind = kEdge;
         else if (reaches_end) kind = (p.wrap && y < p.Ho - 1) ? kTail : kEdge;
         // every pass but the first of a row continues the previous pass of this wave
-        if (ch > 0) compute(std::true_type{}, AN, AP, pendP, pd, base);
-        else compute(std::false_type{}, AN, AP, pendP, pd, base);
-        pendP = false;
-        pd.tw = tw_lane + c0; pd.tr = tr_lane + c0; pd.trn = tr_lane + c0n;
-        pd.orow = p.out + kb * plane + rowoff + X;
-        pd.X = X;
-        pd.kind = kind;
-        pd.head = needs_head;
-        if (PIPE) pendN = true;
-        else flush(AN, pd);
-    };
-    if (PIPE) {
-#pragma unroll 1
-        for (int q = 0; q < npass; q += 2) {
-            one_pass(acc0, acc1, pend0, pend1);
-            if (q + 1 < npass) one_pass(acc1, acc0, pend1, pend0);
-        }
-    } else {
-#pragma unroll 1
-        for (int q = 0; q < npass; ++q) one_pass(acc0, acc0, pend0, pend1);
+        if (ch > 0) compute(std::true_type{}, acc, base);
+        else compute(std::false_type{}, acc, base);
+        const PassOut pd{tw_lane + c0, tr_lane + c0, tr_lane + c0n,
+                         p.out + kb * plane + rowoff + X, X, kind, needs_head};
+        write_back(acc, pd);
     }
-    if (pend0) flush(acc0, pd);
-    if (pend1) flush(acc1, pd);
 }
 
 namespace {
 
-template <int F, int TW, int TR, int NBW, int WPE, bool PIPE, bool NT>
+template <int F, int TW, int TR, int NBW, int WPE>
 int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
     SingleParams p;
@@ -363,7 +333,7 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups;
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
-    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE, PIPE, NT>),
+    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE>),
                        dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
@@ -399,10 +369,10 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         }
     }
     switch (cfg) {
-    case 1: return launch_cfg<F, 1024, 4, 4, 2, false, true>(img, filt, out, s, st);
-    case 2: return launch_cfg<F, 512, 8, 4, 3, false, true>(img, filt, out, s, st);
-    case 3: return launch_cfg<F, 256, 2, 4, 3, false, true>(img, filt, out, s, st);
-    default: return launch_cfg<F, 512, 4, 4, 3, false, true>(img, filt, out, s, st);
+    case 1: return launch_cfg<F, 1024, 4, 4, 2>(img, filt, out, s, st);
+    case 2: return launch_cfg<F, 512, 8, 4, 3>(img, filt, out, s, st);
+    case 3: return launch_cfg<F, 256, 2, 4, 3>(img, filt, out, s, st);
+    default: return launch_cfg<F, 512, 4, 4, 3>(img, filt, out, s, st);
     }
 }
 
