@@ -136,9 +136,9 @@ struct GenGeom {
     static constexpr int EPT0 = (T + TPF - 1) / TPF;
     static constexpr int EPT = VEC ? (EPT0 + 3) / 4 * 4 : EPT0;   // reduction indices per thread
     static constexpr int NFI = VEC ? EPT / 4 : EPT;  // filter loads per thread per chunk
-    // rows of the filter block in LDS: with 16-byte loads every thread's run is written whole
-    // (rows beyond TP are never read), so the write addresses need no test
-    static constexpr int TROWS = (VEC && TPF * EPT > TP) ? TPF * EPT : TP;
+    // rows of the filter block in LDS: every thread's run is written whole (rows beyond T are
+    // never read), so the write addresses need no test
+    static constexpr int TROWS = TPF * EPT > TP ? TPF * EPT : TP;
     static constexpr int NI = IMAX + NFI;            // staging items per thread per chunk
     static_assert(NBUF == 2 || (NBUF == 3 && SL >= 4), "three LDS slots need at least four steps");
     // steps that carry staging items (every chunk has them); with three slots the barrier sits
@@ -211,7 +211,6 @@ general_tiled_kernel(GenParams p)
     const int64_t in_bytes = (int64_t)p.N * p.C * HW * 4, filt_words = (int64_t)p.K * CFF;
     __amdgpu_buffer_rsrc_t irs = __builtin_amdgcn_make_buffer_rsrc((void*)p.in, 0, 0, kRsrcFlags);
     __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)p.filt, 0, 0, kRsrcFlags);
-    int tlim_f = T, tlim_c = T;                 // reduction indices really present in the chunk
     auto setup_fetch = [&](int tile) __attribute__((always_inline)) {
         const int strip = min(fdiv(tile, p.d_strip), p.nstrips - 1);
         const int rem = tile - strip * per_strip;
@@ -252,7 +251,6 @@ general_tiled_kernel(GenParams p)
     auto set_chunk = [&](int chunk) __attribute__((always_inline)) {
         const int cidx = chunk / NG, g = chunk - cidx * NG;
         const int c0 = cidx * CSH;
-        tlim_f = CSH * ((g == NG - 1 ? RGL : RG) * F);
         const int64_t ioff = (int64_t)c0 * HW * 4;
         const int64_t ibytes = ileft - ioff;
         irs = __builtin_amdgcn_make_buffer_rsrc((void*)(ibase + ioff), 0,
@@ -269,7 +267,9 @@ general_tiled_kernel(GenParams p)
 #pragma unroll
     for (int e = 0; e < 4; ++e) wrow[e] = we0 * LDK + wkl + e * LDK;
     // Staging item w < IMAX is an image word, item IMAX + q a filter load (one word, or four).
-    // A thread whose filter lies beyond K has offsets beyond the end of the filter bank.
+    // A thread whose filter lies beyond K has offsets beyond the end of the filter bank.  A
+    // run may reach past the chunk's reduction indices (into the next row group, channel or
+    // filter): those words land in rows of the filter block that no step reads.
     auto fetch_item = [&](int w) __attribute__((always_inline)) {
         if (w < IMAX) {
             ireg[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(irs, ig[w], 0, 0));
@@ -292,17 +292,10 @@ general_tiled_kernel(GenParams p)
         } else if (VEC) {
             const int q = w - IMAX;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int t = we0 + 4 * q + e;
-                if (TROWS >= TPF * EPT) slot[wrow[e] + 4 * q * LDK] = wreg[4 * q + e];
-                else slot[t < T ? t * LDK + wkl : trash_word] = wreg[4 * q + e];
-            }
+            for (int e = 0; e < 4; ++e) slot[wrow[e] + 4 * q * LDK] = wreg[4 * q + e];
         } else {
             const int q = w - IMAX;
-            const int t = we0 + q;
-            // only the chunk of a shorter last row group has reduction indices to blank out
-            const float v = (TL != T && t >= tlim_c) ? 0.f : wreg[q];
-            slot[t < T ? t * LDK + wkl : trash_word] = v;
+            slot[wrow[0] + q * LDK] = wreg[q];
         }
     };
 
@@ -370,9 +363,17 @@ general_tiled_kernel(GenParams p)
             if (TL != T && (TL & 1) && t1 == TL) addr = (shortg && h) ? zero_word : addr;
             b[nt] = slot[addr];
         }
+        // the second tap of a padded pair takes a zero weight as well as a zero pixel: whatever
+        // follows the chunk's last weight (another filter's, possibly not finite) stays out
+        const bool pad = t1 >= T;
+        const bool pad_short = TL != T && (TL & 1) && t1 == TL;
 #pragma unroll
-        for (int mt = 0; mt < MW; ++mt)
-            a[mt] = slot[wb[mt] + t0 * LDK];
+        for (int mt = 0; mt < MW; ++mt) {
+            int addr = wb[mt] + t0 * LDK;
+            if (pad) addr = h ? zero_word : addr;
+            if (pad_short) addr = (shortg && h) ? zero_word : addr;
+            a[mt] = slot[addr];
+        }
     };
 
     v16f acc[MW][NW];
@@ -458,18 +459,14 @@ general_tiled_kernel(GenParams p)
     };
 
     // ---- prologue: constant LDS words, first unit into slot 0, second unit into registers ------
-    for (int b = 0; b < NBUF; ++b) {
+    for (int b = 0; b < NBUF; ++b)
         if (tid == 0) lds[b * BUF + zero_word] = 0.f;
-        if (TP != T)                         // the padding reduction index carries zero weights
-            for (int k = tid; k < MT; k += kThreads) lds[b * BUF + T * LDK + k] = 0.f;
-    }
     int ftile = fdiv(u0, p.d_nch), fchunk = u0 - ftile * nch;   // the unit being requested
     const int ftile_first = ftile;
     setup_fetch(ftile);
     set_chunk(fchunk);
 #pragma unroll
     for (int w = 0; w < NI; ++w) fetch_item(w);
-    tlim_c = tlim_f;
 #pragma unroll
     for (int w = 0; w < NI; ++w) commit_item(w, lds);
     auto advance_fetch = [&]() __attribute__((always_inline)) {
@@ -506,7 +503,6 @@ general_tiled_kernel(GenParams p)
         const bool has1 = u + 1 < u1, has2 = u + 2 < u1;
         const bool tile_ends = chunk == nch - 1 || !has1;
         // the unit in the registers moves to LDS during this trip; the next one is requested
-        tlim_c = tlim_f;
         if (has2) advance_fetch();
         const bool shortg = is_short(chunk);         // this chunk ends after SL steps
         // keep the tap addresses from being expanded into one register each outside the loop
@@ -514,10 +510,8 @@ general_tiled_kernel(GenParams p)
         for (int nt = 0; nt < NW; ++nt) asm volatile("" : "+v"(bb[nt]));
 #pragma unroll
         for (int mt = 0; mt < MW; ++mt) asm volatile("" : "+v"(wb[mt]));
-        if (VEC) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(wrow[e]));
-        }
+        for (int e = 0; e < (VEC ? 4 : 1); ++e) asm volatile("" : "+v"(wrow[e]));
 #pragma unroll
         for (int s = 0; s < S; ++s) {
             if (s >= SL && shortg) continue;                 // uniform; compiled away when SL == S

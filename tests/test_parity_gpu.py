@@ -158,6 +158,47 @@ def test_general_integer_inputs_are_bit_exact(shape):
         np.testing.assert_array_equal(run_general(x, f, variant), o32)
 
 
+# odd reduction lengths per chunk (padding taps) with 5x5, 7x7, 9x9, 11x11 filters, three
+# channels of 3x3; a filter count that is not a multiple of the filter tile
+@pytest.mark.parametrize("shape", [(2, 2, 14, 15, 5, 5), (1, 3, 16, 16, 6, 3), (1, 2, 20, 21, 4, 11),
+                                   (1, 1, 16, 40, 3, 7), (1, 2, 12, 30, 3, 9), (1, 1, 9, 9, 2, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_general_non_finite_filter_stays_in_its_own_map(shape):
+    """IEEE propagation: a NaN / Inf weight reaches the outputs of its own filter only.  The
+    padding taps of the matrix-core steps sit next to other filters' weights in memory."""
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(77 + F, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    for bad in range(K):
+        fb = f.copy()
+        fb[bad] = np.nan
+        fb[bad, 0, 0, 0] = np.inf
+        for variant in (SIMPLE, TILED) + tuple(_tile_variants(False)):
+            got = run_general(x, fb, variant)
+            assert not np.isfinite(got[:, bad]).any(), f"{shape} variant {variant}: filter {bad} finite"
+            keep = [k for k in range(K) if k != bad]
+            assert_within_bound(got[:, keep], acc[:, keep], mag[:, keep],
+                                f"general {shape} variant {variant} with filter {bad} non-finite")
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 14, 15, 5, 5), (2, 3, 16, 16, 6, 3), (1, 2, 20, 21, 4, 11)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_general_non_finite_pixel_reaches_only_the_windows_that_hold_it(shape):
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(91 + F, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    for (n, c, y0, x0) in [(0, 0, 0, 0), (N - 1, C - 1, H - 1, W - 1), (0, C - 1, H // 2, W // 3)]:
+        xb = x.copy()
+        xb[n, c, y0, x0] = np.nan
+        hit = np.zeros(acc.shape, dtype=bool)      # outputs whose window holds the pixel
+        hit[n, :, max(0, y0 - F + 1):y0 + 1, max(0, x0 - F + 1):x0 + 1] = True
+        for variant in (SIMPLE, TILED) + tuple(_tile_variants(False)):
+            got = run_general(xb, f, variant)
+            assert np.isnan(got[hit]).all(), f"{shape} variant {variant}: NaN pixel lost"
+            clean = np.where(hit, acc.astype(np.float32), got)
+            assert_within_bound(clean, acc, mag, f"general {shape} variant {variant} NaN pixel {(n, c, y0, x0)}")
+
+
 @pytest.mark.parametrize("shape", [(60, 300, 40, 3), (40, 41, 64, 5), (30, 270, 7, 11)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_single_channel_integer_inputs_are_bit_exact(shape):
