@@ -20,23 +20,27 @@ constexpr int kChunkBig = F == 1 ? 16 : F == 2 ? 8 : F == 3 ? 4 : F == 4 ? 2 : 1
 constexpr int kChunkSmall = F == 1 ? 4 : F == 2 ? 2 : F == 3 ? 3 : 1;   // 3: RGB inputs
 // filter rows per chunk: whole filters up to 5x5, groups of rows above (see GenGeom)
 constexpr int kRowGroup = F <= 5 ? F : F == 6 ? 3 : F == 9 ? 3 : F == 10 ? 5 : 4;
-// image words a thread stages per chunk: small filters have small halos
-constexpr int kImaxF = (F >= 2 && F <= 4) ? 8 : 16;
+// image words a thread stages per chunk: eight cover a 256-pixel tile of the widest column
+// strips with its halo rows; 1x1 filters (sixteen channels per chunk) take sixteen, and the
+// larger filters have a second set of kernels with sixteen for shapes (tiny maps, where a
+// tile spans many images) whose image block does not fit in eight
+constexpr int kImaxF = F == 1 ? 16 : 8;
+constexpr bool kSecondImax = F >= 5;
 
 // Three LDS slots when three chunks with the largest image block fit twice on a CU (or at
 // least once, for chunks with enough steps); two otherwise.
-template <int CSH, int MT>
+template <int CSH, int MT, int IMAX>
 constexpr int nbuf_for()
 {
     constexpr int RG = CSH == 1 ? kRowGroup : F, NG = (F + RG - 1) / RG, RGL = F - (NG - 1) * RG;
     constexpr int T = CSH * RG * F, TP = T + (T & 1), S = (CSH * RGL * F + 1) / 2;
-    constexpr long slot = 4L * ((long)(TP + 16) * (MT + 1) + kImaxF * kThreads + 8);   // rows: see TROWS
+    constexpr long slot = 4L * ((long)(TP + 16) * (MT + 1) + IMAX * kThreads + 8);   // rows: see TROWS
     return (S >= 4 && 3 * slot <= kGenLdsLimit) ? 3 : 2;
 }
 
-template <int CSH, bool VEC>
-int launch_tile(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
-                int tile_cfg, const GenSched& sched, bool dry)
+template <int CSH, bool VEC, int IMAX>
+int launch_tile_imax(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
+                     int tile_cfg, const GenSched& sched, bool dry)
 {
     // Four waves side by side in every tile, each with all the filters of its pixels.
     // tile 0: 64 filters x 128 pixels, 2 x 1 blocks per wave (light on registers: three
@@ -46,10 +50,26 @@ int launch_tile(const float* in, const float* filt, float* out, const Shape& s, 
     // four on any of twenty layer shapes and is no longer compiled.)
     constexpr int RG = CSH == 1 ? kRowGroup : F;
     if (tile_cfg == 1)
-        return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 2>(in, filt, out, s, st, sched, dry);
+        return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, IMAX, VEC, nbuf_for<CSH, 64, IMAX>(), 2>(in, filt, out, s, st, sched, dry);
     if (tile_cfg == 2)
-        return gen_try_launch<F, CSH, RG, 1, 2, 1, 4, kImaxF, VEC, nbuf_for<CSH, 32>(), 3>(in, filt, out, s, st, sched, dry);
-    return gen_try_launch<F, CSH, RG, 2, 1, 1, 4, kImaxF, VEC, nbuf_for<CSH, 64>(), 3>(in, filt, out, s, st, sched, dry);
+        return gen_try_launch<F, CSH, RG, 1, 2, 1, 4, IMAX, VEC, nbuf_for<CSH, 32, IMAX>(), 3>(in, filt, out, s, st, sched, dry);
+    return gen_try_launch<F, CSH, RG, 2, 1, 1, 4, IMAX, VEC, nbuf_for<CSH, 64, IMAX>(), 3>(in, filt, out, s, st, sched, dry);
+}
+
+// The kernels with the small image block first, as long as they can keep the widest column
+// strips; then the large one; then the small one with narrower strips.
+template <int CSH, bool VEC>
+int launch_tile(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
+                int tile_cfg, const GenSched& sched, bool dry)
+{
+    if (!kSecondImax) return launch_tile_imax<CSH, VEC, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
+    GenSched widest = sched;
+    widest.widest_only = true;
+    int rc = launch_tile_imax<CSH, VEC, kImaxF>(in, filt, out, s, st, tile_cfg, widest, dry);
+    if (rc != DCONV_UNSUPPORTED) return rc;
+    rc = launch_tile_imax<CSH, VEC, kSecondImax ? 16 : kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
+    if (rc != DCONV_UNSUPPORTED) return rc;
+    return launch_tile_imax<CSH, VEC, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
 }
 
 template <int CSH>

@@ -78,7 +78,7 @@ struct GenParams {
     int bw;          // width of a column strip of the output (the last strip may be narrower)
     int nstrips;
     int LS;          // LDS row stride of the image block: bw + F - 1
-    int RS;          // LDS row slots per channel
+    int RS;          // rows of the image block per channel
     int pt_full;     // pixel tiles in a full-width strip
     int KB;          // filter tiles
     int nch;         // channel chunks per tile
@@ -90,8 +90,9 @@ struct GenParams {
     FastDiv d_wsf;   // by bw, the width of a full strip
     FastDiv d_wsl;   // by the width of the last strip
     FastDiv d_ho;    // by Ho
-    FastDiv d_h;     // by H
+    FastDiv d_hc;    // by Hc
     FastDiv d_nch;   // by nch
+    int Hc;          // image-block rows set aside per image: Ho + RG - 1
 };
 
 // Reduction index t of a chunk <-> (channel in chunk, filter row within the chunk's row group,
@@ -221,14 +222,17 @@ general_tiled_kernel(GenParams p)
         const FastDiv d_ws{last_strip ? p.d_wsl.m : p.d_wsf.m, last_strip ? p.d_wsl.sh : p.d_wsf.sh, ws};
         const int total_p = p.N * p.Ho * ws;
         const int p0 = ptile * NT;
-        // input rows are numbered n*H + y over the batch; the tile touches rows G0 .. G0+nslots-1
+        // The image block of a chunk holds, for every output row of the tile, the RG input rows
+        // of the chunk's filter rows: block row (n - n_first)*Hc + (y - y_first) + i for output
+        // row y of image n and filter row i of the group, with Hc = Ho + RG - 1 rows set
+        // aside per image.  Which input row that is depends on the group only through a shift
+        // of RG*W words per group, which goes into the chunk's buffer base (set_chunk).
         const int Q0 = fdiv(p0, d_ws);
         const int n_first = fdiv(Q0, p.d_ho);
         const int y_first = Q0 - n_first * p.Ho;
-        const int G0 = n_first * p.H + y_first;
         const int Ql = fdiv(min(p0 + NT, total_p) - 1, d_ws);
         const int nl = fdiv(Ql, p.d_ho);
-        const int nslots = nl * p.H + (Ql - nl * p.Ho) - G0 + F;
+        const int nslots = (nl - n_first) * p.Hc + (Ql - nl * p.Ho) - y_first + RG;
 #pragma unroll
         for (int it = 0; it < IMAX; ++it) {
             const int e = tid + it * kThreads;
@@ -236,8 +240,8 @@ general_tiled_kernel(GenParams p)
             if (e < img_words) {
                 const int cc = e / PL, r2 = e - cc * PL;
                 const int slot = r2 / LS, col = r2 - slot * LS;
-                const int dn = fdiv(y_first + slot, p.d_h);          // images past the first one
-                const int yy = y_first + slot - dn * p.H;
+                const int dn = fdiv(y_first + slot, p.d_hc);         // images past the first one
+                const int yy = y_first + slot - dn * p.Hc;           // input row, for the first group
                 if (slot < nslots && n_first + dn < p.N && x0 + col < p.W)
                     g = (uint32_t)(((dn * p.C + cc) * p.H + yy) * p.W + x0 + col) * 4u;
             }
@@ -251,7 +255,7 @@ general_tiled_kernel(GenParams p)
     auto set_chunk = [&](int chunk) __attribute__((always_inline)) {
         const int cidx = chunk / NG, g = chunk - cidx * NG;
         const int c0 = cidx * CSH;
-        const int64_t ioff = (int64_t)c0 * HW * 4;
+        const int64_t ioff = ((int64_t)c0 * HW + (int64_t)g * (RG * p.W)) * 4;
         const int64_t ibytes = ileft - ioff;
         irs = __builtin_amdgcn_make_buffer_rsrc((void*)(ibase + ioff), 0,
                                                 (int)min(ibytes, (int64_t)0x7FFFFFFF), kRsrcFlags);
@@ -317,7 +321,7 @@ general_tiled_kernel(GenParams p)
         const int p0 = ptile * NT;
         const int Q0 = fdiv(p0, d_ws);
         const int n_first = fdiv(Q0, p.d_ho);
-        const int G0 = n_first * p.H + (Q0 - n_first * p.Ho);
+        const int y_first = Q0 - n_first * p.Ho;
         const int k0 = kb * MT;
         kleft = p.K - k0 - 32 * wm * MW - 4 * h;
         obase_t = p.out + ((int64_t)n_first * p.K + k0) * plane;
@@ -329,7 +333,7 @@ general_tiled_kernel(GenParams p)
             const int pc = valid[nt] ? pp : total_p - 1;
             const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
             const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
-            base[nt] = TROWS * LDK + (n * p.H + y - G0) * LS + xl;
+            base[nt] = TROWS * LDK + ((n - n_first) * p.Hc + y - y_first) * LS + xl;
             oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
                                   y * p.Wo + x0 + xl) * 4u;
         }
@@ -345,7 +349,7 @@ general_tiled_kernel(GenParams p)
     int wb[MW];
 #pragma unroll
     for (int mt = 0; mt < MW; ++mt) wb[mt] = h * LDK + wm * (MW * 32) + l32 + mt * 32;
-    // operands of step s of the chunk in `slot`; bb: the lane's pixels at the chunk's first row;
+    // operands of step s of the chunk in `slot`; bb: the lane's pixels at the group's first row;
     // shortg: the chunk is a last row group with fewer rows (its odd tap count is padded here)
     auto load_ops = [&](int s, const float* slot, const int (&bb)[NW], bool shortg, float (&a)[MW],
                         float (&b)[NW]) __attribute__((always_inline)) {
@@ -482,17 +486,9 @@ general_tiled_kernel(GenParams p)
     zero_acc();
     __syncthreads();
 
-    // the lane's pixels in the image block, at the first filter row of the chunk's row group
-    int bb[NW];
     auto is_short = [&](int ch) __attribute__((always_inline)) { return TL != T && ch % NG == NG - 1; };
-    auto set_bb = [&](int ch) __attribute__((always_inline)) {
-        const int i0LS = (ch % NG) * (RG * LS);
-#pragma unroll
-        for (int nt = 0; nt < NW; ++nt) bb[nt] = base[nt] + i0LS;
-    };
     float a0[MW], b0[NW], a1[MW], b1[NW];
-    set_bb(chunk);
-    load_ops(0, lds, bb, is_short(chunk), a0, b0);
+    load_ops(0, lds, base, is_short(chunk), a0, b0);
     int bi = 0;                                            // LDS slot of the unit being consumed
 
     // ---- main loop: one (tile, chunk) unit per trip --------------------------------------------
@@ -507,7 +503,7 @@ general_tiled_kernel(GenParams p)
         const bool shortg = is_short(chunk);         // this chunk ends after SL steps
         // keep the tap addresses from being expanded into one register each outside the loop
 #pragma unroll
-        for (int nt = 0; nt < NW; ++nt) asm volatile("" : "+v"(bb[nt]));
+        for (int nt = 0; nt < NW; ++nt) asm volatile("" : "+v"(base[nt]));
 #pragma unroll
         for (int mt = 0; mt < MW; ++mt) asm volatile("" : "+v"(wb[mt]));
 #pragma unroll
@@ -520,11 +516,9 @@ general_tiled_kernel(GenParams p)
             const bool last_step = s == S - 1 || (s == SL - 1 && shortg);
             // Operands of step s+1 are requested from LDS before the matrix-core instructions
             // of step s are issued, so a wave never waits for LDS with the matrix pipe idle.
-            if (!last_step) load_ops(s + 1, cur, bb, shortg, (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
-            else if (NBUF == 3 && !tile_ends) {
-                set_bb(chunk + 1);
-                load_ops(0, nxt, bb, is_short(chunk + 1), (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
-            }
+            if (!last_step) load_ops(s + 1, cur, base, shortg, (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
+            else if (NBUF == 3 && !tile_ends)
+                load_ops(0, nxt, base, is_short(chunk + 1), (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
             if (s < NS) {
 #pragma unroll
                 for (int q = 0; q < IPS; ++q)
@@ -551,12 +545,11 @@ general_tiled_kernel(GenParams p)
                 ++tile; chunk = 0; from_first = true;
                 setup_compute(tile);
                 zero_acc();
-                set_bb(0);
-                load_ops(0, nxt, bb, is_short(0), a0, b0);
+                load_ops(0, nxt, base, is_short(0), a0, b0);
             }
         } else {
             ++chunk;
-            if (NBUF == 2) { set_bb(chunk); load_ops(0, nxt, bb, is_short(chunk), a0, b0); }
+            if (NBUF == 2) load_ops(0, nxt, base, is_short(chunk), a0, b0);
             else if (((shortg ? SL : S) & 1) != 0) {   // the operands requested across the chunk end
 #pragma unroll
                 for (int mt = 0; mt < MW; ++mt) a0[mt] = a1[mt];
@@ -577,11 +570,12 @@ struct GenPlan {
 
 // Column strips and LDS image-block geometry for tiles of NT pixels: the widest strips (at
 // most 128 columns) whose image block of CSH channels a workgroup can stage with `imax`
-// words per thread.
-inline GenPlan make_gen_plan(const Shape& s, int NT, int CSH, int imax)
+// words per thread (with `widest_only`, the widest strips or nothing).
+inline GenPlan make_gen_plan(const Shape& s, int NT, int CSH, int imax, int rg, bool widest_only)
 {
     GenPlan pl{};
-    for (int nstrips = (s.Wo + 127) / 128; nstrips <= s.Wo; ++nstrips) {
+    const int first = (s.Wo + 127) / 128;
+    for (int nstrips = first; nstrips <= (widest_only ? first : s.Wo); ++nstrips) {
         pl.bw = (s.Wo + nstrips - 1) / nstrips;
         pl.nstrips = (s.Wo + pl.bw - 1) / pl.bw;
         pl.LS = pl.bw + s.F - 1;
@@ -589,9 +583,10 @@ inline GenPlan make_gen_plan(const Shape& s, int NT, int CSH, int imax)
         // over every strip width from the narrowest (the last strip) to bw ...
         const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
         const int rows = NT >= 2 ? (NT - 2) / wmin + 2 : 1;
-        // ... and crosses at most this many image boundaries, each adding F-1 input rows.
+        // ... and crosses at most this many image boundaries; every image it touches adds the
+        // rg-1 further input rows that a group of rg filter rows reaches below an output row.
         const int cross = rows >= 2 ? (rows - 2) / s.Ho + 1 : 0;
-        pl.RS = rows + (s.F - 1) * (cross + 1);
+        pl.RS = rows + (rg - 1) * (cross + 1);
         pl.pt_full = (int)(((int64_t)s.N * s.Ho * pl.bw + NT - 1) / NT);
         pl.pt_last = (int)(((int64_t)s.N * s.Ho * wmin + NT - 1) / NT);
         if ((int64_t)CSH * pl.RS * pl.LS <= (int64_t)imax * kThreads) { pl.ok = true; return pl; }
@@ -604,6 +599,7 @@ inline GenPlan make_gen_plan(const Shape& s, int NT, int CSH, int imax)
 struct GenSched {
     int mode;          // 0: decide by shape, 1: whole tiles only, 2: cut inside tiles
     int force_G;       // > 0: this many workgroups (tests), 0: what the chip holds
+    bool widest_only;  // refuse shapes whose image block needs narrower column strips
 };
 
 // Workspace of one (device, stream): grown on demand by the dispatcher.
@@ -623,7 +619,7 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
 {
     using Gm = GenGeom<F, CSH, RG, MW, NW, WM, WN, IMAX, VEC, NBUF, OCC>;
     constexpr int MT = Gm::MT, NT = Gm::NT, TP = Gm::TP, LDK = Gm::LDK;
-    const GenPlan pl = make_gen_plan(s, NT, CSH, IMAX);
+    const GenPlan pl = make_gen_plan(s, NT, CSH, IMAX, RG, sched.widest_only);
     if (!pl.ok) return DCONV_UNSUPPORTED;
     const int64_t img_words = (int64_t)CSH * pl.RS * pl.LS;
     const int64_t buf_words = ((int64_t)Gm::TROWS * LDK + img_words + 2 + 3) & ~3LL;
@@ -706,8 +702,8 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     GenParams p{in, filt, out, ws.part, ws.cnt, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo,
                 pl.bw, pl.nstrips, pl.LS, pl.RS, pl.pt_full, KB, nch, (int)tiles, G, split,
                 make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
-                make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho), make_fastdiv(s.H),
-                make_fastdiv(nch)};
+                make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho), make_fastdiv(s.Ho + RG - 1),
+                make_fastdiv(nch), s.Ho + RG - 1};
     hipLaunchKernelGGL(kern, dim3((unsigned)G), dim3(kThreads), (size_t)lds_bytes, st, p);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
