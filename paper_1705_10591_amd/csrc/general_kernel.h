@@ -41,6 +41,7 @@
 //    the tile.  Nobody waits for anybody, so every workgroup always exits, and
 //    the result does not depend on the order of arrival.
 #pragma once
+#include <algorithm>
 #include "common.h"
 #include "../../include/dconv.h"
 
@@ -77,7 +78,7 @@ struct GenParams {
     int N, C, H, W, K, Ho, Wo;
     int bw;          // width of a column strip of the output (the last strip may be narrower)
     int nstrips;
-    int LS;          // LDS row stride of the image block: bw + F - 1
+    int LS;          // LDS row stride of the image block: bw + F - 1, rounded up to a multiple of 4
     int RS;          // rows of the image block per channel
     int pt_full;     // pixel tiles in a full-width strip
     int KB;          // filter tiles
@@ -114,7 +115,8 @@ __device__ __forceinline__ int unit_owner(int v, int U, int G) {
 //   RG:   filter rows per chunk; RG < F (large filters, one channel per chunk) cuts a channel
 //         into row groups so that the filter block of a chunk stays small; the last group
 //         may have fewer rows, its chunk then ends after fewer steps
-//   IMAX: image words a thread stages per chunk, at most
+//   IMAX: image words a thread stages per chunk, at most (a multiple of four: the image block
+//         moves in 16-byte pieces)
 //   VEC:  filter runs are fetched 16 B at a time (needs 16 B alignment of every run)
 //   NBUF: chunks held in LDS
 //   OCC:  workgroups per CU the register budget is cut for
@@ -140,7 +142,10 @@ struct GenGeom {
     // rows of the filter block in LDS: every thread's run is written whole (rows beyond T are
     // never read), so the write addresses need no test
     static constexpr int TROWS = TPF * EPT > TP ? TPF * EPT : TP;
-    static constexpr int NI = IMAX + NFI;            // staging items per thread per chunk
+    static_assert(IMAX % 4 == 0, "16-byte image pieces");
+    static constexpr int NII = IMAX / 4;             // image loads per thread per chunk
+    static constexpr int NI = NII + NFI;             // staging items per thread per chunk
+    static constexpr int IOFF = (TROWS * LDK + 3) & ~3;   // first word of the image block in a slot
     static_assert(NBUF == 2 || (NBUF == 3 && SL >= 4), "three LDS slots need at least four steps");
     // steps that carry staging items (every chunk has them); with three slots the barrier sits
     // two steps before the chunk's end
@@ -157,9 +162,9 @@ general_tiled_kernel(GenParams p)
     constexpr int NG = Gm::NG, RGL = Gm::RGL, TL = Gm::TL, SL = Gm::SL;
     constexpr int MT = Gm::MT, NT = Gm::NT, FF = Gm::FF, T = Gm::T, TP = Gm::TP, S = Gm::S;
     constexpr int LDK = Gm::LDK, TPF = Gm::TPF, EPT = Gm::EPT, NFI = Gm::NFI, NI = Gm::NI;
-    constexpr int NS = Gm::NS, IPS = Gm::IPS, TROWS = Gm::TROWS;
+    constexpr int NS = Gm::NS, IPS = Gm::IPS, TROWS = Gm::TROWS, NII = Gm::NII, IOFF = Gm::IOFF;
 
-    extern __shared__ float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ int s_old;
 
     const int tid = threadIdx.x;
@@ -169,11 +174,12 @@ general_tiled_kernel(GenParams p)
     const int wm = wave / WN, wn = wave % WN;
 
     const int LS = p.LS, PL = p.RS * p.LS;
-    const int img_words = CSH * PL;
-    // one LDS slot: filter block [TP][LDK], image block [CSH][RS][LS], a zero word, a trash word
-    const int zero_word = TROWS * LDK + img_words;
-    const int trash_word = zero_word + 1;
-    const int BUF = (TROWS * LDK + img_words + 2 + 3) & ~3;
+    const int img_words = CSH * PL;             // a multiple of four: LS is
+    // one LDS slot: filter block [TROWS][LDK], image block [CSH][RS][LS] on a 16-byte boundary,
+    // a zero word (and three spare ones), four trash words
+    const int zero_word = IOFF + img_words;
+    const int trash_word = zero_word + 4;
+    const int BUF = IOFF + img_words + 8;
 
     // Workgroups are handed to the 8 XCDs round-robin by their id; give each XCD one contiguous
     // stretch of the unit list so that neighbouring tiles share its L2.
@@ -203,7 +209,7 @@ general_tiled_kernel(GenParams p)
     // because the two may belong to different tiles.
     constexpr uint32_t kNowhere = 0xC0000000u;  // beyond every extent (extents are at most 2^31)
     constexpr int kRsrcFlags = 0x00020000;      // raw buffer of 32-bit words
-    uint32_t ig[IMAX];       // image: byte offset from in[n_first][c0][0][0], or kNowhere
+    uint32_t ig[NII];        // image: byte offset of a 4-word piece from in[n_first][c0][0][0], or kNowhere
     const int wkl = tid / TPF, we0 = (tid % TPF) * EPT;
     const uint32_t wofs = (uint32_t)(wkl * CFF + we0) * 4u;   // filter: byte offset from filt[k0][c0][0][0]
     const char* ibase = (const char*)p.in;      // in[n_first][0][0][0] of the tile being requested
@@ -234,8 +240,8 @@ general_tiled_kernel(GenParams p)
         const int nl = fdiv(Ql, p.d_ho);
         const int nslots = (nl - n_first) * p.Hc + (Ql - nl * p.Ho) - y_first + RG;
 #pragma unroll
-        for (int it = 0; it < IMAX; ++it) {
-            const int e = tid + it * kThreads;
+        for (int it = 0; it < NII; ++it) {
+            const int e = 4 * (tid + it * kThreads);           // LS is a multiple of four: one row
             uint32_t g = kNowhere;
             if (e < img_words) {
                 const int cc = e / PL, r2 = e - cc * PL;
@@ -270,35 +276,41 @@ general_tiled_kernel(GenParams p)
     int wrow[4];             // LDS word of this thread's filter run, one base per word of a 16-byte load
 #pragma unroll
     for (int e = 0; e < 4; ++e) wrow[e] = we0 * LDK + wkl + e * LDK;
-    // Staging item w < IMAX is an image word, item IMAX + q a filter load (one word, or four).
+    // Staging item w < NII is a piece of four image words, item NII + q a filter load (one word,
+    // or four).  Image pieces start at any 4-byte boundary of HBM; the words of a piece that lie
+    // beyond the end of the input read as zero one by one, those beyond the end of an image row
+    // are the head of the next row and land in columns that no valid pixel reads.
     // A thread whose filter lies beyond K has offsets beyond the end of the filter bank.  A
     // run may reach past the chunk's reduction indices (into the next row group, channel or
     // filter): those words land in rows of the filter block that no step reads.
     auto fetch_item = [&](int w) __attribute__((always_inline)) {
-        if (w < IMAX) {
-            ireg[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(irs, ig[w], 0, 0));
+        if (w < NII) {
+            const v4f v = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(irs, ig[w], 0, 0));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ireg[4 * w + e] = v[e];
         } else if (VEC) {
-            const int q = w - IMAX;
+            const int q = w - NII;
             // (the whole 16 bytes are reinterpreted at once: converting the builtin's result
             // element by element through another vector type drops all but the first word)
             const v4f v = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs + 16u * q, 0, 0));
 #pragma unroll
             for (int e = 0; e < 4; ++e) wreg[4 * q + e] = v[e];
         } else {
-            const int q = w - IMAX;
+            const int q = w - NII;
             wreg[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrs, wofs + 4u * q, 0, 0));
         }
     };
     auto commit_item = [&](int w, float* slot) __attribute__((always_inline)) {
-        if (w < IMAX) {
-            const int e = tid + w * kThreads;
-            slot[e < img_words ? TROWS * LDK + e : trash_word] = ireg[w];
+        if (w < NII) {
+            const int e = 4 * (tid + w * kThreads);
+            *reinterpret_cast<v4f*>(slot + (e < img_words ? IOFF + e : trash_word)) =
+                (v4f){ireg[4 * w], ireg[4 * w + 1], ireg[4 * w + 2], ireg[4 * w + 3]};
         } else if (VEC) {
-            const int q = w - IMAX;
+            const int q = w - NII;
 #pragma unroll
             for (int e = 0; e < 4; ++e) slot[wrow[e] + 4 * q * LDK] = wreg[4 * q + e];
         } else {
-            const int q = w - IMAX;
+            const int q = w - NII;
             slot[wrow[0] + q * LDK] = wreg[q];
         }
     };
@@ -333,7 +345,7 @@ general_tiled_kernel(GenParams p)
             const int pc = valid[nt] ? pp : total_p - 1;
             const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
             const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
-            base[nt] = TROWS * LDK + ((n - n_first) * p.Hc + y - y_first) * LS + xl;
+            base[nt] = IOFF + ((n - n_first) * p.Hc + y - y_first) * LS + xl;
             oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
                                   y * p.Wo + x0 + xl) * 4u;
         }
@@ -578,14 +590,15 @@ inline GenPlan make_gen_plan(const Shape& s, int NT, int CSH, int imax, int rg, 
     for (int nstrips = first; nstrips <= (widest_only ? first : s.Wo); ++nstrips) {
         pl.bw = (s.Wo + nstrips - 1) / nstrips;
         pl.nstrips = (s.Wo + pl.bw - 1) / pl.bw;
-        pl.LS = pl.bw + s.F - 1;
+        pl.LS = (pl.bw + s.F - 1 + 3) & ~3;      // whole 16-byte pieces per row
         // A run of NT consecutive strip pixels touches at most this many output rows, taken
         // over every strip width from the narrowest (the last strip) to bw ...
         const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
-        const int rows = NT >= 2 ? (NT - 2) / wmin + 2 : 1;
+        const int64_t all_rows = (int64_t)s.N * s.Ho;          // (there are no more than these)
+        const int rows = (int)std::min<int64_t>(NT >= 2 ? (NT - 2) / wmin + 2 : 1, all_rows);
         // ... and crosses at most this many image boundaries; every image it touches adds the
         // rg-1 further input rows that a group of rg filter rows reaches below an output row.
-        const int cross = rows >= 2 ? (rows - 2) / s.Ho + 1 : 0;
+        const int cross = std::min(rows >= 2 ? (rows - 2) / s.Ho + 1 : 0, s.N - 1);
         pl.RS = rows + (rg - 1) * (cross + 1);
         pl.pt_full = (int)(((int64_t)s.N * s.Ho * pl.bw + NT - 1) / NT);
         pl.pt_last = (int)(((int64_t)s.N * s.Ho * wmin + NT - 1) / NT);
@@ -622,7 +635,7 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     const GenPlan pl = make_gen_plan(s, NT, CSH, IMAX, RG, sched.widest_only);
     if (!pl.ok) return DCONV_UNSUPPORTED;
     const int64_t img_words = (int64_t)CSH * pl.RS * pl.LS;
-    const int64_t buf_words = ((int64_t)Gm::TROWS * LDK + img_words + 2 + 3) & ~3LL;
+    const int64_t buf_words = Gm::IOFF + img_words + 8;
     const int64_t lds_bytes = NBUF * 4 * buf_words;
     if (lds_bytes > kGenLdsLimit) return DCONV_UNSUPPORTED;
     const int KB = (s.K + MT - 1) / MT;

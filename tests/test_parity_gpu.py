@@ -187,7 +187,9 @@ def test_general_non_finite_pixel_reaches_only_the_windows_that_hold_it(shape):
     N, C, H, W, K, F = shape
     x, f = wl.random_case(91 + F, N, C, H, W, K, F)
     acc, mag, _ = oracle.general(x, f)
-    for (n, c, y0, x0) in [(0, 0, 0, 0), (N - 1, C - 1, H - 1, W - 1), (0, C - 1, H // 2, W // 3)]:
+    # (column 0 of a middle row sits right behind the end of the row above it in memory)
+    for (n, c, y0, x0) in [(0, 0, 0, 0), (N - 1, C - 1, H - 1, W - 1), (0, C - 1, H // 2, W // 3),
+                           (N - 1, 0, H // 2, 0), (0, C - 1, H - 1, 0)]:
         xb = x.copy()
         xb[n, c, y0, x0] = np.nan
         hit = np.zeros(acc.shape, dtype=bool)      # outputs whose window holds the pixel
