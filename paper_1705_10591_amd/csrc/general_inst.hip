@@ -38,7 +38,7 @@ constexpr int nbuf_for()
     return (S >= 4 && 3 * slot <= kGenLdsLimit) ? 3 : 2;
 }
 
-template <int CSH, bool VEC, int IMAX>
+template <int CSH, int IMAX>
 int launch_tile_imax(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                      int tile_cfg, const GenSched& sched, bool dry)
 {
@@ -50,37 +50,26 @@ int launch_tile_imax(const float* in, const float* filt, float* out, const Shape
     // four on any of twenty layer shapes and is no longer compiled.)
     constexpr int RG = CSH == 1 ? kRowGroup : F;
     if (tile_cfg == 1)
-        return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, IMAX, VEC, nbuf_for<CSH, 64, IMAX>(), 2>(in, filt, out, s, st, sched, dry);
+        return gen_try_launch<F, CSH, RG, 2, 2, 1, 4, IMAX, nbuf_for<CSH, 64, IMAX>(), 2>(in, filt, out, s, st, sched, dry);
     if (tile_cfg == 2)
-        return gen_try_launch<F, CSH, RG, 1, 2, 1, 4, IMAX, VEC, nbuf_for<CSH, 32, IMAX>(), 3>(in, filt, out, s, st, sched, dry);
-    return gen_try_launch<F, CSH, RG, 2, 1, 1, 4, IMAX, VEC, nbuf_for<CSH, 64, IMAX>(), 3>(in, filt, out, s, st, sched, dry);
+        return gen_try_launch<F, CSH, RG, 1, 2, 1, 4, IMAX, nbuf_for<CSH, 32, IMAX>(), 3>(in, filt, out, s, st, sched, dry);
+    return gen_try_launch<F, CSH, RG, 2, 1, 1, 4, IMAX, nbuf_for<CSH, 64, IMAX>(), 3>(in, filt, out, s, st, sched, dry);
 }
 
 // The kernels with the small image block first, as long as they can keep the widest column
 // strips; then the large one; then the small one with narrower strips.
-template <int CSH, bool VEC>
+template <int CSH>
 int launch_tile(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                 int tile_cfg, const GenSched& sched, bool dry)
 {
-    if (!kSecondImax) return launch_tile_imax<CSH, VEC, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
+    if (!kSecondImax) return launch_tile_imax<CSH, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
     GenSched widest = sched;
     widest.widest_only = true;
-    int rc = launch_tile_imax<CSH, VEC, kImaxF>(in, filt, out, s, st, tile_cfg, widest, dry);
+    int rc = launch_tile_imax<CSH, kImaxF>(in, filt, out, s, st, tile_cfg, widest, dry);
     if (rc != DCONV_UNSUPPORTED) return rc;
-    rc = launch_tile_imax<CSH, VEC, kSecondImax ? 16 : kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
+    rc = launch_tile_imax<CSH, kSecondImax ? 16 : kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
     if (rc != DCONV_UNSUPPORTED) return rc;
-    return launch_tile_imax<CSH, VEC, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
-}
-
-template <int CSH>
-int launch_chunk(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
-                 int tile_cfg, const GenSched& sched, bool dry)
-{
-    // 16-byte filter loads need every run of a chunk to start on a 16-byte boundary
-    constexpr bool can_vec = (CSH * F * F) % 4 == 0 && (CSH > 1 || kRowGroup == F);
-    if (can_vec && ((int64_t)s.C * F * F) % 4 == 0 && s.C % CSH == 0 && (dry || ((uintptr_t)filt & 15) == 0))
-        return launch_tile<CSH, can_vec>(in, filt, out, s, st, tile_cfg, sched, dry);
-    return launch_tile<CSH, false>(in, filt, out, s, st, tile_cfg, sched, dry);
+    return launch_tile_imax<CSH, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
 }
 
 }  // namespace
@@ -92,14 +81,14 @@ int gen_launch_for_F<DCONV_F>(const float* in, const float* filt, float* out, co
     // the largest compiled chunk that divides the channel count (one channel always does)
     int rc = DCONV_UNSUPPORTED;
     if (s.C % kChunkBig == 0) {
-        rc = launch_chunk<kChunkBig>(in, filt, out, s, st, tile_cfg, sched, dry);
+        rc = launch_tile<kChunkBig>(in, filt, out, s, st, tile_cfg, sched, dry);
         if (rc != DCONV_UNSUPPORTED) return rc;
     }
     if (kChunkSmall != kChunkBig && s.C % kChunkSmall == 0) {
-        rc = launch_chunk<kChunkSmall>(in, filt, out, s, st, tile_cfg, sched, dry);
+        rc = launch_tile<kChunkSmall>(in, filt, out, s, st, tile_cfg, sched, dry);
         if (rc != DCONV_UNSUPPORTED) return rc;
     }
-    if (kChunkSmall != 1) rc = launch_chunk<1>(in, filt, out, s, st, tile_cfg, sched, dry);
+    if (kChunkSmall != 1) rc = launch_tile<1>(in, filt, out, s, st, tile_cfg, sched, dry);
     return rc;
 }
 

@@ -117,13 +117,11 @@ __device__ __forceinline__ int unit_owner(int v, int U, int G) {
 //         may have fewer rows, its chunk then ends after fewer steps
 //   IMAX: image words a thread stages per chunk, at most (a multiple of four: the image block
 //         moves in 16-byte pieces)
-//   VEC:  filter runs are fetched 16 B at a time (needs 16 B alignment of every run)
 //   NBUF: chunks held in LDS
 //   OCC:  workgroups per CU the register budget is cut for
-template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, bool VEC, int NBUF, int OCC>
+template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, int NBUF, int OCC>
 struct GenGeom {
     static_assert(RG >= 1 && RG <= F && (RG == F || CSH == 1), "row groups need one channel per chunk");
-    static_assert(!VEC || RG == F, "16-byte filter loads only with whole channels");
     static constexpr int NG = (F + RG - 1) / RG;     // row groups per channel
     static constexpr int RGL = F - (NG - 1) * RG;    // filter rows in the last group
     static constexpr int MT = 32 * MW * WM;          // filters per tile
@@ -136,9 +134,8 @@ struct GenGeom {
     static constexpr int SL = (TL + 1) / 2;
     static constexpr int LDK = MT + 1;               // odd row stride: transposing writes hit 32 banks
     static constexpr int TPF = kThreads / MT;        // threads that share one filter when staging
-    static constexpr int EPT0 = (T + TPF - 1) / TPF;
-    static constexpr int EPT = VEC ? (EPT0 + 3) / 4 * 4 : EPT0;   // reduction indices per thread
-    static constexpr int NFI = VEC ? EPT / 4 : EPT;  // filter loads per thread per chunk
+    static constexpr int EPT = (T + TPF - 1) / TPF;  // reduction indices per thread
+    static constexpr int NFI = (EPT + 3) / 4;        // 16-byte filter loads per thread per chunk
     // rows of the filter block in LDS: every thread's run is written whole (rows beyond T are
     // never read), so the write addresses need no test
     static constexpr int TROWS = TPF * EPT > TP ? TPF * EPT : TP;
@@ -153,12 +150,12 @@ struct GenGeom {
     static constexpr int IPS = (NI + NS - 1) / NS;   // items per step
 };
 
-template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, bool VEC, int NBUF, int OCC>
+template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, int NBUF, int OCC>
 __global__ void __launch_bounds__(kThreads, OCC)
 general_tiled_kernel(GenParams p)
 {
     static_assert(WM * WN * kWave == kThreads, "four waves per workgroup");
-    using Gm = GenGeom<F, CSH, RG, MW, NW, WM, WN, IMAX, VEC, NBUF, OCC>;
+    using Gm = GenGeom<F, CSH, RG, MW, NW, WM, WN, IMAX, NBUF, OCC>;
     constexpr int NG = Gm::NG, RGL = Gm::RGL, TL = Gm::TL, SL = Gm::SL;
     constexpr int MT = Gm::MT, NT = Gm::NT, FF = Gm::FF, T = Gm::T, TP = Gm::TP, S = Gm::S;
     constexpr int LDK = Gm::LDK, TPF = Gm::TPF, EPT = Gm::EPT, NFI = Gm::NFI, NI = Gm::NI;
@@ -272,7 +269,7 @@ general_tiled_kernel(GenParams p)
     };
 
     float ireg[IMAX];
-    float wreg[EPT];
+    float wreg[4 * NFI];     // (the last load may bring words of the next thread's run: not committed)
     int wrow[4];             // LDS word of this thread's filter run, one base per word of a 16-byte load
 #pragma unroll
     for (int e = 0; e < 4; ++e) wrow[e] = we0 * LDK + wkl + e * LDK;
@@ -285,19 +282,16 @@ general_tiled_kernel(GenParams p)
     // filter): those words land in rows of the filter block that no step reads.
     auto fetch_item = [&](int w) __attribute__((always_inline)) {
         if (w < NII) {
+            // (the whole 16 bytes are reinterpreted at once: converting the builtin's result
+            // element by element through another vector type drops all but the first word)
             const v4f v = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(irs, ig[w], 0, 0));
 #pragma unroll
             for (int e = 0; e < 4; ++e) ireg[4 * w + e] = v[e];
-        } else if (VEC) {
+        } else {
             const int q = w - NII;
-            // (the whole 16 bytes are reinterpreted at once: converting the builtin's result
-            // element by element through another vector type drops all but the first word)
             const v4f v = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs + 16u * q, 0, 0));
 #pragma unroll
             for (int e = 0; e < 4; ++e) wreg[4 * q + e] = v[e];
-        } else {
-            const int q = w - NII;
-            wreg[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrs, wofs + 4u * q, 0, 0));
         }
     };
     auto commit_item = [&](int w, float* slot) __attribute__((always_inline)) {
@@ -305,13 +299,11 @@ general_tiled_kernel(GenParams p)
             const int e = 4 * (tid + w * kThreads);
             *reinterpret_cast<v4f*>(slot + (e < img_words ? IOFF + e : trash_word)) =
                 (v4f){ireg[4 * w], ireg[4 * w + 1], ireg[4 * w + 2], ireg[4 * w + 3]};
-        } else if (VEC) {
-            const int q = w - NII;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) slot[wrow[e] + 4 * q * LDK] = wreg[4 * q + e];
         } else {
             const int q = w - NII;
-            slot[wrow[0] + q * LDK] = wreg[q];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * q + e < EPT) slot[wrow[e] + 4 * q * LDK] = wreg[4 * q + e];
         }
     };
 
@@ -519,7 +511,7 @@ general_tiled_kernel(GenParams p)
 #pragma unroll
         for (int mt = 0; mt < MW; ++mt) asm volatile("" : "+v"(wb[mt]));
 #pragma unroll
-        for (int e = 0; e < (VEC ? 4 : 1); ++e) asm volatile("" : "+v"(wrow[e]));
+        for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(wrow[e]));
 #pragma unroll
         for (int s = 0; s < S; ++s) {
             if (s >= SL && shortg) continue;                 // uniform; compiled away when SL == S
@@ -626,11 +618,11 @@ GenWorkspace gen_workspace(hipStream_t st, size_t part_floats, size_t ncnt);
 
 constexpr int kGenLdsLimit = 160 * 1024 - 256;     // dynamic LDS; the rest is for the static word
 
-template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, bool VEC, int NBUF, int OCC>
+template <int F, int CSH, int RG, int MW, int NW, int WM, int WN, int IMAX, int NBUF, int OCC>
 int gen_try_launch(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                    const GenSched& sched, bool dry)
 {
-    using Gm = GenGeom<F, CSH, RG, MW, NW, WM, WN, IMAX, VEC, NBUF, OCC>;
+    using Gm = GenGeom<F, CSH, RG, MW, NW, WM, WN, IMAX, NBUF, OCC>;
     constexpr int MT = Gm::MT, NT = Gm::NT, TP = Gm::TP, LDK = Gm::LDK;
     const GenPlan pl = make_gen_plan(s, NT, CSH, IMAX, RG, sched.widest_only);
     if (!pl.ok) return DCONV_UNSUPPORTED;
@@ -656,11 +648,8 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
             return DCONV_UNSUPPORTED;
     }
     if (dry) return DCONV_OK;
-    // 16-byte filter loads: the dispatcher only picks VEC when every run is aligned
-    if (VEC && (((int64_t)s.C * F * F) % 4 != 0 || s.C % CSH != 0 || ((uintptr_t)filt & 15) != 0))
-        return DCONV_UNSUPPORTED;
 
-    auto kern = general_tiled_kernel<F, CSH, RG, MW, NW, WM, WN, IMAX, VEC, NBUF, OCC>;
+    auto kern = general_tiled_kernel<F, CSH, RG, MW, NW, WM, WN, IMAX, NBUF, OCC>;
     // Workgroups the chip holds at once for this LDS size (at most OCC per CU are used): cached
     // per instantiation for the last LDS size seen.  A race between threads can only pair the
     // count with another shape's LDS size, which changes the grid size and nothing else:
