@@ -99,8 +99,8 @@ int launch_any(const float* in, const float* filt, float* out, const Shape& s, h
 // Tile shape by problem shape, from the tile search (paper_1705_10591_amd.tune) over twenty
 // layer shapes.  Up to 32 filters: the 32 x 256 tile, so that half of every filter block is not
 // padding.  Up to 64 filters: 64 x 256 when the work divides finely enough over the chip with it
-// (many tiles, or so many chunks per tile that sharing tiles is cheap), else 32 x 256, which
-// doubles the number of tiles.  More filters: 64 x 256 on large maps, 64 x 128 (three workgroups
+// (many tiles, or so many chunks per tile that sharing tiles is cheap), else 64 x 128, which
+// doubles the number of tiles (and fits three workgroups per CU).  More filters: 64 x 256 on large maps, 64 x 128 (three workgroups
 // per CU) on small ones.
 int shape_for(const Shape& s)
 {
@@ -109,7 +109,7 @@ int shape_for(const Shape& s)
     if (s.K <= 64) {
         const int64_t wide_tiles = (px + 255) / 256;
         const int64_t chunks = ((int64_t)s.C * s.F * s.F + 35) / 36;
-        return (wide_tiles >= 1024 || wide_tiles * chunks >= 12000) ? 1 : 2;
+        return (wide_tiles >= 1024 || wide_tiles * chunks >= 12000) ? 1 : 0;
     }
     return px >= 16384 ? 1 : 0;
 }
