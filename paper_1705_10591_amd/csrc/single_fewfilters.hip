@@ -39,16 +39,20 @@ struct FewParams {
 };
 
 constexpr int kFewTW = 256;          // tile width: 64 lanes x 4 columns
-constexpr int kFewRPW = 8;           // output rows per wave
-constexpr int kFewTR = 4 * kFewRPW;  // tile rows: four waves, one band each
+// Output rows per wave (RPW; a tile has four bands of that many rows, one per wave).  Short bands
+// mean more halo rows per output row but smaller tiles, so more workgroups share a CU and more
+// loads are in flight: measured on 4096 x 4096 images, four rows win for filters up to 3x3
+// (12-16 % over eight) and for one or two filters up to 5x5, eight rows from there on.
+constexpr int few_rpw(int F, int K) { return (F <= 3 || (F <= 5 && K <= 2)) ? 4 : 8; }
 
 // filters held in scalar registers at a time: at most 64 weights
 constexpr int few_kb(int F) { return F * F <= 16 ? 4 : F * F <= 32 ? 2 : 1; }
 
-template <int F>
+template <int F, int RPW>
 __global__ void __launch_bounds__(kThreads)
 single_few_kernel(FewParams p)
 {
+    constexpr int kFewRPW = RPW, kFewTR = 4 * RPW;
     constexpr int FF = F * F;
     constexpr int KB = few_kb(F);
     constexpr int WIN = 4 + F - 1;                 // window columns of a lane
@@ -145,14 +149,21 @@ single_few_kernel(FewParams p)
     }
 }
 
+template <int F, int RPW>
+int launch_few_rows(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
+{
+    FewParams p{img, filt, out, s.H, s.W, s.K, s.Ho, s.Wo, (s.Wo + kFewTW - 1) / kFewTW};
+    const int64_t tiles = (int64_t)p.tiles_x * ((s.Ho + 4 * RPW - 1) / (4 * RPW));
+    if (tiles > 2147483647LL) return DCONV_UNSUPPORTED;
+    hipLaunchKernelGGL((single_few_kernel<F, RPW>), dim3((unsigned)tiles), dim3(kThreads), 0, st, p);
+    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+}
+
 template <int F>
 int launch_few_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
-    FewParams p{img, filt, out, s.H, s.W, s.K, s.Ho, s.Wo, (s.Wo + kFewTW - 1) / kFewTW};
-    const int64_t tiles = (int64_t)p.tiles_x * ((s.Ho + kFewTR - 1) / kFewTR);
-    if (tiles > 2147483647LL) return DCONV_UNSUPPORTED;
-    hipLaunchKernelGGL(single_few_kernel<F>, dim3((unsigned)tiles), dim3(kThreads), 0, st, p);
-    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+    if (F <= 5 && few_rpw(F, s.K) == 4) return launch_few_rows<F, (F <= 5 ? 4 : 8)>(img, filt, out, s, st);
+    return launch_few_rows<F, 8>(img, filt, out, s, st);
 }
 
 }  // namespace
@@ -170,7 +181,8 @@ bool single_few_supports(const Shape& s)
 // the chip.
 bool single_few_preferred(const Shape& s)
 {
-    const int64_t tiles = (int64_t)((s.Wo + kFewTW - 1) / kFewTW) * ((s.Ho + kFewTR - 1) / kFewTR);
+    const int tr = 4 * few_rpw(s.F, s.K);
+    const int64_t tiles = (int64_t)((s.Wo + kFewTW - 1) / kFewTW) * ((s.Ho + tr - 1) / tr);
     return single_few_supports(s) && (s.K <= 8 || (s.K <= 16 && s.F >= 5)) && tiles >= 512;
 }
 
