@@ -106,6 +106,33 @@ int dconv_general_v(const float *in, int N, int C, int H, int W,
                     float *out, int variant, void *stream);
 
 /*
+ * General case for 16-bit inputs with fp32 accumulation: the paper's closing
+ * remark (Sec. 6) that its width-matching model carries over to short data
+ * types.  The packed unit is the channel run, so channels are innermost:
+ *   in   [N][H][W][C]            device, read, fp16 or bf16 bit patterns
+ *   filt [K][F][F][C]            device, read, same type
+ *   out  [N][K][H-F+1][W-F+1]    device, written, fp32
+ *   out[n][k][y][x] = sum_i sum_j sum_c in[n][y+i][x+j][c] * filt[k][i][j][c]
+ * Products of two 16-bit values are exact in fp32; sums are fp32 in
+ * unspecified order.  The matrix-core kernel needs C to be a multiple of 16,
+ * F <= 11 and 16-byte aligned inputs; other shapes run on a
+ * one-thread-per-output kernel (any valid shape, 2-byte alignment).
+ * Errors as for dconv_general; a base pointer that is not 2-byte aligned ->
+ * DCONV_BAD_SHAPE.
+ */
+enum { DCONV_DTYPE_F16 = 0, DCONV_DTYPE_BF16 = 1 };
+int dconv_general_f16(const void *in, int N, int C, int H, int W,
+                      const void *filt, int K, int F,
+                      float *out, void *stream);
+int dconv_general_bf16(const void *in, int N, int C, int H, int W,
+                       const void *filt, int K, int F,
+                       float *out, void *stream);
+/* dtype: DCONV_DTYPE_*; variant: DCONV_VARIANT_AUTO, _SIMPLE or _TILED. */
+int dconv_general_half_v(const void *in, int N, int C, int H, int W,
+                         const void *filt, int K, int F,
+                         float *out, int dtype, int variant, void *stream);
+
+/*
  * Number of tile configurations compiled into the tiled kernel of the
  * single-channel case (single_channel != 0) or of the general case
  * (single_channel == 0).  The paper picks its tile sizes by exploring the

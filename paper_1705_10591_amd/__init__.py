@@ -23,7 +23,9 @@ STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAU
 
 EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
            "dconv_general_v", "dconv_status_string", "dconv_version",
-           "dconv_tile_config_count", "dconv_release_workspace")
+           "dconv_tile_config_count", "dconv_release_workspace",
+           "dconv_general_f16", "dconv_general_bf16", "dconv_general_half_v")
+DTYPE_F16, DTYPE_BF16 = 0, 1
 
 _lib = None
 
@@ -48,9 +50,13 @@ def load_library() -> ctypes.CDLL:
         lib.dconv_single_channel_v.argtypes = [p, i, i, p, i, i, p, i, p]
         lib.dconv_general.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_v.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
+        lib.dconv_general_f16.argtypes = [p, i, i, i, i, p, i, i, p, p]
+        lib.dconv_general_bf16.argtypes = [p, i, i, i, i, p, i, i, p, p]
+        lib.dconv_general_half_v.argtypes = [p, i, i, i, i, p, i, i, p, i, i, p]
         for name in ("dconv_single_channel", "dconv_single_channel_v",
                      "dconv_general", "dconv_general_v", "dconv_version",
-                     "dconv_release_workspace"):
+                     "dconv_release_workspace", "dconv_general_f16", "dconv_general_bf16",
+                     "dconv_general_half_v"):
             getattr(lib, name).restype = i
         lib.dconv_tile_config_count.argtypes = [i]
         lib.dconv_tile_config_count.restype = i
@@ -139,6 +145,38 @@ def dconv_general(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None 
     with torch.cuda.device(x.device):
         rc = load_library().dconv_general_v(
             x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), int(variant),
+            _stream_ptr(x.device))
+    _raise(rc)
+    return out
+
+
+def dconv_general_half(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
+                       variant: int = VARIANT_AUTO) -> torch.Tensor:
+    """16-bit inputs, channels innermost, fp32 accumulation and output:
+    out[n,k,y,x] = sum_{i,j,c} x[n,y+i,x+j,c] * filt[k,i,j,c]
+    x: [N,H,W,C], filt: [K,F,F,C], both torch.float16 or both torch.bfloat16."""
+    for t, what in ((x, "in"), (filt, "filt")):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dim() == 4 and t.is_contiguous()
+                and t.dtype in (torch.float16, torch.bfloat16)):
+            raise TypeError(f"{what} must be a contiguous float16 or bfloat16 CUDA tensor with 4 dims")
+    if x.dtype != filt.dtype:
+        raise TypeError("in and filt must have the same type")
+    N, H, W, C = x.shape
+    K, F, F2, C2 = filt.shape
+    if C2 != C or F != F2:
+        raise ValueError("filter shape does not match the input")
+    if F > H or F > W:
+        _raise(STATUS_BAD_SHAPE)
+    if out is None:
+        out = torch.empty((N, K, H - F + 1, W - F + 1), dtype=torch.float32, device=x.device)
+    else:
+        _check(out, 4, "out")
+        if tuple(out.shape) != (N, K, H - F + 1, W - F + 1):
+            raise ValueError("out has the wrong shape")
+    dtype = DTYPE_BF16 if x.dtype == torch.bfloat16 else DTYPE_F16
+    with torch.cuda.device(x.device):
+        rc = load_library().dconv_general_half_v(
+            x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), dtype, int(variant),
             _stream_ptr(x.device))
     _raise(rc)
     return out

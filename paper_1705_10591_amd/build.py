@@ -11,10 +11,12 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libdconv.so"
 BUILD = PKG / "_build"
-# (source, extra flags, object name); the general-case kernel is compiled once per filter side
+# (source, extra flags, object name); the general-case kernels are compiled once per filter side
 SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", [], "single"), ("single_fewfilters.hip", [], "single_fewfilters"),
            ("general.hip", [], "general")] + \
-          [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 12)]
+          [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 12)] + \
+          [("half.hip", [], "half")] + \
+          [("half_inst.hip", [f"-DDCONV_F={f}"], f"half_f{f}") for f in range(1, 12)]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed fp32 VALU forms are switched off for all device code (the host pass

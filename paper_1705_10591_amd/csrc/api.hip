@@ -93,6 +93,30 @@ int dconv_general(const float* in, int N, int C, int H, int W, const float* filt
     return dconv_general_v(in, N, C, H, W, filt, K, F, out, DCONV_VARIANT_AUTO, stream);
 }
 
+int dconv_general_half_v(const void* in, int N, int C, int H, int W, const void* filt, int K, int F,
+                         float* out, int dtype, int variant, void* stream)
+{
+    Shape s;
+    const int rc = validate(in, filt, out, N, C, H, W, K, F, &s);
+    if (rc != DCONV_OK) return rc;
+    if (dtype != DCONV_DTYPE_F16 && dtype != DCONV_DTYPE_BF16) return DCONV_UNSUPPORTED;
+    if ((((uintptr_t)in) & 1) != 0 || (((uintptr_t)filt) & 1) != 0) return DCONV_BAD_SHAPE;
+    return dconv::launch_general_half(in, filt, out, s, (hipStream_t)stream, dtype == DCONV_DTYPE_BF16,
+                                      variant);
+}
+
+int dconv_general_f16(const void* in, int N, int C, int H, int W, const void* filt, int K, int F,
+                      float* out, void* stream)
+{
+    return dconv_general_half_v(in, N, C, H, W, filt, K, F, out, DCONV_DTYPE_F16, DCONV_VARIANT_AUTO, stream);
+}
+
+int dconv_general_bf16(const void* in, int N, int C, int H, int W, const void* filt, int K, int F,
+                       float* out, void* stream)
+{
+    return dconv_general_half_v(in, N, C, H, W, filt, K, F, out, DCONV_DTYPE_BF16, DCONV_VARIANT_AUTO, stream);
+}
+
 const char* dconv_status_string(int status)
 {
     switch (status) {
@@ -116,6 +140,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1003; }
+int dconv_version(void) { return 1004; }
 
 }  // extern "C"

@@ -1,0 +1,382 @@
+// General-case direct convolution for 16-bit inputs (fp16 / bf16) with fp32 accumulation,
+// gfx950: the paper's closing remark (Sec. 6) that its model -- match the width of what a
+// thread reads from on-chip memory to the width of a bank -- carries over to short data types,
+// worked out for CDNA4.
+//
+// LDS banks are 4 bytes wide, so a lane that read one 2-byte pixel per access would use half
+// of every bank cycle and the matrix cores want whole runs of the reduction index per lane
+// anyway: v_mfma_f32_32x32x16_{f16,bf16} takes EIGHT consecutive reduction indices per lane
+// (16 bytes) for each operand.  The unit that is packed is the CHANNEL run: with channels
+// innermost in memory (in[N][H][W][C], filt[K][F][F][C]) the sixteen channels of one pixel are
+// 32 contiguous bytes in HBM and in LDS, a lane reads its eight with one 16-byte LDS access at
+// any tap offset, and one matrix-core step consumes one tap of sixteen channels.  The rest is
+// Algorithm 2 as in the fp32 kernel: (filter block) x (pixel block) tiles, channel chunks
+// staged in LDS with the next chunk prefetched into registers during the arithmetic (the
+// paper's double buffering, Sec. 4.3), the image block kept as it lies in memory and read at
+// shifted addresses.  No transposition is needed on the way into LDS: both blocks are copied
+// in 16-byte pieces, pixel after pixel and tap after tap.
+//
+//  * tile: 64 filters x 256 output pixels, four waves side by side, each 64 filters x 64
+//    pixels = 2 x 2 matrix-core blocks; pixels are numbered along (n, y, x) of a column strip
+//    as in the fp32 kernel, so narrow maps lose no lanes;
+//  * chunk: sixteen channels x RG filter rows; one step per tap (i, j) of the group; the image
+//    block of a chunk holds only the input rows its row group touches;
+//  * loads go through range-checked buffer descriptors (zero beyond the extent: filters beyond
+//    K, rows beyond the batch), so no lane tests anything.
+//
+// The channel count must be a multiple of sixteen and both inputs 16-byte aligned; other
+// shapes run on a plain one-thread-per-output kernel.
+#pragma once
+#include <algorithm>
+#include "common.h"
+#include "general_kernel.h"
+#include "../../include/dconv.h"
+
+namespace dconv {
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef __bf16 v8b __attribute__((ext_vector_type(8)));
+
+// D(32x32) += A(32x16) * B(16x32), 16-bit in, fp32 accumulate.  Lane l holds reduction
+// indices 8 * (l / 32) .. + 7 of row (A) / column (B) l % 32; D is laid out as for mfma_32x32x2.
+template <bool BF16>
+__device__ __forceinline__ v16f mfma_32x32x16(v4f a, v4f b, v16f acc) {
+    if (BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a),
+                                                       __builtin_bit_cast(v8b, b), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a),
+                                                  __builtin_bit_cast(v8h, b), acc, 0, 0, 0);
+}
+
+struct HalfParams {
+    const char* in;      // [N][H][W][C], 2-byte elements
+    const char* filt;    // [K][F][F][C]
+    float* out;          // [N][K][Ho][Wo]
+    int N, C, H, W, K, Ho, Wo;
+    int bw;              // width of a column strip of the output (the last strip may be narrower)
+    int nstrips;
+    int LS;              // pixels per row of the image block: bw + F - 1
+    int RS;              // rows of the image block
+    int pt_full;         // pixel tiles in a full-width strip
+    int KB;              // filter tiles
+    int tiles;           // ((nstrips - 1) * pt_full + pt_last) * KB
+    int per_xcd;         // tiles per XCD (grid = 8 * per_xcd)
+    int Hc;              // image-block rows set aside per image: Ho + RG - 1
+    FastDiv d_strip;     // by pt_full * KB
+    FastDiv d_kb;        // by KB
+    FastDiv d_wsf;       // by bw
+    FastDiv d_wsl;       // by the width of the last strip
+    FastDiv d_ho;        // by Ho
+    FastDiv d_hc;        // by Hc
+    FastDiv d_ls;        // by LS
+};
+
+constexpr int kHalfMT = 64, kHalfNT = 256;
+constexpr int kHalfCK = 16;                    // channels per chunk = reduction indices per step
+constexpr int kHalfImgItems = 6;               // 16-byte image pieces a thread stages per chunk
+
+// RG: filter rows per chunk (the last group of a filter may be shorter).
+template <int F, int RG, bool BF16>
+__global__ void __launch_bounds__(kThreads, 2)
+general_half_kernel(HalfParams p)
+{
+    constexpr int NG = (F + RG - 1) / RG, RGL = F - (NG - 1) * RG;
+    constexpr int S = RG * F, SL = RGL * F;             // steps of a chunk / of a last-group chunk
+    constexpr int MW = 2, NW = 2, MT = kHalfMT, NT = kHalfNT;
+    constexpr int FPIECES = S * MT * 2;                 // 16-byte pieces of the filter block
+    constexpr int NFI = (FPIECES + kThreads - 1) / kThreads;
+    constexpr int NII = kHalfImgItems;
+    constexpr int FB = FPIECES * 4;                     // words of the filter block
+    constexpr uint32_t kNowhere = 0xC0000000u;          // beyond every extent (at most 2^31)
+    constexpr int kRsrcFlags = 0x00020000;
+
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, l32 = lane & 31;
+
+    // each XCD (workgroups go to the eight of them round-robin) gets a contiguous run of tiles
+    const int tile = (int)(blockIdx.x % 8) * p.per_xcd + (int)(blockIdx.x / 8);
+    if (tile >= p.tiles) return;                        // uniform: before any barrier
+
+    const int LS = p.LS;
+    const int img_pieces = 2 * p.RS * LS;
+    const int SLOT = FB + 4 * img_pieces;               // words per LDS slot: filter block, image block
+    const int64_t plane = (int64_t)p.Ho * p.Wo;
+    const int CB = p.C * 2;                             // bytes per pixel (all channels)
+
+    // ---- where the tile lies -------------------------------------------------------------------
+    const int per_strip = p.pt_full * p.KB;
+    const int strip = min(fdiv(tile, p.d_strip), p.nstrips - 1);
+    const int rem = tile - strip * per_strip;
+    const int ptile = fdiv(rem, p.d_kb), kb = rem - ptile * p.KB;
+    const int x0 = strip * p.bw;
+    const int ws = min(p.bw, p.Wo - x0);
+    const bool last_strip = strip == p.nstrips - 1;
+    const FastDiv d_ws{last_strip ? p.d_wsl.m : p.d_wsf.m, last_strip ? p.d_wsl.sh : p.d_wsf.sh, ws};
+    const int total_p = p.N * p.Ho * ws;
+    const int p0 = ptile * NT;
+    const int Q0 = fdiv(p0, d_ws);
+    const int n_first = fdiv(Q0, p.d_ho);
+    const int y_first = Q0 - n_first * p.Ho;
+    const int Ql = fdiv(min(p0 + NT, total_p) - 1, d_ws);
+    const int nl = fdiv(Ql, p.d_ho);
+    // block row (n - n_first) * Hc + (y - y_first) + i holds input row y + (group's first filter
+    // row) + i of image n; the group's shift goes into the chunk's buffer base
+    const int nslots = (nl - n_first) * p.Hc + (Ql - nl * p.Ho) - y_first + RG;
+    const int k0 = kb * MT;
+
+    // ---- staging: byte offsets of this thread's pieces, the same for every chunk ---------------
+    uint32_t ig[NII];        // from in[n_first][0][0][0] (+ chunk shift), or kNowhere
+#pragma unroll
+    for (int it = 0; it < NII; ++it) {
+        const int e = tid + it * kThreads;
+        uint32_t g = kNowhere;
+        if (e < img_pieces) {
+            const int pix = e >> 1, half = e & 1;
+            const int row = fdiv(pix, p.d_ls), col = pix - row * LS;
+            const int dn = fdiv(y_first + row, p.d_hc);
+            const int yy = y_first + row - dn * p.Hc;
+            if (row < nslots && n_first + dn < p.N && x0 + col < p.W)
+                g = (uint32_t)(((dn * p.H + yy) * p.W + x0 + col) * CB + half * 16);
+        }
+        ig[it] = g;
+    }
+    uint32_t wg[NFI];        // from filt[k0][group's first row][0][0] (+ channel shift)
+#pragma unroll
+    for (int it = 0; it < NFI; ++it) {
+        const int e = tid + it * kThreads;
+        const int t = e / (2 * MT), k = (e >> 1) % MT, half = e & 1;
+        // (filters beyond K lie beyond the end of the bank: the range check returns zero)
+        wg[it] = e < FPIECES ? (uint32_t)((k * (F * F) + t) * CB + half * 16) : kNowhere;
+    }
+    const int64_t in_bytes = (int64_t)p.N * p.H * p.W * CB;
+    const int64_t filt_bytes = (int64_t)p.K * (F * F) * CB;
+    const int64_t ifirst = (int64_t)n_first * p.H * p.W * CB;
+    const int64_t wfirst = (int64_t)k0 * (F * F) * CB;
+    const int nch = p.C / kHalfCK * NG;
+
+    v4f ireg[NII], wreg[NFI];
+    auto fetch = [&](int chunk) __attribute__((always_inline)) {
+        const int cidx = chunk / NG, g = chunk - cidx * NG;
+        const int64_t ioff = ifirst + (int64_t)g * RG * p.W * CB + cidx * (kHalfCK * 2);
+        const __amdgpu_buffer_rsrc_t irs = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(p.in + ioff), 0, (int)min(in_bytes - ioff, (int64_t)0x7FFFFFFF), kRsrcFlags);
+        const int64_t woff = wfirst + (int64_t)g * (RG * F) * CB + cidx * (kHalfCK * 2);
+        const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(p.filt + woff), 0, (int)min(filt_bytes - woff, (int64_t)0x7FFFFFFF), kRsrcFlags);
+#pragma unroll
+        for (int it = 0; it < NII; ++it)
+            ireg[it] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(irs, ig[it], 0, 0));
+#pragma unroll
+        for (int it = 0; it < NFI; ++it)
+            wreg[it] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrs, wg[it], 0, 0));
+    };
+    // pieces beyond the blocks go to sixteen spare bytes behind the slots
+    const int trash = 2 * SLOT;
+    auto commit = [&](float* slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < NII; ++it) {
+            const int e = tid + it * kThreads;
+            *reinterpret_cast<v4f*>(e < img_pieces ? slot + FB + 4 * e : lds + trash) = ireg[it];
+        }
+#pragma unroll
+        for (int it = 0; it < NFI; ++it) {
+            const int e = tid + it * kThreads;
+            *reinterpret_cast<v4f*>(e < FPIECES ? slot + 4 * e : lds + trash) = wreg[it];
+        }
+    };
+
+    // ---- the compute side ------------------------------------------------------------------------
+    int base[NW];            // LDS word (within a slot) of the lane's 16 bytes of its pixel at tap (0, 0)
+    uint32_t oofs[NW];       // byte offset of out[n][k0 + 32*mt.. + 4*h][y][x] from out[n_first][k0][0][0]
+    bool valid[NW];
+    const int kleft = p.K - k0 - 4 * h;
+    float* obase_t = p.out + ((int64_t)n_first * p.K + k0) * plane;
+    {
+        const int kplane = p.K * (int)plane;
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt) {
+            const int pp = p0 + (wave * NW + nt) * 32 + l32;
+            valid[nt] = pp < total_p;
+            const int pc = valid[nt] ? pp : total_p - 1;
+            const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
+            const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
+            base[nt] = FB + ((((n - n_first) * p.Hc + y - y_first) * LS + xl) * 2 + h) * 4;
+            oofs[nt] = (uint32_t)((n - n_first) * kplane + (4 * h) * (int)plane + y * p.Wo + x0 + xl) * 4u;
+        }
+    }
+    int wb[MW];
+#pragma unroll
+    for (int mt = 0; mt < MW; ++mt) wb[mt] = ((mt * 32 + l32) * 2 + h) * 4;
+    auto load_ops = [&](int s, const float* slot, v4f (&a)[MW], v4f (&b)[NW]) __attribute__((always_inline)) {
+        const int i = s / F, j = s % F;
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt)
+            b[nt] = *reinterpret_cast<const v4f*>(slot + base[nt] + (i * LS + j) * 8);
+#pragma unroll
+        for (int mt = 0; mt < MW; ++mt)
+            a[mt] = *reinterpret_cast<const v4f*>(slot + wb[mt] + s * (MT * 8));
+    };
+
+    v16f acc[MW][NW];
+#pragma unroll
+    for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NW; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
+
+    // ---- chunks: compute chunk u from one slot while chunk u+1 is on its way to the registers ---
+    fetch(0);
+    commit(lds);
+    __syncthreads();
+    for (int u = 0; u < nch; ++u) {
+        const float* cur = lds + (u & 1) * SLOT;
+        float* nxt = lds + ((u + 1) & 1) * SLOT;
+        if (u + 1 < nch) fetch(u + 1);
+        const bool shortg = SL != S && (u % NG) == NG - 1;     // a last row group: fewer steps
+        v4f a0[MW], b0[NW], a1[MW], b1[NW];
+        load_ops(0, cur, a0, b0);
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (s >= SL && shortg) continue;                   // uniform; compiled away when SL == S
+            v4f (&a)[MW] = (s & 1) ? a1 : a0;
+            v4f (&b)[NW] = (s & 1) ? b1 : b0;
+            const bool last_step = s == S - 1 || (s == SL - 1 && shortg);
+            if (!last_step) load_ops(s + 1, cur, (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
+#pragma unroll
+            for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NW; ++nt)
+                    acc[mt][nt] = mfma_32x32x16<BF16>(a[mt], b[nt], acc[mt][nt]);
+        }
+        // slot `nxt` was last read during chunk u-1, which every wave left before the barrier
+        // that ended it
+        if (u + 1 < nch) commit(nxt);
+        __syncthreads();
+    }
+
+    // ---- write back: 32 lanes hold 32 consecutive pixels of one output map ---------------------
+#pragma unroll
+    for (int mt = 0; mt < MW; ++mt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int kk = mt * 32 + mfma_row(r, 0);
+            char* ob = (char*)(obase_t + kk * plane);
+#pragma unroll
+            for (int nt = 0; nt < NW; ++nt)
+                if (valid[nt] && kk < kleft)
+                    *reinterpret_cast<float*>(ob + oofs[nt]) = acc[mt][nt][r];
+        }
+    }
+}
+
+// One thread per output element, any shape and alignment.
+template <bool BF16>
+__global__ void __launch_bounds__(kThreads)
+simple_half_kernel(const unsigned short* in, const unsigned short* filt, float* out,
+                   int N, int C, int H, int W, int K, int F, int Ho, int Wo)
+{
+    const int64_t total = (int64_t)N * K * Ho * Wo;
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= total) return;
+    const int x = (int)(o % Wo), y = (int)((o / Wo) % Ho);
+    const int k = (int)((o / ((int64_t)Wo * Ho)) % K), n = (int)(o / ((int64_t)Wo * Ho * K));
+    auto cvt = [](unsigned short v) {
+        if (BF16) return __builtin_bit_cast(float, (uint32_t)v << 16);
+        return (float)__builtin_bit_cast(_Float16, v);
+    };
+    float acc = 0.f;
+    for (int i = 0; i < F; ++i)
+        for (int j = 0; j < F; ++j) {
+            const unsigned short* px = in + (((int64_t)n * H + y + i) * W + x + j) * C;
+            const unsigned short* wt = filt + (((int64_t)k * F + i) * F + j) * C;
+            for (int c = 0; c < C; ++c) acc = __builtin_fmaf(cvt(px[c]), cvt(wt[c]), acc);
+        }
+    out[o] = acc;
+}
+
+// ---- host side -----------------------------------------------------------------------------------
+
+struct HalfPlan {
+    int bw, nstrips, LS, RS, pt_full, pt_last;
+    bool ok;
+};
+
+// The widest column strips (at most 128 columns) whose image block a workgroup can stage with
+// kHalfImgItems pieces per thread.
+inline HalfPlan make_half_plan(const Shape& s, int rg)
+{
+    HalfPlan pl{};
+    constexpr int NT = kHalfNT;
+    for (int nstrips = (s.Wo + 127) / 128; nstrips <= s.Wo; ++nstrips) {
+        pl.bw = (s.Wo + nstrips - 1) / nstrips;
+        pl.nstrips = (s.Wo + pl.bw - 1) / pl.bw;
+        pl.LS = pl.bw + s.F - 1;
+        const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
+        const int64_t all_rows = (int64_t)s.N * s.Ho;
+        const int rows = (int)std::min<int64_t>((NT - 2) / wmin + 2, all_rows);
+        const int cross = std::min(rows >= 2 ? (rows - 2) / s.Ho + 1 : 0, s.N - 1);
+        pl.RS = rows + (rg - 1) * (cross + 1);
+        pl.pt_full = (int)(((int64_t)s.N * s.Ho * pl.bw + NT - 1) / NT);
+        pl.pt_last = (int)(((int64_t)s.N * s.Ho * wmin + NT - 1) / NT);
+        if (2LL * pl.RS * pl.LS <= (int64_t)kHalfImgItems * kThreads) { pl.ok = true; return pl; }
+    }
+    pl.ok = false;
+    return pl;
+}
+
+template <int F, int RG, bool BF16>
+int half_try_launch(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st, bool dry)
+{
+    constexpr int MT = kHalfMT, NT = kHalfNT, S = RG * F;
+    if (s.C % kHalfCK != 0) return DCONV_UNSUPPORTED;
+    const HalfPlan pl = make_half_plan(s, RG);
+    if (!pl.ok) return DCONV_UNSUPPORTED;
+    const int64_t slot_words = (int64_t)S * MT * 8 + 8LL * pl.RS * pl.LS;
+    const int64_t lds_bytes = 4 * (2 * slot_words + 4);
+    if (lds_bytes > kGenLdsLimit) return DCONV_UNSUPPORTED;
+    const int KB = (s.K + MT - 1) / MT;
+    const int64_t tiles = ((int64_t)(pl.nstrips - 1) * pl.pt_full + pl.pt_last) * KB;
+    if (tiles > 2000000000LL || (int64_t)s.N * s.Ho * s.Wo > 2147483647LL) return DCONV_UNSUPPORTED;
+    // lanes address HBM with 32-bit byte offsets from per-tile bases: what a tile can reach from
+    // its first image, its first filter and its first output map must lie within 2 GiB
+    {
+        const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
+        const int64_t span = NT / ((int64_t)s.Ho * wmin) + 2;
+        const int64_t plane = (int64_t)s.Ho * s.Wo;
+        const int64_t lim = 1LL << 31;
+        if (span * s.H * s.W * s.C * 2 >= lim || (span * s.K * plane + (MT + 1) * plane) * 4 >= lim ||
+            (int64_t)(MT + 1) * F * F * s.C * 2 >= lim)
+            return DCONV_UNSUPPORTED;
+    }
+    if (dry) return DCONV_OK;
+    if ((((uintptr_t)in) & 15) != 0 || (((uintptr_t)filt) & 15) != 0) return DCONV_UNSUPPORTED;
+
+    auto kern = general_half_kernel<F, RG, BF16>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kGenLdsLimit) != hipSuccess)
+            return DCONV_LAUNCH_FAILED;
+        attr_set = true;
+    }
+    const int per_xcd = (int)((tiles + 7) / 8);
+    HalfParams p{(const char*)in, (const char*)filt, out, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo,
+                 pl.bw, pl.nstrips, pl.LS, pl.RS, pl.pt_full, KB, (int)tiles, per_xcd, s.Ho + RG - 1,
+                 make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
+                 make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho),
+                 make_fastdiv(s.Ho + RG - 1), make_fastdiv(pl.LS)};
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(kThreads), (size_t)lds_bytes, st, p);
+    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+}
+
+// Implemented once per filter side, each in its own translation unit.
+template <int F>
+int half_launch_for_F(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
+                      bool bf16, bool dry);
+
+}  // namespace dconv

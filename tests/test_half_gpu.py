@@ -1,0 +1,142 @@
+"""Parity of the 16-bit (fp16 / bf16) general-case entry point with the fp64 oracle, through the C ABI.
+
+The oracle is the same plain definition as for fp32, evaluated on the 16-bit values widened
+to float32 (exact); layouts differ (channels innermost on the device), so the test transposes.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_1705_10591_amd as dconv
+from helpers import assert_within_bound
+
+pytestmark = pytest.mark.gpu
+
+SIMPLE, TILED, AUTO = dconv.VARIANT_SIMPLE, dconv.VARIANT_TILED, dconv.VARIANT_AUTO
+TORCH_TYPE = {"f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def dev16(bits_nchw_like: np.ndarray, kind: str) -> torch.Tensor:
+    """uint16 patterns in [.., C, H, W] order -> device tensor in [.., H, W, C] order."""
+    nhwc = np.ascontiguousarray(np.moveaxis(bits_nchw_like, 1, -1))
+    return torch.from_numpy(nhwc.view(np.int16)).view(TORCH_TYPE[kind]).to("cuda")
+
+
+def run_half(xb, fb, kind, variant):
+    print(f"half {kind} N,C,H,W={xb.shape} K,F={fb.shape[0]},{fb.shape[-1]} variant={variant}", flush=True)
+    out = dconv.dconv_general_half(dev16(xb, kind), dev16(fb, kind), variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def rounded_case(seed, shape, kind, integer=False):
+    N, C, H, W, K, F = shape
+    x, f = (wl.integer_case if integer else wl.random_case)(seed, N, C, H, W, K, F)
+    xr, xb = wl.to_16bit(x, kind)
+    fr, fb = wl.to_16bit(f, kind)
+    return xr, fr, xb, fb
+
+
+# (N, C, H, W, K, F) with C a multiple of 16: the matrix-core kernel
+HALF_SHAPES = [
+    (2, 16, 20, 23, 5, 3),
+    (1, 32, 30, 30, 70, 3),       # two filter tiles, ragged
+    (3, 16, 28, 28, 130, 3),      # pixel blocks wrap over rows and images
+    (2, 16, 24, 150, 33, 5),      # several column strips; row groups of 2, 2, 1
+    (1, 48, 12, 300, 8, 2),
+    (2, 16, 27, 31, 64, 11),      # one filter row per chunk
+    (1, 64, 9, 9, 3, 1),
+    (2, 32, 16, 16, 3, 4),
+    (1, 16, 20, 20, 9, 7),
+    (5, 16, 8, 8, 4, 3),          # tiny images: one pixel block spans several images
+    (3, 16, 5, 5, 4, 5),          # filter as large as the image
+    (1, 16, 14, 14, 2, 9),
+    (1, 32, 13, 12, 3, 10),
+    (2, 16, 11, 10, 2, 6),
+    (1, 16, 12, 11, 2, 8),
+    (7, 32, 9, 35, 96, 3),
+]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", HALF_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_half_small_shapes(shape, kind):
+    xr, fr, xb, fb = rounded_case(900 + shape[-1], shape, kind)
+    acc, mag, _ = oracle.general(xr, fr)
+    for variant in (TILED, SIMPLE):
+        got = run_half(xb, fb, kind, variant)
+        assert_within_bound(got, acc, mag, f"half {kind} {shape} variant {variant}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 32, 28, 28, 70, 3), (1, 16, 30, 140, 64, 11), (3, 48, 12, 12, 9, 5)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_half_integer_inputs_are_bit_exact(shape, kind):
+    xr, fr, xb, fb = rounded_case(3, shape, kind, integer=True)
+    assert np.array_equal(xr, wl.integer_case(3, *shape)[0])        # small integers are representable
+    _, _, o32, _ = oracle.general(xr, fr, want32=True)
+    for variant in (TILED, SIMPLE):
+        np.testing.assert_array_equal(run_half(xb, fb, kind, variant), o32)
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 20, 23, 5, 3), (1, 24, 14, 15, 7, 5), (2, 1, 9, 9, 2, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_half_channel_counts_without_a_matrix_core_kernel_fall_back(shape, kind):
+    xr, fr, xb, fb = rounded_case(17, shape, kind)
+    acc, mag, _ = oracle.general(xr, fr)
+    assert_within_bound(run_half(xb, fb, kind, AUTO), acc, mag, f"half {kind} {shape} auto")
+    with pytest.raises(dconv.DconvError) as e:
+        run_half(xb, fb, kind, TILED)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_half_non_finite_filter_stays_in_its_own_map(kind):
+    shape = (2, 16, 14, 15, 5, 5)
+    xr, fr, xb, fb = rounded_case(5, shape, kind)
+    acc, mag, _ = oracle.general(xr, fr)
+    inf_bits = {"f16": 0x7C00, "bf16": 0x7F80}[kind]
+    for bad in (0, 2, 4):
+        fbad = fb.copy()
+        fbad[bad] = inf_bits + 1            # a NaN pattern
+        fbad[bad, 0, 0, 0] = inf_bits
+        got = run_half(xb, fbad, kind, TILED)
+        assert not np.isfinite(got[:, bad]).any()
+        keep = [k for k in range(shape[4]) if k != bad]
+        assert_within_bound(got[:, keep], acc[:, keep], mag[:, keep], f"half {kind} filter {bad} non-finite")
+
+
+def test_half_output_guard_bands_stay_untouched():
+    shape = (2, 16, 13, 29, 37, 3)
+    N, C, H, W, K, F = shape
+    xr, fr, xb, fb = rounded_case(8, shape, "f16")
+    acc, mag, _ = oracle.general(xr, fr)
+    Ho, Wo = H - F + 1, W - F + 1
+    n_out, guard = N * K * Ho * Wo, 4096
+    buf = torch.full((n_out + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+    out = buf[guard:guard + n_out].view(N, K, Ho, Wo)
+    dconv.dconv_general_half(dev16(xb, "f16"), dev16(fb, "f16"), out=out, variant=TILED)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert np.isnan(host[:guard]).all() and np.isnan(host[guard + n_out:]).all()
+    assert_within_bound(host[guard:guard + n_out].reshape(N, K, Ho, Wo), acc, mag, "half guard bands")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("name", ["G2", "G3"])
+def test_half_config_shapes_sampled(name, kind):
+    """The fp32 benchmark shapes G2 and G3 (channel counts 64 and 256) with 16-bit inputs."""
+    w = wl.CONFIGS[name]
+    x, f = wl.make_inputs(w)
+    xr, xb = wl.to_16bit(x.reshape(w.N, w.C, w.H, w.W), kind)
+    fr, fb = wl.to_16bit(f.reshape(w.K, w.C, w.F, w.F), kind)
+    out = dconv.dconv_general_half(dev16(xb, kind), dev16(fb, kind), variant=TILED)
+    torch.cuda.synchronize()
+    total = out.numel()
+    idx = wl.sample_indices(31, total, 4000)
+    got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    acc, mag = oracle.general_at(xr, fr, idx)
+    assert_within_bound(got, acc, mag, f"half {kind} {name} sampled")

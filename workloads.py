@@ -142,6 +142,23 @@ def integer_case(seed: int, N: int, C: int, H: int, W: int, K: int, F: int):
     return x, f
 
 
+def to_16bit(a: np.ndarray, kind: str):
+    """Round float32 values to the nearest fp16 ("f16") or bf16 ("bf16") value, ties to even.
+
+    Returns (the rounded values as float32, their 16-bit patterns as uint16): the first go to
+    the oracle, the second to the device.  Values must be finite and within the type's range.
+    """
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if kind == "f16":
+        h = a.astype(np.float16)
+        return h.astype(np.float32), h.view(np.uint16)
+    if kind == "bf16":
+        u = a.view(np.uint32)
+        bits = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
+        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32), bits
+    raise ValueError(kind)
+
+
 def sample_indices(seed: int, total: int, count: int) -> np.ndarray:
     """`count` flat output indices in [0, total): the first, the last and seeded random ones."""
     rng = np.random.default_rng(SEED_BASE * 13 + seed)
