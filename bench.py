@@ -25,6 +25,7 @@ sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 (matrix / packed vector), published
+MFMA16_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 / bf16 matrix cores, published
 
 
 def parse_args():
@@ -250,6 +251,34 @@ def main():
             "bound": "mfma", "kernel": "dconv_general", "workload": "G3",
             "achieved": round(g["G3"]["gflops"] / 1e3, 3), "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": g["G3"]["frac_fp32_peak"], "traffic": read_traffic("dconv_general_G3")}
+
+    if not args.no_extra_configs and not args.only:
+        # the next row of the scope: the same general-case shapes with 16-bit inputs (channels
+        # innermost, fp32 accumulation), priced against the dense 16-bit matrix-core peak
+        half = []
+        for name in ("G2", "G3"):
+            w = allw[name]
+            xw, fw = wl.make_inputs(w)
+            x4 = torch.from_numpy(xw.reshape(w.N, w.C, w.H, w.W)).cuda().permute(0, 2, 3, 1).contiguous()
+            f4 = torch.from_numpy(fw.reshape(w.K, w.C, w.F, w.F)).cuda().permute(0, 2, 3, 1).contiguous()
+            for kind, tt in (("f16", torch.float16), ("bf16", torch.bfloat16)):
+                xh, fh = x4.to(tt), f4.to(tt)
+                out = torch.empty(w.out_shape(), dtype=torch.float32, device="cuda")
+                from paper_1705_10591_amd import dconv_general_half as dconv_half
+                r = lambda: dconv_half(xh, fh, out=out)
+                m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
+                half.append({"name": f"{name}_{kind}", "kernel": f"dconv_general_{kind}", "shape": config_entry(w, m)["shape"],
+                             "layout": "in[N][H][W][C], filt[K][F][F][C], out[N][K][Ho][Wo] fp32",
+                             "ms": round(m, 5), "gflops": round(w.flops / (m * 1e-3) / 1e9, 1),
+                             "frac_mfma16_peak": round(w.flops / (m * 1e-3) / 1e12 / MFMA16_PEAK_TFLOPS, 4)})
+                del out, xh, fh
+            del x4, f4
+            torch.cuda.empty_cache()
+        result["per_config_16bit"] = half
+        best = max(half, key=lambda e: e["gflops"])
+        result["roofline_16bit"] = {"bound": "mfma", "kernel": best["kernel"], "workload": best["name"],
+                                    "achieved": round(best["gflops"] / 1e3, 3), "peak": MFMA16_PEAK_TFLOPS,
+                                    "unit": "TFLOP/s", "frac": best["frac_mfma16_peak"], "traffic": None}
 
     if args.paper_sweep:
         sweep = []

@@ -95,3 +95,19 @@ def test_python_binding_refuses_cpu_tensors():
         dconv.dconv_general(torch.zeros(1, 1, 4, 4), torch.zeros(1, 1, 3, 3))
     with pytest.raises(TypeError):
         dconv.dconv_single_channel(torch.zeros(4, 4), torch.zeros(1, 3, 3))
+
+
+def test_16_bit_entry_points_validate_before_launching():
+    lib = dconv.load_library()
+    ok_dims = (1, 16, 8, 8)
+    for fn in (lib.dconv_general_f16, lib.dconv_general_bf16):
+        assert fn(None, *ok_dims, FAKE, 2, 3, FAKE, None) == dconv.STATUS_NULL_POINTER
+        assert fn(FAKE, *ok_dims, FAKE, 2, 3, None, None) == dconv.STATUS_NULL_POINTER
+        assert fn(FAKE, 1, 16, 4, 8, FAKE, 2, 5, FAKE, None) == dconv.STATUS_BAD_SHAPE
+        assert fn(FAKE, 1, 0, 8, 8, FAKE, 2, 3, FAKE, None) == dconv.STATUS_BAD_SHAPE
+    odd = ctypes.c_void_p(0x1001)             # 16-bit data cannot start at an odd address
+    assert lib.dconv_general_f16(odd, *ok_dims, FAKE, 2, 3, FAKE, None) == dconv.STATUS_BAD_SHAPE
+    # unknown element type / a variant the 16-bit path does not have
+    assert lib.dconv_general_half_v(FAKE, *ok_dims, FAKE, 2, 3, FAKE, 7, 0, None) == dconv.STATUS_UNSUPPORTED
+    assert lib.dconv_general_half_v(FAKE, *ok_dims, FAKE, 2, 3, FAKE, 0, dconv.VARIANT_FEW_FILTERS, None) \
+        == dconv.STATUS_UNSUPPORTED
