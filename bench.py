@@ -85,6 +85,28 @@ def make_runner(w):
     return (lambda: dconv.dconv_general(xd, fd, out=out)), (x, f)
 
 
+def make_half_runner(w, kind):
+    """The general-case shape `w` with 16-bit inputs (kind: "f16" or "bf16"), channels innermost."""
+    import torch
+    import workloads as wl
+    from paper_1705_10591_amd import dconv_general_half
+    tt = torch.float16 if kind == "f16" else torch.bfloat16
+    x, f = wl.make_inputs(w)
+    xh = torch.from_numpy(x.reshape(w.N, w.C, w.H, w.W)).cuda().permute(0, 2, 3, 1).contiguous().to(tt)
+    fh = torch.from_numpy(f.reshape(w.K, w.C, w.F, w.F)).cuda().permute(0, 2, 3, 1).contiguous().to(tt)
+    out = torch.empty(w.out_shape(), dtype=torch.float32, device="cuda")
+    return lambda: dconv_general_half(xh, fh, out=out)
+
+
+def half_entry(w, kind, ms):
+    gflops = w.flops / (ms * 1e-3) / 1e9
+    return {"name": f"{w.name}_{kind}", "kernel": f"dconv_general_{kind}",
+            "shape": {"N": w.N, "C": w.C, "H": w.H, "W": w.W, "K": w.K, "F": w.F},
+            "layout": "in[N][H][W][C], filt[K][F][F][C], out[N][K][Ho][Wo] fp32",
+            "ms": round(ms, 5), "gflops": round(gflops, 1),
+            "frac_mfma16_peak": round(gflops / 1e3 / MFMA16_PEAK_TFLOPS, 4)}
+
+
 def config_entry(w, ms):
     gflops = w.flops / (ms * 1e-3) / 1e9
     gbs = w.algorithmic_bytes / (ms * 1e-3) / 1e9
@@ -182,6 +204,30 @@ def main():
     allw = dict(wl.CONFIGS)
     allw.update({v.name: v for v in wl.S2_SWEEP.values()})
     allw.update(wl.PAPER_SWEEP)
+    if args.only and args.only.rsplit("_", 1)[-1] in ("f16", "bf16") and args.only.rsplit("_", 1)[0] in allw:
+        # one of the 16-bit configurations on its own (for profiles): the same JSON shape
+        wname, kind = args.only.rsplit("_", 1)
+        w = allw[wname]
+        run = make_half_runner(w, kind)
+        ms, wall_ms = time_launches(run, args.steps, args.warmup, warm_ms=60.0)
+        e = half_entry(w, kind, ms)
+        if args.copy_calibration:
+            a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+            b = torch.empty_like(a)
+            for _ in range(3):
+                b.copy_(a)
+            torch.cuda.synchronize()
+        print(json.dumps({
+            "metric": "GFLOP/s (direct convolution with 16-bit inputs and fp32 accumulation, per conv shape)",
+            "value": e["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": kind, "data": "synthetic",
+            "config": {"workload": f"{e['name']}: {e['kernel']} " + json.dumps(e["shape"]).replace('"', "")},
+            "roofline": {"bound": "mfma", "achieved": round(e["gflops"] / 1e3, 3), "peak": MFMA16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": e["frac_mfma16_peak"], "kernel": e["kernel"],
+                         "kernel_ms": round(ms, 5), "traffic": read_traffic(f"{e['kernel']}_{e['name']}")}}),
+              flush=True)
+        return
     head = allw[args.only] if args.only else wl.S2
 
     run, (x, f) = make_runner(head)
@@ -257,28 +303,18 @@ def main():
         # innermost, fp32 accumulation), priced against the dense 16-bit matrix-core peak
         half = []
         for name in ("G2", "G3"):
-            w = allw[name]
-            xw, fw = wl.make_inputs(w)
-            x4 = torch.from_numpy(xw.reshape(w.N, w.C, w.H, w.W)).cuda().permute(0, 2, 3, 1).contiguous()
-            f4 = torch.from_numpy(fw.reshape(w.K, w.C, w.F, w.F)).cuda().permute(0, 2, 3, 1).contiguous()
-            for kind, tt in (("f16", torch.float16), ("bf16", torch.bfloat16)):
-                xh, fh = x4.to(tt), f4.to(tt)
-                out = torch.empty(w.out_shape(), dtype=torch.float32, device="cuda")
-                from paper_1705_10591_amd import dconv_general_half as dconv_half
-                r = lambda: dconv_half(xh, fh, out=out)
+            for kind in ("f16", "bf16"):
+                r = make_half_runner(allw[name], kind)
                 m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
-                half.append({"name": f"{name}_{kind}", "kernel": f"dconv_general_{kind}", "shape": config_entry(w, m)["shape"],
-                             "layout": "in[N][H][W][C], filt[K][F][F][C], out[N][K][Ho][Wo] fp32",
-                             "ms": round(m, 5), "gflops": round(w.flops / (m * 1e-3) / 1e9, 1),
-                             "frac_mfma16_peak": round(w.flops / (m * 1e-3) / 1e12 / MFMA16_PEAK_TFLOPS, 4)})
-                del out, xh, fh
-            del x4, f4
-            torch.cuda.empty_cache()
+                half.append(half_entry(allw[name], kind, m))
+                del r
+                torch.cuda.empty_cache()
         result["per_config_16bit"] = half
         best = max(half, key=lambda e: e["gflops"])
         result["roofline_16bit"] = {"bound": "mfma", "kernel": best["kernel"], "workload": best["name"],
                                     "achieved": round(best["gflops"] / 1e3, 3), "peak": MFMA16_PEAK_TFLOPS,
-                                    "unit": "TFLOP/s", "frac": best["frac_mfma16_peak"], "traffic": None}
+                                    "unit": "TFLOP/s", "frac": best["frac_mfma16_peak"],
+                                    "traffic": read_traffic(f"{best['kernel']}_{best['name']}")}
 
     if args.paper_sweep:
         sweep = []
