@@ -26,6 +26,7 @@ sys.path.insert(0, str(ROOT))
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 (matrix / packed vector), published
 MFMA16_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 / bf16 matrix cores, published
+MFMA8_PEAK_TOPS = 5000.0       # MI355X dense int8 matrix cores, published
 
 
 def parse_args():
@@ -86,10 +87,16 @@ def make_runner(w):
 
 
 def make_half_runner(w, kind):
-    """The general-case shape `w` with 16-bit inputs (kind: "f16" or "bf16"), channels innermost."""
+    """The general-case shape `w` with short inputs (kind: "f16", "bf16" or "i8"), channels innermost."""
     import torch
     import workloads as wl
-    from paper_1705_10591_amd import dconv_general_half
+    from paper_1705_10591_amd import dconv_general_half, dconv_general_i8
+    if kind == "i8":
+        g = torch.Generator(device="cuda").manual_seed(w.seed)
+        xi = torch.randint(-128, 128, (w.N, w.H, w.W, w.C), generator=g, device="cuda", dtype=torch.int8)
+        fi = torch.randint(-128, 128, (w.K, w.F, w.F, w.C), generator=g, device="cuda", dtype=torch.int8)
+        outi = torch.empty(w.out_shape(), dtype=torch.int32, device="cuda")
+        return lambda: dconv_general_i8(xi, fi, out=outi)
     tt = torch.float16 if kind == "f16" else torch.bfloat16
     x, f = wl.make_inputs(w)
     xh = torch.from_numpy(x.reshape(w.N, w.C, w.H, w.W)).cuda().permute(0, 2, 3, 1).contiguous().to(tt)
@@ -100,11 +107,12 @@ def make_half_runner(w, kind):
 
 def half_entry(w, kind, ms):
     gflops = w.flops / (ms * 1e-3) / 1e9
+    peak = MFMA8_PEAK_TOPS if kind == "i8" else MFMA16_PEAK_TFLOPS
     return {"name": f"{w.name}_{kind}", "kernel": f"dconv_general_{kind}",
             "shape": {"N": w.N, "C": w.C, "H": w.H, "W": w.W, "K": w.K, "F": w.F},
-            "layout": "in[N][H][W][C], filt[K][F][F][C], out[N][K][Ho][Wo] fp32",
-            "ms": round(ms, 5), "gflops": round(gflops, 1),
-            "frac_mfma16_peak": round(gflops / 1e3 / MFMA16_PEAK_TFLOPS, 4)}
+            "layout": "in[N][H][W][C], filt[K][F][F][C], out[N][K][Ho][Wo] " + ("int32" if kind == "i8" else "fp32"),
+            "ms": round(ms, 5), "gflops": round(gflops, 1), "peak_tflops": peak,
+            "frac_mfma_peak": round(gflops / 1e3 / peak, 4)}
 
 
 def config_entry(w, ms):
@@ -204,7 +212,7 @@ def main():
     allw = dict(wl.CONFIGS)
     allw.update({v.name: v for v in wl.S2_SWEEP.values()})
     allw.update(wl.PAPER_SWEEP)
-    if args.only and args.only.rsplit("_", 1)[-1] in ("f16", "bf16") and args.only.rsplit("_", 1)[0] in allw:
+    if args.only and args.only.rsplit("_", 1)[-1] in ("f16", "bf16", "i8") and args.only.rsplit("_", 1)[0] in allw:
         # one of the 16-bit configurations on its own (for profiles): the same JSON shape
         wname, kind = args.only.rsplit("_", 1)
         w = allw[wname]
@@ -218,13 +226,13 @@ def main():
                 b.copy_(a)
             torch.cuda.synchronize()
         print(json.dumps({
-            "metric": "GFLOP/s (direct convolution with 16-bit inputs and fp32 accumulation, per conv shape)",
+            "metric": "GFLOP/s (direct convolution with 16-bit or 8-bit inputs, per conv shape)",
             "value": e["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": kind, "data": "synthetic",
             "config": {"workload": f"{e['name']}: {e['kernel']} " + json.dumps(e["shape"]).replace('"', "")},
-            "roofline": {"bound": "mfma", "achieved": round(e["gflops"] / 1e3, 3), "peak": MFMA16_PEAK_TFLOPS,
-                         "unit": "TFLOP/s", "frac": e["frac_mfma16_peak"], "kernel": e["kernel"],
+            "roofline": {"bound": "mfma", "achieved": round(e["gflops"] / 1e3, 3), "peak": e["peak_tflops"],
+                         "unit": "TFLOP/s", "frac": e["frac_mfma_peak"], "kernel": e["kernel"],
                          "kernel_ms": round(ms, 5), "traffic": read_traffic(f"{e['kernel']}_{e['name']}")}}),
               flush=True)
         return
@@ -299,21 +307,21 @@ def main():
             "frac": g["G3"]["frac_fp32_peak"], "traffic": read_traffic("dconv_general_G3")}
 
     if not args.no_extra_configs and not args.only:
-        # the next row of the scope: the same general-case shapes with 16-bit inputs (channels
-        # innermost, fp32 accumulation), priced against the dense 16-bit matrix-core peak
+        # the next row of the scope: the same general-case shapes with fp16, bf16 and int8 inputs
+        # (channels innermost), priced against the dense matrix-core peak of their type
         half = []
         for name in ("G2", "G3"):
-            for kind in ("f16", "bf16"):
+            for kind in ("f16", "bf16", "i8"):
                 r = make_half_runner(allw[name], kind)
                 m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
                 half.append(half_entry(allw[name], kind, m))
                 del r
                 torch.cuda.empty_cache()
-        result["per_config_16bit"] = half
-        best = max(half, key=lambda e: e["gflops"])
+        result["per_config_short_types"] = half
+        best = max((e for e in half if not e["name"].endswith("_i8")), key=lambda e: e["gflops"])
         result["roofline_16bit"] = {"bound": "mfma", "kernel": best["kernel"], "workload": best["name"],
                                     "achieved": round(best["gflops"] / 1e3, 3), "peak": MFMA16_PEAK_TFLOPS,
-                                    "unit": "TFLOP/s", "frac": best["frac_mfma16_peak"],
+                                    "unit": "TFLOP/s", "frac": best["frac_mfma_peak"],
                                     "traffic": read_traffic(f"{best['kernel']}_{best['name']}")}
 
     if args.paper_sweep:

@@ -120,17 +120,33 @@ int dconv_general_v(const float *in, int N, int C, int H, int W,
  * Errors as for dconv_general; a base pointer that is not 2-byte aligned ->
  * DCONV_BAD_SHAPE.
  */
-enum { DCONV_DTYPE_F16 = 0, DCONV_DTYPE_BF16 = 1 };
+enum { DCONV_DTYPE_F16 = 0, DCONV_DTYPE_BF16 = 1, DCONV_DTYPE_I8 = 2 };
 int dconv_general_f16(const void *in, int N, int C, int H, int W,
                       const void *filt, int K, int F,
                       float *out, void *stream);
 int dconv_general_bf16(const void *in, int N, int C, int H, int W,
                        const void *filt, int K, int F,
                        float *out, void *stream);
-/* dtype: DCONV_DTYPE_*; variant: DCONV_VARIANT_AUTO, _SIMPLE or _TILED. */
+/* dtype: DCONV_DTYPE_F16 or _BF16; variant: DCONV_VARIANT_AUTO, _SIMPLE or _TILED. */
 int dconv_general_half_v(const void *in, int N, int C, int H, int W,
                          const void *filt, int K, int F,
                          float *out, int dtype, int variant, void *stream);
+
+/*
+ * The same with signed 8-bit integer inputs and exact int32 sums:
+ *   in   [N][H][W][C] int8, filt [K][F][F][C] int8, out [N][K][Ho][Wo] int32
+ * (|sum| <= C*F*F*2^14 must fit int32, which it does for every shape the
+ * 2^31-1 element limits admit with C*F*F < 2^17; larger reductions wrap as
+ * int32 arithmetic does).  The matrix-core kernel needs C to be a multiple of
+ * 32, F <= 11 and 16-byte aligned inputs; other shapes run on the
+ * one-thread-per-output kernel.  variant as for dconv_general_half_v.
+ */
+int dconv_general_i8(const void *in, int N, int C, int H, int W,
+                     const void *filt, int K, int F,
+                     int *out, void *stream);
+int dconv_general_i8_v(const void *in, int N, int C, int H, int W,
+                       const void *filt, int K, int F,
+                       int *out, int variant, void *stream);
 
 /*
  * Number of tile configurations compiled into the tiled kernel of the

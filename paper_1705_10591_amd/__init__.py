@@ -24,8 +24,9 @@ STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAU
 EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
            "dconv_general_v", "dconv_status_string", "dconv_version",
            "dconv_tile_config_count", "dconv_release_workspace",
-           "dconv_general_f16", "dconv_general_bf16", "dconv_general_half_v")
-DTYPE_F16, DTYPE_BF16 = 0, 1
+           "dconv_general_f16", "dconv_general_bf16", "dconv_general_half_v",
+           "dconv_general_i8", "dconv_general_i8_v")
+DTYPE_F16, DTYPE_BF16, DTYPE_I8 = 0, 1, 2
 
 _lib = None
 
@@ -53,10 +54,12 @@ def load_library() -> ctypes.CDLL:
         lib.dconv_general_f16.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_bf16.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_half_v.argtypes = [p, i, i, i, i, p, i, i, p, i, i, p]
+        lib.dconv_general_i8.argtypes = [p, i, i, i, i, p, i, i, p, p]
+        lib.dconv_general_i8_v.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
         for name in ("dconv_single_channel", "dconv_single_channel_v",
                      "dconv_general", "dconv_general_v", "dconv_version",
                      "dconv_release_workspace", "dconv_general_f16", "dconv_general_bf16",
-                     "dconv_general_half_v"):
+                     "dconv_general_half_v", "dconv_general_i8", "dconv_general_i8_v"):
             getattr(lib, name).restype = i
         lib.dconv_tile_config_count.argtypes = [i]
         lib.dconv_tile_config_count.restype = i
@@ -177,6 +180,33 @@ def dconv_general_half(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | 
     with torch.cuda.device(x.device):
         rc = load_library().dconv_general_half_v(
             x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), dtype, int(variant),
+            _stream_ptr(x.device))
+    _raise(rc)
+    return out
+
+
+def dconv_general_i8(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
+                     variant: int = VARIANT_AUTO) -> torch.Tensor:
+    """Signed 8-bit inputs, channels innermost, exact int32 sums:
+    out[n,k,y,x] = sum_{i,j,c} x[n,y+i,x+j,c] * filt[k,i,j,c];  x: [N,H,W,C], filt: [K,F,F,C], torch.int8."""
+    for t, what in ((x, "in"), (filt, "filt")):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dim() == 4 and t.is_contiguous()
+                and t.dtype == torch.int8):
+            raise TypeError(f"{what} must be a contiguous int8 CUDA tensor with 4 dims")
+    N, H, W, C = x.shape
+    K, F, F2, C2 = filt.shape
+    if C2 != C or F != F2:
+        raise ValueError("filter shape does not match the input")
+    if F > H or F > W:
+        _raise(STATUS_BAD_SHAPE)
+    shape = (N, K, H - F + 1, W - F + 1)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    elif not (out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and tuple(out.shape) == shape):
+        raise TypeError("out must be a contiguous int32 CUDA tensor of the output shape")
+    with torch.cuda.device(x.device):
+        rc = load_library().dconv_general_i8_v(
+            x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), int(variant),
             _stream_ptr(x.device))
     _raise(rc)
     return out

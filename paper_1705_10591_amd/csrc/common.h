@@ -49,8 +49,9 @@ bool single_few_preferred(const Shape& s);     // ... and is the better choice f
 bool single_tiled_supports(const Shape& s);
 bool general_tiled_supports(const Shape& s);
 void release_general_workspaces();
-// 16-bit inputs (fp16 or bf16 bit patterns), channels innermost; variant: AUTO, SIMPLE or TILED.
+// Short data types (dtype: DCONV_DTYPE_*), channels innermost; variant: AUTO, SIMPLE or TILED.
+// `out` receives fp32 values, or int32 bit patterns for 8-bit integer inputs.
 int launch_general_half(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                        bool bf16, int variant);
+                        int dtype, int variant);
 
 }  // namespace dconv

@@ -1,4 +1,4 @@
-// Dispatch of the 16-bit general case: the matrix-core kernel where the shape allows it, the
+// Dispatch of the general case for short data types (fp16, bf16, int8): the matrix-core kernel where the shape allows it, the
 // one-thread-per-output kernel otherwise.
 #include "half_kernel.h"
 
@@ -7,51 +7,48 @@ namespace dconv {
 namespace {
 
 int launch_tiled(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                 bool bf16, bool dry)
+                 int dtype, bool dry)
 {
     switch (s.F) {
-    case 1: return half_launch_for_F<1>(in, filt, out, s, st, bf16, dry);
-    case 2: return half_launch_for_F<2>(in, filt, out, s, st, bf16, dry);
-    case 3: return half_launch_for_F<3>(in, filt, out, s, st, bf16, dry);
-    case 4: return half_launch_for_F<4>(in, filt, out, s, st, bf16, dry);
-    case 5: return half_launch_for_F<5>(in, filt, out, s, st, bf16, dry);
-    case 6: return half_launch_for_F<6>(in, filt, out, s, st, bf16, dry);
-    case 7: return half_launch_for_F<7>(in, filt, out, s, st, bf16, dry);
-    case 8: return half_launch_for_F<8>(in, filt, out, s, st, bf16, dry);
-    case 9: return half_launch_for_F<9>(in, filt, out, s, st, bf16, dry);
-    case 10: return half_launch_for_F<10>(in, filt, out, s, st, bf16, dry);
-    case 11: return half_launch_for_F<11>(in, filt, out, s, st, bf16, dry);
+    case 1: return half_launch_for_F<1>(in, filt, out, s, st, dtype, dry);
+    case 2: return half_launch_for_F<2>(in, filt, out, s, st, dtype, dry);
+    case 3: return half_launch_for_F<3>(in, filt, out, s, st, dtype, dry);
+    case 4: return half_launch_for_F<4>(in, filt, out, s, st, dtype, dry);
+    case 5: return half_launch_for_F<5>(in, filt, out, s, st, dtype, dry);
+    case 6: return half_launch_for_F<6>(in, filt, out, s, st, dtype, dry);
+    case 7: return half_launch_for_F<7>(in, filt, out, s, st, dtype, dry);
+    case 8: return half_launch_for_F<8>(in, filt, out, s, st, dtype, dry);
+    case 9: return half_launch_for_F<9>(in, filt, out, s, st, dtype, dry);
+    case 10: return half_launch_for_F<10>(in, filt, out, s, st, dtype, dry);
+    case 11: return half_launch_for_F<11>(in, filt, out, s, st, dtype, dry);
     default: return DCONV_UNSUPPORTED;
     }
 }
 
 int launch_simple_half(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                       bool bf16)
+                       int dtype)
 {
     const int64_t total = (int64_t)s.N * s.K * s.Ho * s.Wo;
     const int64_t blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 2147483647LL) return DCONV_UNSUPPORTED;
-    const unsigned short* i16 = (const unsigned short*)in;
-    const unsigned short* f16 = (const unsigned short*)filt;
-    if (bf16)
-        hipLaunchKernelGGL(simple_half_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, st,
-                           i16, f16, out, s.N, s.C, s.H, s.W, s.K, s.F, s.Ho, s.Wo);
-    else
-        hipLaunchKernelGGL(simple_half_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, st,
-                           i16, f16, out, s.N, s.C, s.H, s.W, s.K, s.F, s.Ho, s.Wo);
+    auto kern = dtype == kI8 ? simple_half_kernel<kI8>
+              : dtype == kBF16 ? simple_half_kernel<kBF16> : simple_half_kernel<kF16>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kThreads), 0, st,
+                       in, filt, out, s.N, s.C, s.H, s.W, s.K, s.F, s.Ho, s.Wo);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
 }  // namespace
 
 int launch_general_half(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                        bool bf16, int variant)
+                        int dtype, int variant)
 {
-    if (variant == DCONV_VARIANT_SIMPLE) return launch_simple_half(in, filt, out, s, st, bf16);
+    if (dtype != kF16 && dtype != kBF16 && dtype != kI8) return DCONV_UNSUPPORTED;
+    if (variant == DCONV_VARIANT_SIMPLE) return launch_simple_half(in, filt, out, s, st, dtype);
     if (variant != DCONV_VARIANT_AUTO && variant != DCONV_VARIANT_TILED) return DCONV_UNSUPPORTED;
-    const int rc = launch_tiled(in, filt, out, s, st, bf16, false);
+    const int rc = launch_tiled(in, filt, out, s, st, dtype, false);
     if (rc == DCONV_UNSUPPORTED && variant == DCONV_VARIANT_AUTO)
-        return launch_simple_half(in, filt, out, s, st, bf16);
+        return launch_simple_half(in, filt, out, s, st, dtype);
     return rc;
 }
 

@@ -1,5 +1,5 @@
 // Instantiations of the 16-bit general-case kernel for ONE filter side (DCONV_F, given on the
-// compiler command line), fp16 and bf16.
+// compiler command line): fp16, bf16 and int8.
 #include "half_kernel.h"
 
 #ifndef DCONV_F
@@ -17,10 +17,14 @@ constexpr int kRowGroup = F <= 3 ? F : F <= 6 ? 2 : 1;
 
 template <>
 int half_launch_for_F<DCONV_F>(const void* in, const void* filt, float* out, const Shape& s,
-                               hipStream_t st, bool bf16, bool dry)
+                               hipStream_t st, int dtype, bool dry)
 {
-    return bf16 ? half_try_launch<F, kRowGroup, true>(in, filt, out, s, st, dry)
-                : half_try_launch<F, kRowGroup, false>(in, filt, out, s, st, dry);
+    switch (dtype) {
+    case kF16: return half_try_launch<F, kRowGroup, kF16>(in, filt, out, s, st, dry);
+    case kBF16: return half_try_launch<F, kRowGroup, kBF16>(in, filt, out, s, st, dry);
+    case kI8: return half_try_launch<F, kRowGroup, kI8>(in, filt, out, s, st, dry);
+    default: return DCONV_UNSUPPORTED;
+    }
 }
 
 }  // namespace dconv

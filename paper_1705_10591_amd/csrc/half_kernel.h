@@ -26,6 +26,10 @@
 //
 // The channel count must be a multiple of sixteen and both inputs 16-byte aligned; other
 // shapes run on a plain one-thread-per-output kernel.
+//
+// The same kernel serves 8-bit integers (v_mfma_i32_32x32x32_i8: sixteen bytes per lane are
+// sixteen channels, a pixel's 32-byte run is 32 channels, sums are exact in int32): only the
+// element size, the channels per chunk and the matrix-core instruction differ.
 #pragma once
 #include <algorithm>
 #include "common.h"
@@ -36,12 +40,24 @@ namespace dconv {
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef __bf16 v8b __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 
-// D(32x32) += A(32x16) * B(16x32), 16-bit in, fp32 accumulate.  Lane l holds reduction
-// indices 8 * (l / 32) .. + 7 of row (A) / column (B) l % 32; D is laid out as for mfma_32x32x2.
-template <bool BF16>
-__device__ __forceinline__ v16f mfma_32x32x16(v4f a, v4f b, v16f acc) {
-    if (BF16)
+// element types of the short-data-type kernels (the values of DCONV_DTYPE_*)
+enum : int { kF16 = 0, kBF16 = 1, kI8 = 2 };
+constexpr int elem_bytes(int dt) { return dt == kI8 ? 1 : 2; }
+
+// D(32x32) += A(32 x 16 bytes' worth) * B(the same x 32): 16-bit in with fp32 accumulation, or
+// 8-bit integers with int32 accumulation (the accumulator registers then hold integers; they
+// are only ever moved, never added to outside the matrix cores).  Lane l holds the sixteen
+// bytes of reduction indices of half l / 32 of row (A) / column (B) l % 32; D is laid out as
+// for mfma_32x32x2.
+template <int DT>
+__device__ __forceinline__ v16f mfma_16B(v4f a, v4f b, v16f acc) {
+    if (DT == kI8)
+        return __builtin_bit_cast(v16f, __builtin_amdgcn_mfma_i32_32x32x32_i8(
+            __builtin_bit_cast(v4i, a), __builtin_bit_cast(v4i, b), __builtin_bit_cast(v16i, acc), 0, 0, 0));
+    if (DT == kBF16)
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a),
                                                        __builtin_bit_cast(v8b, b), acc, 0, 0, 0);
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a),
@@ -49,9 +65,9 @@ __device__ __forceinline__ v16f mfma_32x32x16(v4f a, v4f b, v16f acc) {
 }
 
 struct HalfParams {
-    const char* in;      // [N][H][W][C], 2-byte elements
+    const char* in;      // [N][H][W][C], 2-byte or 1-byte elements
     const char* filt;    // [K][F][F][C]
-    float* out;          // [N][K][Ho][Wo]
+    float* out;          // [N][K][Ho][Wo], fp32 (int32 bit patterns for 8-bit inputs)
     int N, C, H, W, K, Ho, Wo;
     int bw;              // width of a column strip of the output (the last strip may be narrower)
     int nstrips;
@@ -72,14 +88,15 @@ struct HalfParams {
 };
 
 constexpr int kHalfMT = 64, kHalfNT = 256;
-constexpr int kHalfCK = 16;                    // channels per chunk = reduction indices per step
+constexpr int kHalfChunkBytes = 32;            // bytes of a pixel's channel run per chunk: one step
 constexpr int kHalfImgItems = 6;               // 16-byte image pieces a thread stages per chunk
 
 // RG: filter rows per chunk (the last group of a filter may be shorter).
-template <int F, int RG, bool BF16>
+template <int F, int RG, int DT>
 __global__ void __launch_bounds__(kThreads, 2)
 general_half_kernel(HalfParams p)
 {
+    constexpr int CK = kHalfChunkBytes / elem_bytes(DT);    // channels per chunk
     constexpr int NG = (F + RG - 1) / RG, RGL = F - (NG - 1) * RG;
     constexpr int S = RG * F, SL = RGL * F;             // steps of a chunk / of a last-group chunk
     constexpr int MW = 2, NW = 2, MT = kHalfMT, NT = kHalfNT;
@@ -105,7 +122,7 @@ general_half_kernel(HalfParams p)
     const int img_pieces = 2 * p.RS * LS;
     const int SLOT = FB + 4 * img_pieces;               // words per LDS slot: filter block, image block
     const int64_t plane = (int64_t)p.Ho * p.Wo;
-    const int CB = p.C * 2;                             // bytes per pixel (all channels)
+    const int CB = p.C * elem_bytes(DT);                // bytes per pixel (all channels)
 
     // ---- where the tile lies -------------------------------------------------------------------
     const int per_strip = p.pt_full * p.KB;
@@ -156,15 +173,15 @@ general_half_kernel(HalfParams p)
     const int64_t filt_bytes = (int64_t)p.K * (F * F) * CB;
     const int64_t ifirst = (int64_t)n_first * p.H * p.W * CB;
     const int64_t wfirst = (int64_t)k0 * (F * F) * CB;
-    const int nch = p.C / kHalfCK * NG;
+    const int nch = p.C / CK * NG;
 
     v4f ireg[NII], wreg[NFI];
     auto fetch = [&](int chunk) __attribute__((always_inline)) {
         const int cidx = chunk / NG, g = chunk - cidx * NG;
-        const int64_t ioff = ifirst + (int64_t)g * RG * p.W * CB + cidx * (kHalfCK * 2);
+        const int64_t ioff = ifirst + (int64_t)g * RG * p.W * CB + cidx * kHalfChunkBytes;
         const __amdgpu_buffer_rsrc_t irs = __builtin_amdgcn_make_buffer_rsrc(
             (void*)(p.in + ioff), 0, (int)min(in_bytes - ioff, (int64_t)0x7FFFFFFF), kRsrcFlags);
-        const int64_t woff = wfirst + (int64_t)g * (RG * F) * CB + cidx * (kHalfCK * 2);
+        const int64_t woff = wfirst + (int64_t)g * (RG * F) * CB + cidx * kHalfChunkBytes;
         const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
             (void*)(p.filt + woff), 0, (int)min(filt_bytes - woff, (int64_t)0x7FFFFFFF), kRsrcFlags);
 #pragma unroll
@@ -251,7 +268,7 @@ general_half_kernel(HalfParams p)
             for (int mt = 0; mt < MW; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < NW; ++nt)
-                    acc[mt][nt] = mfma_32x32x16<BF16>(a[mt], b[nt], acc[mt][nt]);
+                    acc[mt][nt] = mfma_16B<DT>(a[mt], b[nt], acc[mt][nt]);
         }
         // slot `nxt` was last read during chunk u-1, which every wave left before the barrier
         // that ended it
@@ -275,9 +292,9 @@ general_half_kernel(HalfParams p)
 }
 
 // One thread per output element, any shape and alignment.
-template <bool BF16>
+template <int DT>
 __global__ void __launch_bounds__(kThreads)
-simple_half_kernel(const unsigned short* in, const unsigned short* filt, float* out,
+simple_half_kernel(const void* in_, const void* filt_, float* out,
                    int N, int C, int H, int W, int K, int F, int Ho, int Wo)
 {
     const int64_t total = (int64_t)N * K * Ho * Wo;
@@ -285,8 +302,23 @@ simple_half_kernel(const unsigned short* in, const unsigned short* filt, float* 
     if (o >= total) return;
     const int x = (int)(o % Wo), y = (int)((o / Wo) % Ho);
     const int k = (int)((o / ((int64_t)Wo * Ho)) % K), n = (int)(o / ((int64_t)Wo * Ho * K));
+    if (DT == kI8) {
+        const signed char* in = (const signed char*)in_;
+        const signed char* filt = (const signed char*)filt_;
+        int acc = 0;
+        for (int i = 0; i < F; ++i)
+            for (int j = 0; j < F; ++j) {
+                const signed char* px = in + (((int64_t)n * H + y + i) * W + x + j) * C;
+                const signed char* wt = filt + (((int64_t)k * F + i) * F + j) * C;
+                for (int c = 0; c < C; ++c) acc += (int)px[c] * (int)wt[c];
+            }
+        out[o] = __builtin_bit_cast(float, acc);
+        return;
+    }
+    const unsigned short* in = (const unsigned short*)in_;
+    const unsigned short* filt = (const unsigned short*)filt_;
     auto cvt = [](unsigned short v) {
-        if (BF16) return __builtin_bit_cast(float, (uint32_t)v << 16);
+        if (DT == kBF16) return __builtin_bit_cast(float, (uint32_t)v << 16);
         return (float)__builtin_bit_cast(_Float16, v);
     };
     float acc = 0.f;
@@ -329,11 +361,12 @@ inline HalfPlan make_half_plan(const Shape& s, int rg)
     return pl;
 }
 
-template <int F, int RG, bool BF16>
+template <int F, int RG, int DT>
 int half_try_launch(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st, bool dry)
 {
     constexpr int MT = kHalfMT, NT = kHalfNT, S = RG * F;
-    if (s.C % kHalfCK != 0) return DCONV_UNSUPPORTED;
+    constexpr int EB = elem_bytes(DT);
+    if (s.C % (kHalfChunkBytes / EB) != 0) return DCONV_UNSUPPORTED;
     const HalfPlan pl = make_half_plan(s, RG);
     if (!pl.ok) return DCONV_UNSUPPORTED;
     const int64_t slot_words = (int64_t)S * MT * 8 + 8LL * pl.RS * pl.LS;
@@ -349,14 +382,14 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
         const int64_t span = NT / ((int64_t)s.Ho * wmin) + 2;
         const int64_t plane = (int64_t)s.Ho * s.Wo;
         const int64_t lim = 1LL << 31;
-        if (span * s.H * s.W * s.C * 2 >= lim || (span * s.K * plane + (MT + 1) * plane) * 4 >= lim ||
-            (int64_t)(MT + 1) * F * F * s.C * 2 >= lim)
+        if (span * s.H * s.W * s.C * EB >= lim || (span * s.K * plane + (MT + 1) * plane) * 4 >= lim ||
+            (int64_t)(MT + 1) * F * F * s.C * EB >= lim)
             return DCONV_UNSUPPORTED;
     }
     if (dry) return DCONV_OK;
     if ((((uintptr_t)in) & 15) != 0 || (((uintptr_t)filt) & 15) != 0) return DCONV_UNSUPPORTED;
 
-    auto kern = general_half_kernel<F, RG, BF16>;
+    auto kern = general_half_kernel<F, RG, DT>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -377,6 +410,6 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
 // Implemented once per filter side, each in its own translation unit.
 template <int F>
 int half_launch_for_F(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                      bool bf16, bool dry);
+                      int dtype, bool dry);
 
 }  // namespace dconv

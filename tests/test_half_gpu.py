@@ -140,3 +140,77 @@ def test_half_config_shapes_sampled(name, kind):
     got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
     acc, mag = oracle.general_at(xr, fr, idx)
     assert_within_bound(got, acc, mag, f"half {kind} {name} sampled")
+
+
+# ---- 8-bit integers: exact int32 sums, compared bit for bit -----------------------------------
+
+def int8_case(seed, shape):
+    N, C, H, W, K, F = shape
+    rng = np.random.default_rng(1705 + seed)
+    x = rng.integers(-128, 128, size=(N, C, H, W)).astype(np.int8)
+    f = rng.integers(-128, 128, size=(K, C, F, F)).astype(np.int8)
+    return x, f
+
+
+def run_i8(x, f, variant):
+    print(f"int8 N,C,H,W={x.shape} K,F={f.shape[0]},{f.shape[-1]} variant={variant}", flush=True)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(np.moveaxis(a, 1, -1))).to("cuda")
+    out = dconv.dconv_general_i8(to_dev(x), to_dev(f), variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def exact_i8(x, f):
+    """The oracle's fp64 sums are exact here (all terms are integers below 2**14, at most a few
+    thousand of them)."""
+    acc, _, _ = oracle.general(x.astype(np.float32), f.astype(np.float32))
+    assert np.array_equal(acc, np.rint(acc))
+    return acc.astype(np.int64)
+
+
+I8_SHAPES = [
+    (2, 32, 20, 23, 5, 3), (1, 64, 30, 30, 70, 3), (3, 32, 28, 28, 130, 3), (2, 32, 24, 150, 33, 5),
+    (1, 96, 12, 300, 8, 2), (2, 32, 27, 31, 64, 11), (1, 64, 9, 9, 3, 1), (1, 32, 20, 20, 9, 7),
+    (5, 32, 8, 8, 4, 3), (3, 32, 5, 5, 4, 5), (1, 32, 13, 12, 3, 10), (7, 64, 9, 35, 96, 3),
+]
+
+
+@pytest.mark.parametrize("shape", I8_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_int8_small_shapes_are_exact(shape):
+    x, f = int8_case(shape[-1], shape)
+    want = exact_i8(x, f)
+    for variant in (TILED, SIMPLE):
+        np.testing.assert_array_equal(run_i8(x, f, variant).astype(np.int64), want)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 20, 23, 5, 3), (1, 48, 14, 15, 7, 5), (2, 16, 9, 9, 2, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_int8_channel_counts_without_a_matrix_core_kernel_fall_back(shape):
+    x, f = int8_case(11, shape)
+    np.testing.assert_array_equal(run_i8(x, f, AUTO).astype(np.int64), exact_i8(x, f))
+    with pytest.raises(dconv.DconvError) as e:
+        run_i8(x, f, TILED)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
+
+
+def test_int8_extreme_values_do_not_overflow_early():
+    """All pixels and weights at -128: the largest products; C*F*F*2**14 still fits int32."""
+    shape = (1, 64, 12, 40, 3, 5)
+    N, C, H, W, K, F = shape
+    x = np.full((N, C, H, W), -128, np.int8)
+    f = np.full((K, C, F, F), -128, np.int8)
+    got = run_i8(x, f, TILED)
+    assert (got == C * F * F * 16384).all()
+
+
+@pytest.mark.parametrize("name", ["G2", "G3"])
+def test_int8_config_shapes_sampled(name):
+    w = wl.CONFIGS[name]
+    x, f = int8_case(77, (w.N, w.C, w.H, w.W, w.K, w.F))
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(np.moveaxis(a, 1, -1))).to("cuda")
+    out = dconv.dconv_general_i8(to_dev(x), to_dev(f), variant=TILED)
+    torch.cuda.synchronize()
+    idx = wl.sample_indices(32, out.numel(), 4000)
+    got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy().astype(np.int64)
+    acc, _ = oracle.general_at(x.astype(np.float32), f.astype(np.float32), idx)
+    np.testing.assert_array_equal(got, acc.astype(np.int64))
