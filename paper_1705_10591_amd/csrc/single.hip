@@ -342,8 +342,9 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
 // on 4096 x 4096 images with 64 filters: the output stream bounds the time up to 5x5 and wide
 // tiles (fewer first-of-row passes, which cannot take over a block) win; from 7x7 on the matrix
 // cores bound it and, for the largest filters, taller tiles (fewer halo rows staged per output
-// row) win.  Small images get small tiles so that the launch still covers the chip.
-constexpr int kSingleConfigs = 4;
+// row) win.  Small images get small tiles so that the launch still covers the chip; with up to
+// 32 filters (one filter block, rows dealt to the waves) the smallest, 128 x 4.
+constexpr int kSingleConfigs = 5;
 
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
@@ -356,22 +357,31 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
             return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
         };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
-        if (F <= 4) {
+        const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4);
+        if (s.K <= 32 && t128 < ((F <= 4 && s.K > 16) ? 8192 : 1536)) {
+            // one filter block: the four waves of a workgroup take one row each, and on images up
+            // to about 768^2 (1080p for a full block of small filters) the smallest tile, one pass
+            // per wave, is the shortest chain of latencies
+            cfg = 4;
+        } else if (s.K <= 32 && F < 8 && s.Wo < 3072) {
+            cfg = 0;
+        } else if (F <= 4) {
             cfg = items(512, 4) < 1280 ? 3 : 0;
         } else if (items(512, 4) < 384) {
             cfg = 3;
         } else if (F >= 8) {
             cfg = items(512, 8) >= 512 ? 2 : 0;
-        } else if (s.Wo >= 3072) {
-            cfg = 1;
         } else {
-            cfg = items(512, 8) >= 256 ? 2 : 0;
+            // 5x5 .. 7x7: the small tile keeps its lead over a wide range of mid-sized problems
+            const int64_t it = items(512, 4);
+            cfg = (it >= 520 && it < 4200) ? 3 : 0;
         }
     }
     switch (cfg) {
     case 1: return launch_cfg<F, 1024, 4, 4, 2>(img, filt, out, s, st);
     case 2: return launch_cfg<F, 512, 8, 4, 3>(img, filt, out, s, st);
     case 3: return launch_cfg<F, 256, 2, 4, 3>(img, filt, out, s, st);
+    case 4: return launch_cfg<F, 128, 4, 4, 3>(img, filt, out, s, st);
     default: return launch_cfg<F, 512, 4, 4, 3>(img, filt, out, s, st);
     }
 }

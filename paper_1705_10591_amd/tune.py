@@ -73,7 +73,10 @@ TABLE_SINGLE = [(4096, 4096, 64, 5), (4096, 4096, 64, 3), (4096, 4096, 64, 7), (
                 (2048, 2048, 64, 5), (2048, 2048, 64, 9), (1024, 1024, 64, 5), (1024, 1024, 64, 9),
                 (1024, 1024, 64, 3), (512, 512, 64, 3), (1080, 1920, 32, 3), (1080, 1920, 64, 7),
                 (256, 256, 16, 3), (1536, 1536, 128, 3), (3000, 3000, 64, 5), (2048, 2048, 256, 5),
-                (720, 1280, 96, 5)]
+                (720, 1280, 96, 5),
+                # up to 32 filters: one filter block, rows dealt to the waves
+                (256, 256, 32, 5), (512, 512, 32, 3), (768, 768, 16, 3), (768, 768, 32, 5),
+                (1024, 1024, 16, 3), (1024, 1024, 16, 5), (1024, 1024, 32, 7), (2048, 2048, 16, 3)]
 TABLE_GENERAL = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (64, 3, 224, 224, 64, 11),
                  (32, 128, 56, 56, 128, 3), (32, 256, 14, 14, 256, 3), (16, 64, 112, 112, 128, 3),
                  (64, 32, 32, 32, 32, 3), (32, 96, 27, 27, 256, 5), (16, 64, 224, 224, 64, 3),
