@@ -127,7 +127,9 @@ int dconv_general_f16(const void *in, int N, int C, int H, int W,
 int dconv_general_bf16(const void *in, int N, int C, int H, int W,
                        const void *filt, int K, int F,
                        float *out, void *stream);
-/* dtype: DCONV_DTYPE_F16 or _BF16; variant: DCONV_VARIANT_AUTO, _SIMPLE or _TILED. */
+/* dtype: DCONV_DTYPE_F16 or _BF16; variant: DCONV_VARIANT_AUTO, _SIMPLE, _TILED, or
+ * DCONV_VARIANT_TILED_CFG0 + i to force a tile shape of the matrix-core kernel
+ * (0: 64 filters x 256 pixels, 1: 128 x 512), for tests and tuning. */
 int dconv_general_half_v(const void *in, int N, int C, int H, int W,
                          const void *filt, int K, int F,
                          float *out, int dtype, int variant, void *stream);

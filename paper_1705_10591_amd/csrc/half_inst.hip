@@ -10,21 +10,27 @@ namespace dconv {
 
 namespace {
 constexpr int F = DCONV_F;
-// filter rows per chunk: 7 to 12 matrix-core steps per chunk where the filter allows it (a
-// step is one tap of sixteen channels); the filter block of a chunk is 2 KiB per step
-constexpr int kRowGroup = F <= 3 ? F : F <= 6 ? 2 : 1;
+constexpr int kRowGroup = half_row_group(F);
 }  // namespace
+
+template <class TL>
+int launch_dtype(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
+                 int dtype, bool dry)
+{
+    switch (dtype) {
+    case kF16: return half_try_launch<F, kRowGroup, kF16, TL>(in, filt, out, s, st, dry);
+    case kBF16: return half_try_launch<F, kRowGroup, kBF16, TL>(in, filt, out, s, st, dry);
+    case kI8: return half_try_launch<F, kRowGroup, kI8, TL>(in, filt, out, s, st, dry);
+    default: return DCONV_UNSUPPORTED;
+    }
+}
 
 template <>
 int half_launch_for_F<DCONV_F>(const void* in, const void* filt, float* out, const Shape& s,
-                               hipStream_t st, int dtype, bool dry)
+                               hipStream_t st, int dtype, bool large_tile, bool dry)
 {
-    switch (dtype) {
-    case kF16: return half_try_launch<F, kRowGroup, kF16>(in, filt, out, s, st, dry);
-    case kBF16: return half_try_launch<F, kRowGroup, kBF16>(in, filt, out, s, st, dry);
-    case kI8: return half_try_launch<F, kRowGroup, kI8>(in, filt, out, s, st, dry);
-    default: return DCONV_UNSUPPORTED;
-    }
+    return large_tile ? launch_dtype<HalfTileLarge>(in, filt, out, s, st, dtype, dry)
+                      : launch_dtype<HalfTileSmall>(in, filt, out, s, st, dtype, dry);
 }
 
 }  // namespace dconv

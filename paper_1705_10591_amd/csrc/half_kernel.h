@@ -87,22 +87,41 @@ struct HalfParams {
     FastDiv d_ls;        // by LS
 };
 
-constexpr int kHalfMT = 64, kHalfNT = 256;
 constexpr int kHalfChunkBytes = 32;            // bytes of a pixel's channel run per chunk: one step
-constexpr int kHalfImgItems = 6;               // 16-byte image pieces a thread stages per chunk
+// Filter rows per chunk: 7 to 12 matrix-core steps per chunk where the filter allows it (a step
+// is one tap of a 32-byte channel run); the filter block of a chunk is 2 KiB per step and 64 filters.
+constexpr int half_row_group(int F) { return F <= 3 ? F : F <= 6 ? 2 : 1; }
+
+// Tile shapes: WM x WN waves per workgroup, each with MW x NW matrix-core blocks; NII: 16-byte
+// image pieces a thread stages per chunk, at most.
+//   small: 64 filters x 256 pixels, four waves side by side with 2 x 2 blocks each
+//   large: 128 filters x 512 pixels, 2 x 4 waves with 2 x 4 blocks each: a quarter fewer LDS
+//          operand reads per matrix-core instruction (six per eight instead of four per four),
+//          half the staging per instruction, chunks twice as long; 512 threads, one workgroup
+//          per CU
+template <int MW_, int NW_, int WM_, int WN_, int NII_>
+struct HalfTile {
+    static constexpr int MW = MW_, NW = NW_, WM = WM_, WN = WN_, NII = NII_;
+    static constexpr int THREADS = kWave * WM * WN;
+    static constexpr int MT = 32 * MW * WM, NT = 32 * NW * WN;
+    static constexpr int WPS = THREADS / 256;           // waves per SIMD the workgroup brings: 2 in all
+};
+using HalfTileSmall = HalfTile<2, 2, 1, 4, 6>;
+using HalfTileLarge = HalfTile<2, 4, 2, 4, 4>;
 
 // RG: filter rows per chunk (the last group of a filter may be shorter).
-template <int F, int RG, int DT>
-__global__ void __launch_bounds__(kThreads, 2)
+template <int F, int RG, int DT, class TL>
+__global__ void __launch_bounds__(TL::THREADS, 2)
 general_half_kernel(HalfParams p)
 {
+    constexpr int THREADS = TL::THREADS;
     constexpr int CK = kHalfChunkBytes / elem_bytes(DT);    // channels per chunk
     constexpr int NG = (F + RG - 1) / RG, RGL = F - (NG - 1) * RG;
     constexpr int S = RG * F, SL = RGL * F;             // steps of a chunk / of a last-group chunk
-    constexpr int MW = 2, NW = 2, MT = kHalfMT, NT = kHalfNT;
+    constexpr int MW = TL::MW, NW = TL::NW, WN = TL::WN, MT = TL::MT, NT = TL::NT;
     constexpr int FPIECES = S * MT * 2;                 // 16-byte pieces of the filter block
-    constexpr int NFI = (FPIECES + kThreads - 1) / kThreads;
-    constexpr int NII = kHalfImgItems;
+    constexpr int NFI = (FPIECES + THREADS - 1) / THREADS;
+    constexpr int NII = TL::NII;
     constexpr int FB = FPIECES * 4;                     // words of the filter block
     constexpr uint32_t kNowhere = 0xC0000000u;          // beyond every extent (at most 2^31)
     constexpr int kRsrcFlags = 0x00020000;
@@ -113,6 +132,7 @@ general_half_kernel(HalfParams p)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, l32 = lane & 31;
+    const int wm = wave / WN, wn = wave % WN;
 
     // each XCD (workgroups go to the eight of them round-robin) gets a contiguous run of tiles
     const int tile = (int)(blockIdx.x % 8) * p.per_xcd + (int)(blockIdx.x / 8);
@@ -149,7 +169,7 @@ general_half_kernel(HalfParams p)
     uint32_t ig[NII];        // from in[n_first][0][0][0] (+ chunk shift), or kNowhere
 #pragma unroll
     for (int it = 0; it < NII; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * THREADS;
         uint32_t g = kNowhere;
         if (e < img_pieces) {
             const int pix = e >> 1, half = e & 1;
@@ -164,7 +184,7 @@ general_half_kernel(HalfParams p)
     uint32_t wg[NFI];        // from filt[k0][group's first row][0][0] (+ channel shift)
 #pragma unroll
     for (int it = 0; it < NFI; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * THREADS;
         const int t = e / (2 * MT), k = (e >> 1) % MT, half = e & 1;
         // (filters beyond K lie beyond the end of the bank: the range check returns zero)
         wg[it] = e < FPIECES ? (uint32_t)((k * (F * F) + t) * CB + half * 16) : kNowhere;
@@ -193,41 +213,50 @@ general_half_kernel(HalfParams p)
     };
     // pieces beyond the blocks go to sixteen spare bytes behind the slots
     const int trash = 2 * SLOT;
-    auto commit = [&](float* slot) __attribute__((always_inline)) {
-#pragma unroll
-        for (int it = 0; it < NII; ++it) {
-            const int e = tid + it * kThreads;
-            *reinterpret_cast<v4f*>(e < img_pieces ? slot + FB + 4 * e : lds + trash) = ireg[it];
-        }
-#pragma unroll
-        for (int it = 0; it < NFI; ++it) {
-            const int e = tid + it * kThreads;
-            *reinterpret_cast<v4f*>(e < FPIECES ? slot + 4 * e : lds + trash) = wreg[it];
+    // staging item k < NII is an image piece, item NII + q a filter piece
+    constexpr int NI = NII + NFI;
+    auto commit_item = [&](int k, float* slot) __attribute__((always_inline)) {
+        if (k < NII) {
+            const int e = tid + k * THREADS;
+            *reinterpret_cast<v4f*>(e < img_pieces ? slot + FB + 4 * e : lds + trash) = ireg[k];
+        } else {
+            const int e = tid + (k - NII) * THREADS;
+            *reinterpret_cast<v4f*>(e < FPIECES ? slot + 4 * e : lds + trash) = wreg[k - NII];
         }
     };
+    auto commit = [&](float* slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < NI; ++k) commit_item(k, slot);
+    };
+    // Inside a chunk the items go to the other slot during the second half of the steps, a few
+    // per step, so that their LDS writes issue between matrix-core instructions: item k at step
+    // kFirstCommit + k / kPerStep (the loads were all issued when the chunk began).
+    constexpr int kFirstCommit = S / 2;
+    constexpr int kPerStep = (NI + (S - kFirstCommit) - 1) / (S - kFirstCommit);
 
     // ---- the compute side ------------------------------------------------------------------------
     int base[NW];            // LDS word (within a slot) of the lane's 16 bytes of its pixel at tap (0, 0)
-    uint32_t oofs[NW];       // byte offset of out[n][k0 + 32*mt.. + 4*h][y][x] from out[n_first][k0][0][0]
+    uint32_t oofs[NW];       // byte offset of out[n][k0 + 32*wm*MW + 4*h][y][x] from out[n_first][k0][0][0]
     bool valid[NW];
-    const int kleft = p.K - k0 - 4 * h;
+    const int kleft = p.K - k0 - 32 * wm * MW - 4 * h;
     float* obase_t = p.out + ((int64_t)n_first * p.K + k0) * plane;
     {
         const int kplane = p.K * (int)plane;
 #pragma unroll
         for (int nt = 0; nt < NW; ++nt) {
-            const int pp = p0 + (wave * NW + nt) * 32 + l32;
+            const int pp = p0 + (wn * NW + nt) * 32 + l32;
             valid[nt] = pp < total_p;
             const int pc = valid[nt] ? pp : total_p - 1;
             const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
             const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
             base[nt] = FB + ((((n - n_first) * p.Hc + y - y_first) * LS + xl) * 2 + h) * 4;
-            oofs[nt] = (uint32_t)((n - n_first) * kplane + (4 * h) * (int)plane + y * p.Wo + x0 + xl) * 4u;
+            oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
+                                  y * p.Wo + x0 + xl) * 4u;
         }
     }
     int wb[MW];
 #pragma unroll
-    for (int mt = 0; mt < MW; ++mt) wb[mt] = ((mt * 32 + l32) * 2 + h) * 4;
+    for (int mt = 0; mt < MW; ++mt) wb[mt] = (((wm * MW + mt) * 32 + l32) * 2 + h) * 4;
     auto load_ops = [&](int s, const float* slot, v4f (&a)[MW], v4f (&b)[NW]) __attribute__((always_inline)) {
         const int i = s / F, j = s % F;
 #pragma unroll
@@ -264,15 +293,24 @@ general_half_kernel(HalfParams p)
             v4f (&b)[NW] = (s & 1) ? b1 : b0;
             const bool last_step = s == S - 1 || (s == SL - 1 && shortg);
             if (!last_step) load_ops(s + 1, cur, (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
+            // slot `nxt` was last read during chunk u-1, which every wave left before the barrier
+            // that ended it
+            if (s >= kFirstCommit && u + 1 < nch) {
+#pragma unroll
+                for (int q = 0; q < kPerStep; ++q)
+                    if ((s - kFirstCommit) * kPerStep + q < NI) commit_item((s - kFirstCommit) * kPerStep + q, nxt);
+            }
 #pragma unroll
             for (int mt = 0; mt < MW; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < NW; ++nt)
                     acc[mt][nt] = mfma_16B<DT>(a[mt], b[nt], acc[mt][nt]);
         }
-        // slot `nxt` was last read during chunk u-1, which every wave left before the barrier
-        // that ended it
-        if (u + 1 < nch) commit(nxt);
+        if (shortg && u + 1 < nch) {             // the items of the steps that were left out
+#pragma unroll
+            for (int k = 0; k < NI; ++k)
+                if (kFirstCommit + k / kPerStep >= SL) commit_item(k, nxt);
+        }
         __syncthreads();
     }
 
@@ -338,12 +376,11 @@ struct HalfPlan {
     bool ok;
 };
 
-// The widest column strips (at most 128 columns) whose image block a workgroup can stage with
-// kHalfImgItems pieces per thread.
-inline HalfPlan make_half_plan(const Shape& s, int rg)
+// The widest column strips (at most 128 columns) whose image block a workgroup of `threads`
+// threads can stage with `nii` pieces per thread, for tiles of NT pixels.
+inline HalfPlan make_half_plan(const Shape& s, int rg, int NT, int nii, int threads)
 {
     HalfPlan pl{};
-    constexpr int NT = kHalfNT;
     for (int nstrips = (s.Wo + 127) / 128; nstrips <= s.Wo; ++nstrips) {
         pl.bw = (s.Wo + nstrips - 1) / nstrips;
         pl.nstrips = (s.Wo + pl.bw - 1) / pl.bw;
@@ -355,19 +392,19 @@ inline HalfPlan make_half_plan(const Shape& s, int rg)
         pl.RS = rows + (rg - 1) * (cross + 1);
         pl.pt_full = (int)(((int64_t)s.N * s.Ho * pl.bw + NT - 1) / NT);
         pl.pt_last = (int)(((int64_t)s.N * s.Ho * wmin + NT - 1) / NT);
-        if (2LL * pl.RS * pl.LS <= (int64_t)kHalfImgItems * kThreads) { pl.ok = true; return pl; }
+        if (2LL * pl.RS * pl.LS <= (int64_t)nii * threads) { pl.ok = true; return pl; }
     }
     pl.ok = false;
     return pl;
 }
 
-template <int F, int RG, int DT>
+template <int F, int RG, int DT, class TL>
 int half_try_launch(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st, bool dry)
 {
-    constexpr int MT = kHalfMT, NT = kHalfNT, S = RG * F;
+    constexpr int MT = TL::MT, NT = TL::NT, S = RG * F;
     constexpr int EB = elem_bytes(DT);
     if (s.C % (kHalfChunkBytes / EB) != 0) return DCONV_UNSUPPORTED;
-    const HalfPlan pl = make_half_plan(s, RG);
+    const HalfPlan pl = make_half_plan(s, RG, NT, TL::NII, TL::THREADS);
     if (!pl.ok) return DCONV_UNSUPPORTED;
     const int64_t slot_words = (int64_t)S * MT * 8 + 8LL * pl.RS * pl.LS;
     const int64_t lds_bytes = 4 * (2 * slot_words + 4);
@@ -389,7 +426,7 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
     if (dry) return DCONV_OK;
     if ((((uintptr_t)in) & 15) != 0 || (((uintptr_t)filt) & 15) != 0) return DCONV_UNSUPPORTED;
 
-    auto kern = general_half_kernel<F, RG, DT>;
+    auto kern = general_half_kernel<F, RG, DT, TL>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -403,13 +440,13 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
                  make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
                  make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho),
                  make_fastdiv(s.Ho + RG - 1), make_fastdiv(pl.LS)};
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(kThreads), (size_t)lds_bytes, st, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(TL::THREADS), (size_t)lds_bytes, st, p);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
 // Implemented once per filter side, each in its own translation unit.
 template <int F>
 int half_launch_for_F(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                      int dtype, bool dry);
+                      int dtype, bool large_tile, bool dry);
 
 }  // namespace dconv

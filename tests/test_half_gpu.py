@@ -16,6 +16,9 @@ pytestmark = pytest.mark.gpu
 
 SIMPLE, TILED, AUTO = dconv.VARIANT_SIMPLE, dconv.VARIANT_TILED, dconv.VARIANT_AUTO
 TORCH_TYPE = {"f16": torch.float16, "bf16": torch.bfloat16}
+# the matrix-core kernel with its tile shape forced: 64 filters x 256 pixels, 128 x 512
+TILE_SMALL, TILE_LARGE = dconv.VARIANT_TILED_CFG0, dconv.VARIANT_TILED_CFG0 + 1
+KERNELS = [TILED, SIMPLE, TILE_SMALL, TILE_LARGE]
 
 
 def dev16(bits_nchw_like: np.ndarray, kind: str) -> torch.Tensor:
@@ -65,7 +68,7 @@ HALF_SHAPES = [
 def test_half_small_shapes(shape, kind):
     xr, fr, xb, fb = rounded_case(900 + shape[-1], shape, kind)
     acc, mag, _ = oracle.general(xr, fr)
-    for variant in (TILED, SIMPLE):
+    for variant in KERNELS:
         got = run_half(xb, fb, kind, variant)
         assert_within_bound(got, acc, mag, f"half {kind} {shape} variant {variant}")
 
@@ -77,7 +80,7 @@ def test_half_integer_inputs_are_bit_exact(shape, kind):
     xr, fr, xb, fb = rounded_case(3, shape, kind, integer=True)
     assert np.array_equal(xr, wl.integer_case(3, *shape)[0])        # small integers are representable
     _, _, o32, _ = oracle.general(xr, fr, want32=True)
-    for variant in (TILED, SIMPLE):
+    for variant in KERNELS:
         np.testing.assert_array_equal(run_half(xb, fb, kind, variant), o32)
 
 
@@ -103,10 +106,11 @@ def test_half_non_finite_filter_stays_in_its_own_map(kind):
         fbad = fb.copy()
         fbad[bad] = inf_bits + 1            # a NaN pattern
         fbad[bad, 0, 0, 0] = inf_bits
-        got = run_half(xb, fbad, kind, TILED)
-        assert not np.isfinite(got[:, bad]).any()
-        keep = [k for k in range(shape[4]) if k != bad]
-        assert_within_bound(got[:, keep], acc[:, keep], mag[:, keep], f"half {kind} filter {bad} non-finite")
+        for variant in (TILE_SMALL, TILE_LARGE):
+            got = run_half(xb, fbad, kind, variant)
+            assert not np.isfinite(got[:, bad]).any()
+            keep = [k for k in range(shape[4]) if k != bad]
+            assert_within_bound(got[:, keep], acc[:, keep], mag[:, keep], f"half {kind} filter {bad} non-finite")
 
 
 def test_half_output_guard_bands_stay_untouched():
@@ -118,22 +122,25 @@ def test_half_output_guard_bands_stay_untouched():
     n_out, guard = N * K * Ho * Wo, 4096
     buf = torch.full((n_out + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
     out = buf[guard:guard + n_out].view(N, K, Ho, Wo)
-    dconv.dconv_general_half(dev16(xb, "f16"), dev16(fb, "f16"), out=out, variant=TILED)
-    torch.cuda.synchronize()
-    host = buf.cpu().numpy()
-    assert np.isnan(host[:guard]).all() and np.isnan(host[guard + n_out:]).all()
-    assert_within_bound(host[guard:guard + n_out].reshape(N, K, Ho, Wo), acc, mag, "half guard bands")
+    for variant in (TILE_SMALL, TILE_LARGE):
+        buf.fill_(float("nan"))
+        dconv.dconv_general_half(dev16(xb, "f16"), dev16(fb, "f16"), out=out, variant=variant)
+        torch.cuda.synchronize()
+        host = buf.cpu().numpy()
+        assert np.isnan(host[:guard]).all() and np.isnan(host[guard + n_out:]).all()
+        assert_within_bound(host[guard:guard + n_out].reshape(N, K, Ho, Wo), acc, mag, "half guard bands")
 
 
+@pytest.mark.parametrize("variant", [TILED, TILE_SMALL, TILE_LARGE], ids=["auto", "small", "large"])
 @pytest.mark.parametrize("kind", ["f16", "bf16"])
 @pytest.mark.parametrize("name", ["G2", "G3"])
-def test_half_config_shapes_sampled(name, kind):
+def test_half_config_shapes_sampled(name, kind, variant):
     """The fp32 benchmark shapes G2 and G3 (channel counts 64 and 256) with 16-bit inputs."""
     w = wl.CONFIGS[name]
     x, f = wl.make_inputs(w)
     xr, xb = wl.to_16bit(x.reshape(w.N, w.C, w.H, w.W), kind)
     fr, fb = wl.to_16bit(f.reshape(w.K, w.C, w.F, w.F), kind)
-    out = dconv.dconv_general_half(dev16(xb, kind), dev16(fb, kind), variant=TILED)
+    out = dconv.dconv_general_half(dev16(xb, kind), dev16(fb, kind), variant=variant)
     torch.cuda.synchronize()
     total = out.numel()
     idx = wl.sample_indices(31, total, 4000)
@@ -179,7 +186,7 @@ I8_SHAPES = [
 def test_int8_small_shapes_are_exact(shape):
     x, f = int8_case(shape[-1], shape)
     want = exact_i8(x, f)
-    for variant in (TILED, SIMPLE):
+    for variant in KERNELS:
         np.testing.assert_array_equal(run_i8(x, f, variant).astype(np.int64), want)
 
 
@@ -203,12 +210,13 @@ def test_int8_extreme_values_do_not_overflow_early():
     assert (got == C * F * F * 16384).all()
 
 
+@pytest.mark.parametrize("variant", [TILED, TILE_SMALL, TILE_LARGE], ids=["auto", "small", "large"])
 @pytest.mark.parametrize("name", ["G2", "G3"])
-def test_int8_config_shapes_sampled(name):
+def test_int8_config_shapes_sampled(name, variant):
     w = wl.CONFIGS[name]
     x, f = int8_case(77, (w.N, w.C, w.H, w.W, w.K, w.F))
     to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(np.moveaxis(a, 1, -1))).to("cuda")
-    out = dconv.dconv_general_i8(to_dev(x), to_dev(f), variant=TILED)
+    out = dconv.dconv_general_i8(to_dev(x), to_dev(f), variant=variant)
     torch.cuda.synchronize()
     idx = wl.sample_indices(32, out.numel(), 4000)
     got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy().astype(np.int64)
