@@ -14,11 +14,14 @@
 // staged in LDS with the next chunk prefetched into registers during the arithmetic (the
 // paper's double buffering, Sec. 4.3), the image block kept as it lies in memory and read at
 // shifted addresses.  No transposition is needed on the way into LDS: both blocks are copied
-// in 16-byte pieces, pixel after pixel and tap after tap.
+// in 16-byte pieces, pixel after pixel and tap after tap.  What bounds the kernel on chip is
+// what the paper names for its general case (Sec. 4.3): the bandwidth of the on-chip memory,
+// 16 bytes per lane, operand and matrix-core instruction.
 //
 //  * tile: 64 filters x 256 output pixels, four waves side by side, each 64 filters x 64
-//    pixels = 2 x 2 matrix-core blocks; pixels are numbered along (n, y, x) of a column strip
-//    as in the fp32 kernel, so narrow maps lose no lanes;
+//    pixels = 2 x 2 matrix-core blocks (or 128 x 512 with eight waves of 2 x 4 blocks, see
+//    HalfTile); pixels are numbered along (n, y, x) of a column strip as in the fp32 kernel,
+//    so narrow maps lose no lanes;
 //  * chunk: sixteen channels x RG filter rows; one step per tap (i, j) of the group; the image
 //    block of a chunk holds only the input rows its row group touches;
 //  * loads go through range-checked buffer descriptors (zero beyond the extent: filters beyond
@@ -104,7 +107,6 @@ struct HalfTile {
     static constexpr int MW = MW_, NW = NW_, WM = WM_, WN = WN_, NII = NII_;
     static constexpr int THREADS = kWave * WM * WN;
     static constexpr int MT = 32 * MW * WM, NT = 32 * NW * WN;
-    static constexpr int WPS = THREADS / 256;           // waves per SIMD the workgroup brings: 2 in all
 };
 using HalfTileSmall = HalfTile<2, 2, 1, 4, 6>;
 using HalfTileLarge = HalfTile<2, 4, 2, 4, 4>;
