@@ -215,15 +215,24 @@ general_half_kernel(HalfParams p)
     };
     // pieces beyond the blocks go to sixteen spare bytes behind the slots
     const int trash = 2 * SLOT;
+    // In LDS the two 16-byte halves of a 32-byte channel run lie in two planes, so that the 32
+    // lanes of a half-wave (all of one half: that is the matrix-core operand layout) read 512
+    // contiguous bytes instead of every other 16-byte piece, which would use half the banks:
+    // image block [half][row][col] x 16 B, filter block [tap][half][filter] x 16 B.  Piece e of
+    // a block is (pixel or tap-and-filter e / 2, half e % 2), as in HBM.
+    static_assert(THREADS % (2 * MT) == 0, "a thread's filter pieces differ by whole taps");
+    const int img_plane = p.RS * LS;                    // pieces per plane of the image block
+    const int ipos = (tid & 1) * img_plane + (tid >> 1);                       // + it * THREADS / 2
+    const int wpos = (tid / (2 * MT)) * (2 * MT) + (tid & 1) * MT + (tid >> 1) % MT;   // + it * THREADS
     // staging item k < NII is an image piece, item NII + q a filter piece
     constexpr int NI = NII + NFI;
     auto commit_item = [&](int k, float* slot) __attribute__((always_inline)) {
         if (k < NII) {
             const int e = tid + k * THREADS;
-            *reinterpret_cast<v4f*>(e < img_pieces ? slot + FB + 4 * e : lds + trash) = ireg[k];
+            *reinterpret_cast<v4f*>(e < img_pieces ? slot + FB + 4 * (ipos + k * (THREADS / 2)) : lds + trash) = ireg[k];
         } else {
             const int e = tid + (k - NII) * THREADS;
-            *reinterpret_cast<v4f*>(e < FPIECES ? slot + 4 * e : lds + trash) = wreg[k - NII];
+            *reinterpret_cast<v4f*>(e < FPIECES ? slot + 4 * (wpos + (k - NII) * THREADS) : lds + trash) = wreg[k - NII];
         }
     };
     auto commit = [&](float* slot) __attribute__((always_inline)) {
@@ -251,19 +260,19 @@ general_half_kernel(HalfParams p)
             const int pc = valid[nt] ? pp : total_p - 1;
             const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
             const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
-            base[nt] = FB + ((((n - n_first) * p.Hc + y - y_first) * LS + xl) * 2 + h) * 4;
+            base[nt] = FB + (h * (p.RS * LS) + ((n - n_first) * p.Hc + y - y_first) * LS + xl) * 4;
             oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
                                   y * p.Wo + x0 + xl) * 4u;
         }
     }
     int wb[MW];
 #pragma unroll
-    for (int mt = 0; mt < MW; ++mt) wb[mt] = (((wm * MW + mt) * 32 + l32) * 2 + h) * 4;
+    for (int mt = 0; mt < MW; ++mt) wb[mt] = (h * MT + (wm * MW + mt) * 32 + l32) * 4;
     auto load_ops = [&](int s, const float* slot, v4f (&a)[MW], v4f (&b)[NW]) __attribute__((always_inline)) {
         const int i = s / F, j = s % F;
 #pragma unroll
         for (int nt = 0; nt < NW; ++nt)
-            b[nt] = *reinterpret_cast<const v4f*>(slot + base[nt] + (i * LS + j) * 8);
+            b[nt] = *reinterpret_cast<const v4f*>(slot + base[nt] + (i * LS + j) * 4);
 #pragma unroll
         for (int mt = 0; mt < MW; ++mt)
             a[mt] = *reinterpret_cast<const v4f*>(slot + wb[mt] + s * (MT * 8));
