@@ -475,6 +475,11 @@ general_tiled_kernel(GenParams p)
     set_chunk(fchunk);
 #pragma unroll
     for (int w = 0; w < NI; ++w) fetch_item(w);
+    // (the compute-side setup runs while the first loads are on their way)
+    int tile = ftile_first, chunk = u0 - tile * nch;       // the unit being consumed
+    bool from_first = chunk == 0;                          // this workgroup summed the tile's chunk 0
+    setup_compute(tile);
+    zero_acc();
 #pragma unroll
     for (int w = 0; w < NI; ++w) commit_item(w, lds);
     auto advance_fetch = [&]() __attribute__((always_inline)) {
@@ -484,10 +489,6 @@ general_tiled_kernel(GenParams p)
     if (u0 + 1 < u1) advance_fetch();
 #pragma unroll
     for (int w = 0; w < NI; ++w) fetch_item(w);           // unit u0+1 (or u0 again: never used)
-    int tile = ftile_first, chunk = u0 - tile * nch;       // the unit being consumed
-    bool from_first = chunk == 0;                          // this workgroup summed the tile's chunk 0
-    setup_compute(tile);
-    zero_acc();
     __syncthreads();
 
     auto is_short = [&](int ch) __attribute__((always_inline)) { return TL != T && ch % NG == NG - 1; };
