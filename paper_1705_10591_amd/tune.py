@@ -9,7 +9,8 @@ that the rules can be checked or re-derived on another chip.
 
     python -m paper_1705_10591_amd.tune single H W K F
     python -m paper_1705_10591_amd.tune general N C H W K F
-    python -m paper_1705_10591_amd.tune table single|general     (the shapes the rules were set on)
+    python -m paper_1705_10591_amd.tune bf16 N C H W K F          (general case, bf16 inputs)
+    python -m paper_1705_10591_amd.tune table single|general|bf16 (the shapes the rules were set on)
 """
 from __future__ import annotations
 
@@ -39,6 +40,11 @@ def _time(fn, warm_ms: float = 40.0, steps: int = 20) -> float:
     return e0.elapsed_time(e1) / steps
 
 
+def _config_count(kind: str) -> int:
+    # the short-data-type kernel has two tile shapes (64 filters x 256 pixels, 128 x 512)
+    return 2 if kind == "bf16" else dconv.tile_config_count(kind == "single")
+
+
 def tune(kind: str, dims, steps: int = 20):
     """Return [(label, ms or None)] for the library's choice and every tile configuration."""
     gen = torch.Generator(device="cuda").manual_seed(1705)
@@ -48,6 +54,12 @@ def tune(kind: str, dims, steps: int = 20):
         f = torch.rand(K, F, F, device="cuda", generator=gen) - 0.5
         out = torch.empty(K, H - F + 1, W - F + 1, device="cuda")
         call = lambda v: dconv.dconv_single_channel(x, f, out=out, variant=v)
+    elif kind == "bf16":
+        N, C, H, W, K, F = dims
+        x = torch.rand(N, H, W, C, device="cuda", generator=gen).to(torch.bfloat16)
+        f = ((torch.rand(K, F, F, C, device="cuda", generator=gen) - 0.5) * 0.1).to(torch.bfloat16)
+        out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda")
+        call = lambda v: dconv.dconv_general_half(x, f, out=out, variant=v)
     else:
         N, C, H, W, K, F = dims
         x = torch.rand(N, C, H, W, device="cuda", generator=gen)
@@ -55,7 +67,7 @@ def tune(kind: str, dims, steps: int = 20):
         out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda")
         call = lambda v: dconv.dconv_general(x, f, out=out, variant=v)
     rows = [("library choice", _time(lambda: call(dconv.VARIANT_AUTO), steps=steps))]
-    for i in range(dconv.tile_config_count(kind == "single")):
+    for i in range(_config_count(kind)):
         v = dconv.VARIANT_TILED_CFG0 + i
         try:
             call(v)
@@ -86,10 +98,16 @@ TABLE_GENERAL = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (64, 3, 224
                  (8, 128, 112, 112, 128, 3), (64, 512, 7, 7, 512, 3)]
 
 
+TABLE_BF16 = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (32, 128, 56, 56, 128, 3),
+              (64, 64, 112, 112, 128, 3), (32, 64, 56, 56, 64, 5), (32, 128, 56, 56, 256, 5),
+              (64, 256, 56, 56, 256, 3), (128, 512, 14, 14, 512, 1), (32, 64, 56, 56, 128, 7),
+              (16, 512, 14, 14, 512, 3), (64, 128, 28, 28, 128, 3), (8, 128, 112, 112, 128, 3)]
+
+
 def table(kind: str) -> None:
     """One line per shape: the library's choice and every configuration, in microseconds."""
-    shapes = TABLE_SINGLE if kind == "single" else TABLE_GENERAL
-    n = dconv.tile_config_count(kind == "single")
+    shapes = {"single": TABLE_SINGLE, "general": TABLE_GENERAL, "bf16": TABLE_BF16}[kind]
+    n = _config_count(kind)
     print(f"# {kind}: microseconds per launch; columns: library choice, configurations 0..{n - 1} "
           "(n/a = cannot hold the shape), fastest configuration, library / fastest")
     for sh in shapes:
@@ -102,13 +120,13 @@ def table(kind: str) -> None:
 
 
 def main(argv):
-    if len(argv) == 2 and argv[0] == "table" and argv[1] in ("single", "general"):
+    if len(argv) == 2 and argv[0] == "table" and argv[1] in ("single", "general", "bf16"):
         if not torch.cuda.is_available():
             print("tune needs a GPU", file=sys.stderr)
             return 2
         table(argv[1])
         return 0
-    if len(argv) < 2 or argv[0] not in ("single", "general") or \
+    if len(argv) < 2 or argv[0] not in ("single", "general", "bf16") or \
             len(argv) - 1 != (4 if argv[0] == "single" else 6):
         print(__doc__)
         return 2
