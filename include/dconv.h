@@ -56,7 +56,7 @@ enum {
                               /* single-channel case only, F <= 7: vector-ALU
                                  kernel with a sliding register window (the
                                  paper's Algorithm 1 as it stands); what AUTO
-                                 picks for up to 8 filters (16 from 5x5 on) on
+                                 picks for up to 12 filters (20 from 5x5 on) on
                                  large images                                    */
     DCONV_VARIANT_TILED_CFG0 = 0x100
                               /* DCONV_VARIANT_TILED_CFG0 + i: the tiled kernel

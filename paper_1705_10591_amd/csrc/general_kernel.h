@@ -433,10 +433,14 @@ general_tiled_kernel(GenParams p)
                 for (int r = 0; r < 16; ++r)
                     __hip_atomic_store(mine + ((mt * NW + nt) * 16 + r) * kWave, acc[mt][nt][r],
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // every store of this workgroup has been acknowledged ...
+        // Every store of this workgroup has to be acknowledged (performed at device scope)
+        // before its arrival is counted.  A workgroup-scope fence does not wait for that and a
+        // device-scope one would write back the whole L2: each wave waits for its own stores
+        // (s_waitcnt vmcnt(0), all other counters left alone), then the workgroup meets.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
-        if (tid == 0)                        // ... before its arrival is counted
+        if (tid == 0)
             s_old = __hip_atomic_fetch_add(&p.cnt[first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         const int old = s_old;

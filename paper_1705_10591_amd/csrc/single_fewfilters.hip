@@ -11,8 +11,8 @@
 //    downwards with a window of F image rows in registers: every step reads ONE
 //    new image row segment from LDS (16 bytes per lane and instruction) and
 //    reuses the other F-1 rows, which is the paper's sliding register window;
-//  * the filters are wave-uniform: a group of KB filters sits in scalar
-//    registers (the counterpart of the constant-cache broadcast), so each
+//  * the filters are wave-uniform: the weights of one filter at a time sit in
+//    scalar registers (the counterpart of the constant-cache broadcast), so each
 //    multiply-add takes its weight from a scalar operand and its pixel from the
 //    window;
 //  * the four outputs of a lane are stored as 16 bytes, a wave writes 1 KiB of
@@ -20,8 +20,8 @@
 // What differs: no rolling one-row prefetch from global memory (several
 // workgroups share a CU and overlap each other's loads); the window does not
 // shift, the row loop is unrolled so that the ring index is a compile-time
-// constant; filter groups are the outer loop, so a group's weights are fetched
-// once per wave and tile.
+// constant; the filters are the outer loop, so a filter's weights are fetched
+// once per wave and tile (one load, issued a filter ahead).
 #include <type_traits>
 #include "common.h"
 #include "../../include/dconv.h"
@@ -36,6 +36,8 @@ struct FewParams {
     float* out;
     int H, W, K, Ho, Wo;
     int tiles_x;
+    int tiles;       // all tiles
+    int per_xcd;     // tiles per XCD (the grid has 8 * per_xcd workgroups)
 };
 
 constexpr int kFewTW = 256;          // tile width: 64 lanes x 4 columns
@@ -45,8 +47,6 @@ constexpr int kFewTW = 256;          // tile width: 64 lanes x 4 columns
 // (12-16 % over eight) and for one or two filters up to 5x5, eight rows from there on.
 constexpr int few_rpw(int F, int K) { return (F <= 3 || (F <= 5 && K <= 2)) ? 4 : 8; }
 
-// filters held in scalar registers at a time: at most 64 weights
-constexpr int few_kb(int F) { return F * F <= 16 ? 4 : F * F <= 32 ? 2 : 1; }
 
 template <int F, int RPW>
 __global__ void __launch_bounds__(kThreads)
@@ -54,7 +54,6 @@ single_few_kernel(FewParams p)
 {
     constexpr int kFewRPW = RPW, kFewTR = 4 * RPW;
     constexpr int FF = F * F;
-    constexpr int KB = few_kb(F);
     constexpr int WIN = 4 + F - 1;                 // window columns of a lane
     constexpr int NV = (WIN + 3) / 4;              // 16-byte LDS reads per window row
     constexpr int LS = kFewTW + 4 * NV - 4;        // LDS row stride: the last lane's reads stay in the row
@@ -66,7 +65,11 @@ single_few_kernel(FewParams p)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int ty = blockIdx.x / p.tiles_x, tx = blockIdx.x - ty * p.tiles_x;
+    // Workgroups go to the eight XCDs round-robin; each XCD gets a contiguous run of tiles, so
+    // that the 128-byte output lines two neighbouring tiles share meet in one L2 and leave it whole.
+    const int tile = (int)(blockIdx.x % 8) * p.per_xcd + (int)(blockIdx.x / 8);
+    if (tile >= p.tiles) return;                   // uniform: before any barrier
+    const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
     const int x0 = tx * kFewTW, y0 = ty * kFewTR;
 
     // ---- stage the tile (zeros outside the image), coalesced along rows -------------------
@@ -97,52 +100,50 @@ single_few_kernel(FewParams p)
         }
     };
 
-    for (int k0 = 0; k0 < p.K; k0 += KB) {         // filter groups: uniform loop
-        // the group's weights, wave-uniform and kept in scalar registers
-        float wgt[KB][FF];
+    // One filter at a time (more at once cost registers, hence occupancy, and were slower for
+    // every filter count measured).  Its F*F weights arrive with ONE load, lane t taking weight
+    // t, issued while the previous filter is being computed, and are moved to scalar registers
+    // (the counterpart of the constant-cache broadcast) tap by tap.
+    static_assert(FF <= kWave, "one lane per weight");
+    auto load_weights = [&](int k) {
+        return (lane < FF && k < p.K) ? p.filt[(int64_t)k * FF + lane] : 0.f;
+    };
+    float wnext = load_weights(0);
+    for (int k = 0; k < p.K; ++k) {                // uniform loop
+        const float wv = wnext;
+        wnext = load_weights(k + 1);
+        float wgt[FF];
 #pragma unroll
-        for (int kk = 0; kk < KB; ++kk)
-#pragma unroll
-            for (int t = 0; t < FF; ++t)
-                wgt[kk][t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(
-                    int, (k0 + kk < p.K) ? p.filt[(int64_t)(k0 + kk) * FF + t] : 0.f)));
+        for (int t = 0; t < FF; ++t)
+            wgt[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), t));
 
         float win[F][4 * NV];
 #pragma unroll
         for (int i = 0; i < F - 1; ++i) load_row(i, win[i]);
+        float* plane_k = p.out + (int64_t)k * plane;
 #pragma unroll
         for (int rr = 0; rr < kFewRPW; ++rr) {
             load_row(rr + F - 1, win[(rr + F - 1) % F]);
-            float acc[KB][4];
-#pragma unroll
-            for (int kk = 0; kk < KB; ++kk)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) acc[kk][e] = 0.f;
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int i = 0; i < F; ++i)
 #pragma unroll
                 for (int j = 0; j < F; ++j)
 #pragma unroll
-                    for (int kk = 0; kk < KB; ++kk)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            acc[kk][e] = __builtin_fmaf(win[(rr + i) % F][j + e], wgt[kk][i * F + j], acc[kk][e]);
+                    for (int e = 0; e < 4; ++e)
+                        acc[e] = __builtin_fmaf(win[(rr + i) % F][j + e], wgt[i * F + j], acc[e]);
             const int y = y0 + r0 + rr;
             if (y < p.Ho) {
+                float* dst = plane_k + (int64_t)y * p.Wo + xo;
+                // 16 bytes at once where they fit (rows start at any 4-byte offset: the store
+                // is declared 4-byte aligned), single words at the row end
+                typedef float v4f_a4 __attribute__((ext_vector_type(4), aligned(4)));
+                if (xo + 3 < p.Wo) {
+                    *reinterpret_cast<v4f_a4*>(dst) = (v4f_a4){acc[0], acc[1], acc[2], acc[3]};
+                } else {
 #pragma unroll
-                for (int kk = 0; kk < KB; ++kk) {
-                    if (k0 + kk >= p.K) break;
-                    float* dst = p.out + (int64_t)(k0 + kk) * plane + (int64_t)y * p.Wo + xo;
-                    // 16 bytes at once where they fit (rows start at any 4-byte offset: the store
-                    // is declared 4-byte aligned), single words at the row end
-                    typedef float v4f_a4 __attribute__((ext_vector_type(4), aligned(4)));
-                    if (xo + 3 < p.Wo) {
-                        *reinterpret_cast<v4f_a4*>(dst) = (v4f_a4){acc[kk][0], acc[kk][1], acc[kk][2], acc[kk][3]};
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (xo + e < p.Wo) dst[e] = acc[kk][e];
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        if (xo + e < p.Wo) dst[e] = acc[e];
                 }
             }
         }
@@ -152,10 +153,12 @@ single_few_kernel(FewParams p)
 template <int F, int RPW>
 int launch_few_rows(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
-    FewParams p{img, filt, out, s.H, s.W, s.K, s.Ho, s.Wo, (s.Wo + kFewTW - 1) / kFewTW};
+    FewParams p{img, filt, out, s.H, s.W, s.K, s.Ho, s.Wo, (s.Wo + kFewTW - 1) / kFewTW, 0, 0};
     const int64_t tiles = (int64_t)p.tiles_x * ((s.Ho + 4 * RPW - 1) / (4 * RPW));
-    if (tiles > 2147483647LL) return DCONV_UNSUPPORTED;
-    hipLaunchKernelGGL((single_few_kernel<F, RPW>), dim3((unsigned)tiles), dim3(kThreads), 0, st, p);
+    if (tiles > 2000000000LL) return DCONV_UNSUPPORTED;
+    p.tiles = (int)tiles;
+    p.per_xcd = (int)((tiles + 7) / 8);
+    hipLaunchKernelGGL((single_few_kernel<F, RPW>), dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
@@ -175,15 +178,15 @@ bool single_few_supports(const Shape& s)
     return s.N == 1 && s.C == 1 && s.F >= 1 && s.F <= 7;
 }
 
-// Worth it (measured against the matrix-core kernel on 4096 x 4096 and 1920 x 1080 images): few
-// enough filters that a 32-filter matrix-core block would be mostly empty -- up to 8, up to 16
-// from 5x5 filters on, where the padding of the block costs more -- and enough tiles to cover
-// the chip.
+// Worth it (measured against the matrix-core kernel on 4096 x 4096, 1920 x 1080 and 1024 x 1024
+// images): few enough filters that a 32-filter matrix-core block would be mostly empty -- up
+// to 12, up to 20 from 5x5 filters on, where the padding of the block costs more -- and enough
+// tiles to cover the chip.
 bool single_few_preferred(const Shape& s)
 {
     const int tr = 4 * few_rpw(s.F, s.K);
     const int64_t tiles = (int64_t)((s.Wo + kFewTW - 1) / kFewTW) * ((s.Ho + tr - 1) / tr);
-    return single_few_supports(s) && (s.K <= 8 || (s.K <= 16 && s.F >= 5)) && tiles >= 512;
+    return single_few_supports(s) && s.K <= (s.F <= 4 ? 12 : 20) && tiles >= (s.K <= 8 ? 256 : 512);
 }
 
 int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)

@@ -148,6 +148,29 @@ def test_general_every_tile_configuration(shape):
         np.testing.assert_array_equal(run_general(xi, fi, variant), o32)
 
 
+@pytest.mark.parametrize("shape", [(9, 24, 9, 35, 96, 3), (4, 64, 28, 28, 128, 3)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_general_shared_tiles_repeat_exactly(shape):
+    """Tiles summed by several workgroups meet in the workspace: the partial sums of every
+    workgroup must have arrived before its arrival is counted.  Many launches in a row, every
+    schedule that shares tiles, integer inputs (any lost or early-read word shows)."""
+    N, C, H, W, K, F = shape
+    xi, fi = wl.integer_case(90 + F, N, C, H, W, K, F)
+    _, _, o32, _ = oracle.general(xi, fi, want32=True)
+    want = torch.from_numpy(o32).to("cuda")
+    xd, fd = dev(xi), dev(fi)
+    out = torch.empty_like(want)
+    shapes, schedules = 3, 4
+    for tile in range(shapes):
+        for schedule in (2, 3):
+            variant = dconv.VARIANT_TILED_CFG0 + schedule * shapes + tile
+            print(f"general shared tiles {shape} variant {variant} x40", flush=True)
+            for _ in range(40):
+                out.fill_(float("nan"))
+                dconv.dconv_general(xd, fd, out=out, variant=variant)
+                assert bool(torch.equal(out, want)), f"variant {variant}"
+
+
 @pytest.mark.parametrize("shape", [(2, 8, 28, 28, 70, 3), (1, 3, 30, 140, 64, 11), (3, 6, 12, 12, 9, 5)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_general_integer_inputs_are_bit_exact(shape):
