@@ -151,6 +151,23 @@ int dconv_general_i8_v(const void *in, int N, int C, int H, int W,
                        int *out, int variant, void *stream);
 
 /*
+ * The general case on short data types with every choice explicit: dtype
+ * (DCONV_DTYPE_*), layout, variant (as for dconv_general_half_v); `out` is fp32
+ * for the 16-bit types and int32 for int8.  Layouts:
+ *   DCONV_LAYOUT_CHANNELS_LAST    in [N][H][W][C],        filt [K][F][F][C]
+ *   DCONV_LAYOUT_CHANNEL_BLOCKED  in [N][C/cb][H][W][cb], filt [K][C/cb][F][F][cb]
+ * with cb = 16 channels for the 16-bit types and 32 for int8 (32 bytes: the
+ * unit a matrix-core step consumes per pixel).  In the blocked layout the
+ * kernel's staging loads are contiguous along image rows instead of gathering
+ * 32 bytes out of every pixel's channel run; C must be a multiple of cb
+ * (otherwise DCONV_BAD_SHAPE).  Everything else as for dconv_general_f16.
+ */
+enum { DCONV_LAYOUT_CHANNELS_LAST = 0, DCONV_LAYOUT_CHANNEL_BLOCKED = 1 };
+int dconv_general_lowp(const void *in, int N, int C, int H, int W,
+                       const void *filt, int K, int F,
+                       void *out, int dtype, int layout, int variant, void *stream);
+
+/*
  * Number of tile configurations compiled into the tiled kernel of the
  * single-channel case (single_channel != 0) or of the general case
  * (single_channel == 0).  The paper picks its tile sizes by exploring the

@@ -25,8 +25,9 @@ EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
            "dconv_general_v", "dconv_status_string", "dconv_version",
            "dconv_tile_config_count", "dconv_release_workspace",
            "dconv_general_f16", "dconv_general_bf16", "dconv_general_half_v",
-           "dconv_general_i8", "dconv_general_i8_v")
+           "dconv_general_i8", "dconv_general_i8_v", "dconv_general_lowp")
 DTYPE_F16, DTYPE_BF16, DTYPE_I8 = 0, 1, 2
+LAYOUT_CHANNELS_LAST, LAYOUT_CHANNEL_BLOCKED = 0, 1
 
 _lib = None
 
@@ -56,10 +57,12 @@ def load_library() -> ctypes.CDLL:
         lib.dconv_general_half_v.argtypes = [p, i, i, i, i, p, i, i, p, i, i, p]
         lib.dconv_general_i8.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_i8_v.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
+        lib.dconv_general_lowp.argtypes = [p, i, i, i, i, p, i, i, p, i, i, i, p]
         for name in ("dconv_single_channel", "dconv_single_channel_v",
                      "dconv_general", "dconv_general_v", "dconv_version",
                      "dconv_release_workspace", "dconv_general_f16", "dconv_general_bf16",
-                     "dconv_general_half_v", "dconv_general_i8", "dconv_general_i8_v"):
+                     "dconv_general_half_v", "dconv_general_i8", "dconv_general_i8_v",
+                     "dconv_general_lowp"):
             getattr(lib, name).restype = i
         lib.dconv_tile_config_count.argtypes = [i]
         lib.dconv_tile_config_count.restype = i
@@ -153,60 +156,54 @@ def dconv_general(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None 
     return out
 
 
-def dconv_general_half(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
-                       variant: int = VARIANT_AUTO) -> torch.Tensor:
-    """16-bit inputs, channels innermost, fp32 accumulation and output:
-    out[n,k,y,x] = sum_{i,j,c} x[n,y+i,x+j,c] * filt[k,i,j,c]
-    x: [N,H,W,C], filt: [K,F,F,C], both torch.float16 or both torch.bfloat16."""
+def _lowp(x, filt, out, variant, blocked, types, out_type):
     for t, what in ((x, "in"), (filt, "filt")):
-        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dim() == 4 and t.is_contiguous()
-                and t.dtype in (torch.float16, torch.bfloat16)):
-            raise TypeError(f"{what} must be a contiguous float16 or bfloat16 CUDA tensor with 4 dims")
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dim() == (5 if blocked else 4)
+                and t.is_contiguous() and t.dtype in types):
+            raise TypeError(f"{what} must be a contiguous CUDA tensor of type {types} with "
+                            f"{5 if blocked else 4} dims")
     if x.dtype != filt.dtype:
         raise TypeError("in and filt must have the same type")
-    N, H, W, C = x.shape
-    K, F, F2, C2 = filt.shape
-    if C2 != C or F != F2:
-        raise ValueError("filter shape does not match the input")
-    if F > H or F > W:
-        _raise(STATUS_BAD_SHAPE)
-    if out is None:
-        out = torch.empty((N, K, H - F + 1, W - F + 1), dtype=torch.float32, device=x.device)
+    if blocked:
+        N, CG, H, W, cb = x.shape
+        K, CG2, F, F2, cb2 = filt.shape
+        if cb * x.element_size() != 32 or (CG2, cb2) != (CG, cb):
+            raise ValueError("channel blocks must be 32 bytes and match between in and filt")
+        C = CG * cb
     else:
-        _check(out, 4, "out")
-        if tuple(out.shape) != (N, K, H - F + 1, W - F + 1):
-            raise ValueError("out has the wrong shape")
-    dtype = DTYPE_BF16 if x.dtype == torch.bfloat16 else DTYPE_F16
-    with torch.cuda.device(x.device):
-        rc = load_library().dconv_general_half_v(
-            x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), dtype, int(variant),
-            _stream_ptr(x.device))
-    _raise(rc)
-    return out
-
-
-def dconv_general_i8(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
-                     variant: int = VARIANT_AUTO) -> torch.Tensor:
-    """Signed 8-bit inputs, channels innermost, exact int32 sums:
-    out[n,k,y,x] = sum_{i,j,c} x[n,y+i,x+j,c] * filt[k,i,j,c];  x: [N,H,W,C], filt: [K,F,F,C], torch.int8."""
-    for t, what in ((x, "in"), (filt, "filt")):
-        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dim() == 4 and t.is_contiguous()
-                and t.dtype == torch.int8):
-            raise TypeError(f"{what} must be a contiguous int8 CUDA tensor with 4 dims")
-    N, H, W, C = x.shape
-    K, F, F2, C2 = filt.shape
-    if C2 != C or F != F2:
-        raise ValueError("filter shape does not match the input")
+        N, H, W, C = x.shape
+        K, F, F2, C2 = filt.shape
+        if C2 != C:
+            raise ValueError("filter shape does not match the input")
+    if F != F2:
+        raise ValueError("filters must be square")
     if F > H or F > W:
         _raise(STATUS_BAD_SHAPE)
     shape = (N, K, H - F + 1, W - F + 1)
     if out is None:
-        out = torch.empty(shape, dtype=torch.int32, device=x.device)
-    elif not (out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and tuple(out.shape) == shape):
-        raise TypeError("out must be a contiguous int32 CUDA tensor of the output shape")
+        out = torch.empty(shape, dtype=out_type, device=x.device)
+    elif not (isinstance(out, torch.Tensor) and out.is_cuda and out.dtype == out_type
+              and out.is_contiguous() and tuple(out.shape) == shape):
+        raise TypeError(f"out must be a contiguous {out_type} CUDA tensor of shape {shape}")
+    dtype = {torch.float16: DTYPE_F16, torch.bfloat16: DTYPE_BF16, torch.int8: DTYPE_I8}[x.dtype]
     with torch.cuda.device(x.device):
-        rc = load_library().dconv_general_i8_v(
-            x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), int(variant),
-            _stream_ptr(x.device))
+        rc = load_library().dconv_general_lowp(
+            x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), dtype,
+            LAYOUT_CHANNEL_BLOCKED if blocked else LAYOUT_CHANNELS_LAST, int(variant), _stream_ptr(x.device))
     _raise(rc)
     return out
+
+
+def dconv_general_half(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
+                       variant: int = VARIANT_AUTO, blocked: bool = False) -> torch.Tensor:
+    """16-bit inputs (both torch.float16 or both torch.bfloat16), fp32 accumulation and output:
+    out[n,k,y,x] = sum_{i,j,c} in[n,y+i,x+j,c] * filt[k,i,j,c].
+    Channels last: x [N,H,W,C], filt [K,F,F,C]; blocked: x [N,C/16,H,W,16], filt [K,C/16,F,F,16]."""
+    return _lowp(x, filt, out, variant, blocked, (torch.float16, torch.bfloat16), torch.float32)
+
+
+def dconv_general_i8(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
+                     variant: int = VARIANT_AUTO, blocked: bool = False) -> torch.Tensor:
+    """Signed 8-bit inputs, exact int32 sums and output.  Channels last: x [N,H,W,C],
+    filt [K,F,F,C]; blocked: x [N,C/32,H,W,32], filt [K,C/32,F,F,32]."""
+    return _lowp(x, filt, out, variant, blocked, (torch.int8,), torch.int32)

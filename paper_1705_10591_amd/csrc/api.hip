@@ -101,7 +101,19 @@ int dconv_general_half_v(const void* in, int N, int C, int H, int W, const void*
     if (rc != DCONV_OK) return rc;
     if (dtype != DCONV_DTYPE_F16 && dtype != DCONV_DTYPE_BF16) return DCONV_UNSUPPORTED;
     if ((((uintptr_t)in) & 1) != 0 || (((uintptr_t)filt) & 1) != 0) return DCONV_BAD_SHAPE;
-    return dconv::launch_general_half(in, filt, out, s, (hipStream_t)stream, dtype, variant);
+    return dconv::launch_general_half(in, filt, out, s, (hipStream_t)stream, dtype,
+                                      DCONV_LAYOUT_CHANNELS_LAST, variant);
+}
+
+int dconv_general_lowp(const void* in, int N, int C, int H, int W, const void* filt, int K, int F,
+                       void* out, int dtype, int layout, int variant, void* stream)
+{
+    Shape s;
+    const int rc = validate(in, filt, out, N, C, H, W, K, F, &s);
+    if (rc != DCONV_OK) return rc;
+    if (dtype != DCONV_DTYPE_I8 && ((((uintptr_t)in) & 1) != 0 || (((uintptr_t)filt) & 1) != 0))
+        return DCONV_BAD_SHAPE;
+    return dconv::launch_general_half(in, filt, (float*)out, s, (hipStream_t)stream, dtype, layout, variant);
 }
 
 int dconv_general_i8_v(const void* in, int N, int C, int H, int W, const void* filt, int K, int F,
@@ -110,7 +122,8 @@ int dconv_general_i8_v(const void* in, int N, int C, int H, int W, const void* f
     Shape s;
     const int rc = validate(in, filt, out, N, C, H, W, K, F, &s);
     if (rc != DCONV_OK) return rc;
-    return dconv::launch_general_half(in, filt, (float*)out, s, (hipStream_t)stream, DCONV_DTYPE_I8, variant);
+    return dconv::launch_general_half(in, filt, (float*)out, s, (hipStream_t)stream, DCONV_DTYPE_I8,
+                                      DCONV_LAYOUT_CHANNELS_LAST, variant);
 }
 
 int dconv_general_i8(const void* in, int N, int C, int H, int W, const void* filt, int K, int F,
@@ -154,6 +167,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1005; }
+int dconv_version(void) { return 1006; }
 
 }  // extern "C"

@@ -49,9 +49,9 @@ bool single_few_preferred(const Shape& s);     // ... and is the better choice f
 bool single_tiled_supports(const Shape& s);
 bool general_tiled_supports(const Shape& s);
 void release_general_workspaces();
-// Short data types (dtype: DCONV_DTYPE_*), channels innermost; variant: AUTO, SIMPLE or TILED.
-// `out` receives fp32 values, or int32 bit patterns for 8-bit integer inputs.
+// Short data types (dtype: DCONV_DTYPE_*, layout: DCONV_LAYOUT_*); variant: AUTO, SIMPLE, TILED
+// or TILED_CFG0 + i.  `out` receives fp32 values, or int32 bit patterns for 8-bit integer inputs.
 int launch_general_half(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                        int dtype, int variant);
+                        int dtype, int layout, int variant);
 
 }  // namespace dconv

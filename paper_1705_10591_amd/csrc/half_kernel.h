@@ -81,6 +81,12 @@ struct HalfParams {
     int tiles;           // ((nstrips - 1) * pt_full + pt_last) * KB
     int per_xcd;         // tiles per XCD (grid = 8 * per_xcd)
     int Hc;              // image-block rows set aside per image: Ho + RG - 1
+    // Layout of the inputs in bytes.  Channels last ([N][H][W][C], [K][F][F][C]): pixels and taps
+    // are a whole channel run apart, channel groups 32 bytes.  Channel-blocked
+    // ([N][C/cb][H][W][cb], [K][C/cb][F][F][cb] with cb = 32 bytes' worth of channels): pixels
+    // and taps are 32 bytes apart, channel groups a whole plane / filter-group.
+    int ps, gs;          // image: pixel stride, channel-group stride
+    int ts, fgs;         // filters: tap stride, channel-group stride
     FastDiv d_strip;     // by pt_full * KB
     FastDiv d_kb;        // by KB
     FastDiv d_wsf;       // by bw
@@ -179,7 +185,7 @@ general_half_kernel(HalfParams p)
             const int dn = fdiv(y_first + row, p.d_hc);
             const int yy = y_first + row - dn * p.Hc;
             if (row < nslots && n_first + dn < p.N && x0 + col < p.W)
-                g = (uint32_t)(((dn * p.H + yy) * p.W + x0 + col) * CB + half * 16);
+                g = (uint32_t)(dn * (p.H * p.W * CB) + (yy * p.W + x0 + col) * p.ps + half * 16);
         }
         ig[it] = g;
     }
@@ -189,7 +195,7 @@ general_half_kernel(HalfParams p)
         const int e = tid + it * THREADS;
         const int t = e / (2 * MT), k = (e >> 1) % MT, half = e & 1;
         // (filters beyond K lie beyond the end of the bank: the range check returns zero)
-        wg[it] = e < FPIECES ? (uint32_t)((k * (F * F) + t) * CB + half * 16) : kNowhere;
+        wg[it] = e < FPIECES ? (uint32_t)(k * (F * F) * CB + t * p.ts + half * 16) : kNowhere;
     }
     const int64_t in_bytes = (int64_t)p.N * p.H * p.W * CB;
     const int64_t filt_bytes = (int64_t)p.K * (F * F) * CB;
@@ -200,10 +206,10 @@ general_half_kernel(HalfParams p)
     v4f ireg[NII], wreg[NFI];
     auto fetch = [&](int chunk) __attribute__((always_inline)) {
         const int cidx = chunk / NG, g = chunk - cidx * NG;
-        const int64_t ioff = ifirst + (int64_t)g * RG * p.W * CB + cidx * kHalfChunkBytes;
+        const int64_t ioff = ifirst + (int64_t)g * RG * p.W * p.ps + (int64_t)cidx * p.gs;
         const __amdgpu_buffer_rsrc_t irs = __builtin_amdgcn_make_buffer_rsrc(
             (void*)(p.in + ioff), 0, (int)min(in_bytes - ioff, (int64_t)0x7FFFFFFF), kRsrcFlags);
-        const int64_t woff = wfirst + (int64_t)g * (RG * F) * CB + cidx * kHalfChunkBytes;
+        const int64_t woff = wfirst + (int64_t)g * (RG * F) * p.ts + (int64_t)cidx * p.fgs;
         const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
             (void*)(p.filt + woff), 0, (int)min(filt_bytes - woff, (int64_t)0x7FFFFFFF), kRsrcFlags);
 #pragma unroll
@@ -344,8 +350,15 @@ general_half_kernel(HalfParams p)
 template <int DT>
 __global__ void __launch_bounds__(kThreads)
 simple_half_kernel(const void* in_, const void* filt_, float* out,
-                   int N, int C, int H, int W, int K, int F, int Ho, int Wo)
+                   int N, int C, int H, int W, int K, int F, int Ho, int Wo, int blocked)
 {
+    // element index of channel c of pixel / tap `pos` (a flat [N][H][W] or [K][F][F] position
+    // within image or filter `outer`, `inner` positions each)
+    constexpr int cb = kHalfChunkBytes / elem_bytes(DT);
+    auto at = [&](int64_t outer, int64_t inner_count, int64_t pos, int c) -> int64_t {
+        if (!blocked) return (outer * inner_count + pos) * C + c;
+        return ((outer * (C / cb) + c / cb) * inner_count + pos) * cb + c % cb;
+    };
     const int64_t total = (int64_t)N * K * Ho * Wo;
     const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (o >= total) return;
@@ -356,11 +369,10 @@ simple_half_kernel(const void* in_, const void* filt_, float* out,
         const signed char* filt = (const signed char*)filt_;
         int acc = 0;
         for (int i = 0; i < F; ++i)
-            for (int j = 0; j < F; ++j) {
-                const signed char* px = in + (((int64_t)n * H + y + i) * W + x + j) * C;
-                const signed char* wt = filt + (((int64_t)k * F + i) * F + j) * C;
-                for (int c = 0; c < C; ++c) acc += (int)px[c] * (int)wt[c];
-            }
+            for (int j = 0; j < F; ++j)
+                for (int c = 0; c < C; ++c)
+                    acc += (int)in[at(n, (int64_t)H * W, (int64_t)(y + i) * W + x + j, c)] *
+                           (int)filt[at(k, F * F, i * F + j, c)];
         out[o] = __builtin_bit_cast(float, acc);
         return;
     }
@@ -372,11 +384,10 @@ simple_half_kernel(const void* in_, const void* filt_, float* out,
     };
     float acc = 0.f;
     for (int i = 0; i < F; ++i)
-        for (int j = 0; j < F; ++j) {
-            const unsigned short* px = in + (((int64_t)n * H + y + i) * W + x + j) * C;
-            const unsigned short* wt = filt + (((int64_t)k * F + i) * F + j) * C;
-            for (int c = 0; c < C; ++c) acc = __builtin_fmaf(cvt(px[c]), cvt(wt[c]), acc);
-        }
+        for (int j = 0; j < F; ++j)
+            for (int c = 0; c < C; ++c)
+                acc = __builtin_fmaf(cvt(in[at(n, (int64_t)H * W, (int64_t)(y + i) * W + x + j, c)]),
+                                     cvt(filt[at(k, F * F, i * F + j, c)]), acc);
     out[o] = acc;
 }
 
@@ -410,7 +421,8 @@ inline HalfPlan make_half_plan(const Shape& s, int rg, int NT, int nii, int thre
 }
 
 template <int F, int RG, int DT, class TL>
-int half_try_launch(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st, bool dry)
+int half_try_launch(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st, bool dry,
+                    bool blocked)
 {
     constexpr int MT = TL::MT, NT = TL::NT, S = RG * F;
     constexpr int EB = elem_bytes(DT);
@@ -448,6 +460,8 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
     const int per_xcd = (int)((tiles + 7) / 8);
     HalfParams p{(const char*)in, (const char*)filt, out, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo,
                  pl.bw, pl.nstrips, pl.LS, pl.RS, pl.pt_full, KB, (int)tiles, per_xcd, s.Ho + RG - 1,
+                 blocked ? kHalfChunkBytes : s.C * EB, blocked ? s.H * s.W * kHalfChunkBytes : kHalfChunkBytes,
+                 blocked ? kHalfChunkBytes : s.C * EB, blocked ? F * F * kHalfChunkBytes : kHalfChunkBytes,
                  make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
                  make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho),
                  make_fastdiv(s.Ho + RG - 1), make_fastdiv(pl.LS)};
@@ -458,6 +472,6 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
 // Implemented once per filter side, each in its own translation unit.
 template <int F>
 int half_launch_for_F(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                      int dtype, bool large_tile, bool dry);
+                      int dtype, bool large_tile, bool blocked, bool dry);
 
 }  // namespace dconv

@@ -113,6 +113,11 @@ def test_16_bit_entry_points_validate_before_launching():
         == dconv.STATUS_UNSUPPORTED
     assert lib.dconv_general_half_v(FAKE, *ok_dims, FAKE, 2, 3, FAKE, dconv.DTYPE_I8, 0, None) \
         == dconv.STATUS_UNSUPPORTED          # int8 has entry points of its own (int32 output)
+    assert lib.dconv_general_lowp(FAKE, *ok_dims, FAKE, 2, 3, FAKE, 0, 5, 0, None) == dconv.STATUS_UNSUPPORTED
+    assert lib.dconv_general_lowp(FAKE, *ok_dims, FAKE, 2, 3, FAKE, 9, 0, 0, None) == dconv.STATUS_UNSUPPORTED
+    assert lib.dconv_general_lowp(FAKE, 1, 24, 8, 8, FAKE, 2, 3, FAKE, 0, dconv.LAYOUT_CHANNEL_BLOCKED, 0, None) \
+        == dconv.STATUS_BAD_SHAPE            # a blocked layout has whole blocks of channels only
+    assert lib.dconv_general_lowp(None, *ok_dims, FAKE, 2, 3, FAKE, 0, 0, 0, None) == dconv.STATUS_NULL_POINTER
     assert lib.dconv_general_i8(None, *ok_dims, FAKE, 2, 3, FAKE, None) == dconv.STATUS_NULL_POINTER
     assert lib.dconv_general_i8(FAKE, 1, 32, 4, 8, FAKE, 2, 5, FAKE, None) == dconv.STATUS_BAD_SHAPE
     assert lib.dconv_general_i8_v(FAKE, *ok_dims, FAKE, 2, 3, FAKE, dconv.VARIANT_FEW_FILTERS, None) \

@@ -222,3 +222,70 @@ def test_int8_config_shapes_sampled(name, variant):
     got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy().astype(np.int64)
     acc, _ = oracle.general_at(x.astype(np.float32), f.astype(np.float32), idx)
     np.testing.assert_array_equal(got, acc.astype(np.int64))
+
+
+# ---- the channel-blocked layout ------------------------------------------------------------------
+
+def to_blocked(a_nchw_like: np.ndarray, cb: int) -> np.ndarray:
+    """[X][C][A][B] -> [X][C/cb][A][B][cb]."""
+    X, C, A, B = a_nchw_like.shape
+    return np.ascontiguousarray(a_nchw_like.reshape(X, C // cb, cb, A, B).transpose(0, 1, 3, 4, 2))
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("shape", [(2, 32, 20, 23, 5, 3), (3, 64, 28, 28, 130, 3), (2, 32, 24, 150, 33, 5),
+                                   (2, 32, 27, 31, 64, 11), (5, 32, 8, 8, 4, 3), (1, 96, 13, 12, 3, 10),
+                                   (1, 128, 9, 9, 3, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_blocked_layout_small_shapes(shape, kind):
+    if kind == "i8":
+        x, f = int8_case(shape[-1] + 50, shape)
+        want = exact_i8(x, f)
+        xb, fb = torch.from_numpy(to_blocked(x, 32)).cuda(), torch.from_numpy(to_blocked(f, 32)).cuda()
+        for variant in KERNELS:
+            print(f"int8 blocked {shape} variant {variant}", flush=True)
+            got = dconv.dconv_general_i8(xb, fb, variant=variant, blocked=True)
+            np.testing.assert_array_equal(got.cpu().numpy().astype(np.int64), want)
+        return
+    xr, fr, xbits, fbits = rounded_case(950 + shape[-1], shape, kind)
+    acc, mag, _ = oracle.general(xr, fr)
+    as_t = lambda bits: torch.from_numpy(to_blocked(bits, 16).view(np.int16)).view(TORCH_TYPE[kind]).cuda()
+    xb, fb = as_t(xbits), as_t(fbits)
+    for variant in KERNELS:
+        print(f"half {kind} blocked {shape} variant {variant}", flush=True)
+        got = dconv.dconv_general_half(xb, fb, variant=variant, blocked=True)
+        assert_within_bound(got.cpu().numpy(), acc, mag, f"half {kind} blocked {shape} variant {variant}")
+
+
+@pytest.mark.parametrize("kind", ["bf16", "i8"])
+def test_blocked_layout_G3_sampled(kind):
+    w = wl.CONFIGS["G3"]
+    if kind == "i8":
+        x, f = int8_case(78, (w.N, w.C, w.H, w.W, w.K, w.F))
+        out = dconv.dconv_general_i8(torch.from_numpy(to_blocked(x, 32)).cuda(),
+                                     torch.from_numpy(to_blocked(f, 32)).cuda(), blocked=True)
+        idx = wl.sample_indices(33, out.numel(), 4000)
+        got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy().astype(np.int64)
+        acc, _ = oracle.general_at(x.astype(np.float32), f.astype(np.float32), idx)
+        np.testing.assert_array_equal(got, acc.astype(np.int64))
+        return
+    x, f = wl.make_inputs(w)
+    xr, xbits = wl.to_16bit(x.reshape(w.N, w.C, w.H, w.W), kind)
+    fr, fbits = wl.to_16bit(f.reshape(w.K, w.C, w.F, w.F), kind)
+    as_t = lambda bits: torch.from_numpy(to_blocked(bits, 16).view(np.int16)).view(TORCH_TYPE[kind]).cuda()
+    out = dconv.dconv_general_half(as_t(xbits), as_t(fbits), blocked=True)
+    torch.cuda.synchronize()
+    idx = wl.sample_indices(34, out.numel(), 4000)
+    got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    acc, mag = oracle.general_at(xr, fr, idx)
+    assert_within_bound(got, acc, mag, f"half {kind} blocked G3 sampled")
+
+
+def test_blocked_layout_needs_whole_channel_blocks():
+    lib = dconv.load_library()
+    x = torch.zeros(1, 8, 8, 24, dtype=torch.float16, device="cuda")      # 24 channels: not a multiple of 16
+    f = torch.zeros(2, 3, 3, 24, dtype=torch.float16, device="cuda")
+    out = torch.zeros(1, 2, 6, 6, dtype=torch.float32, device="cuda")
+    rc = lib.dconv_general_lowp(x.data_ptr(), 1, 24, 8, 8, f.data_ptr(), 2, 3, out.data_ptr(),
+                                dconv.DTYPE_F16, dconv.LAYOUT_CHANNEL_BLOCKED, 0, None)
+    assert rc == dconv.STATUS_BAD_SHAPE
