@@ -217,13 +217,18 @@ def main():
     allw = dict(wl.CONFIGS)
     allw.update({v.name: v for v in wl.S2_SWEEP.values()})
     allw.update(wl.PAPER_SWEEP)
-    if args.only and args.only.rsplit("_", 1)[-1] in ("f16", "bf16", "i8") and args.only.rsplit("_", 1)[0] in allw:
-        # one of the 16-bit configurations on its own (for profiles): the same JSON shape
-        wname, kind = args.only.rsplit("_", 1)
+    only, only_blocked = args.only, False
+    if only and only.endswith("_blocked"):          # e.g. G3_bf16_blocked: the channel-blocked layout
+        only, only_blocked = only[:-len("_blocked")], True
+    if only and only.rsplit("_", 1)[-1] in ("f16", "bf16", "i8") and only.rsplit("_", 1)[0] in allw:
+        # one of the short-data-type configurations on its own (for profiles): the same JSON shape
+        wname, kind = only.rsplit("_", 1)
         w = allw[wname]
-        run = make_half_runner(w, kind)
+        run = make_half_runner(w, kind, blocked=only_blocked)
         ms, wall_ms = time_launches(run, args.steps, args.warmup, warm_ms=60.0)
         e = half_entry(w, kind, ms)
+        if only_blocked:
+            e["name"] += "_blocked"
         if args.copy_calibration:
             a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
             b = torch.empty_like(a)

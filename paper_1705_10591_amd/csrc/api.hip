@@ -167,6 +167,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1006; }
+int dconv_version(void) { return 1007; }
 
 }  // extern "C"

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace dconv {
 
@@ -28,6 +29,21 @@ __device__ __forceinline__ constexpr int mfma_row(int r, int h) {
 struct LaunchResult {
     int status;      // dconv_status
 };
+
+// Kernels that use more dynamic LDS than the default limit have it raised once per device (the
+// attribute belongs to the kernel on the current device): `done` holds one bit per device, one
+// word per kernel.  A race between threads only repeats the call.
+inline bool raise_lds_limit(const void* kernel, int bytes, std::atomic<uint64_t>& done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return false;
+    if (dev < 64) done.fetch_or(bit, std::memory_order_release);
+    return true;
+}
 
 // Shape of one problem, general layout (the single-channel case has N = C = 1).
 struct Shape {

@@ -659,15 +659,10 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     // per instantiation for the last LDS size seen.  A race between threads can only pair the
     // count with another shape's LDS size, which changes the grid size and nothing else:
     // no workgroup ever waits for another one.
-    static bool attr_set = false;
+    static std::atomic<uint64_t> lds_limit_raised{0};
     static int64_t cached_lds = -1;
     static int cached_chip = 0;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kGenLdsLimit) != hipSuccess)
-            return DCONV_LAUNCH_FAILED;
-        attr_set = true;
-    }
+    if (!raise_lds_limit((const void*)kern, kGenLdsLimit, lds_limit_raised)) return DCONV_LAUNCH_FAILED;
     if (cached_lds != lds_bytes) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||

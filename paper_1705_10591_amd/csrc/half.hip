@@ -7,20 +7,20 @@ namespace dconv {
 namespace {
 
 int launch_tiled(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                 int dtype, bool large_tile, bool blocked, bool dry)
+                 int dtype, int config, bool blocked, bool dry)
 {
     switch (s.F) {
-    case 1: return half_launch_for_F<1>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 2: return half_launch_for_F<2>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 3: return half_launch_for_F<3>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 4: return half_launch_for_F<4>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 5: return half_launch_for_F<5>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 6: return half_launch_for_F<6>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 7: return half_launch_for_F<7>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 8: return half_launch_for_F<8>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 9: return half_launch_for_F<9>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 10: return half_launch_for_F<10>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
-    case 11: return half_launch_for_F<11>(in, filt, out, s, st, dtype, large_tile, blocked, dry);
+    case 1: return half_launch_for_F<1>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 2: return half_launch_for_F<2>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 3: return half_launch_for_F<3>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 4: return half_launch_for_F<4>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 5: return half_launch_for_F<5>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 6: return half_launch_for_F<6>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 7: return half_launch_for_F<7>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 8: return half_launch_for_F<8>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 9: return half_launch_for_F<9>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 10: return half_launch_for_F<10>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 11: return half_launch_for_F<11>(in, filt, out, s, st, dtype, config, blocked, dry);
     default: return DCONV_UNSUPPORTED;
     }
 }
@@ -38,16 +38,36 @@ int launch_simple_half(const void* in, const void* filt, float* out, const Shape
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
-// The large tile (128 filters x 512 pixels) where its filter tile is mostly full, there are
-// enough tiles for most of the CUs (one workgroup each) and a tile has enough chunks to pay for
-// its longer prologue and write-back; the small one otherwise.  (Measured on ten layer shapes:
-// 10-25 % faster where chosen.)
-bool large_tile_preferred(const Shape& s, int dtype)
+// Which tile configuration a shape gets.  The large tile (128 filters x 512 pixels, one workgroup
+// per CU) does the work of four small ones (64 x 256, two workgroups per CU) in the time of
+// about three (fewer operand reads and half the staging per matrix-core instruction; measured
+// 2.5 to 3.4 over shapes and boxes), so it wins where its tiles fill the CUs in whole rounds:
+// compare rounds x time per tile.  Its filter tile has to be mostly full and a tile long enough
+// to pay for the longer prologue and write-back.
+// Staging (see general_half_kernel): the small tile goes directly into LDS when a pixel's
+// channel block is contiguous with its neighbours' (blocked layout) and through registers
+// otherwise; the large tile goes directly in both layouts, except that with chunks of one or
+// two steps (1x1 filters) the register path is faster on channels-last inputs and the small
+// tile, whose two workgroups per CU hide the barrier after every chunk better, on blocked ones
+// (measured: 12 and 20 %).
+int preferred_config(const Shape& s, int dtype, bool blocked)
 {
-    const int64_t tiles = (((int64_t)s.N * s.Ho * s.Wo + 511) / 512) * ((s.K + 127) / 128);
+    const int small_cfg = blocked ? 2 : 0;
     const int rg = half_row_group(s.F);
     const int chunks = s.C / (kHalfChunkBytes / elem_bytes(dtype)) * ((s.F + rg - 1) / rg);
-    return s.K >= 96 && tiles >= 128 && chunks >= 8;
+    const bool short_chunks = rg * s.F <= 2;
+    if (s.K < 96 || chunks < 8 || (blocked && short_chunks)) return small_cfg;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    const int64_t px = (int64_t)s.N * s.Ho * s.Wo;
+    const int64_t large = ((px + 511) / 512) * ((s.K + 127) / 128);
+    const int64_t small = ((px + 255) / 256) * ((s.K + 63) / 64);
+    const double large_cost = (double)((large + cus - 1) / cus) * 2.95;
+    const double small_cost = (double)((small + cus - 1) / cus);
+    if (large_cost >= small_cost) return small_cfg;
+    return short_chunks ? 1 : 3;
 }
 
 }  // namespace
@@ -61,13 +81,14 @@ int launch_general_half(const void* in, const void* filt, float* out, const Shap
     // a blocked layout exists only for whole blocks of channels
     if (blocked && s.C % (kHalfChunkBytes / elem_bytes(dtype)) != 0) return DCONV_BAD_SHAPE;
     if (variant == DCONV_VARIANT_SIMPLE) return launch_simple_half(in, filt, out, s, st, dtype, blocked);
-    // the two tile shapes of the matrix-core kernel, forced (tests, tuning)
-    if (variant == DCONV_VARIANT_TILED_CFG0 || variant == DCONV_VARIANT_TILED_CFG0 + 1)
-        return launch_tiled(in, filt, out, s, st, dtype, variant == DCONV_VARIANT_TILED_CFG0 + 1, blocked, false);
+    // one tile configuration of the matrix-core kernel, forced (tests, tuning)
+    if (variant >= DCONV_VARIANT_TILED_CFG0 && variant < DCONV_VARIANT_TILED_CFG0 + kHalfConfigs)
+        return launch_tiled(in, filt, out, s, st, dtype, variant - DCONV_VARIANT_TILED_CFG0, blocked, false);
     if (variant != DCONV_VARIANT_AUTO && variant != DCONV_VARIANT_TILED) return DCONV_UNSUPPORTED;
-    int rc = DCONV_UNSUPPORTED;
-    if (large_tile_preferred(s, dtype)) rc = launch_tiled(in, filt, out, s, st, dtype, true, blocked, false);
-    if (rc == DCONV_UNSUPPORTED) rc = launch_tiled(in, filt, out, s, st, dtype, false, blocked, false);
+    const int cfg = preferred_config(s, dtype, blocked);
+    int rc = launch_tiled(in, filt, out, s, st, dtype, cfg, blocked, false);
+    // (the small tiles hold every shape the large one does, and the register-staged one the most)
+    if (rc == DCONV_UNSUPPORTED && cfg != 0) rc = launch_tiled(in, filt, out, s, st, dtype, 0, blocked, false);
     if (rc == DCONV_UNSUPPORTED && variant == DCONV_VARIANT_AUTO)
         return launch_simple_half(in, filt, out, s, st, dtype, blocked);
     return rc;

@@ -13,24 +13,29 @@ constexpr int F = DCONV_F;
 constexpr int kRowGroup = half_row_group(F);
 }  // namespace
 
-template <class TL>
+template <class TL, bool DIRECT>
 int launch_dtype(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
                  int dtype, bool blocked, bool dry)
 {
     switch (dtype) {
-    case kF16: return half_try_launch<F, kRowGroup, kF16, TL>(in, filt, out, s, st, dry, blocked);
-    case kBF16: return half_try_launch<F, kRowGroup, kBF16, TL>(in, filt, out, s, st, dry, blocked);
-    case kI8: return half_try_launch<F, kRowGroup, kI8, TL>(in, filt, out, s, st, dry, blocked);
+    case kF16: return half_try_launch<F, kRowGroup, kF16, TL, DIRECT>(in, filt, out, s, st, dry, blocked);
+    case kBF16: return half_try_launch<F, kRowGroup, kBF16, TL, DIRECT>(in, filt, out, s, st, dry, blocked);
+    case kI8: return half_try_launch<F, kRowGroup, kI8, TL, DIRECT>(in, filt, out, s, st, dry, blocked);
     default: return DCONV_UNSUPPORTED;
     }
 }
 
 template <>
 int half_launch_for_F<DCONV_F>(const void* in, const void* filt, float* out, const Shape& s,
-                               hipStream_t st, int dtype, bool large_tile, bool blocked, bool dry)
+                               hipStream_t st, int dtype, int config, bool blocked, bool dry)
 {
-    return large_tile ? launch_dtype<HalfTileLarge>(in, filt, out, s, st, dtype, blocked, dry)
-                      : launch_dtype<HalfTileSmall>(in, filt, out, s, st, dtype, blocked, dry);
+    switch (config) {
+    case 0: return launch_dtype<HalfTileSmall, false>(in, filt, out, s, st, dtype, blocked, dry);
+    case 1: return launch_dtype<HalfTileLarge, false>(in, filt, out, s, st, dtype, blocked, dry);
+    case 2: return launch_dtype<HalfTileSmall, true>(in, filt, out, s, st, dtype, blocked, dry);
+    case 3: return launch_dtype<HalfTileLarge, true>(in, filt, out, s, st, dtype, blocked, dry);
+    default: return DCONV_UNSUPPORTED;
+    }
 }
 
 }  // namespace dconv

@@ -118,7 +118,20 @@ using HalfTileSmall = HalfTile<2, 2, 1, 4, 6>;
 using HalfTileLarge = HalfTile<2, 4, 2, 4, 4>;
 
 // RG: filter rows per chunk (the last group of a filter may be shorter).
-template <int F, int RG, int DT, class TL>
+// DIRECT: how a chunk travels from HBM to LDS.
+//   true:  16-byte buffer loads with the LDS bit set: lane l of a wave writes piece l of the 64
+//          consecutive LDS pieces the instruction is given, whatever HBM offset the lane asks
+//          for (out-of-range lanes write zeros).  A staged chunk never sits in registers, the
+//          requests are spread over the steps of the previous chunk and have all of it to
+//          arrive.  Consecutive lanes must then bring consecutive pieces of an LDS plane, i.e.
+//          the same 16-byte half of consecutive pixels (or filters): in HBM that is 16 bytes out
+//          of every pixel's run.
+//   false: through registers (requested when the previous chunk begins, written to LDS during
+//          the second half of its steps).  Lanes 2q and 2q+1 bring the two halves of pixel q,
+//          32 contiguous bytes in HBM: half as many memory lines per load instruction, which
+//          is what bounds the staging of the small tile when a pixel's channel run is long
+//          (channels-last layout; measured: 25-35 % faster there than DIRECT).
+template <int F, int RG, int DT, class TL, bool DIRECT>
 __global__ void __launch_bounds__(TL::THREADS, 2)
 general_half_kernel(HalfParams p)
 {
@@ -147,8 +160,14 @@ general_half_kernel(HalfParams p)
     if (tile >= p.tiles) return;                        // uniform: before any barrier
 
     const int LS = p.LS;
-    const int img_pieces = 2 * p.RS * LS;
-    const int SLOT = FB + 4 * img_pieces;               // words per LDS slot: filter block, image block
+    // In LDS the two 16-byte halves of a 32-byte channel run lie in two planes, so that the 32
+    // lanes of a half-wave (all of one half: that is the matrix-core operand layout) read 512
+    // contiguous bytes instead of every other 16-byte piece, which would use half the banks:
+    // image block [half][row][col] x 16 B, filter block [tap][half][filter] x 16 B.
+    const int img_plane = p.RS * LS;                    // pieces per plane of the image block
+    const int img_pieces = 2 * img_plane;
+    // words per LDS slot: filter block, image block (DIRECT: rounded up to whole waves of pieces)
+    const int SLOT = FB + 4 * (DIRECT ? (img_pieces + 63) & ~63 : img_pieces);
     const int64_t plane = (int64_t)p.Ho * p.Wo;
     const int CB = p.C * elem_bytes(DT);                // bytes per pixel (all channels)
 
@@ -173,14 +192,19 @@ general_half_kernel(HalfParams p)
     const int nslots = (nl - n_first) * p.Hc + (Ql - nl * p.Ho) - y_first + RG;
     const int k0 = kb * MT;
 
-    // ---- staging: byte offsets of this thread's pieces, the same for every chunk ---------------
+    // ---- staging: thread tid brings pieces tid + it * THREADS of each block; their byte offsets
+    // in HBM are the same for every chunk.  Piece e is (half, pixel) = (e / img_plane,
+    // e % img_plane) of the image block and (tap, half, filter) in that order of the filter block
+    // when DIRECT -- the order of the pieces in LDS -- and (pixel e / 2, half e % 2), (tap,
+    // filter, half) otherwise -- their order in HBM.
     uint32_t ig[NII];        // from in[n_first][0][0][0] (+ chunk shift), or kNowhere
 #pragma unroll
     for (int it = 0; it < NII; ++it) {
         const int e = tid + it * THREADS;
         uint32_t g = kNowhere;
         if (e < img_pieces) {
-            const int pix = e >> 1, half = e & 1;
+            const int half = DIRECT ? (e >= img_plane ? 1 : 0) : (e & 1);
+            const int pix = DIRECT ? e - half * img_plane : e >> 1;
             const int row = fdiv(pix, p.d_ls), col = pix - row * LS;
             const int dn = fdiv(y_first + row, p.d_hc);
             const int yy = y_first + row - dn * p.Hc;
@@ -189,11 +213,13 @@ general_half_kernel(HalfParams p)
         }
         ig[it] = g;
     }
+    static_assert(THREADS % (2 * MT) == 0, "a thread's filter pieces differ by whole taps");
     uint32_t wg[NFI];        // from filt[k0][group's first row][0][0] (+ channel shift)
 #pragma unroll
     for (int it = 0; it < NFI; ++it) {
         const int e = tid + it * THREADS;
-        const int t = e / (2 * MT), k = (e >> 1) % MT, half = e & 1;
+        const int t = e / (2 * MT);
+        const int half = DIRECT ? (e / MT) & 1 : e & 1, k = DIRECT ? e % MT : (e >> 1) % MT;
         // (filters beyond K lie beyond the end of the bank: the range check returns zero)
         wg[it] = e < FPIECES ? (uint32_t)(k * (F * F) * CB + t * p.ts + half * 16) : kNowhere;
     }
@@ -203,51 +229,69 @@ general_half_kernel(HalfParams p)
     const int64_t wfirst = (int64_t)k0 * (F * F) * CB;
     const int nch = p.C / CK * NG;
 
-    v4f ireg[NII], wreg[NFI];
-    auto fetch = [&](int chunk) __attribute__((always_inline)) {
+    __amdgpu_buffer_rsrc_t irs, wrs;                    // descriptors of the chunk being fetched
+    auto set_chunk = [&](int chunk) __attribute__((always_inline)) {
         const int cidx = chunk / NG, g = chunk - cidx * NG;
         const int64_t ioff = ifirst + (int64_t)g * RG * p.W * p.ps + (int64_t)cidx * p.gs;
-        const __amdgpu_buffer_rsrc_t irs = __builtin_amdgcn_make_buffer_rsrc(
+        irs = __builtin_amdgcn_make_buffer_rsrc(
             (void*)(p.in + ioff), 0, (int)min(in_bytes - ioff, (int64_t)0x7FFFFFFF), kRsrcFlags);
         const int64_t woff = wfirst + (int64_t)g * (RG * F) * p.ts + (int64_t)cidx * p.fgs;
-        const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        wrs = __builtin_amdgcn_make_buffer_rsrc(
             (void*)(p.filt + woff), 0, (int)min(filt_bytes - woff, (int64_t)0x7FFFFFFF), kRsrcFlags);
-#pragma unroll
-        for (int it = 0; it < NII; ++it)
-            ireg[it] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(irs, ig[it], 0, 0));
-#pragma unroll
-        for (int it = 0; it < NFI; ++it)
-            wreg[it] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrs, wg[it], 0, 0));
     };
-    // pieces beyond the blocks go to sixteen spare bytes behind the slots
-    const int trash = 2 * SLOT;
-    // In LDS the two 16-byte halves of a 32-byte channel run lie in two planes, so that the 32
-    // lanes of a half-wave (all of one half: that is the matrix-core operand layout) read 512
-    // contiguous bytes instead of every other 16-byte piece, which would use half the banks:
-    // image block [half][row][col] x 16 B, filter block [tap][half][filter] x 16 B.  Piece e of
-    // a block is (pixel or tap-and-filter e / 2, half e % 2), as in HBM.
-    static_assert(THREADS % (2 * MT) == 0, "a thread's filter pieces differ by whole taps");
-    const int img_plane = p.RS * LS;                    // pieces per plane of the image block
-    const int ipos = (tid & 1) * img_plane + (tid >> 1);                       // + it * THREADS / 2
-    const int wpos = (tid / (2 * MT)) * (2 * MT) + (tid & 1) * MT + (tid >> 1) % MT;   // + it * THREADS
     // staging item k < NII is an image piece, item NII + q a filter piece
     constexpr int NI = NII + NFI;
+
+    // DIRECT.  A wave skips the items that lie wholly beyond a block (uniform); the last wave of
+    // the image block may write zeros into the padding behind it.  Inside a chunk item k is
+    // requested at step k * kSpread / NI.  The large tile spreads its requests over all the steps
+    // every chunk has, so that a workgroup's requests do not reach the memory pipeline in one
+    // burst (10 % on large layers); the small tile, whose steps are half as long and whose two
+    // workgroups per CU already interleave, does better with them in the first steps (measured).
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    const int wave_piece = wave * kWave;                // first piece of this wave within an item
+    auto fetch_item = [&](int k, float* slot) __attribute__((always_inline)) {
+        if (k < NII) {
+            if (k * THREADS + wave_piece < img_pieces)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    irs, (lds_ptr)(slot + FB + 4 * (k * THREADS + wave_piece)), 16, (int)ig[k], 0, 0, 0);
+        } else {
+            const int q = k - NII;
+            if (q * THREADS + wave_piece < FPIECES)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    wrs, (lds_ptr)(slot + 4 * (q * THREADS + wave_piece)), 16, (int)wg[q], 0, 0, 0);
+        }
+    };
+    constexpr int kSteps0 = SL < S ? SL : S;
+    constexpr int kSpread = THREADS == 512 ? kSteps0 : (kSteps0 > 8 ? kSteps0 - 7 : 1);
+
+    // not DIRECT.  All loads of a chunk are issued when the previous chunk begins; item k goes to
+    // LDS at step kFirstCommit + k / kPerStep of it, so that the LDS writes issue between
+    // matrix-core instructions.  Pieces beyond the blocks go to sixteen spare bytes behind the
+    // slots.
+    v4f ireg[DIRECT ? 1 : NII], wreg[DIRECT ? 1 : NFI];
+    const int trash = 2 * SLOT;
+    const int ipos = (tid & 1) * img_plane + (tid >> 1);                       // + it * THREADS / 2
+    const int wpos = (tid / (2 * MT)) * (2 * MT) + (tid & 1) * MT + (tid >> 1) % MT;   // + it * THREADS
+    auto load_regs = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < NII; ++it)
+            ireg[DIRECT ? 0 : it] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(irs, ig[it], 0, 0));
+#pragma unroll
+        for (int it = 0; it < NFI; ++it)
+            wreg[DIRECT ? 0 : it] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(wrs, wg[it], 0, 0));
+    };
     auto commit_item = [&](int k, float* slot) __attribute__((always_inline)) {
         if (k < NII) {
             const int e = tid + k * THREADS;
-            *reinterpret_cast<v4f*>(e < img_pieces ? slot + FB + 4 * (ipos + k * (THREADS / 2)) : lds + trash) = ireg[k];
+            *reinterpret_cast<v4f*>(e < img_pieces ? slot + FB + 4 * (ipos + k * (THREADS / 2)) : lds + trash) =
+                ireg[DIRECT ? 0 : k];
         } else {
             const int e = tid + (k - NII) * THREADS;
-            *reinterpret_cast<v4f*>(e < FPIECES ? slot + 4 * (wpos + (k - NII) * THREADS) : lds + trash) = wreg[k - NII];
+            *reinterpret_cast<v4f*>(e < FPIECES ? slot + 4 * (wpos + (k - NII) * THREADS) : lds + trash) =
+                wreg[DIRECT ? 0 : k - NII];
         }
     };
-    auto commit = [&](float* slot) __attribute__((always_inline)) {
-#pragma unroll
-        for (int k = 0; k < NI; ++k) commit_item(k, slot);
-    };
-    // Inside a chunk the items go to the other slot during the second half of the steps, a few
-    // per step, so that their LDS writes issue between matrix-core instructions: item k at step
-    // kFirstCommit + k / kPerStep (the loads were all issued when the chunk began).
     constexpr int kFirstCommit = S / 2;
     constexpr int kPerStep = (NI + (S - kFirstCommit) - 1) / (S - kFirstCommit);
 
@@ -292,14 +336,28 @@ general_half_kernel(HalfParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
 
-    // ---- chunks: compute chunk u from one slot while chunk u+1 is on its way to the registers ---
-    fetch(0);
-    commit(lds);
+    // ---- chunks: compute chunk u from one slot while chunk u+1 travels to the other ------------
+    set_chunk(0);
+    if constexpr (DIRECT) {
+#pragma unroll
+        for (int k = 0; k < NI; ++k) fetch_item(k, lds);
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wave's pieces are in LDS
+    } else {
+        load_regs();
+#pragma unroll
+        for (int k = 0; k < NI; ++k) commit_item(k, lds);
+    }
     __syncthreads();
     for (int u = 0; u < nch; ++u) {
         const float* cur = lds + (u & 1) * SLOT;
+        // the other slot was last read during chunk u-1, which every wave left before the barrier
+        // that ended it
         float* nxt = lds + ((u + 1) & 1) * SLOT;
-        if (u + 1 < nch) fetch(u + 1);
+        const bool more = u + 1 < nch;
+        if (more) {
+            set_chunk(u + 1);
+            if constexpr (!DIRECT) load_regs();
+        }
         const bool shortg = SL != S && (u % NG) == NG - 1;     // a last row group: fewer steps
         v4f a0[MW], b0[NW], a1[MW], b1[NW];
         load_ops(0, cur, a0, b0);
@@ -310,12 +368,16 @@ general_half_kernel(HalfParams p)
             v4f (&b)[NW] = (s & 1) ? b1 : b0;
             const bool last_step = s == S - 1 || (s == SL - 1 && shortg);
             if (!last_step) load_ops(s + 1, cur, (s & 1) ? a0 : a1, (s & 1) ? b0 : b1);
-            // slot `nxt` was last read during chunk u-1, which every wave left before the barrier
-            // that ended it
-            if (s >= kFirstCommit && u + 1 < nch) {
+            if (more) {
+                if constexpr (DIRECT) {
 #pragma unroll
-                for (int q = 0; q < kPerStep; ++q)
-                    if ((s - kFirstCommit) * kPerStep + q < NI) commit_item((s - kFirstCommit) * kPerStep + q, nxt);
+                    for (int k = 0; k < NI; ++k)
+                        if (k * kSpread / NI == s) fetch_item(k, nxt);
+                } else if (s >= kFirstCommit) {
+#pragma unroll
+                    for (int q = 0; q < kPerStep; ++q)
+                        if ((s - kFirstCommit) * kPerStep + q < NI) commit_item((s - kFirstCommit) * kPerStep + q, nxt);
+                }
             }
 #pragma unroll
             for (int mt = 0; mt < MW; ++mt)
@@ -323,7 +385,9 @@ general_half_kernel(HalfParams p)
                 for (int nt = 0; nt < NW; ++nt)
                     acc[mt][nt] = mfma_16B<DT>(a[mt], b[nt], acc[mt][nt]);
         }
-        if (shortg && u + 1 < nch) {             // the items of the steps that were left out
+        if constexpr (DIRECT) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's pieces of chunk u+1 have landed
+        } else if (shortg && more) {             // the items of the steps that were left out
 #pragma unroll
             for (int k = 0; k < NI; ++k)
                 if (kFirstCommit + k / kPerStep >= SL) commit_item(k, nxt);
@@ -420,7 +484,7 @@ inline HalfPlan make_half_plan(const Shape& s, int rg, int NT, int nii, int thre
     return pl;
 }
 
-template <int F, int RG, int DT, class TL>
+template <int F, int RG, int DT, class TL, bool DIRECT>
 int half_try_launch(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st, bool dry,
                     bool blocked)
 {
@@ -429,8 +493,10 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
     if (s.C % (kHalfChunkBytes / EB) != 0) return DCONV_UNSUPPORTED;
     const HalfPlan pl = make_half_plan(s, RG, NT, TL::NII, TL::THREADS);
     if (!pl.ok) return DCONV_UNSUPPORTED;
-    const int64_t slot_words = (int64_t)S * MT * 8 + 8LL * pl.RS * pl.LS;
-    const int64_t lds_bytes = 4 * (2 * slot_words + 4);
+    // two slots (filter block, image block), as the kernel lays them out
+    const int64_t img_pieces = 2LL * pl.RS * pl.LS;
+    const int64_t slot_words = (int64_t)S * MT * 8 + 4 * (DIRECT ? (img_pieces + 63) & ~63LL : img_pieces);
+    const int64_t lds_bytes = 4 * (2 * slot_words + (DIRECT ? 0 : 4));
     if (lds_bytes > kGenLdsLimit) return DCONV_UNSUPPORTED;
     const int KB = (s.K + MT - 1) / MT;
     const int64_t tiles = ((int64_t)(pl.nstrips - 1) * pl.pt_full + pl.pt_last) * KB;
@@ -449,14 +515,9 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
     if (dry) return DCONV_OK;
     if ((((uintptr_t)in) & 15) != 0 || (((uintptr_t)filt) & 15) != 0) return DCONV_UNSUPPORTED;
 
-    auto kern = general_half_kernel<F, RG, DT, TL>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kGenLdsLimit) != hipSuccess)
-            return DCONV_LAUNCH_FAILED;
-        attr_set = true;
-    }
+    auto kern = general_half_kernel<F, RG, DT, TL, DIRECT>;
+    static std::atomic<uint64_t> lds_limit_raised{0};
+    if (!raise_lds_limit((const void*)kern, kGenLdsLimit, lds_limit_raised)) return DCONV_LAUNCH_FAILED;
     const int per_xcd = (int)((tiles + 7) / 8);
     HalfParams p{(const char*)in, (const char*)filt, out, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo,
                  pl.bw, pl.nstrips, pl.LS, pl.RS, pl.pt_full, KB, (int)tiles, per_xcd, s.Ho + RG - 1,
@@ -469,9 +530,14 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
+// Tile configurations of the short-data-type kernel (DCONV_VARIANT_TILED_CFG0 + i forces one):
+// 0: small tile, 1: large tile, both staged through registers; 2: small tile, 3: large tile,
+// both staged directly into LDS.
+constexpr int kHalfConfigs = 4;
+
 // Implemented once per filter side, each in its own translation unit.
 template <int F>
 int half_launch_for_F(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
-                      int dtype, bool large_tile, bool blocked, bool dry);
+                      int dtype, int config, bool blocked, bool dry);
 
 }  // namespace dconv

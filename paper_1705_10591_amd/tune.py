@@ -10,7 +10,9 @@ that the rules can be checked or re-derived on another chip.
     python -m paper_1705_10591_amd.tune single H W K F
     python -m paper_1705_10591_amd.tune general N C H W K F
     python -m paper_1705_10591_amd.tune bf16 N C H W K F          (general case, bf16 inputs)
-    python -m paper_1705_10591_amd.tune table single|general|bf16 (the shapes the rules were set on)
+    python -m paper_1705_10591_amd.tune bf16-blocked N C H W K F  (the same, channel-blocked layout)
+    python -m paper_1705_10591_amd.tune table single|general|bf16|bf16-blocked
+                                                                  (the shapes the rules were set on)
 """
 from __future__ import annotations
 
@@ -41,8 +43,9 @@ def _time(fn, warm_ms: float = 40.0, steps: int = 20) -> float:
 
 
 def _config_count(kind: str) -> int:
-    # the short-data-type kernel has two tile shapes (64 filters x 256 pixels, 128 x 512)
-    return 2 if kind == "bf16" else dconv.tile_config_count(kind == "single")
+    # the short-data-type kernel: 64 filters x 256 pixels and 128 x 512 staged through registers,
+    # the same two staged directly into LDS
+    return 4 if kind.startswith("bf16") else dconv.tile_config_count(kind == "single")
 
 
 def tune(kind: str, dims, steps: int = 20):
@@ -54,12 +57,14 @@ def tune(kind: str, dims, steps: int = 20):
         f = torch.rand(K, F, F, device="cuda", generator=gen) - 0.5
         out = torch.empty(K, H - F + 1, W - F + 1, device="cuda")
         call = lambda v: dconv.dconv_single_channel(x, f, out=out, variant=v)
-    elif kind == "bf16":
+    elif kind.startswith("bf16"):
         N, C, H, W, K, F = dims
-        x = torch.rand(N, H, W, C, device="cuda", generator=gen).to(torch.bfloat16)
-        f = ((torch.rand(K, F, F, C, device="cuda", generator=gen) - 0.5) * 0.1).to(torch.bfloat16)
+        blocked = kind == "bf16-blocked"
+        xs, fs = ((N, C // 16, H, W, 16), (K, C // 16, F, F, 16)) if blocked else ((N, H, W, C), (K, F, F, C))
+        x = torch.rand(*xs, device="cuda", generator=gen).to(torch.bfloat16)
+        f = ((torch.rand(*fs, device="cuda", generator=gen) - 0.5) * 0.1).to(torch.bfloat16)
         out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda")
-        call = lambda v: dconv.dconv_general_half(x, f, out=out, variant=v)
+        call = lambda v: dconv.dconv_general_half(x, f, out=out, variant=v, blocked=blocked)
     else:
         N, C, H, W, K, F = dims
         x = torch.rand(N, C, H, W, device="cuda", generator=gen)
@@ -104,9 +109,13 @@ TABLE_BF16 = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (32, 128, 56, 
               (16, 512, 14, 14, 512, 3), (64, 128, 28, 28, 128, 3), (8, 128, 112, 112, 128, 3)]
 
 
+KINDS = ("single", "general", "bf16", "bf16-blocked")
+
+
 def table(kind: str) -> None:
     """One line per shape: the library's choice and every configuration, in microseconds."""
-    shapes = {"single": TABLE_SINGLE, "general": TABLE_GENERAL, "bf16": TABLE_BF16}[kind]
+    shapes = {"single": TABLE_SINGLE, "general": TABLE_GENERAL, "bf16": TABLE_BF16,
+              "bf16-blocked": TABLE_BF16}[kind]
     n = _config_count(kind)
     print(f"# {kind}: microseconds per launch; columns: library choice, configurations 0..{n - 1} "
           "(n/a = cannot hold the shape), fastest configuration, library / fastest")
@@ -120,13 +129,13 @@ def table(kind: str) -> None:
 
 
 def main(argv):
-    if len(argv) == 2 and argv[0] == "table" and argv[1] in ("single", "general", "bf16"):
+    if len(argv) == 2 and argv[0] == "table" and argv[1] in KINDS:
         if not torch.cuda.is_available():
             print("tune needs a GPU", file=sys.stderr)
             return 2
         table(argv[1])
         return 0
-    if len(argv) < 2 or argv[0] not in ("single", "general", "bf16") or \
+    if len(argv) < 2 or argv[0] not in KINDS or \
             len(argv) - 1 != (4 if argv[0] == "single" else 6):
         print(__doc__)
         return 2

@@ -17,8 +17,10 @@ pytestmark = pytest.mark.gpu
 SIMPLE, TILED, AUTO = dconv.VARIANT_SIMPLE, dconv.VARIANT_TILED, dconv.VARIANT_AUTO
 TORCH_TYPE = {"f16": torch.float16, "bf16": torch.bfloat16}
 # the matrix-core kernel with its tile shape forced: 64 filters x 256 pixels, 128 x 512
-TILE_SMALL, TILE_LARGE = dconv.VARIANT_TILED_CFG0, dconv.VARIANT_TILED_CFG0 + 1
-KERNELS = [TILED, SIMPLE, TILE_SMALL, TILE_LARGE]
+# small and large tile staged through registers, small and large tile staged directly into LDS
+TILE_SMALL, TILE_LARGE, TILE_SMALL_DIRECT, TILE_LARGE_DIRECT = (dconv.VARIANT_TILED_CFG0 + i for i in range(4))
+TILES = (TILE_SMALL, TILE_LARGE, TILE_SMALL_DIRECT, TILE_LARGE_DIRECT)
+KERNELS = [TILED, SIMPLE, *TILES]
 
 
 def dev16(bits_nchw_like: np.ndarray, kind: str) -> torch.Tensor:
@@ -106,7 +108,7 @@ def test_half_non_finite_filter_stays_in_its_own_map(kind):
         fbad = fb.copy()
         fbad[bad] = inf_bits + 1            # a NaN pattern
         fbad[bad, 0, 0, 0] = inf_bits
-        for variant in (TILE_SMALL, TILE_LARGE):
+        for variant in TILES:
             got = run_half(xb, fbad, kind, variant)
             assert not np.isfinite(got[:, bad]).any()
             keep = [k for k in range(shape[4]) if k != bad]
@@ -122,7 +124,7 @@ def test_half_output_guard_bands_stay_untouched():
     n_out, guard = N * K * Ho * Wo, 4096
     buf = torch.full((n_out + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
     out = buf[guard:guard + n_out].view(N, K, Ho, Wo)
-    for variant in (TILE_SMALL, TILE_LARGE):
+    for variant in TILES:
         buf.fill_(float("nan"))
         dconv.dconv_general_half(dev16(xb, "f16"), dev16(fb, "f16"), out=out, variant=variant)
         torch.cuda.synchronize()
@@ -131,7 +133,8 @@ def test_half_output_guard_bands_stay_untouched():
         assert_within_bound(host[guard:guard + n_out].reshape(N, K, Ho, Wo), acc, mag, "half guard bands")
 
 
-@pytest.mark.parametrize("variant", [TILED, TILE_SMALL, TILE_LARGE], ids=["auto", "small", "large"])
+@pytest.mark.parametrize("variant", [TILED, *TILES],
+                         ids=["auto", "small", "large", "small-direct", "large-direct"])
 @pytest.mark.parametrize("kind", ["f16", "bf16"])
 @pytest.mark.parametrize("name", ["G2", "G3"])
 def test_half_config_shapes_sampled(name, kind, variant):
@@ -210,7 +213,8 @@ def test_int8_extreme_values_do_not_overflow_early():
     assert (got == C * F * F * 16384).all()
 
 
-@pytest.mark.parametrize("variant", [TILED, TILE_SMALL, TILE_LARGE], ids=["auto", "small", "large"])
+@pytest.mark.parametrize("variant", [TILED, *TILES],
+                         ids=["auto", "small", "large", "small-direct", "large-direct"])
 @pytest.mark.parametrize("name", ["G2", "G3"])
 def test_int8_config_shapes_sampled(name, variant):
     w = wl.CONFIGS[name]
