@@ -74,6 +74,32 @@ def time_launches(fn, steps, warmup, warm_ms=0.0):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
+def graph_replay_ms(fn, launches=20, replays=20):
+    """Per-launch time of `fn` when `launches` calls are captured into one HIP graph and the graph
+    is replayed: what a launch-bound caller gets (the calls only enqueue kernels, so they can be
+    captured once they have run once on the capture stream)."""
+    import torch
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        fn()
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        for _ in range(launches):
+            fn()
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * launches)
+
+
 def make_runner(w):
     import torch
     import workloads as wl
@@ -294,6 +320,9 @@ def main():
             r, (xw, fw) = make_runner(w)
             m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
             e = config_entry(w, m)
+            if name in ("S1", "G2"):
+                # the two launch-bound configurations: the same calls replayed from a HIP graph
+                e["ms_graph_replay"] = round(graph_replay_ms(r), 5)
             del r
             torch.cuda.empty_cache()
             if name == "S1":

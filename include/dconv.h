@@ -180,6 +180,15 @@ int dconv_general_lowp(const void *in, int N, int C, int H, int W,
 int dconv_tile_config_count(int single_channel);
 
 /*
+ * HIP graph capture.  Every entry point only enqueues kernels on `stream` (no
+ * synchronisation, no host-side reads), so calls can be captured into a graph
+ * and replayed.  The one exception is the workspace of dconv_general described
+ * below: the first call that needs it on a stream allocates and clears it,
+ * which is not allowed while that stream is capturing.  Run the calls once on
+ * the stream before capturing on it.
+ */
+
+/*
  * dconv_general keeps one device workspace per (device, stream) it has been
  * called on: when the tiles of a shape do not spread evenly over the chip, a
  * tile is summed over channels by several workgroups and their partial sums

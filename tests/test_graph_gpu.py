@@ -1,0 +1,81 @@
+"""The entry points under HIP graph capture: captured once, replayed several times.
+
+Every entry point only enqueues kernels on the stream it is given, so a sequence of calls can be
+captured into a graph and replayed without the launch cost of each call.  dconv_general may
+allocate (and clear) its workspace on the first call that needs it on a stream, which is not
+allowed while capturing: the calls are run once on the capture stream beforehand.
+
+Each replay is checked against the eager results bit for bit (the kernels are deterministic,
+shared tiles included), with the outputs cleared and eager work of the same library between the
+replays, and the eager results against the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_1705_10591_amd as dconv
+from helpers import assert_within_bound
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def test_captured_graph_replays_match_eager_calls():
+    shared = dconv.VARIANT_TILED_CFG0 + 2 * 3 + 1      # 64 x 256 tile, tiles shared between workgroups
+    x1, f1 = wl.random_case(31, 1, 1, 200, 300, 16, 3)
+    img, fs = x1[0, 0], f1[:, 0]
+    xg, fg = wl.random_case(32, 2, 8, 30, 30, 70, 3)
+    xs, fsh = wl.random_case(33, 3, 16, 28, 28, 130, 3)
+    xh, fh = wl.random_case(34, 2, 32, 20, 23, 40, 3)
+    xhr, xhb = wl.to_16bit(xh, "bf16")              # rounded values for the oracle, bits for the device
+    fhr, fhb = wl.to_16bit(fh, "bf16")
+
+    d_img, d_fs, d_xg, d_fg, d_xs, d_fsh = map(dev, (img, fs, xg, fg, xs, fsh))
+    d_xh, d_fh = (torch.from_numpy(np.ascontiguousarray(np.moveaxis(b, 1, -1)).view(np.int16))
+                  .view(torch.bfloat16).to("cuda") for b in (xhb, fhb))       # channels last
+    outs = [torch.empty(16, 198, 298, device="cuda"), torch.empty(2, 70, 28, 28, device="cuda"),
+            torch.empty(3, 130, 26, 26, device="cuda"), torch.empty(2, 40, 18, 21, device="cuda")]
+
+    def enqueue():
+        dconv.dconv_single_channel(d_img, d_fs, out=outs[0])
+        dconv.dconv_general(d_xg, d_fg, out=outs[1])
+        dconv.dconv_general(d_xs, d_fsh, out=outs[2], variant=shared)
+        dconv.dconv_general_half(d_xh, d_fh, out=outs[3])
+
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        enqueue()                      # on the capture stream: its workspace exists from here on
+    s.synchronize()
+    eager = [o.clone() for o in outs]
+
+    print("capturing four launches into one graph", flush=True)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        enqueue()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        print(f"replay {rep}", flush=True)
+        g.replay()
+        torch.cuda.synchronize()
+        for i, (o, e) in enumerate(zip(outs, eager)):
+            assert torch.equal(o, e), f"replay {rep}, launch {i}"
+        # eager work of the same kernels between replays (other buffers, default stream)
+        other = dconv.dconv_general(d_xs, d_fsh, variant=shared)
+        torch.cuda.synchronize()
+        assert torch.equal(other, eager[2])
+
+    acc, mag, _ = oracle.single_channel(img, fs)
+    assert_within_bound(eager[0].cpu().numpy(), acc, mag, "single channel")
+    for (x, f), e, what in (((xg, fg), eager[1], "general"), ((xs, fsh), eager[2], "general, shared tiles")):
+        acc, mag, _ = oracle.general(x, f)
+        assert_within_bound(e.cpu().numpy(), acc, mag, what)
+    acc, mag, _ = oracle.general(xhr, fhr)
+    assert_within_bound(eager[3].cpu().numpy(), acc, mag, "general bf16")
