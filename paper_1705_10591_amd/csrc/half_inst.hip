@@ -11,8 +11,9 @@ namespace dconv {
 namespace {
 constexpr int F = DCONV_F;
 constexpr int kRowGroup = half_row_group(F);
-}  // namespace
 
+// (This helper depends on F without naming it in its template arguments: it must stay local to
+// the translation unit, or the linker may keep one filter side's copy for all of them.)
 template <class TL, bool DIRECT>
 int launch_dtype(const void* in, const void* filt, float* out, const Shape& s, hipStream_t st,
                  int dtype, bool blocked, bool dry)
@@ -24,6 +25,8 @@ int launch_dtype(const void* in, const void* filt, float* out, const Shape& s, h
     default: return DCONV_UNSUPPORTED;
     }
 }
+
+}  // namespace
 
 template <>
 int half_launch_for_F<DCONV_F>(const void* in, const void* filt, float* out, const Shape& s,
