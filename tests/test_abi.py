@@ -122,3 +122,20 @@ def test_16_bit_entry_points_validate_before_launching():
     assert lib.dconv_general_i8(FAKE, 1, 32, 4, 8, FAKE, 2, 5, FAKE, None) == dconv.STATUS_BAD_SHAPE
     assert lib.dconv_general_i8_v(FAKE, *ok_dims, FAKE, 2, 3, FAKE, dconv.VARIANT_FEW_FILTERS, None) \
         == dconv.STATUS_UNSUPPORTED
+
+
+@pytest.mark.gpu
+def test_lds_width_microbenchmark_runs_and_narrow_units_lose_bandwidth():
+    """The paper's bank-width experiment on the LDS: 2-byte units get about half of 4-byte ones."""
+    import subprocess
+    from paper_1705_10591_amd.build import LDS_BENCH
+    if not LDS_BENCH.exists():
+        pytest.skip("lds_width_bench is not built (python -m paper_1705_10591_amd.build)")
+    r = subprocess.run([str(LDS_BENCH)], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, r.stderr
+    rate = {(m.group(1), int(m.group(2))): float(m.group(3))
+            for m in re.finditer(r"(read|write)\s+(\d+) B per lane:\s+[\d.]+ ms\s+([\d.]+) B/clk/CU", r.stdout)}
+    assert len(rate) == 8, r.stdout
+    assert rate[("read", 2)] < 0.6 * rate[("read", 4)]
+    assert rate[("read", 4)] < 0.6 * rate[("read", 8)]
+    assert rate[("read", 16)] > rate[("read", 8)]
