@@ -10,9 +10,10 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libdconv.so"
-# standalone microbenchmark of LDS access widths (the paper's bank-width experiment); no part of
-# the library
+# standalone microbenchmarks, no part of the library: LDS access widths (the paper's bank-width
+# experiment) and the hardware rates that shaped the kernels
 LDS_BENCH = PKG / "lds_width_bench"
+HW_BENCH = PKG / "hw_bench"
 BUILD = PKG / "_build"
 # (source, extra flags, object name); the general-case kernels are compiled once per filter side
 SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", [], "single"), ("single_fewfilters.hip", [], "single_fewfilters"),
@@ -53,12 +54,13 @@ def build(verbose: bool = False) -> Path:
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr[-4000:]}")
     os.replace(tmp, LIB)
-    cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], str(CSRC / "lds_width_bench.hip"), "-o", str(LDS_BENCH)]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed for lds_width_bench.hip:\n{r.stderr[-4000:]}")
+    for exe in (LDS_BENCH, HW_BENCH):
+        cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], str(CSRC / (exe.name + ".hip")), "-o", str(exe)]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed for {exe.name}.hip:\n{r.stderr[-4000:]}")
     if verbose:
-        print(f"built {LIB} and {LDS_BENCH}")
+        print(f"built {LIB}, {LDS_BENCH.name} and {HW_BENCH.name}")
     return LIB
 
 

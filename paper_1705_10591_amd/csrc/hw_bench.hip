@@ -1,0 +1,156 @@
+// Microbenchmarks of the hardware rates that shaped the kernels (standalone program, no part of
+// libdconv.so):
+//   1. HBM: fill, read and copy rates, and the rate of the single-channel kernel's store pattern
+//      -- 128-byte runs, 32 consecutive pixels of one output map -- when the rows of a map are a
+//      whole number of 128-byte lines long (runs cover lines exactly) and when they are not (most
+//      runs straddle two lines, each written in two pieces);
+//   2. the fp32 matrix-core loop of the general kernel (two operand pairs from LDS per four
+//      v_mfma_f32_32x32x2_f32) bare and with 8, 16, 32 integer vector-ALU instructions added per
+//      four matrix-core instructions: what an ordinary vector instruction costs the matrix cores.
+#include <hip/hip_runtime.h>
+#include <cstdio>
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+#define CHECK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { \
+    fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_)); return 1; } } while (0)
+
+// ---- 1. HBM ---------------------------------------------------------------------------------------
+
+__global__ void fill16(v4f* o, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) o[i] = (v4f){1, 2, 3, 4};
+}
+__global__ void read16(const v4f* a, float* o, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    float s = 0.f;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) { v4f v = a[i]; s += v[0] + v[3]; }
+    if (s == 123.456f) o[0] = s;          // never true for the zeros read: keeps the loads alive
+}
+__global__ void copy16(const v4f* a, v4f* o, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) o[i] = a[i];
+}
+// 32 maps of `rows` x `w` floats.  A wave takes a 128-pixel segment of one row and writes it to
+// all 32 maps: the lanes of half h write 32 consecutive pixels (128 bytes) of map 2 q + h.
+template <bool NT>
+__global__ void store_runs(float* o, int w, int rows) {
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    const int h = lane >> 5, l = lane & 31;
+    const int segs = (w + 127) / 128, total = rows * segs, nwaves = (gridDim.x * blockDim.x) >> 6;
+    for (int it = wave; it < total; it += nwaves) {
+        const int r = it / segs, s = it % segs;
+        for (int q = 0; q < 16; ++q) {
+            float* row = o + ((size_t)(2 * q + h) * rows + r) * w;
+            for (int nb = 0; nb < 4; ++nb) {
+                const int x = s * 128 + nb * 32 + l;
+                if (x < w) {
+                    if (NT) __builtin_nontemporal_store(1.f, row + x);
+                    else row[x] = 1.f;
+                }
+            }
+        }
+    }
+}
+
+// ---- 2. matrix cores next to vector-ALU work ----------------------------------------------------
+
+// NV integer vector instructions per four matrix-core instructions; 36 steps between barriers.
+template <int NV>
+__global__ void __launch_bounds__(256, 2) mfma_loop(float* o, int trips) {
+    __shared__ float sh[12288];
+    for (int i = threadIdx.x; i < 12288; i += 256) sh[i] = i * 0.001f;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int busy[8];
+    for (int i = 0; i < 8; ++i) busy[i] = threadIdx.x + i;
+    v16f acc[4];
+    for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+    const int ba = (lane >> 5) * 129 + (wave & 1) * 64 + (lane & 31);         // weights: 73 rows of 129 words
+    const int bb = 9288 + (lane & 31) + (lane >> 5) + (wave >> 1) * 64;       // pixels: rows of 28 words
+    for (int t = 0; t < trips; ++t) {
+        float a0 = sh[ba], a1 = sh[ba + 32], b0 = sh[bb], b1 = sh[bb + 32];
+#pragma unroll
+        for (int s = 0; s < 36; ++s) {
+            float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+            if (s + 1 < 36) {         // operands of the next step, requested before this step's arithmetic
+                na0 = sh[ba + (2 * s + 2) * 129];
+                na1 = sh[ba + (2 * s + 2) * 129 + 32];
+                nb0 = sh[bb + ((s + 1) % 9) * 28 + ((s + 1) / 9) * 280];
+                nb1 = sh[bb + 32 + ((s + 1) % 9) * 28 + ((s + 1) / 9) * 280];
+            }
+#pragma unroll
+            for (int v = 0; v < NV; ++v) busy[v & 7] = busy[v & 7] * 3 + lane + s;
+            __builtin_amdgcn_sched_barrier(0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[3], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+        }
+        __syncthreads();
+    }
+    float r = 0.f;
+    for (int i = 0; i < 8; ++i) r += (float)busy[i];
+    for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) r += acc[n][i];
+    o[blockIdx.x * 256 + threadIdx.x] = r;
+}
+
+template <class L>
+int time_ms(L launch, int reps, float* ms) {
+    hipEvent_t a, b;
+    CHECK(hipEventCreate(&a));
+    CHECK(hipEventCreate(&b));
+    launch();
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(a));
+    for (int i = 0; i < reps; ++i) launch();
+    CHECK(hipEventRecord(b));
+    CHECK(hipEventSynchronize(b));
+    CHECK(hipEventElapsedTime(ms, a, b));
+    *ms /= reps;
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int main() {
+    int cus = 0;
+    CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0));
+    const size_t bytes = (size_t)4 << 30, n16 = bytes / 16;
+    float *a = nullptr, *b = nullptr;
+    CHECK(hipMalloc(&a, bytes));
+    CHECK(hipMalloc(&b, bytes));
+    CHECK(hipMemset(a, 0, bytes));
+    float ms = 0.f;
+    printf("# HBM, 4 GiB buffers, %d CUs\n", cus);
+    if (time_ms([&] { hipLaunchKernelGGL(fill16, dim3(8192), dim3(256), 0, 0, (v4f*)b, n16); }, 5, &ms)) return 1;
+    printf("fill, 16 B per lane:                        %7.3f ms  %6.0f GB/s\n", ms, bytes / ms / 1e6);
+    if (time_ms([&] { hipLaunchKernelGGL(read16, dim3(8192), dim3(256), 0, 0, (const v4f*)a, b, n16); }, 5, &ms)) return 1;
+    printf("read, 16 B per lane:                        %7.3f ms  %6.0f GB/s\n", ms, bytes / ms / 1e6);
+    if (time_ms([&] { hipLaunchKernelGGL(copy16, dim3(8192), dim3(256), 0, 0, (const v4f*)a, (v4f*)b, n16); }, 5, &ms)) return 1;
+    printf("copy, 16 B per lane (read + written):       %7.3f ms  %6.0f GB/s\n", ms, 2.0 * bytes / ms / 1e6);
+    for (int w : {4096, 4092}) {
+        const int rows = w == 4096 ? 8176 : 8184;           // 32 maps just under 4 GiB
+        const size_t total = (size_t)32 * rows * w * 4;
+        if (total > bytes) return 1;
+        if (time_ms([&] { hipLaunchKernelGGL(store_runs<false>, dim3(8192), dim3(256), 0, 0, b, w, rows); }, 3, &ms)) return 1;
+        printf("128 B runs, rows of %d floats:              %7.3f ms  %6.0f GB/s\n", w, ms, total / ms / 1e6);
+        if (time_ms([&] { hipLaunchKernelGGL(store_runs<true>, dim3(8192), dim3(256), 0, 0, b, w, rows); }, 3, &ms)) return 1;
+        printf("128 B runs, rows of %d floats, nontemporal: %7.3f ms  %6.0f GB/s\n", w, ms, total / ms / 1e6);
+    }
+    printf("# fp32 matrix-core loop fed from LDS, 2 workgroups of 4 waves per CU, 36 steps per barrier\n");
+    const int blocks = 2 * cus, trips = 2000;
+    const double flop = (double)blocks * 4 * trips * 36 * 4 * 4096.0;
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<0>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    printf("no other vector instructions:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<8>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    printf("+ 8 integer VALU per 4 MFMA:                %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<16>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    printf("+ 16 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<32>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    printf("+ 32 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    CHECK(hipFree(a));
+    CHECK(hipFree(b));
+    return 0;
+}

@@ -139,3 +139,20 @@ def test_lds_width_microbenchmark_runs_and_narrow_units_lose_bandwidth():
     assert rate[("read", 2)] < 0.6 * rate[("read", 4)]
     assert rate[("read", 4)] < 0.6 * rate[("read", 8)]
     assert rate[("read", 16)] > rate[("read", 8)]
+
+
+@pytest.mark.gpu
+def test_hardware_rate_microbenchmark_runs():
+    """Straddled 128-byte runs are written much slower than aligned ones; vector-ALU work next to
+    the matrix-core loop costs matrix-core time."""
+    import subprocess
+    from paper_1705_10591_amd.build import HW_BENCH
+    if not HW_BENCH.exists():
+        pytest.skip("hw_bench is not built (python -m paper_1705_10591_amd.build)")
+    r = subprocess.run([str(HW_BENCH)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    val = {m.group(1).strip(): float(m.group(2))
+           for m in re.finditer(r"^([^#\n][^:]*):\s+[\d.]+ ms\s+([\d.]+) (?:GB/s|TFLOP/s)", r.stdout, re.M)}
+    assert len(val) == 11, r.stdout
+    assert val["128 B runs, rows of 4092 floats"] < 0.8 * val["128 B runs, rows of 4096 floats"]
+    assert val["+ 32 integer VALU per 4 MFMA"] < 0.8 * val["no other vector instructions"]
