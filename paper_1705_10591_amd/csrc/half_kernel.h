@@ -250,6 +250,9 @@ general_half_kernel(HalfParams p)
     // workgroups per CU already interleave, does better with them in the first steps (measured).
     typedef __attribute__((address_space(3))) void* lds_ptr;
     const int wave_piece = wave * kWave;                // first piece of this wave within an item
+    // (The offset argument is cast to the builtin's own type, int: given an unsigned value the
+    // host pass of hipcc 7.2 leaves the kernel's launch stub out of the object without a
+    // diagnostic, and the library then fails to load.)
     auto fetch_item = [&](int k, float* slot) __attribute__((always_inline)) {
         if (k < NII) {
             if (k * THREADS + wave_piece < img_pieces)
