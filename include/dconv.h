@@ -58,10 +58,19 @@ enum {
                                  paper's Algorithm 1 as it stands); what AUTO
                                  picks for up to 12 filters (20 from 5x5 on) on
                                  large images                                    */
-    DCONV_VARIANT_TILED_CFG0 = 0x100
+    DCONV_VARIANT_SPECIAL_CASE = 4,
+                              /* dconv_general with C = 1 only: the tiled kernel
+                                 of the single-channel case with the N images as
+                                 further work items; what AUTO picks for large
+                                 output volumes of wide images with small filters */
+    DCONV_VARIANT_TILED_CFG0 = 0x100,
                               /* DCONV_VARIANT_TILED_CFG0 + i: the tiled kernel
                                  with tile configuration i forced, 0 <= i <
                                  dconv_tile_config_count(); for tests and tuners */
+    DCONV_VARIANT_SPECIAL_CASE_CFG0 = 0x200
+                              /* + i: DCONV_VARIANT_SPECIAL_CASE with tile
+                                 configuration i of the single-channel case,
+                                 0 <= i < dconv_tile_config_count(1)             */
 };
 
 /*
@@ -87,6 +96,9 @@ int dconv_single_channel(const float *img, int H, int W,
  *   out  [N][K][H-F+1][W-F+1]    device, written
  * Errors as above; additionally N, C <= 0, or more than 2^31-1 elements in
  * `in`, in `filt` or in one image's output [K][Ho][Wo], -> DCONV_BAD_SHAPE.
+ * With C = 1 this is the special case of Sec. 3 applied to N images: the
+ * automatic choice runs them on the single-channel kernel (all images in one
+ * launch) where that is the faster one, see DCONV_VARIANT_SPECIAL_CASE.
  */
 int dconv_general(const float *in, int N, int C, int H, int W,
                   const float *filt, int K, int F,

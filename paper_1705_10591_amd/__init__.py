@@ -19,6 +19,8 @@ LIB_PATH = _PKG / "libdconv.so"
 
 VARIANT_AUTO, VARIANT_SIMPLE, VARIANT_TILED, VARIANT_FEW_FILTERS = 0, 1, 2, 3
 VARIANT_TILED_CFG0 = 0x100     # + i: tiled kernel with tile configuration i forced
+VARIANT_SPECIAL_CASE = 4       # dconv_general with one channel: the single-channel tiled kernel
+VARIANT_SPECIAL_CASE_CFG0 = 0x200   # + i: the same with its tile configuration i forced
 STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAUNCH_FAILED = range(5)
 
 EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",

@@ -49,10 +49,11 @@ struct SingleParams {
     const float* img;
     const float* filt;
     float* out;
+    int N;           // images (each convolved with the same filters); img and out are dense over n
     int H, W, K, Ho, Wo;
     int tiles_x, tiles_y;
     int fbw;         // 32-filter blocks handled by one workgroup: 1, 2 or 4
-    int fgroups;     // filter groups (of 32*fbw filters); work items = tiles * fgroups
+    int fgroups;     // filter groups (of 32*fbw filters); work items = N * tiles * fgroups
     int per_xcd;     // work items per XCD (the chip has 8), see the mapping in the kernel
     int wrap;        // 1: row ends are completed with the head of the next row (wide images)
 };
@@ -96,9 +97,13 @@ single_tiled_kernel(SingleParams p)
     // Workgroups are handed to the 8 XCDs round-robin by their linear id.  Give each XCD one
     // contiguous range of work items (a band of the image), walked along x, so that its L2
     // sees neighbouring tiles and every XCD gets the same mix of edge and interior tiles.
-    const int item = (blockIdx.x % 8) * p.per_xcd + blockIdx.x / 8;
+    const int item_all = (blockIdx.x % 8) * p.per_xcd + blockIdx.x / 8;
     const int ntiles = p.tiles_x * p.tiles_y;
-    if (item >= ntiles * p.fgroups) return;                // uniform: before any barrier
+    const int per_image = ntiles * p.fgroups;
+    const int n = item_all / per_image, item = item_all - n * per_image;
+    if (n >= p.N) return;                                  // uniform: before any barrier
+    const float* img = p.img + (int64_t)n * p.H * p.W;
+    float* out = p.out + (int64_t)n * p.K * p.Ho * p.Wo;
     const int fgroup = item / ntiles, tile = item - fgroup * ntiles;
     const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
     const int x0 = tx * TW, y0 = ty * TR;
@@ -123,8 +128,8 @@ single_tiled_kernel(SingleParams p)
         const int cols = min(PC0, p.W - x0);
         const int rows_ok = min(ROWS, p.H - y0);
         const int prow_ok = wrap_tile ? min(ROWS, p.H - y0 - 1) : 0;
-        const float* src = p.img + (int64_t)y0 * p.W + x0;
-        const float* psrc = p.img + (int64_t)(y0 + 1) * p.W - PC0;
+        const float* src = img + (int64_t)y0 * p.W + x0;
+        const float* psrc = img + (int64_t)(y0 + 1) * p.W - PC0;
         // all loads are issued before the first LDS store: one trip to HBM, not one per batch
         constexpr int UN = (TOTAL + kThreads - 1) / kThreads;
         float v[UN];
@@ -149,7 +154,7 @@ single_tiled_kernel(SingleParams p)
 
     const int64_t plane = (int64_t)p.Ho * p.Wo;
     const int pm = (int)(plane & 31);
-    const int a0 = (int)(((uintptr_t)p.out >> 2) & 31);   // misalignment of the buffer itself
+    const int a0 = (int)(((uintptr_t)out >> 2) & 31);     // misalignment of this image's output
     const int rows_here = min(TR, p.Ho - y0);
     const int dY = h * (LS - (F - 1));          // second tap of a pair sits on the next row
     const int kb = fb * 32;
@@ -309,7 +314,7 @@ single_tiled_kernel(SingleParams p)
         if (ch > 0) compute(std::true_type{}, acc, base);
         else compute(std::false_type{}, acc, base);
         const PassOut pd{tw_lane + c0, tr_lane + c0, tr_lane + c0n,
-                         p.out + kb * plane + rowoff + X, X, kind, needs_head};
+                         out + kb * plane + rowoff + X, X, kind, needs_head};
         write_back(acc, pd);
     }
 }
@@ -321,6 +326,7 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
 {
     SingleParams p;
     p.img = img; p.filt = filt; p.out = out;
+    p.N = s.N;
     p.H = s.H; p.W = s.W; p.K = s.K; p.Ho = s.Ho; p.Wo = s.Wo;
     p.tiles_x = (s.Wo + TW - 1) / TW;
     p.tiles_y = (s.Ho + TR - 1) / TR;
@@ -330,7 +336,7 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     // Completing row ends with the next row's head needs a pass to span at most one row end,
     // and every pass that reaches the row end to lie in the last tile column.
     p.wrap = (s.Wo >= 2 * (32 * NBW + 32) && (p.tiles_x - 1) * TW + 32 <= s.Wo) ? 1 : 0;
-    const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups;
+    const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups * s.N;
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
     hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE>),
@@ -352,12 +358,14 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
 {
     if (cfg >= kSingleConfigs) return DCONV_UNSUPPORTED;
     if (cfg < 0) {
-        const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4;
+        // (work items of all images count: a batch of small images fills the chip like one
+        // large image)
+        const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4 * s.N;
         auto items = [&](int tw, int tr) {
             return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
         };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
-        const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4);
+        const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
         if (s.K <= 32 && t128 < ((F <= 4 && s.K > 16) ? 8192 : 1536)) {
             // one filter block: the four waves of a workgroup take one row each, and on images up
             // to about 768^2 (1080p for a full block of small filters) the smallest tile, one pass
@@ -391,8 +399,24 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
 bool single_tiled_supports(const Shape& s)
 {
     // lane offsets of the write-back are 32-bit: one output plane plus a row must fit
-    return s.N == 1 && s.C == 1 && s.F >= 1 && s.F <= 11 &&
+    return s.N >= 1 && s.C == 1 && s.F >= 1 && s.F <= 11 &&
            (int64_t)s.Ho * s.Wo < (1LL << 29);
+}
+
+// A batch of one-channel images (dconv_general with C = 1): this kernel takes the images as
+// further work items.  It is the better choice where its line-aligned output stream pays: large
+// output volumes (beyond what the memory-side cache absorbs) of images wide enough for its
+// 128-pixel passes, with filters small enough for the output stream to bound the time.  Measured
+// against the general kernel on 128^2 .. 1024^2 images, 32 and 64 filters, 3x3 .. 11x11, 40 M to
+// 320 M outputs: 1.4 to 2.2 times faster where chosen, the general kernel up to 1.9 times
+// faster elsewhere (it numbers its pixels across rows and images and wastes nothing on narrow
+// ones).
+bool single_batch_preferred(const Shape& s)
+{
+    if (!single_tiled_supports(s)) return false;
+    const int64_t outputs = (int64_t)s.N * s.K * s.Ho * s.Wo;
+    if (outputs < 120000000LL) return false;
+    return (s.F <= 5 && s.Wo >= 160) || (s.F <= 8 && s.Wo >= 256);
 }
 
 int single_tile_configs() { return kSingleConfigs; }

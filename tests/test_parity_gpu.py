@@ -534,3 +534,63 @@ def test_shared_tiles_on_two_streams_at_once_and_workspace_release():
     again = dconv.dconv_general(xd, fd, variant=split)
     torch.cuda.synchronize()
     assert torch.equal(again, outs[0][0])
+
+
+# ---- a batch of one-channel images: the special-case kernel with the images as work items ----------
+
+# (N, H, W, K, F): narrow and wide images (row ends completed across rows only on wide ones),
+# several filter groups, image sizes whose planes start at every misalignment
+BATCH_SHAPES = [(3, 20, 23, 5, 3), (4, 9, 700, 40, 5), (2, 37, 41, 130, 3), (5, 12, 330, 33, 7),
+                (7, 8, 8, 4, 3), (2, 30, 270, 7, 11), (3, 6, 1500, 70, 1)]
+
+
+@pytest.mark.parametrize("shape", BATCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_one_channel_batch_on_the_special_case_kernel(shape):
+    N, H, W, K, F = shape
+    x, f = wl.random_case(900 + N + K, N, 1, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    xi, fi = wl.integer_case(950 + N + K, N, 1, H, W, K, F)
+    acci, _, _ = oracle.general(xi, fi)
+    variants = [dconv.VARIANT_SPECIAL_CASE] + [dconv.VARIANT_SPECIAL_CASE_CFG0 + i
+                                               for i in range(dconv.tile_config_count(True))]
+    for v in variants:
+        assert_within_bound(run_general(x, f, v), acc, mag, f"batch {shape} variant {v:#x}")
+        np.testing.assert_array_equal(run_general(xi, fi, v), acci.astype(np.float32))
+
+
+def test_one_channel_batch_guard_bands_and_refusals():
+    N, H, W, K, F = 3, 21, 340, 37, 5
+    x, f = wl.random_case(970, N, 1, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    total = N * K * (H - F + 1) * (W - F + 1)
+    guard = 1001                      # an output buffer that starts in the middle of a 128-byte line
+    buf = torch.full((total + 2 * guard,), float("nan"), device="cuda")
+    out = buf[guard:guard + total].view(N, K, H - F + 1, W - F + 1)
+    dconv.dconv_general(dev(x), dev(f), out=out, variant=dconv.VARIANT_SPECIAL_CASE)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + total:]).all()
+    assert_within_bound(out.cpu().numpy(), acc, mag, "batch with guard bands")
+    # more than one channel: not the special case
+    x2, f2 = wl.random_case(971, 2, 2, 12, 12, 3, 3)
+    with pytest.raises(dconv.DconvError) as e:
+        run_general(x2, f2, dconv.VARIANT_SPECIAL_CASE)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
+
+
+def test_one_channel_batch_automatic_choice_large_volume_sampled():
+    """128 M outputs of 300-wide images with 3x3 filters: the automatic choice is the special-case
+    kernel; checked on sampled outputs and against the general kernel on one image."""
+    N, H, W, K, F = 24, 300, 302, 64, 3
+    x, f = wl.random_case(980, N, 1, H, W, K, F)
+    xd, fd = dev(x), dev(f)
+    out = dconv.dconv_general(xd, fd)
+    torch.cuda.synchronize()
+    idx = wl.sample_indices(981, out.numel(), 20000)
+    got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    acc, mag = oracle.general_at(x, f, idx)
+    assert_within_bound(got, acc, mag, "one-channel batch, automatic choice")
+    last = dconv.dconv_general(xd[N - 1:], fd, variant=TILED)           # the general kernel
+    torch.cuda.synchronize()
+    accl, magl, _ = oracle.general(x[N - 1:], f)
+    assert_within_bound(out[N - 1:].cpu().numpy(), accl, magl, "last image, special-case kernel")
+    assert_within_bound(last.cpu().numpy(), accl, magl, "last image, general kernel")

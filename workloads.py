@@ -96,6 +96,9 @@ PAPER_SWEEP = {w.name: w for w in (
     _mk("B_32_F3", "general", 128, 64, 32, 32, 128, 3, "u01", "he", 36),  # very small images
     _mk("B_32_F5", "general", 128, 64, 32, 32, 128, 5, "u01", "he", 37),
     _mk("B_32_F7", "general", 128, 64, 32, 32, 128, 7, "u01", "he", 38),
+    # the special case on a batch: one-channel images through dconv_general
+    _mk("A_N16_512_F5", "general", 16, 1, 512, 512, 64, 5, "u11", "u11", 39),
+    _mk("A_N256_28_F5", "general", 256, 1, 28, 28, 32, 5, "u11", "u11", 40),   # small images: general kernel
 )}
 
 
