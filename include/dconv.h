@@ -59,9 +59,11 @@ enum {
                                  picks for up to 12 filters (20 from 5x5 on) on
                                  large images                                    */
     DCONV_VARIANT_SPECIAL_CASE = 4,
-                              /* dconv_general with C = 1 only: the tiled kernel
-                                 of the single-channel case with the N images as
-                                 further work items; what AUTO picks for large
+                              /* dconv_general with C = 1 (any filter up to
+                                 11x11) or C <= 4 (filters up to 5x5) only: the
+                                 tiled kernel of the single-channel case, the N
+                                 images as further work items and the channels
+                                 as further taps; what AUTO picks for large
                                  output volumes of wide images with small filters */
     DCONV_VARIANT_TILED_CFG0 = 0x100,
                               /* DCONV_VARIANT_TILED_CFG0 + i: the tiled kernel
@@ -98,7 +100,8 @@ int dconv_single_channel(const float *img, int H, int W,
  * `in`, in `filt` or in one image's output [K][Ho][Wo], -> DCONV_BAD_SHAPE.
  * With C = 1 this is the special case of Sec. 3 applied to N images: the
  * automatic choice runs them on the single-channel kernel (all images in one
- * launch) where that is the faster one, see DCONV_VARIANT_SPECIAL_CASE.
+ * launch) where that is the faster one, and likewise two to four channels
+ * with small filters, see DCONV_VARIANT_SPECIAL_CASE.
  */
 int dconv_general(const float *in, int N, int C, int H, int W,
                   const float *filt, int K, int F,

@@ -80,15 +80,17 @@ int dconv_general_v(const float* in, int N, int C, int H, int W, const float* fi
     if (variant == DCONV_VARIANT_SPECIAL_CASE ||
         (variant >= DCONV_VARIANT_SPECIAL_CASE_CFG0 &&
          variant < DCONV_VARIANT_SPECIAL_CASE_CFG0 + dconv::single_tile_configs())) {
-        if (C != 1) return DCONV_UNSUPPORTED;
+        if (!dconv::single_tiled_supports(s)) return DCONV_UNSUPPORTED;
         return dispatch(true, in, filt, out, s,
                         variant == DCONV_VARIANT_SPECIAL_CASE
                             ? DCONV_VARIANT_TILED
                             : variant - DCONV_VARIANT_SPECIAL_CASE_CFG0 + DCONV_VARIANT_TILED_CFG0,
                         stream);
     }
-    if (C == 1 && variant == DCONV_VARIANT_AUTO &&
-        (N == 1 || dconv::single_batch_preferred(s) ||
+    // (the same kernel takes two to four channels with small filters: such shapes are bound by
+    // the output stream like the one-channel case)
+    if (variant == DCONV_VARIANT_AUTO &&
+        ((N == 1 && C == 1) || dconv::single_batch_preferred(s) ||
          (dconv::single_tiled_supports(s) && !dconv::general_tiled_supports(s))))
         return dispatch(true, in, filt, out, s, variant, stream);
     return dispatch(false, in, filt, out, s, variant, stream);
@@ -180,6 +182,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1008; }
+int dconv_version(void) { return 1009; }
 
 }  // extern "C"

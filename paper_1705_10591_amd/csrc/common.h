@@ -63,7 +63,7 @@ int launch_single_few(const float* img, const float* filt, float* out, const Sha
 bool single_few_supports(const Shape& s);      // the few-filters kernel can run the shape
 bool single_few_preferred(const Shape& s);     // ... and is the better choice for it
 bool single_tiled_supports(const Shape& s);
-bool single_batch_preferred(const Shape& s);   // C = 1, N > 1: the special-case kernel is the better choice
+bool single_batch_preferred(const Shape& s);   // dconv_general with up to four channels: the special-case kernel is the better choice
 bool general_tiled_supports(const Shape& s);
 void release_general_workspaces();
 // Short data types (dtype: DCONV_DTYPE_*, layout: DCONV_LAYOUT_*); variant: AUTO, SIMPLE, TILED

@@ -118,17 +118,45 @@ int shape_for(const Shape& s)
 
 int general_tile_configs() { return kShapes * kSchedules; }
 
-bool general_tiled_supports(const Shape& s)
+namespace {
+
+bool whole_batch_supported(const Shape& s)
 {
     const GenSched sched{0, 0};
     return launch_any(nullptr, nullptr, nullptr, s, nullptr, shape_for(s), sched, true) == DCONV_OK ||
            launch_any(nullptr, nullptr, nullptr, s, nullptr, 0, sched, true) == DCONV_OK;
 }
 
+// A batch whose images are so large that a tile reaching from one image into the next would need
+// more than 32 bits of lane offset runs image by image (each launch is long: nothing is lost).
+bool per_image_supported(const Shape& s, Shape* one)
+{
+    *one = s;
+    one->N = 1;
+    return s.N > 1 && whole_batch_supported(*one);
+}
+
+}  // namespace
+
+bool general_tiled_supports(const Shape& s)
+{
+    Shape one;
+    return whole_batch_supported(s) || per_image_supported(s, &one);
+}
+
 int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
                          hipStream_t st, int cfg)
 {
     if (cfg >= kShapes * kSchedules) return DCONV_UNSUPPORTED;
+    Shape one;
+    if (!whole_batch_supported(s) && per_image_supported(s, &one)) {
+        const int64_t in_image = (int64_t)s.C * s.H * s.W, out_image = (int64_t)s.K * s.Ho * s.Wo;
+        for (int n = 0; n < s.N; ++n) {
+            const int rc = launch_general_tiled(in + n * in_image, filt, out + n * out_image, one, st, cfg);
+            if (rc != DCONV_OK) return rc;
+        }
+        return DCONV_OK;
+    }
     if (cfg < 0) {
         const GenSched sched{0, 0};
         int rc = launch_any(in, filt, out, s, st, shape_for(s), sched, false);

@@ -329,7 +329,10 @@ general_tiled_kernel(GenParams p)
         const int k0 = kb * MT;
         kleft = p.K - k0 - 32 * wm * MW - 4 * h;
         obase_t = p.out + ((int64_t)n_first * p.K + k0) * plane;
-        const int kplane = p.K * (int)plane;                  // one image of the output: fits, checked
+        // one image of the output, in words.  The host checks that everything a lane adds to its
+        // tile's base fits 32 bits; where a tile cannot reach a second image this product may
+        // not fit and is multiplied by zero.
+        const uint32_t kplane = (uint32_t)p.K * (uint32_t)plane;
 #pragma unroll
         for (int nt = 0; nt < NW; ++nt) {
             const int pp = p0 + (wn * NW + nt) * 32 + l32;
@@ -338,8 +341,8 @@ general_tiled_kernel(GenParams p)
             const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
             const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
             base[nt] = IOFF + ((n - n_first) * p.Hc + y - y_first) * LS + xl;
-            oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
-                                  y * p.Wo + x0 + xl) * 4u;
+            oofs[nt] = ((uint32_t)(n - n_first) * kplane +
+                        (uint32_t)((32 * wm * MW + 4 * h) * (int)plane + y * p.Wo + x0 + xl)) * 4u;
         }
     };
     // Offsets of the second tap of a pair relative to the first, by kind of pair.
@@ -641,14 +644,17 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     const int64_t tiles = ((int64_t)(pl.nstrips - 1) * pl.pt_full + pl.pt_last) * KB;
     if (tiles * nch > 2147483647LL || (int64_t)s.N * s.Ho * s.Wo > 2147483647LL)
         return DCONV_UNSUPPORTED;
-    // Lanes address HBM with 32-bit byte offsets from per-tile bases: everything one tile can
-    // reach from its first image must lie within 2 GiB.
+    // Lanes address HBM with 32-bit byte offsets from per-tile bases (the first image of the
+    // tile, the chunk's first channel, the tile's first filter; the filter a store belongs to is
+    // in its uniform base): what a lane adds to them must stay below 2 GiB.  A tile of NT pixels
+    // reaches into at most `span` images.
     {
         const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
-        const int64_t span = NT / ((int64_t)s.Ho * wmin) + 2;        // images a tile can touch
+        const int64_t span = std::min<int64_t>(NT / ((int64_t)s.Ho * wmin) + 2, s.N);
         const int64_t plane = (int64_t)s.Ho * s.Wo;
         const int64_t lim = 1LL << 29;                                // floats: 2 GiB
-        if (span * s.C * s.H * s.W >= lim || span * s.K * plane + (MT + 1) * plane >= lim ||
+        if (((span - 1) * s.C + CSH + 1) * s.H * s.W >= lim ||
+            (span - 1) * s.K * plane + (32 * (WM - 1) * MW + 6) * plane >= lim ||
             (int64_t)MT * s.C * F * F >= lim)
             return DCONV_UNSUPPORTED;
     }

@@ -305,7 +305,9 @@ general_half_kernel(HalfParams p)
     const int kleft = p.K - k0 - 32 * wm * MW - 4 * h;
     float* obase_t = p.out + ((int64_t)n_first * p.K + k0) * plane;
     {
-        const int kplane = p.K * (int)plane;
+        // one image of the output, in words; where a tile cannot reach a second image (the host
+        // checks what lanes add to the tile's base) the product may not fit and meets a zero
+        const uint32_t kplane = (uint32_t)p.K * (uint32_t)plane;
 #pragma unroll
         for (int nt = 0; nt < NW; ++nt) {
             const int pp = p0 + (wn * NW + nt) * 32 + l32;
@@ -314,8 +316,8 @@ general_half_kernel(HalfParams p)
             const int Q = fdiv(pc, d_ws), xl = pc - Q * ws;
             const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
             base[nt] = FB + (h * (p.RS * LS) + ((n - n_first) * p.Hc + y - y_first) * LS + xl) * 4;
-            oofs[nt] = (uint32_t)((n - n_first) * kplane + (32 * wm * MW + 4 * h) * (int)plane +
-                                  y * p.Wo + x0 + xl) * 4u;
+            oofs[nt] = ((uint32_t)(n - n_first) * kplane +
+                        (uint32_t)((32 * wm * MW + 4 * h) * (int)plane + y * p.Wo + x0 + xl)) * 4u;
         }
     }
     int wb[MW];
@@ -508,10 +510,13 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
     // its first image, its first filter and its first output map must lie within 2 GiB
     {
         const int wmin = s.Wo - (pl.nstrips - 1) * pl.bw;
-        const int64_t span = NT / ((int64_t)s.Ho * wmin) + 2;
+        const int64_t span = std::min<int64_t>(NT / ((int64_t)s.Ho * wmin) + 2, s.N);   // images a tile reaches
         const int64_t plane = (int64_t)s.Ho * s.Wo;
         const int64_t lim = 1LL << 31;
-        if (span * s.H * s.W * s.C * EB >= lim || (span * s.K * plane + (MT + 1) * plane) * 4 >= lim ||
+        // (the filter a store belongs to is in its uniform base; a lane adds the image, its wave's
+        // first filter, four filters for the upper half-wave, and the pixel)
+        if (span * s.H * s.W * s.C * EB >= lim ||
+            ((span - 1) * s.K * plane + (32 * (TL::WM - 1) * TL::MW + 6) * plane) * 4 >= lim ||
             (int64_t)(MT + 1) * F * F * s.C * EB >= lim)
             return DCONV_UNSUPPORTED;
     }

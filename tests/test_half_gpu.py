@@ -293,3 +293,23 @@ def test_blocked_layout_needs_whole_channel_blocks():
     rc = lib.dconv_general_lowp(x.data_ptr(), 1, 24, 8, 8, f.data_ptr(), 2, 3, out.data_ptr(),
                                 dconv.DTYPE_F16, dconv.LAYOUT_CHANNEL_BLOCKED, 0, None)
     assert rc == dconv.STATUS_BAD_SHAPE
+
+
+def test_half_large_image_sampled():
+    """2.7 GB of output from one image: output planes more than 2 GiB apart."""
+    N, C, H, W, K, F = 1, 16, 2048, 2100, 160, 3
+    x, f = wl.random_case(995, N, C, H, W, K, F)
+    xr, xb = wl.to_16bit(x, "bf16")
+    fr, fb = wl.to_16bit(f, "bf16")
+    for variant in (TILED, TILE_SMALL, TILE_LARGE_DIRECT):
+        print(f"half bf16 large image variant {variant}", flush=True)
+        out = dconv.dconv_general_half(dev16(xb, "bf16"), dev16(fb, "bf16"), variant=variant)
+        torch.cuda.synchronize()
+        total = out.numel()
+        idx = np.unique(np.concatenate([wl.sample_indices(996, total, 20000), np.arange(0, 2048),
+                                        np.arange(total - 2048, total),
+                                        np.arange((1 << 29) - 1024, (1 << 29) + 1024)]))
+        got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+        acc, mag = oracle.general_at(xr, fr, idx)
+        assert_within_bound(got, acc, mag, f"half bf16 large image variant {variant}")
+        del out

@@ -570,8 +570,8 @@ def test_one_channel_batch_guard_bands_and_refusals():
     torch.cuda.synchronize()
     assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + total:]).all()
     assert_within_bound(out.cpu().numpy(), acc, mag, "batch with guard bands")
-    # more than one channel: not the special case
-    x2, f2 = wl.random_case(971, 2, 2, 12, 12, 3, 3)
+    # more channels than the special-case kernel is compiled for
+    x2, f2 = wl.random_case(971, 2, 6, 12, 12, 3, 3)
     with pytest.raises(dconv.DconvError) as e:
         run_general(x2, f2, dconv.VARIANT_SPECIAL_CASE)
     assert e.value.status == dconv.STATUS_UNSUPPORTED
@@ -594,3 +594,85 @@ def test_one_channel_batch_automatic_choice_large_volume_sampled():
     accl, magl, _ = oracle.general(x[N - 1:], f)
     assert_within_bound(out[N - 1:].cpu().numpy(), accl, magl, "last image, special-case kernel")
     assert_within_bound(last.cpu().numpy(), accl, magl, "last image, general kernel")
+
+
+# ---- images so large that output planes lie more than 2 GiB apart ----------------------------------
+
+@pytest.mark.parametrize("shape", [(1, 3, 4096, 4096, 64, 3),      # 4.3 GB of output from one image
+                                   (2, 3, 2048, 2100, 160, 5)],    # 2.7 GB per image: runs image by image
+                         ids=lambda s: "x".join(map(str, s)))
+def test_general_large_images_sampled(shape):
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(990 + K, N, C, H, W, K, F)
+    xd, fd = dev(x), dev(f)
+    print(f"general {shape} automatic choice and tiled kernel", flush=True)
+    out = dconv.dconv_general(xd, fd, variant=TILED)
+    torch.cuda.synchronize()
+    total = out.numel()
+    idx = np.unique(np.concatenate([wl.sample_indices(991, total, 30000),
+                                    np.arange(0, 4096), np.arange(total - 4096, total),
+                                    # around the places where byte offsets cross 2 GiB and 4 GiB
+                                    np.arange((1 << 29) - 2048, (1 << 29) + 2048),
+                                    np.arange(min((1 << 30) - 2048, total - 4096), min((1 << 30) + 2048, total))]))
+    got = out.view(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    acc, mag = oracle.general_at(x, f, idx)
+    assert_within_bound(got, acc, mag, f"general {shape}")
+    auto = dconv.dconv_general(xd, fd)
+    torch.cuda.synchronize()
+    assert torch.equal(auto.view(-1)[torch.from_numpy(idx).to("cuda")], out.view(-1)[torch.from_numpy(idx).to("cuda")])
+
+
+# ---- a few channels on the special-case kernel ---------------------------------------------------------
+
+# (N, C, H, W, K, F)
+FEW_CHANNEL_SHAPES = [(2, 3, 20, 23, 5, 3), (1, 3, 30, 700, 40, 3), (2, 2, 37, 41, 130, 5), (3, 4, 12, 330, 33, 5),
+                      (4, 3, 8, 8, 4, 3), (1, 4, 9, 1500, 70, 1), (2, 3, 40, 300, 64, 5), (1, 2, 17, 290, 9, 4),
+                      (2, 4, 11, 140, 20, 2)]
+
+
+@pytest.mark.parametrize("shape", FEW_CHANNEL_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_few_channels_on_the_special_case_kernel(shape):
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(1000 + C + K, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    xi, fi = wl.integer_case(1050 + C + K, N, C, H, W, K, F)
+    acci, _, _ = oracle.general(xi, fi)
+    ran = 0
+    for v in [dconv.VARIANT_SPECIAL_CASE] + [dconv.VARIANT_SPECIAL_CASE_CFG0 + i for i in range(5)]:
+        try:
+            got = run_general(x, f, v)
+        except dconv.DconvError as e:             # tile configurations 1 and 2 exist for one channel only
+            assert e.status == dconv.STATUS_UNSUPPORTED and v in (dconv.VARIANT_SPECIAL_CASE_CFG0 + 1,
+                                                                  dconv.VARIANT_SPECIAL_CASE_CFG0 + 2)
+            continue
+        ran += 1
+        assert_within_bound(got, acc, mag, f"few channels {shape} variant {v:#x}")
+        np.testing.assert_array_equal(run_general(xi, fi, v), acci.astype(np.float32))
+    assert ran == 4
+
+
+def test_few_channels_refusals():
+    for shape in [(1, 5, 12, 12, 3, 3), (1, 3, 20, 20, 3, 7)]:       # too many channels, filter too large
+        x, f = wl.random_case(1090, *shape)
+        with pytest.raises(dconv.DconvError) as e:
+            run_general(x, f, dconv.VARIANT_SPECIAL_CASE)
+        assert e.value.status == dconv.STATUS_UNSUPPORTED
+
+
+def test_few_channels_automatic_choice_large_volume_sampled():
+    """266 M outputs from RGB images with 3x3 filters: the automatic choice is the special-case
+    kernel; sampled outputs against the oracle, and the general kernel on the same samples."""
+    N, C, H, W, K, F = 16, 3, 512, 512, 64, 3
+    x, f = wl.random_case(1100, N, C, H, W, K, F)
+    xd, fd = dev(x), dev(f)
+    out = dconv.dconv_general(xd, fd)
+    forced = dconv.dconv_general(xd, fd, variant=dconv.VARIANT_SPECIAL_CASE)
+    torch.cuda.synchronize()
+    assert torch.equal(out, forced)                 # the automatic choice is that kernel
+    idx = wl.sample_indices(1101, out.numel(), 20000)
+    sel = torch.from_numpy(idx).to("cuda")
+    acc, mag = oracle.general_at(x, f, idx)
+    assert_within_bound(out.view(-1)[sel].cpu().numpy(), acc, mag, "few channels, automatic choice")
+    gen = dconv.dconv_general(xd, fd, variant=TILED)
+    torch.cuda.synchronize()
+    assert_within_bound(gen.view(-1)[sel].cpu().numpy(), acc, mag, "few channels, general kernel")

@@ -99,6 +99,9 @@ PAPER_SWEEP = {w.name: w for w in (
     # the special case on a batch: one-channel images through dconv_general
     _mk("A_N16_512_F5", "general", 16, 1, 512, 512, 64, 5, "u11", "u11", 39),
     _mk("A_N256_28_F5", "general", 256, 1, 28, 28, 32, 5, "u11", "u11", 40),   # small images: general kernel
+    # three channels, small filters: still bound by the output stream (a first layer on RGB images)
+    _mk("A_C3_N16_512_F3", "general", 16, 3, 512, 512, 64, 3, "u01", "he", 41),
+    _mk("A_C3_N64_224_F3", "general", 64, 3, 224, 224, 64, 3, "u01", "he", 42),
 )}
 
 
