@@ -348,7 +348,9 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     p.fgroups = (fblocks + p.fbw - 1) / p.fbw;
     // Completing row ends with the next row's head needs a pass to span at most one row end,
     // and every pass that reaches the row end to lie in the last tile column.
-    p.wrap = (s.Wo >= 2 * (32 * NBW + 32) && (p.tiles_x - 1) * TW + 32 <= s.Wo) ? 1 : 0;
+    // (a pass computes 32 * NBW + 32 pixels from a multiple of 32 * NBW on: it crosses one row
+    // end at most as soon as a row is that long)
+    p.wrap = (s.Wo >= 32 * NBW + 64 && (p.tiles_x - 1) * TW + 32 <= s.Wo) ? 1 : 0;
     const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups * s.N;
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
