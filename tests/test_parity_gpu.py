@@ -676,3 +676,21 @@ def test_few_channels_automatic_choice_large_volume_sampled():
     gen = dconv.dconv_general(xd, fd, variant=TILED)
     torch.cuda.synchronize()
     assert_within_bound(gen.view(-1)[sel].cpu().numpy(), acc, mag, "few channels, general kernel")
+
+
+@pytest.mark.parametrize("W", [162, 191, 192, 193, 222, 256, 258, 287, 289, 319, 321])
+def test_special_case_kernel_widths_around_the_row_end_rule(W):
+    """From 192 output pixels of width on, the last pass of a row also writes the head of the next
+    row: exact results and untouched guard bands on both sides of that limit, every tile size."""
+    for (N, C, K, F, H) in ((2, 1, 40, 3, 9), (1, 3, 33, 3, 7), (1, 2, 64, 5, 9)):
+        x, f = wl.integer_case(W + K, N, C, H, W, K, F)
+        acc, _, _ = oracle.general(x, f)
+        total = acc.size
+        for i in (0, 3, 4):
+            print(f"special-case kernel W={W} N,C,K,F,H={(N, C, K, F, H)} configuration {i}", flush=True)
+            buf = torch.full((total + 2048,), float("nan"), device="cuda")
+            out = buf[1001:1001 + total].view(acc.shape)          # starts mid-line
+            dconv.dconv_general(dev(x), dev(f), out=out, variant=dconv.VARIANT_SPECIAL_CASE_CFG0 + i)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out.cpu().numpy(), acc.astype(np.float32))
+            assert torch.isnan(buf[:1001]).all() and torch.isnan(buf[1001 + total:]).all()
