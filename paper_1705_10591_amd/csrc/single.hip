@@ -84,9 +84,9 @@ bool single_batch_preferred(const Shape& s)
 {
     if (!single_tiled_supports(s)) return false;
     const int64_t outputs = (int64_t)s.N * s.K * s.Ho * s.Wo;
-    if (outputs < 120000000LL) return false;
+    if (outputs < 100000000LL) return false;
     if (s.C == 1) return (s.F <= 5 && s.Wo >= 160) || (s.F <= 8 && s.Wo >= 256);
-    return s.Wo >= 200 && (s.F <= 3 || (s.C == 2 && s.Wo >= 400));
+    return s.Wo >= 192 && (s.F <= 3 || (s.C == 2 && s.Wo >= 400));
 }
 
 int single_tile_configs() { return kSingleConfigs; }
