@@ -279,7 +279,12 @@ def main():
     entry = config_entry(head, ms)
 
     single = head.kind == "single"
-    hbm_bound = single and head.F <= 5
+    # which roof bounds the workload: the one its time under that roof alone is longer for
+    # (algorithmic bytes at the HBM peak against flops at the fp32 matrix-core peak); for the
+    # single-channel configurations that is HBM up to 5x5 filters
+    t_hbm = entry["algorithmic_gbs"] * ms / HBM_PEAK_GBS
+    t_mfma = entry["gflops"] * ms / (FP32_PEAK_TFLOPS * 1e3)
+    hbm_bound = t_hbm > t_mfma
     if hbm_bound:
         roof = {"bound": "hbm", "achieved": entry["algorithmic_gbs"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(entry["algorithmic_gbs"] / HBM_PEAK_GBS, 4)}
