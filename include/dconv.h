@@ -72,7 +72,9 @@ enum {
     DCONV_VARIANT_SPECIAL_CASE_CFG0 = 0x200
                               /* + i: DCONV_VARIANT_SPECIAL_CASE with tile
                                  configuration i of the single-channel case,
-                                 0 <= i < dconv_tile_config_count(1)             */
+                                 0 <= i < dconv_tile_config_count(1) (with more
+                                 than one channel only 0, 3 and 4 exist; the
+                                 others return DCONV_UNSUPPORTED)                */
 };
 
 /*
