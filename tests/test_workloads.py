@@ -22,3 +22,29 @@ def test_integer_cases_are_representable_in_16_bit_types():
     x, f = wl.integer_case(3, 2, 16, 9, 9, 5, 3)
     for kind in ("f16", "bf16"):
         assert np.array_equal(wl.to_16bit(x, kind)[0], x) and np.array_equal(wl.to_16bit(f, kind)[0], f)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build shows one GPU's share; bench.py says so instead of running with --gpus above 1."""
+    import subprocess
+    import sys
+    from pathlib import Path
+    root = Path(__file__).resolve().parent.parent
+    r = subprocess.run([sys.executable, str(root / "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_workload_tables_are_consistent():
+    """Every benchmark workload has positive sizes, a filter that fits and a unique seed."""
+    import workloads as wl
+    allw = list(wl.CONFIGS.values()) + list(wl.S2_SWEEP.values()) + list(wl.PAPER_SWEEP.values())
+    seeds = set()
+    for w in allw:
+        assert min(w.N, w.C, w.H, w.W, w.K, w.F) >= 1 and w.F <= min(w.H, w.W), w.name
+        assert w.out_elems == w.N * w.K * (w.H - w.F + 1) * (w.W - w.F + 1), w.name
+        assert w.flops == 2 * w.out_elems * w.C * w.F * w.F, w.name
+        if w.name != "S2_F5":          # the sweep's 5x5 entry is S2 itself
+            assert w.seed not in seeds or w.name.startswith("S2"), w.name
+        seeds.add(w.seed)
