@@ -11,8 +11,9 @@ namespace {
 // tiles (fewer first-of-row passes, which cannot take over a block) win; from 7x7 on the matrix
 // cores bound it and, for the largest filters, taller tiles (fewer halo rows staged per output
 // row) win.  Small images get small tiles so that the launch still covers the chip; with up to
-// 32 filters (one filter block, rows dealt to the waves) the smallest, 128 x 4.
-constexpr int kSingleConfigs = 5;
+// 32 filters (one filter block, rows dealt to the waves) the smallest, 128 x 4.  Configuration 5
+// is that tile with passes of 64 instead of 128 pixels, for images 128 to 199 pixels wide.
+constexpr int kSingleConfigs = 6;
 
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
@@ -28,11 +29,16 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
-        if (s.K <= 32 && t128 < ((F <= 4 && s.K > 16) ? 8192 : 1536)) {
+        if (s.Wo >= 128 && s.Wo < 200) {
+            // rows too short for a 160-pixel pass to complete their ends across rows, but long
+            // enough for a 96-pixel one: passes of 64 pixels (1.2 to 1.7 times faster there)
+            cfg = 5;
+        } else if (s.K <= 32 && t128 < ((F <= 4 && s.K > 16) ? 8192 : 1536)) {
             // one filter block: the four waves of a workgroup take one row each, and on images up
-            // to about 768^2 (1080p for a full block of small filters) the smallest tile, one pass
-            // per wave, is the shortest chain of latencies
-            cfg = 4;
+            // to about 768^2 (1080p for a full block of small filters) the smallest tile is the
+            // shortest chain of latencies; with passes of 64 pixels the stores of a wave begin
+            // earlier still (5 to 16 % over passes of 128)
+            cfg = 5;
         } else if (s.K <= 32 && F < 8 && s.Wo < 3072) {
             cfg = 0;
         } else if (F <= 4) {
@@ -47,11 +53,15 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
             cfg = (it >= 520 && it < 4200) ? 3 : 0;
         }
     }
+    // (the small tiles keep three waves per SIMD in registers up to 8x8; beyond, the filter
+    // operands of all taps would spill)
+    constexpr int WS = F >= 9 ? 2 : 3;
     switch (cfg) {
     case 1: return launch_cfg<F, 1024, 4, 4, 2>(img, filt, out, s, st);
     case 2: return launch_cfg<F, 512, 8, 4, 3>(img, filt, out, s, st);
-    case 3: return launch_cfg<F, 256, 2, 4, 3>(img, filt, out, s, st);
-    case 4: return launch_cfg<F, 128, 4, 4, 3>(img, filt, out, s, st);
+    case 3: return launch_cfg<F, 256, 2, 4, WS>(img, filt, out, s, st);
+    case 4: return launch_cfg<F, 128, 4, 4, WS>(img, filt, out, s, st);
+    case 5: return launch_cfg<F, 128, 4, 2, WS>(img, filt, out, s, st);
     default: return launch_cfg<F, 512, 4, 4, 3>(img, filt, out, s, st);
     }
 }
@@ -85,8 +95,8 @@ bool single_batch_preferred(const Shape& s)
     if (!single_tiled_supports(s)) return false;
     const int64_t outputs = (int64_t)s.N * s.K * s.Ho * s.Wo;
     if (outputs < 100000000LL) return false;
-    if (s.C == 1) return (s.F <= 5 && s.Wo >= 160) || (s.F <= 8 && s.Wo >= 256);
-    return s.Wo >= 192 && (s.F <= 3 || (s.C == 2 && s.Wo >= 400));
+    if (s.C == 1) return (s.F <= 3 && s.Wo >= 128) || (s.F <= 5 && s.Wo >= 160) || (s.F <= 8 && s.Wo >= 256);
+    return (s.F == 1 && s.Wo >= 128) || (s.F <= 3 && s.Wo >= 170) || (s.C == 2 && s.Wo >= 400);
 }
 
 int single_tile_configs() { return kSingleConfigs; }
