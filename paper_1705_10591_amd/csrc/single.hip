@@ -42,7 +42,8 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         } else if (s.K <= 32 && F < 8 && s.Wo < 3072) {
             cfg = 0;
         } else if (F <= 4) {
-            cfg = items(512, 4) < 1280 ? 3 : 0;
+            // (mid-sized problems: 256 x 2, or with up to 64 filters 128 x 4 with short passes)
+            cfg = items(512, 4) < 1280 ? (s.K <= 64 ? 5 : 3) : 0;
         } else if (items(512, 4) < 384) {
             cfg = 3;
         } else if (F >= 8) {
