@@ -73,7 +73,7 @@ enum {
                               /* + i: DCONV_VARIANT_SPECIAL_CASE with tile
                                  configuration i of the single-channel case,
                                  0 <= i < dconv_tile_config_count(1) (with more
-                                 than one channel only 0, 3, 4 and 5 exist; the
+                                 than one channel only 0 and 3 to 6 exist; the
                                  others return DCONV_UNSUPPORTED)                */
 };
 

@@ -12,8 +12,9 @@ namespace {
 // cores bound it and, for the largest filters, taller tiles (fewer halo rows staged per output
 // row) win.  Small images get small tiles so that the launch still covers the chip; with up to
 // 32 filters (one filter block, rows dealt to the waves) the smallest, 128 x 4.  Configuration 5
-// is that tile with passes of 64 instead of 128 pixels, for images 128 to 199 pixels wide.
-constexpr int kSingleConfigs = 6;
+// is that tile with passes of 64 instead of 128 pixels, for images 128 to 199 pixels wide, and
+// configuration 6 with passes of 32 pixels, for images 96 to 127 wide.
+constexpr int kSingleConfigs = 7;
 
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
@@ -29,7 +30,9 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
-        if (s.Wo >= 128 && s.Wo < 200) {
+        if (s.Wo >= 96 && s.Wo < 128) {
+            cfg = 6;          // ... and passes of 32 pixels for rows shorter still
+        } else if (s.Wo >= 128 && s.Wo < 200) {
             // rows too short for a 160-pixel pass to complete their ends across rows, but long
             // enough for a 96-pixel one: passes of 64 pixels (1.2 to 1.7 times faster there)
             cfg = 5;
@@ -63,6 +66,7 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
     case 3: return launch_cfg<F, 256, 2, 4, WS>(img, filt, out, s, st);
     case 4: return launch_cfg<F, 128, 4, 4, WS>(img, filt, out, s, st);
     case 5: return launch_cfg<F, 128, 4, 2, WS>(img, filt, out, s, st);
+    case 6: return launch_cfg<F, 128, 4, 1, WS>(img, filt, out, s, st);
     default: return launch_cfg<F, 512, 4, 4, 3>(img, filt, out, s, st);
     }
 }
@@ -96,7 +100,7 @@ bool single_batch_preferred(const Shape& s)
     if (!single_tiled_supports(s)) return false;
     const int64_t outputs = (int64_t)s.N * s.K * s.Ho * s.Wo;
     if (outputs < 100000000LL) return false;
-    if (s.C == 1) return (s.F <= 3 && s.Wo >= 128) || (s.F <= 5 && s.Wo >= 160) || (s.F <= 8 && s.Wo >= 256);
+    if (s.C == 1) return (s.F <= 5 && s.Wo >= 96) || (s.F <= 8 && s.Wo >= 256);
     return (s.F == 1 && s.Wo >= 128) || (s.F <= 3 && s.Wo >= 170) || (s.C == 2 && s.Wo >= 400);
 }
 

@@ -91,7 +91,7 @@ single_tiled_kernel(SingleParams p)
     constexpr int ITS = 8 / RPI;                // store instructions per group of 8 filters
     constexpr int TOTAL = (C * ROWS + 1) * LS;
     constexpr int IMG_WORDS = (TOTAL + 3) & ~3;
-    static_assert(TW % PASS == 0 && (NBW == 2 || NBW == 4 || NBW == 8), "tile shape");
+    static_assert(TW % PASS == 0 && (NBW == 1 || NBW == 2 || NBW == 4 || NBW == 8), "tile shape");
     static_assert((IMG_WORDS + 4 * 8 * SW) * 4 <= 160 * 1024, "tile and strips must fit the LDS of a CU");
 
     __shared__ __attribute__((aligned(16))) float sh[IMG_WORDS + 4 * 8 * SW];

@@ -23,8 +23,8 @@ constexpr bool fits()
 }
 
 // Tile configurations, numbered as in the one-channel case: 0: 512 x 4, or 256 x 4 where that
-// does not fit with all the channels; 3: 256 x 2; 4: 128 x 4; 5: 128 x 4 with passes of 64
-// pixels; cfg < 0 picks one by shape.
+// does not fit with all the channels; 3: 256 x 2; 4: 128 x 4; 5 and 6: 128 x 4 with passes of 64
+// and of 32 pixels; cfg < 0 picks one by shape.
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st, int cfg)
 {
@@ -34,7 +34,7 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
     if (cfg < 0) {
         const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4 * s.N;
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * fgroups;
-        cfg = (s.Wo >= 128 && s.Wo < 192) ? 5 : t128 < 1536 ? 4 : 0;
+        cfg = (s.Wo >= 96 && s.Wo < 128) ? 6 : (s.Wo >= 128 && s.Wo < 192) ? 5 : t128 < 1536 ? 4 : 0;
     }
     if (cfg == 0) {
         if constexpr (fits<F, 512, 4>()) return launch_cfg<F, 512, 4, 4, WPE, C>(img, filt, out, s, st);
@@ -51,6 +51,10 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
     }
     if (cfg == 5) {           // the same tile with passes of 64 pixels (images 128 to 191 wide)
         if constexpr (fits<F, 128, 4>()) return launch_cfg<F, 128, 4, 2, WPE, C>(img, filt, out, s, st);
+        return DCONV_UNSUPPORTED;
+    }
+    if (cfg == 6) {           // ... and of 32 pixels (images 96 to 127 wide)
+        if constexpr (fits<F, 128, 4>()) return launch_cfg<F, 128, 4, 1, WPE, C>(img, filt, out, s, st);
         return DCONV_UNSUPPORTED;
     }
     return DCONV_UNSUPPORTED;

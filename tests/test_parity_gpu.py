@@ -638,7 +638,7 @@ def test_few_channels_on_the_special_case_kernel(shape):
     xi, fi = wl.integer_case(1050 + C + K, N, C, H, W, K, F)
     acci, _, _ = oracle.general(xi, fi)
     ran = 0
-    for v in [dconv.VARIANT_SPECIAL_CASE] + [dconv.VARIANT_SPECIAL_CASE_CFG0 + i for i in range(6)]:
+    for v in [dconv.VARIANT_SPECIAL_CASE] + [dconv.VARIANT_SPECIAL_CASE_CFG0 + i for i in range(7)]:
         try:
             got = run_general(x, f, v)
         except dconv.DconvError as e:             # tile configurations 1 and 2 exist for one channel only
@@ -648,7 +648,7 @@ def test_few_channels_on_the_special_case_kernel(shape):
         ran += 1
         assert_within_bound(got, acc, mag, f"few channels {shape} variant {v:#x}")
         np.testing.assert_array_equal(run_general(xi, fi, v), acci.astype(np.float32))
-    assert ran == 5
+    assert ran == 6
 
 
 def test_few_channels_refusals():
@@ -678,16 +678,16 @@ def test_few_channels_automatic_choice_large_volume_sampled():
     assert_within_bound(gen.view(-1)[sel].cpu().numpy(), acc, mag, "few channels, general kernel")
 
 
-@pytest.mark.parametrize("W", [127, 129, 130, 131, 159, 162, 191, 192, 193, 222, 256, 258, 287, 289, 319, 321])
+@pytest.mark.parametrize("W", [80, 95, 96, 97, 98, 99, 110, 127, 129, 130, 131, 159, 162, 191, 192, 193, 222, 256, 258, 287, 289, 319, 321])
 def test_special_case_kernel_widths_around_the_row_end_rule(W):
-    """From 192 output pixels of width on (128 with passes of 64 pixels), the last pass of a row also
+    """From 192 output pixels of width on (128 with passes of 64 pixels, 96 with 32), the last pass of a row also
     writes the head of the next row: exact results and untouched guard bands on both sides of
     those limits, every tile size."""
     for (N, C, K, F, H) in ((2, 1, 40, 3, 9), (1, 3, 33, 3, 7), (1, 2, 64, 5, 9)):
         x, f = wl.integer_case(W + K, N, C, H, W, K, F)
         acc, _, _ = oracle.general(x, f)
         total = acc.size
-        for i in (0, 3, 4, 5):
+        for i in (0, 3, 4, 5, 6):
             print(f"special-case kernel W={W} N,C,K,F,H={(N, C, K, F, H)} configuration {i}", flush=True)
             buf = torch.full((total + 2048,), float("nan"), device="cuda")
             out = buf[1001:1001 + total].view(acc.shape)          # starts mid-line
