@@ -30,12 +30,11 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
-        if (s.Wo >= 96 && s.Wo < 128) {
-            cfg = 6;          // ... and passes of 32 pixels for rows shorter still
-        } else if (s.Wo >= 128 && s.Wo < 200) {
-            // rows too short for a 160-pixel pass to complete their ends across rows, but long
-            // enough for a 96-pixel one: passes of 64 pixels (1.2 to 1.7 times faster there)
-            cfg = 5;
+        if (s.Wo >= 96 && s.Wo < 200) {
+            // rows too short for a 160-pixel pass to complete their ends across rows: passes of
+            // 64 pixels (from 128 pixels of width on) or of 32, whichever computes fewer blocks
+            // per row (1.2 to 1.7 times faster than the wider passes there)
+            cfg = short_pass_config(s.Wo);
         } else if (s.K <= 32 && t128 < ((F <= 4 && s.K > 16) ? 8192 : 1536)) {
             // one filter block: the four waves of a workgroup take one row each, and on images up
             // to about 768^2 (1080p for a full block of small filters) the smallest tile is the
@@ -101,7 +100,7 @@ bool single_batch_preferred(const Shape& s)
     const int64_t outputs = (int64_t)s.N * s.K * s.Ho * s.Wo;
     if (outputs < 100000000LL) return false;
     if (s.C == 1) return (s.F <= 5 && s.Wo >= 96) || (s.F <= 8 && s.Wo >= 256);
-    return (s.F == 1 && s.Wo >= 128) || (s.F <= 3 && s.Wo >= 170) || (s.C == 2 && s.Wo >= 400);
+    return (s.F == 1 && s.Wo >= 96) || (s.F <= 3 && s.Wo >= 104) || (s.C == 2 && s.Wo >= 400);
 }
 
 int single_tile_configs() { return kSingleConfigs; }

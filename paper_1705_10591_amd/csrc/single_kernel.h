@@ -359,6 +359,16 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
 }
 
+// Images 96 to 199 pixels wide: configuration 5 (128 x 4 tile, passes of 64 pixels) or 6 (passes
+// of 32).  A row of Wo pixels takes ceil(Wo / 64) passes of two new blocks or ceil(Wo / 32) of
+// one (plus the block every pass takes over from the one before); the fewer blocks win, ties go
+// to the wider pass.
+inline int short_pass_config(int Wo)
+{
+    if (Wo < 128) return 6;
+    return 2 * ((Wo + 63) / 64) <= (Wo + 31) / 32 ? 5 : 6;
+}
+
 // The same kernel for a few input channels, implemented once per channel count, each in its own
 // translation unit (single_multi_inst.hip).
 constexpr int kSingleMultiMaxC = 4, kSingleMultiMaxF = 5;

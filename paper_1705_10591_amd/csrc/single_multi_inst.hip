@@ -34,7 +34,7 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
     if (cfg < 0) {
         const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4 * s.N;
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * fgroups;
-        cfg = (s.Wo >= 96 && s.Wo < 128) ? 6 : (s.Wo >= 128 && s.Wo < 192) ? 5 : t128 < 1536 ? 4 : 0;
+        cfg = (s.Wo >= 96 && s.Wo < 192) ? short_pass_config(s.Wo) : t128 < 1536 ? 4 : 0;
     }
     if (cfg == 0) {
         if constexpr (fits<F, 512, 4>()) return launch_cfg<F, 512, 4, 4, WPE, C>(img, filt, out, s, st);
