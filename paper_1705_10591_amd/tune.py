@@ -11,6 +11,9 @@ that the rules can be checked or re-derived on another chip.
     python -m paper_1705_10591_amd.tune general N C H W K F
     python -m paper_1705_10591_amd.tune bf16 N C H W K F          (general case, bf16 inputs)
     python -m paper_1705_10591_amd.tune bf16-blocked N C H W K F  (the same, channel-blocked layout)
+    python -m paper_1705_10591_amd.tune special N C H W K F       (general case with C <= 4: the tile
+                                                                   configurations of the special-case
+                                                                   kernel next to the general kernel)
     python -m paper_1705_10591_amd.tune table single|general|bf16|bf16-blocked
                                                                   (the shapes the rules were set on)
 """
@@ -45,7 +48,7 @@ def _time(fn, warm_ms: float = 40.0, steps: int = 20) -> float:
 def _config_count(kind: str) -> int:
     # the short-data-type kernel: 64 filters x 256 pixels and 128 x 512 staged through registers,
     # the same two staged directly into LDS
-    return 4 if kind.startswith("bf16") else dconv.tile_config_count(kind == "single")
+    return 4 if kind.startswith("bf16") else dconv.tile_config_count(kind in ("single", "special"))
 
 
 def tune(kind: str, dims, steps: int = 20):
@@ -71,9 +74,15 @@ def tune(kind: str, dims, steps: int = 20):
         f = (torch.rand(K, C, F, F, device="cuda", generator=gen) - 0.5) * 0.1
         out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda")
         call = lambda v: dconv.dconv_general(x, f, out=out, variant=v)
-    rows = [("library choice", _time(lambda: call(dconv.VARIANT_AUTO), steps=steps))]
+    if kind == "special":
+        rows = [("library choice", _time(lambda: call(dconv.VARIANT_AUTO), steps=steps)),
+                ("general kernel", _time(lambda: call(dconv.VARIANT_TILED), steps=steps))]
+        first = dconv.VARIANT_SPECIAL_CASE_CFG0
+    else:
+        rows = [("library choice", _time(lambda: call(dconv.VARIANT_AUTO), steps=steps))]
+        first = dconv.VARIANT_TILED_CFG0
     for i in range(_config_count(kind)):
-        v = dconv.VARIANT_TILED_CFG0 + i
+        v = first + i
         try:
             call(v)
         except dconv.DconvError as e:
@@ -109,7 +118,8 @@ TABLE_BF16 = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (32, 128, 56, 
               (16, 512, 14, 14, 512, 3), (64, 128, 28, 28, 128, 3), (8, 128, 112, 112, 128, 3)]
 
 
-KINDS = ("single", "general", "bf16", "bf16-blocked")
+KINDS = ("single", "general", "bf16", "bf16-blocked")     # with a table of shapes
+
 
 
 def table(kind: str) -> None:
@@ -135,7 +145,7 @@ def main(argv):
             return 2
         table(argv[1])
         return 0
-    if len(argv) < 2 or argv[0] not in KINDS or \
+    if len(argv) < 2 or argv[0] not in KINDS + ("special",) or \
             len(argv) - 1 != (4 if argv[0] == "single" else 6):
         print(__doc__)
         return 2
@@ -143,7 +153,7 @@ def main(argv):
         print("tune needs a GPU", file=sys.stderr)
         return 2
     rows = tune(argv[0], [int(a) for a in argv[1:]])
-    best = min((ms for _, ms in rows[1:] if ms is not None), default=None)
+    best = min((ms for label, ms in rows if ms is not None and label != "library choice"), default=None)
     for label, ms in rows:
         mark = " <- fastest" if ms is not None and ms == best and label != "library choice" else ""
         print(f"{label:18s} {'not applicable' if ms is None else f'{ms:9.4f} ms'}{mark}")
