@@ -28,7 +28,10 @@
  *     the buffers must live on that device.
  *   - The return value is a dconv_status; nothing is launched unless
  *     validation passed.  The library never aborts or throws across the ABI.
- *   - Calls are thread-safe.
+ *   - Calls are thread-safe: any number of host threads may call any entry
+ *     point at once, on the same or on different streams (the only shared
+ *     host state, the workspace table of dconv_general, is guarded, and a
+ *     workspace block never moves once a call has been given it).
  */
 #ifndef DCONV_H
 #define DCONV_H
@@ -84,8 +87,8 @@ enum {
  *   filt [K][F][F]         device, read
  *   out  [K][H-F+1][W-F+1] device, written
  * Errors: NULL img/filt/out -> DCONV_NULL_POINTER; H, W, K, F <= 0, F > H or
- * F > W, or more than 2^31-1 elements in img or in one output plane ->
- * DCONV_BAD_SHAPE.
+ * F > W, or more than 2^31-1 elements in img or in the whole output
+ * [K][Ho][Wo] -> DCONV_BAD_SHAPE.
  */
 int dconv_single_channel(const float *img, int H, int W,
                          const float *filt, int K, int F,
@@ -209,13 +212,20 @@ int dconv_tile_config_count(int single_channel);
  * dconv_general keeps one device workspace per (device, stream) it has been
  * called on: when the tiles of a shape do not spread evenly over the chip, a
  * tile is summed over channels by several workgroups and their partial sums
- * meet there (at most 2 * tile * workgroups floats, 64 MiB for the largest
- * tile on a 256-CU chip, plus one int per workgroup).  It is allocated with
- * hipMalloc on the first call that needs it and grown when a later call needs
- * more; no other entry point allocates.  Calls on one stream share it safely
- * (they run in order); calls on different streams use different workspaces.
- * This function frees all of them; the caller must make sure that no
- * dconv_general launch is still running.  Always returns DCONV_OK.
+ * meet there.  The first call that needs it on a stream allocates, with
+ * hipMalloc, what the largest launch on that device can need (256 KiB of
+ * partial sums and four counters per compute unit: 64 MiB + 4 KiB on a 256-CU
+ * chip) and clears the counters on that stream; no other entry point
+ * allocates, and no call synchronises.  The block keeps its address from then
+ * on: later calls on the stream, whatever their shape, use the same block (they
+ * run in order, so they share it safely; calls on different streams use
+ * different blocks), and a graph captured on the stream stays valid while
+ * other calls are made on it.
+ * dconv_release_workspace frees all blocks.  The caller must make sure that no
+ * dconv_general launch is still running and that every graph that holds
+ * captured dconv_general calls has been destroyed (or is never launched
+ * again): a replay after the release would write to freed memory.  Always
+ * returns DCONV_OK.
  */
 int dconv_release_workspace(void);
 

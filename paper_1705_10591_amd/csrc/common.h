@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <atomic>
+#include "../../include/dconv.h"
 
 namespace dconv {
 
@@ -26,9 +27,11 @@ __device__ __forceinline__ constexpr int mfma_row(int r, int h) {
     return 8 * (r / 4) + 4 * h + (r % 4);
 }
 
-struct LaunchResult {
-    int status;      // dconv_status
-};
+// Status of one kernel launch.  hipGetLastError() also hands back (and clears) an error that
+// earlier, unrelated work left behind on this thread: begin_launch() drops such an error before
+// the launch, launch_status() reads what the launch itself left.
+inline void begin_launch() { (void)hipGetLastError(); }
+inline int launch_status() { return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED; }
 
 // Kernels that use more dynamic LDS than the default limit have it raised once per device (the
 // attribute belongs to the kernel on the current device): `done` holds one bit per device, one

@@ -3,6 +3,7 @@
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 #include "general_kernel.h"
 
 namespace dconv {
@@ -11,15 +12,27 @@ namespace dconv {
 // One per (device, stream): launches on one stream run in order and may share it; launches on
 // different streams may overlap and must not.  It holds the partial sums of tiles shared by
 // several workgroups and one arrival counter per workgroup.  The counters are zero between
-// launches: the workgroup that completes a tile resets its counter.  Grown on demand, freed
-// by release_general_workspaces().
+// launches: the workgroup that completes a tile resets its counter.
+//
+// A block, once handed out, keeps its address until release_general_workspaces(): kernel
+// arguments hold it by value, so a HIP graph captured on the stream refers to it for as long as
+// the graph lives.  The first request on a (device, stream) therefore allocates what the
+// largest launch on that device can need (a launch has at most OCC workgroups per CU, each with
+// two partial tiles), and later requests find it large enough.  Should a request ever exceed it
+// (a forced grid), a larger block is allocated beside the old one, which is kept until release.
 namespace {
+
+// floats of partial sums and counters per CU that cover every compiled tile shape:
+// 64 x 256 tiles at two workgroups per CU (2 * 2 * 16384), 64 x 128 or 32 x 256 at three
+constexpr size_t kPartFloatsPerCu = 2 * 2 * 64 * 256;
+constexpr size_t kCountersPerCu = 4;
 
 struct WsEntry {
     float* part = nullptr;
     size_t part_floats = 0;
     int* cnt = nullptr;
     size_t ncnt = 0;
+    std::vector<void*> retired;      // outgrown blocks: freed only by release_general_workspaces()
 };
 std::mutex g_ws_mutex;
 std::map<std::pair<int, hipStream_t>, WsEntry> g_ws;
@@ -28,30 +41,37 @@ std::map<std::pair<int, hipStream_t>, WsEntry> g_ws;
 
 GenWorkspace gen_workspace(hipStream_t st, size_t part_floats, size_t ncnt)
 {
-    int dev = 0;
+    int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return {nullptr, nullptr};
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     WsEntry& e = g_ws[{dev, st}];
+    if (e.part_floats >= part_floats && e.ncnt >= ncnt) return {e.part, e.cnt};
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return {nullptr, nullptr};
     if (e.part_floats < part_floats) {
-        // earlier launches on this stream may still use the old block
-        if (e.part) { (void)hipStreamSynchronize(st); (void)hipFree(e.part); e.part = nullptr; e.part_floats = 0; }
-        if (hipMalloc((void**)&e.part, part_floats * sizeof(float)) != hipSuccess) {
-            e.part = nullptr;
+        const size_t want = std::max(part_floats, kPartFloatsPerCu * (size_t)cus);
+        float* fresh = nullptr;
+        if (hipMalloc((void**)&fresh, want * sizeof(float)) != hipSuccess) {
             (void)hipGetLastError();
             return {nullptr, nullptr};
         }
-        e.part_floats = part_floats;
+        if (e.part) e.retired.push_back(e.part);
+        e.part = fresh;
+        e.part_floats = want;
     }
     if (e.ncnt < ncnt) {
-        if (e.cnt) { (void)hipStreamSynchronize(st); (void)hipFree(e.cnt); e.cnt = nullptr; e.ncnt = 0; }
-        if (hipMalloc((void**)&e.cnt, ncnt * sizeof(int)) != hipSuccess ||
-            hipMemsetAsync(e.cnt, 0, ncnt * sizeof(int), st) != hipSuccess) {
-            if (e.cnt) (void)hipFree(e.cnt);
-            e.cnt = nullptr;
+        const size_t want = std::max(ncnt, kCountersPerCu * (size_t)cus);
+        int* fresh = nullptr;
+        // (the one place where a call may not be captured into a graph: first use on a stream)
+        if (hipMalloc((void**)&fresh, want * sizeof(int)) != hipSuccess ||
+            hipMemsetAsync(fresh, 0, want * sizeof(int), st) != hipSuccess) {
+            if (fresh) (void)hipFree(fresh);
             (void)hipGetLastError();
             return {nullptr, nullptr};
         }
-        e.ncnt = ncnt;
+        if (e.cnt) e.retired.push_back(e.cnt);
+        e.cnt = fresh;
+        e.ncnt = want;
     }
     return {e.part, e.cnt};
 }
@@ -62,6 +82,7 @@ void release_general_workspaces()
     for (auto& kv : g_ws) {
         if (kv.second.part) (void)hipFree(kv.second.part);
         if (kv.second.cnt) (void)hipFree(kv.second.cnt);
+        for (void* q : kv.second.retired) (void)hipFree(q);
     }
     g_ws.clear();
 }

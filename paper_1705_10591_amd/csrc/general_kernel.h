@@ -662,25 +662,26 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
 
     auto kern = general_tiled_kernel<F, CSH, RG, MW, NW, WM, WN, IMAX, NBUF, OCC>;
     // Workgroups the chip holds at once for this LDS size (at most OCC per CU are used): cached
-    // per instantiation for the last LDS size seen.  A race between threads can only pair the
-    // count with another shape's LDS size, which changes the grid size and nothing else:
-    // no workgroup ever waits for another one.
+    // per instantiation for the last (device, LDS size) seen, key and count in one atomic word,
+    // so that threads calling with different shapes can only repeat the query.
     static std::atomic<uint64_t> lds_limit_raised{0};
-    static int64_t cached_lds = -1;
-    static int cached_chip = 0;
+    static std::atomic<uint64_t> cached{0};        // device + 1 (8 bits) | LDS bytes (24) | count (32)
     if (!raise_lds_limit((const void*)kern, kGenLdsLimit, lds_limit_raised)) return DCONV_LAUNCH_FAILED;
-    if (cached_lds != lds_bytes) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return DCONV_LAUNCH_FAILED;
+    const uint64_t key = ((uint64_t)((dev & 0xFF) + 1) << 56) | ((uint64_t)lds_bytes << 32);
+    uint64_t seen = cached.load(std::memory_order_relaxed);
+    if ((seen & ~0xFFFFFFFFull) != key) {
+        int cus = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, kThreads,
                                                          (size_t)lds_bytes) != hipSuccess ||
             cus <= 0 || per_cu <= 0)
             return DCONV_LAUNCH_FAILED;
-        cached_chip = cus * (per_cu > OCC ? OCC : per_cu);
-        cached_lds = lds_bytes;
+        seen = key | (uint32_t)(cus * (per_cu > OCC ? OCC : per_cu));
+        cached.store(seen, std::memory_order_relaxed);
     }
-    const int chip = cached_chip;
+    const int chip = (int)(uint32_t)seen;
 
     // Whole tiles when they spread evenly enough, otherwise cut inside tiles.
     int G, split;
@@ -712,8 +713,9 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
                 make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
                 make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho), make_fastdiv(s.Ho + RG - 1),
                 make_fastdiv(nch), s.Ho + RG - 1};
+    begin_launch();
     hipLaunchKernelGGL(kern, dim3((unsigned)G), dim3(kThreads), (size_t)lds_bytes, st, p);
-    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+    return launch_status();
 }
 
 // Implemented once per filter side, each in its own translation unit.

@@ -29,13 +29,14 @@ int launch_simple_half(const void* in, const void* filt, float* out, const Shape
                        int dtype, bool blocked)
 {
     const int64_t total = (int64_t)s.N * s.K * s.Ho * s.Wo;
-    const int64_t blocks = (total + kThreads - 1) / kThreads;
-    if (blocks > 2147483647LL) return DCONV_UNSUPPORTED;
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 256 * 64) blocks = 256 * 64;     // grid-stride beyond that
     auto kern = dtype == kI8 ? simple_half_kernel<kI8>
               : dtype == kBF16 ? simple_half_kernel<kBF16> : simple_half_kernel<kF16>;
+    begin_launch();
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kThreads), 0, st,
                        in, filt, out, s.N, s.C, s.H, s.W, s.K, s.F, s.Ho, s.Wo, blocked ? 1 : 0);
-    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+    return launch_status();
 }
 
 // Which tile configuration a shape gets.  The large tile (128 filters x 512 pixels, one workgroup

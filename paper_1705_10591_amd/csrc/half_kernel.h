@@ -429,35 +429,46 @@ simple_half_kernel(const void* in_, const void* filt_, float* out,
         return ((outer * (C / cb) + c / cb) * inner_count + pos) * cb + c % cb;
     };
     const int64_t total = (int64_t)N * K * Ho * Wo;
-    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (o >= total) return;
-    const int x = (int)(o % Wo), y = (int)((o / Wo) % Ho);
-    const int k = (int)((o / ((int64_t)Wo * Ho)) % K), n = (int)(o / ((int64_t)Wo * Ho * K));
-    if (DT == kI8) {
-        const signed char* in = (const signed char*)in_;
-        const signed char* filt = (const signed char*)filt_;
-        int acc = 0;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += stride) {
+        const int x = (int)(o % Wo), y = (int)((o / Wo) % Ho);
+        const int k = (int)((o / ((int64_t)Wo * Ho)) % K), n = (int)(o / ((int64_t)Wo * Ho * K));
+        if (DT == kI8) {
+            const signed char* in = (const signed char*)in_;
+            const signed char* filt = (const signed char*)filt_;
+            int acc = 0;
+            for (int i = 0; i < F; ++i)
+                for (int j = 0; j < F; ++j)
+                    for (int c = 0; c < C; ++c)
+                        acc += (int)in[at(n, (int64_t)H * W, (int64_t)(y + i) * W + x + j, c)] *
+                               (int)filt[at(k, F * F, i * F + j, c)];
+            out[o] = __builtin_bit_cast(float, acc);
+            continue;
+        }
+        const unsigned short* in = (const unsigned short*)in_;
+        const unsigned short* filt = (const unsigned short*)filt_;
+        auto cvt = [](unsigned short v) {
+            if (DT == kBF16) return __builtin_bit_cast(float, (uint32_t)v << 16);
+            return (float)__builtin_bit_cast(_Float16, v);
+        };
+        // sums in three levels (runs of 64 channels, taps, the whole), so that the rounding
+        // error grows with the longest level and not with C * F * F
+        float acc = 0.f;
         for (int i = 0; i < F; ++i)
-            for (int j = 0; j < F; ++j)
-                for (int c = 0; c < C; ++c)
-                    acc += (int)in[at(n, (int64_t)H * W, (int64_t)(y + i) * W + x + j, c)] *
-                           (int)filt[at(k, F * F, i * F + j, c)];
-        out[o] = __builtin_bit_cast(float, acc);
-        return;
+            for (int j = 0; j < F; ++j) {
+                float tap = 0.f;
+                for (int c0 = 0; c0 < C; c0 += 64) {
+                    float run = 0.f;
+                    const int c1 = c0 + 64 < C ? c0 + 64 : C;
+                    for (int c = c0; c < c1; ++c)
+                        run = __builtin_fmaf(cvt(in[at(n, (int64_t)H * W, (int64_t)(y + i) * W + x + j, c)]),
+                                             cvt(filt[at(k, F * F, i * F + j, c)]), run);
+                    tap += run;
+                }
+                acc += tap;
+            }
+        out[o] = acc;
     }
-    const unsigned short* in = (const unsigned short*)in_;
-    const unsigned short* filt = (const unsigned short*)filt_;
-    auto cvt = [](unsigned short v) {
-        if (DT == kBF16) return __builtin_bit_cast(float, (uint32_t)v << 16);
-        return (float)__builtin_bit_cast(_Float16, v);
-    };
-    float acc = 0.f;
-    for (int i = 0; i < F; ++i)
-        for (int j = 0; j < F; ++j)
-            for (int c = 0; c < C; ++c)
-                acc = __builtin_fmaf(cvt(in[at(n, (int64_t)H * W, (int64_t)(y + i) * W + x + j, c)]),
-                                     cvt(filt[at(k, F * F, i * F + j, c)]), acc);
-    out[o] = acc;
 }
 
 // ---- host side -----------------------------------------------------------------------------------
@@ -534,8 +545,9 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
                  make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
                  make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho),
                  make_fastdiv(s.Ho + RG - 1), make_fastdiv(pl.LS)};
+    begin_launch();
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(TL::THREADS), (size_t)lds_bytes, st, p);
-    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+    return launch_status();
 }
 
 // Tile configurations of the short-data-type kernel (DCONV_VARIANT_TILED_CFG0 + i forces one):

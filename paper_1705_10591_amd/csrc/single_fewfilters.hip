@@ -158,8 +158,9 @@ int launch_few_rows(const float* img, const float* filt, float* out, const Shape
     if (tiles > 2000000000LL) return DCONV_UNSUPPORTED;
     p.tiles = (int)tiles;
     p.per_xcd = (int)((tiles + 7) / 8);
+    begin_launch();
     hipLaunchKernelGGL((single_few_kernel<F, RPW>), dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
-    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+    return launch_status();
 }
 
 template <int F>

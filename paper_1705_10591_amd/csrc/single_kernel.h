@@ -354,9 +354,10 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     const int64_t items = (int64_t)p.tiles_x * p.tiles_y * p.fgroups * s.N;
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
+    begin_launch();
     hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE, C>),
                        dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
-    return hipGetLastError() == hipSuccess ? DCONV_OK : DCONV_LAUNCH_FAILED;
+    return launch_status();
 }
 
 // Images 96 to 199 pixels wide: configuration 5 (128 x 4 tile, passes of 64 pixels) or 6 (passes
