@@ -46,7 +46,9 @@ typedef enum dconv_status {
     DCONV_BAD_SHAPE = 2,      /* a dimension <= 0, F > H, F > W, or a size that
                                  does not fit the kernels' 32-bit indexing       */
     DCONV_UNSUPPORTED = 3,    /* the requested variant cannot run this shape     */
-    DCONV_LAUNCH_FAILED = 4   /* the HIP runtime reported an error at launch     */
+    DCONV_LAUNCH_FAILED = 4,  /* the HIP runtime reported an error at launch     */
+    DCONV_SCRATCH_EXCEEDED = 5/* dconv_general_noalloc only: the launch would need
+                                 more scratch memory than the static array holds */
 } dconv_status;
 
 /* Kernel variants accepted by the *_v entry points. */
@@ -228,6 +230,30 @@ int dconv_tile_config_count(int single_channel);
  * returns DCONV_OK.
  */
 int dconv_release_workspace(void);
+
+/*
+ * dconv_general_v for callers that cannot allocate device memory: code that is
+ * under HIP graph capture from its first call on, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results (bit for bit:
+ * the same kernels in the same launch configuration) and same errors as
+ * dconv_general_v, but it never calls hipMalloc, hipFree or any allocating
+ * routine: where dconv_general_v would use its workspace, the partial sums and
+ * arrival counters of shared tiles go to a static device array that is part of
+ * the library's code object -- 64 MiB + 16 KiB on every GPU the library runs on,
+ * held until the process ends.  That is room for 512 workgroups with two 64 x 256
+ * partial tiles each and 4096 counters, i.e. for every launch configuration on
+ * a chip of up to 256 compute units; a launch that would need more returns
+ * DCONV_SCRATCH_EXCEEDED and nothing is launched.  Variants that never share
+ * tiles (DCONV_VARIANT_SIMPLE, the special-case kernels) do not touch the array.
+ * The counters a launch uses are cleared on `stream`, by a kernel, before it.
+ * All calls on one GPU share the one array: two dconv_general_noalloc calls
+ * that overlap in time on the same GPU (different streams, or different host
+ * threads whose launches run concurrently) race on it and give wrong results;
+ * the caller must order them.  Calls of the other entry points are unaffected.
+ */
+int dconv_general_noalloc(const float *in, int N, int C, int H, int W,
+                          const float *filt, int K, int F,
+                          float *out, int variant, void *stream);
 
 /* Human-readable name of a status code; static storage, never NULL. */
 const char *dconv_status_string(int status);

@@ -21,13 +21,14 @@ VARIANT_AUTO, VARIANT_SIMPLE, VARIANT_TILED, VARIANT_FEW_FILTERS = 0, 1, 2, 3
 VARIANT_TILED_CFG0 = 0x100     # + i: tiled kernel with tile configuration i forced
 VARIANT_SPECIAL_CASE = 4       # dconv_general with one channel: the single-channel tiled kernel
 VARIANT_SPECIAL_CASE_CFG0 = 0x200   # + i: the same with its tile configuration i forced
-STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAUNCH_FAILED = range(5)
+STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAUNCH_FAILED, \
+    STATUS_SCRATCH_EXCEEDED = range(6)
 
 EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
            "dconv_general_v", "dconv_status_string", "dconv_version",
            "dconv_tile_config_count", "dconv_release_workspace",
            "dconv_general_f16", "dconv_general_bf16", "dconv_general_half_v",
-           "dconv_general_i8", "dconv_general_i8_v", "dconv_general_lowp")
+           "dconv_general_i8", "dconv_general_i8_v", "dconv_general_lowp", "dconv_general_noalloc")
 DTYPE_F16, DTYPE_BF16, DTYPE_I8 = 0, 1, 2
 LAYOUT_CHANNELS_LAST, LAYOUT_CHANNEL_BLOCKED = 0, 1
 
@@ -54,6 +55,7 @@ def load_library() -> ctypes.CDLL:
         lib.dconv_single_channel_v.argtypes = [p, i, i, p, i, i, p, i, p]
         lib.dconv_general.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_v.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
+        lib.dconv_general_noalloc.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
         lib.dconv_general_f16.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_bf16.argtypes = [p, i, i, i, i, p, i, i, p, p]
         lib.dconv_general_half_v.argtypes = [p, i, i, i, i, p, i, i, p, i, i, p]
@@ -61,7 +63,7 @@ def load_library() -> ctypes.CDLL:
         lib.dconv_general_i8_v.argtypes = [p, i, i, i, i, p, i, i, p, i, p]
         lib.dconv_general_lowp.argtypes = [p, i, i, i, i, p, i, i, p, i, i, i, p]
         for name in ("dconv_single_channel", "dconv_single_channel_v",
-                     "dconv_general", "dconv_general_v", "dconv_version",
+                     "dconv_general", "dconv_general_v", "dconv_general_noalloc", "dconv_version",
                      "dconv_release_workspace", "dconv_general_f16", "dconv_general_bf16",
                      "dconv_general_half_v", "dconv_general_i8", "dconv_general_i8_v",
                      "dconv_general_lowp"):
@@ -134,8 +136,11 @@ def dconv_single_channel(img: torch.Tensor, filt: torch.Tensor, out: torch.Tenso
 
 
 def dconv_general(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None = None,
-                  variant: int = VARIANT_AUTO) -> torch.Tensor:
-    """out[n,k,y,x] = sum_{c,i,j} x[n,c,y+i,x+j] * filt[k,c,i,j]."""
+                  variant: int = VARIANT_AUTO, noalloc: bool = False) -> torch.Tensor:
+    """out[n,k,y,x] = sum_{c,i,j} x[n,c,y+i,x+j] * filt[k,c,i,j].
+
+    noalloc: call dconv_general_noalloc (shared tiles meet in the library's static device array;
+    the library allocates nothing; pass `out`, or torch allocates the result)."""
     _check(x, 4, "in")
     _check(filt, 4, "filt")
     N, C, H, W = x.shape
@@ -151,7 +156,8 @@ def dconv_general(x: torch.Tensor, filt: torch.Tensor, out: torch.Tensor | None 
         if tuple(out.shape) != (N, K, H - F + 1, W - F + 1):
             raise ValueError("out has the wrong shape")
     with torch.cuda.device(x.device):
-        rc = load_library().dconv_general_v(
+        lib = load_library()
+        rc = (lib.dconv_general_noalloc if noalloc else lib.dconv_general_v)(
             x.data_ptr(), N, C, H, W, filt.data_ptr(), K, F, out.data_ptr(), int(variant),
             _stream_ptr(x.device))
     _raise(rc)

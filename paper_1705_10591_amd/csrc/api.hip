@@ -27,14 +27,14 @@ int validate(const void* in, const void* filt, const void* out,
 }
 
 int dispatch(bool single, const float* in, const float* filt, float* out,
-             const Shape& s, int variant, void* stream)
+             const Shape& s, int variant, void* stream, bool static_ws = false)
 {
     hipStream_t st = (hipStream_t)stream;
     const bool tiled_ok = single ? dconv::single_tiled_supports(s)
                                  : dconv::general_tiled_supports(s);
     auto tiled = [&](int cfg) {
         return single ? dconv::launch_single_tiled(in, filt, out, s, st, cfg)
-                      : dconv::launch_general_tiled(in, filt, out, s, st, cfg);
+                      : dconv::launch_general_tiled(in, filt, out, s, st, cfg, static_ws);
     };
     switch (variant) {
     case DCONV_VARIANT_AUTO:
@@ -56,21 +56,8 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
     return DCONV_UNSUPPORTED;
 }
 
-}  // namespace
-
-extern "C" {
-
-int dconv_single_channel_v(const float* img, int H, int W, const float* filt, int K, int F,
-                           float* out, int variant, void* stream)
-{
-    Shape s;
-    const int rc = validate(img, filt, out, 1, 1, H, W, K, F, &s);
-    if (rc != DCONV_OK) return rc;
-    return dispatch(true, img, filt, out, s, variant, stream);
-}
-
-int dconv_general_v(const float* in, int N, int C, int H, int W, const float* filt, int K, int F,
-                    float* out, int variant, void* stream)
+int general_entry(const float* in, int N, int C, int H, int W, const float* filt, int K, int F,
+                  float* out, int variant, void* stream, bool static_ws)
 {
     Shape s;
     const int rc = validate(in, filt, out, N, C, H, W, K, F, &s);
@@ -93,7 +80,32 @@ int dconv_general_v(const float* in, int N, int C, int H, int W, const float* fi
         ((N == 1 && C == 1) || dconv::single_batch_preferred(s) ||
          (dconv::single_tiled_supports(s) && !dconv::general_tiled_supports(s))))
         return dispatch(true, in, filt, out, s, variant, stream);
-    return dispatch(false, in, filt, out, s, variant, stream);
+    return dispatch(false, in, filt, out, s, variant, stream, static_ws);
+}
+
+}  // namespace
+
+extern "C" {
+
+int dconv_single_channel_v(const float* img, int H, int W, const float* filt, int K, int F,
+                           float* out, int variant, void* stream)
+{
+    Shape s;
+    const int rc = validate(img, filt, out, 1, 1, H, W, K, F, &s);
+    if (rc != DCONV_OK) return rc;
+    return dispatch(true, img, filt, out, s, variant, stream);
+}
+
+int dconv_general_v(const float* in, int N, int C, int H, int W, const float* filt, int K, int F,
+                    float* out, int variant, void* stream)
+{
+    return general_entry(in, N, C, H, W, filt, K, F, out, variant, stream, false);
+}
+
+int dconv_general_noalloc(const float* in, int N, int C, int H, int W, const float* filt, int K, int F,
+                          float* out, int variant, void* stream)
+{
+    return general_entry(in, N, C, H, W, filt, K, F, out, variant, stream, true);
 }
 
 int dconv_single_channel(const float* img, int H, int W, const float* filt, int K, int F,
@@ -167,6 +179,7 @@ const char* dconv_status_string(int status)
     case DCONV_BAD_SHAPE: return "bad shape";
     case DCONV_UNSUPPORTED: return "variant does not support this shape";
     case DCONV_LAUNCH_FAILED: return "kernel launch failed";
+    case DCONV_SCRATCH_EXCEEDED: return "shape needs more scratch memory than the static device array holds";
     default: return "unknown status";
     }
 }
@@ -182,6 +195,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1009; }
+int dconv_version(void) { return 1010; }
 
 }  // extern "C"

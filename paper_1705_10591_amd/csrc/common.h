@@ -58,8 +58,10 @@ int launch_simple(const float* in, const float* filt, float* out, const Shape& s
 // cfg selects one of the compiled tile configurations; cfg < 0 lets the shape decide.
 int launch_single_tiled(const float* img, const float* filt, float* out, const Shape& s,
                         hipStream_t st, int cfg);
+// static_ws: tiles shared between workgroups meet in the library's static device array instead of
+// an allocated workspace (dconv_general_noalloc)
 int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
-                         hipStream_t st, int cfg);
+                         hipStream_t st, int cfg, bool static_ws);
 int single_tile_configs();
 int general_tile_configs();
 int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st);

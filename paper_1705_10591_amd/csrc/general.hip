@@ -87,6 +87,61 @@ void release_general_workspaces()
     g_ws.clear();
 }
 
+// ---- the static scratch array of dconv_general_noalloc --------------------------------------------
+// The same two things as the workspace above -- arrival counters, then partial sums -- in device
+// memory that comes with the library's code object: every GPU the library runs on holds its own
+// copy of the array, at its own address, from the moment the code object is loaded there until
+// the process ends.  In host code the array's name only stands for the symbol; its address on
+// the current device is looked up once per device and that pointer is what kernels are given.
+// All calls on a device share the array (one call at a time, see dconv.h) and it keeps what the
+// last call left: the counters a launch uses are cleared on its stream before it, by a kernel,
+// so that the call can be captured into a graph.
+namespace {
+
+constexpr size_t kScratchCounters = 4096;               // ints: 16 KiB, then the partial sums
+constexpr size_t kScratchPartFloats = (size_t)16 << 20; // 64 MiB: 512 workgroups x 2 x (64 x 256)
+constexpr size_t kScratchBytes = 4 * (kScratchCounters + kScratchPartFloats);
+constexpr int kMaxDevices = 64;
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};         // device address of `scratch`, per device
+
+__global__ void clear_counters_kernel(int* cnt, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) cnt[i] = 0;
+}
+
+}  // namespace
+
+int gen_static_workspace(hipStream_t st, size_t part_floats, size_t ncnt, GenWorkspace* ws)
+{
+    if (part_floats > kScratchPartFloats || ncnt > kScratchCounters) return DCONV_SCRATCH_EXCEEDED;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DCONV_LAUNCH_FAILED;
+    unsigned char* base;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* q = nullptr;
+            if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) {
+                (void)hipGetLastError();
+                return DCONV_LAUNCH_FAILED;
+            }
+            g_scratch_ptr[dev] = (unsigned char*)q;
+        }
+        base = g_scratch_ptr[dev];
+    }
+    ws->cnt = (int*)base;
+    ws->part = (float*)(base + 4 * kScratchCounters);
+    begin_launch();
+    hipLaunchKernelGGL(clear_counters_kernel, dim3((unsigned)((ncnt + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, st, ws->cnt, (int)ncnt);
+    return launch_status();
+}
+
 // ---- dispatch ----------------------------------------------------------------------------------
 
 namespace {
@@ -143,7 +198,7 @@ namespace {
 
 bool whole_batch_supported(const Shape& s)
 {
-    const GenSched sched{0, 0};
+    const GenSched sched{0, 0, false, false};
     return launch_any(nullptr, nullptr, nullptr, s, nullptr, shape_for(s), sched, true) == DCONV_OK ||
            launch_any(nullptr, nullptr, nullptr, s, nullptr, 0, sched, true) == DCONV_OK;
 }
@@ -166,27 +221,28 @@ bool general_tiled_supports(const Shape& s)
 }
 
 int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
-                         hipStream_t st, int cfg)
+                         hipStream_t st, int cfg, bool static_ws)
 {
     if (cfg >= kShapes * kSchedules) return DCONV_UNSUPPORTED;
     Shape one;
     if (!whole_batch_supported(s) && per_image_supported(s, &one)) {
         const int64_t in_image = (int64_t)s.C * s.H * s.W, out_image = (int64_t)s.K * s.Ho * s.Wo;
         for (int n = 0; n < s.N; ++n) {
-            const int rc = launch_general_tiled(in + n * in_image, filt, out + n * out_image, one, st, cfg);
+            const int rc = launch_general_tiled(in + n * in_image, filt, out + n * out_image, one, st, cfg,
+                                                static_ws);
             if (rc != DCONV_OK) return rc;
         }
         return DCONV_OK;
     }
     if (cfg < 0) {
-        const GenSched sched{0, 0};
+        const GenSched sched{0, 0, false, static_ws};
         int rc = launch_any(in, filt, out, s, st, shape_for(s), sched, false);
         if (rc == DCONV_UNSUPPORTED)
             rc = launch_any(in, filt, out, s, st, 0, sched, false);
         return rc;
     }
     const int schedule = cfg / kShapes;
-    const GenSched sched{schedule == 3 ? 2 : schedule, schedule == 3 ? 7 : 0};
+    const GenSched sched{schedule == 3 ? 2 : schedule, schedule == 3 ? 7 : 0, false, static_ws};
     return launch_any(in, filt, out, s, st, cfg % kShapes, sched, false);
 }
 

@@ -613,6 +613,7 @@ struct GenSched {
     int mode;          // 0: decide by shape, 1: whole tiles only, 2: cut inside tiles
     int force_G;       // > 0: this many workgroups (tests), 0: what the chip holds
     bool widest_only;  // refuse shapes whose image block needs narrower column strips
+    bool static_ws;    // shared tiles meet in the library's static device array: nothing is allocated
 };
 
 // Workspace of one (device, stream): grown on demand by the dispatcher.
@@ -623,6 +624,10 @@ struct GenWorkspace {
 // Returns a workspace with room for `part_floats` floats of partial sums and `ncnt` counters,
 // or nullptr members on allocation failure.
 GenWorkspace gen_workspace(hipStream_t st, size_t part_floats, size_t ncnt);
+// The same room inside the static device array of the current device, its counters cleared on
+// `st` by a small kernel.  Allocates nothing.  Returns a dconv_status: DCONV_SCRATCH_EXCEEDED if
+// the array is too small for the request.
+int gen_static_workspace(hipStream_t st, size_t part_floats, size_t ncnt, GenWorkspace* ws);
 
 constexpr int kGenLdsLimit = 160 * 1024 - 256;     // dynamic LDS; the rest is for the static word
 
@@ -704,7 +709,10 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     if (split && sched.force_G <= 0 && sched.mode == 0 && (int64_t)G > 8 * tiles) G = (int)(8 * tiles);
 
     GenWorkspace ws{nullptr, nullptr};
-    if (split) {
+    if (split && sched.static_ws) {
+        const int rc = gen_static_workspace(st, (size_t)G * 2 * MT * NT, (size_t)G, &ws);
+        if (rc != DCONV_OK) return rc;
+    } else if (split) {
         ws = gen_workspace(st, (size_t)G * 2 * MT * NT, (size_t)G);
         if (!ws.part || !ws.cnt) return DCONV_LAUNCH_FAILED;
     }

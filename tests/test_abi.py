@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_version_and_status_strings():
     assert dconv.version() >= 1003
-    seen = {dconv.status_string(s) for s in range(5)}
-    assert len(seen) == 5 and all(seen)
+    seen = {dconv.status_string(s) for s in range(6)}
+    assert len(seen) == 6 and all(seen)
     assert dconv.status_string(12345)
 
 
