@@ -16,6 +16,7 @@ import argparse
 import json
 import os
 import re
+import subprocess
 import sys
 import time
 from pathlib import Path
@@ -42,9 +43,43 @@ def parse_args():
     ap.add_argument("--paper-sweep", action="store_true",
                     help="also time the other corners the paper sweeps (1x1 filters, one filter, "
                          "5x5 and 7x7 general layers, 32x32 images): entries under 'paper_sweep'")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="do not run the hardware-rate microbenchmark whose fill and matrix-core rates "
+                         "are quoted as measured achievable peaks beside the published ones")
     ap.add_argument("--only", default=None,
                     help="time just this configuration (S1, S2, S2_F3.., G1, G2, G3) as the step")
     return ap.parse_args()
+
+
+def measured_peaks():
+    """Rates this very box sustains, from the standalone microbenchmark built with the library
+    (run as a child process before this process touches the GPU): HBM fill and read with 16 B
+    per lane over 4 GiB, and the bare fp32 matrix-core loop fed from LDS.  None if it cannot run."""
+    exe = ROOT / "paper_1705_10591_amd" / "hw_bench"
+    if not exe.exists():
+        return None
+    try:
+        r = subprocess.run([str(exe), "--quick"], capture_output=True, text=True, timeout=120)
+    except (OSError, subprocess.TimeoutExpired):
+        return None
+    if r.returncode != 0:
+        return None
+    val = {m.group(1).strip(): float(m.group(2))
+           for m in re.finditer(r"^([^#\n][^:]*):\s+[\d.]+ ms\s+([\d.]+) (?:GB/s|TFLOP/s)", r.stdout, re.M)}
+    try:
+        return {"hbm_fill_gbs": val["fill, 16 B per lane"], "hbm_read_gbs": val["read, 16 B per lane"],
+                "fp32_mfma_tflops": val["no other vector instructions"],
+                "source": "paper_1705_10591_amd/hw_bench --quick, same box, before the timed runs"}
+    except KeyError:
+        return None
+
+
+def add_measured(entry, peaks):
+    """Fractions of the measured achievable rates beside the published-peak ones."""
+    if peaks:
+        entry["frac_hbm_fill_measured"] = round(entry["algorithmic_gbs"] / peaks["hbm_fill_gbs"], 4)
+        entry["frac_fp32_mfma_measured"] = round(entry["gflops"] / 1e3 / peaks["fp32_mfma_tflops"], 4)
+    return entry
 
 
 def time_launches(fn, steps, warmup, warm_ms=0.0):
@@ -235,6 +270,7 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "run it with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    peaks = None if (args.no_measured_peaks or args.only) else measured_peaks()
     import torch
     import workloads as wl
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -294,6 +330,13 @@ def main():
     roof["kernel"] = entry["kernel"]
     roof["kernel_ms"] = round(ms, 5)
     roof["traffic"] = read_traffic(f"{entry['kernel']}_{head.name}")
+    roof["traffic_source"] = (f"profiles/{entry['kernel']}_{head.name}_hbm_traffic.txt (rocprofv3 counters of an "
+                              "earlier run of the same command, not measured in this run)")
+    if peaks:
+        measured = peaks["hbm_fill_gbs"] if hbm_bound else peaks["fp32_mfma_tflops"]
+        roof["peak_measured"] = measured
+        roof["frac_measured"] = round(roof["achieved"] / measured, 4)
+    add_measured(entry, peaks)
 
     result = {
         "metric": "GFLOP/s (fp32 direct convolution, per conv shape; % of fp32 peak and HBM GB/s alongside)",
@@ -304,6 +347,8 @@ def main():
         "config": {"workload": f"{head.name}: {entry['kernel']} " + json.dumps(entry["shape"]).replace('"', "")},
         "roofline": roof,
     }
+    if peaks:
+        result["measured_peaks"] = peaks
     del run
     torch.cuda.empty_cache()
 
@@ -324,7 +369,7 @@ def main():
             w = allw[name]
             r, (xw, fw) = make_runner(w)
             m, _ = time_launches(r, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), warm_ms=60.0)
-            e = config_entry(w, m)
+            e = add_measured(config_entry(w, m), peaks)
             if name in ("S1", "G2"):
                 # the two launch-bound configurations: the same calls replayed from a HIP graph
                 e["ms_graph_replay"] = round(graph_replay_ms(r), 5)
@@ -348,7 +393,11 @@ def main():
         result["roofline_general"] = {
             "bound": "mfma", "kernel": "dconv_general", "workload": "G3",
             "achieved": round(g["G3"]["gflops"] / 1e3, 3), "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": g["G3"]["frac_fp32_peak"], "traffic": read_traffic("dconv_general_G3")}
+            "frac": g["G3"]["frac_fp32_peak"], "traffic": read_traffic("dconv_general_G3"),
+            "traffic_source": "profiles/dconv_general_G3_hbm_traffic.txt (earlier run)"}
+        if peaks:
+            result["roofline_general"]["peak_measured"] = peaks["fp32_mfma_tflops"]
+            result["roofline_general"]["frac_measured"] = g["G3"]["frac_fp32_mfma_measured"]
 
     if not args.no_extra_configs and not args.only:
         # the next row of the scope: the same general-case shapes with fp16, bf16 and int8 inputs

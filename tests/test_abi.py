@@ -89,6 +89,35 @@ def test_tile_configuration_variants_are_bounded():
                 == dconv.STATUS_UNSUPPORTED
 
 
+def test_two_threads_in_the_dispatcher_at_once():
+    """Host-side state (shape checks, tile choice, cached launch parameters) under two threads.
+    Without a GPU every call that passes validation ends at the first HIP query with
+    DCONV_LAUNCH_FAILED; what is checked is that concurrent calls neither crash nor disturb each
+    other's validation results."""
+    import threading
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("with a GPU the calls would launch on fake pointers; see tests/test_threads_gpu.py")
+    lib = dconv.load_library()
+    shapes = [(4, 16, 28, 28, 130, 3), (2, 3, 64, 64, 32, 11), (8, 64, 14, 14, 64, 1), (1, 1, 200, 300, 16, 5)]
+    seen = [set(), set()]
+
+    def worker(t):
+        for rep in range(200):
+            N, C, H, W, K, F = shapes[(rep + t) % len(shapes)]
+            seen[t].add(lib.dconv_general(FAKE, N, C, H, W, FAKE, K, F, FAKE, None))
+            seen[t].add(10 + lib.dconv_general(FAKE, N, C, F - 1, W, FAKE, K, F, FAKE, None))
+            seen[t].add(20 + lib.dconv_general_v(FAKE, N, C, H, W, FAKE, K, 13, FAKE, dconv.VARIANT_TILED, None))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    for t in range(2):
+        assert seen[t] == {dconv.STATUS_LAUNCH_FAILED, 10 + dconv.STATUS_BAD_SHAPE, 20 + dconv.STATUS_UNSUPPORTED}
+
+
 def test_python_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(TypeError):

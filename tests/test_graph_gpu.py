@@ -79,3 +79,40 @@ def test_captured_graph_replays_match_eager_calls():
         assert_within_bound(e.cpu().numpy(), acc, mag, what)
     acc, mag, _ = oracle.general(xhr, fhr)
     assert_within_bound(eager[3].cpu().numpy(), acc, mag, "general bf16")
+
+
+def test_graph_stays_valid_when_later_calls_on_its_stream_need_a_larger_workspace():
+    """The workspace of a stream keeps its address: a graph that captured a small shared-tile
+    launch is replayed after a much larger shared-tile call ran eagerly on the same stream."""
+    shared = dconv.VARIANT_TILED_CFG0 + 3 * 3 + 1      # 64 x 256 tile, shared over seven workgroups
+    xs, fs = wl.random_case(41, 3, 16, 28, 28, 130, 3)
+    d_xs, d_fs = dev(xs), dev(fs)
+    out_small = torch.empty(3, 130, 26, 26, device="cuda")
+    big = wl.G3                                         # shares its tiles over the whole chip
+    xb, fb = wl.make_inputs(big)
+    d_xb, d_fb = dev(xb), dev(fb)
+    out_big = torch.empty(big.out_shape(), device="cuda")
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        dconv.dconv_general(d_xs, d_fs, out=out_small, variant=shared)     # first use: allocates
+    s.synchronize()
+    eager_small = out_small.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        dconv.dconv_general(d_xs, d_fs, out=out_small, variant=shared)
+    for rep in range(3):
+        with torch.cuda.stream(s):
+            dconv.dconv_general(d_xb, d_fb, out=out_big)                   # needs the whole block
+        s.synchronize()
+        if rep == 0:
+            eager_big = out_big.clone()
+        assert torch.equal(out_big, eager_big)
+        out_small.fill_(float("nan"))
+        torch.cuda.synchronize()
+        print(f"replay {rep} after the large call", flush=True)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_small, eager_small), f"replay {rep}"
+    acc, mag, _ = oracle.general(xs, fs)
+    assert_within_bound(eager_small.cpu().numpy(), acc, mag, "small shared-tile launch")

@@ -76,6 +76,19 @@ def test_half_small_shapes(shape, kind):
 
 
 @pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_half_fallback_kernel_long_reduction_of_one_sign(kind):
+    """The one-lane-per-output kernel on 18 000 terms of one sign (the worst case for a running
+    sum): it sums level by level, so the error stays within the bound."""
+    shape = (1, 2000, 6, 7, 3, 3)
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(977, N, C, H, W, K, F, "u01", "u01")
+    xr, xb = wl.to_16bit(x, kind)
+    fr, fb = wl.to_16bit(f, kind)
+    acc, mag, _ = oracle.general(xr, fr)
+    assert_within_bound(run_half(xb, fb, kind, SIMPLE), acc, mag, f"half {kind} simple kernel {shape}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
 @pytest.mark.parametrize("shape", [(2, 32, 28, 28, 70, 3), (1, 16, 30, 140, 64, 11), (3, 48, 12, 12, 9, 5)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_half_integer_inputs_are_bit_exact(shape, kind):

@@ -363,6 +363,104 @@ def test_config_G1_sampled_outputs():
     _sampled_check(w, out, x, f, 60000, "G1")
 
 
+def _delta_and_pair_filters(w, rng):
+    """Filters with one unit tap, and filters with a unit tap plus a tap of weight 2 in another
+    channel: out = x1 (exact), resp. x1 + 2 * x2 (one rounding whatever the order of additions,
+    since every other term is an exact zero and 2 * x2 is exact)."""
+    f = np.zeros(w.filt_shape(), np.float32)
+    taps = []
+    for k in range(w.K):
+        c0, a, b = k % w.C, (k // w.C) % w.F, (k * 5 + k // 7) % w.F
+        f[k, c0, a, b] = 1.0
+        second = None
+        if k % 2 == 1 and w.C > 1:
+            c1 = int((c0 + 1 + rng.integers(0, w.C - 1)) % w.C)
+            a1, b1 = int(rng.integers(0, w.F)), int(rng.integers(0, w.F))
+            f[k, c1, a1, b1] = 2.0
+            second = (c1, a1, b1)
+        taps.append(((c0, a, b), second))
+    return f, taps
+
+
+@pytest.mark.parametrize("name", ["G1", "G3"])
+def test_general_configs_delta_filters_whole_output_exact(name):
+    """The whole output of the two large general-case configurations, compared on the device:
+    unit-tap filters reproduce shifted crops of the input bit for bit, in every map, image, row
+    and column, so no tile, strip, chunk or shared-tile boundary can hide a misplaced element."""
+    w = wl.CONFIGS[name]
+    x, _ = wl.make_inputs(w)
+    f, taps = _delta_and_pair_filters(w, np.random.default_rng(w.seed))
+    xd = dev(x)
+    print(f"{name} delta filters", flush=True)
+    out = torch.full(w.out_shape(), float("nan"), device="cuda")
+    dconv.dconv_general(xd, dev(f), out=out)
+    torch.cuda.synchronize()
+    for k, ((c0, a, b), second) in enumerate(taps):
+        want = xd[:, c0, a:a + w.Ho, b:b + w.Wo]
+        if second is not None:
+            c1, a1, b1 = second
+            want = want + 2.0 * xd[:, c1, a1:a1 + w.Ho, b1:b1 + w.Wo]
+        assert torch.equal(out[:, k], want), f"{name} map {k} taps {(c0, a, b)}, {second}"
+
+
+def test_config_G1_whole_rows_at_seams():
+    """Whole output rows of G1 at the first and last rows, around the middle (pixel tiles end
+    anywhere along a row) and in images and maps at both ends, against the oracle."""
+    w = wl.G1
+    x, f = wl.make_inputs(w)
+    out = dconv.dconv_general(dev(x), dev(f))
+    torch.cuda.synchronize()
+    idx = []
+    for n in (0, 31, w.N - 1):
+        for k in (0, 33, w.K - 1):
+            for y in (0, 1, 106, 107, 108, w.Ho - 2, w.Ho - 1):
+                idx.append(((n * w.K + k) * w.Ho + y) * w.Wo + np.arange(w.Wo, dtype=np.int64))
+    idx = np.concatenate(idx)
+    got = out.reshape(-1)[torch.from_numpy(idx).to("cuda")].cpu().numpy()
+    acc, mag = oracle.general_at(x, f, idx)
+    assert_within_bound(got, acc, mag, "G1 whole rows")
+
+
+def test_plain_entry_points_called_directly():
+    """dconv_single_channel and dconv_general as the header declares them (no variant argument),
+    by ctypes with raw device pointers, against the oracle."""
+    import ctypes
+    lib = dconv.load_library()
+    vp = ctypes.c_void_p
+    st = vp(torch.cuda.current_stream().cuda_stream)
+    x, f = wl.random_case(901, 1, 1, 70, 333, 37, 5)
+    img, fs = dev(x[0, 0]), dev(f[:, 0])
+    out = torch.full((37, 66, 329), float("nan"), device="cuda")
+    rc = lib.dconv_single_channel(vp(img.data_ptr()), 70, 333, vp(fs.data_ptr()), 37, 5, vp(out.data_ptr()), st)
+    assert rc == dconv.STATUS_OK
+    torch.cuda.synchronize()
+    acc, mag, _ = oracle.single_channel(x[0, 0], f[:, 0])
+    assert_within_bound(out.cpu().numpy(), acc, mag, "dconv_single_channel by ctypes")
+    x, f = wl.random_case(902, 3, 12, 31, 45, 70, 3)
+    xd, fd = dev(x), dev(f)
+    out = torch.full((3, 70, 29, 43), float("nan"), device="cuda")
+    rc = lib.dconv_general(vp(xd.data_ptr()), 3, 12, 31, 45, vp(fd.data_ptr()), 70, 3, vp(out.data_ptr()), st)
+    assert rc == dconv.STATUS_OK
+    torch.cuda.synchronize()
+    acc, mag, _ = oracle.general(x, f)
+    assert_within_bound(out.cpu().numpy(), acc, mag, "dconv_general by ctypes")
+
+
+@pytest.mark.parametrize("shape", [(1, 128, 20, 22, 8, 13), (2, 300, 14, 14, 5, 12), (1, 1024, 6, 7, 3, 5)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_fallback_kernel_long_reductions_stay_within_the_bound(shape):
+    """The one-lane-per-output kernel on reductions of 10^4 and more terms of one sign (inputs in
+    [0,1], the worst case for a running sum): its sums are taken level by level, so the error
+    does not grow with the number of terms."""
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(950 + F, N, C, H, W, K, F, "u01", "u01")
+    acc, mag, _ = oracle.general(x, f)
+    ratio = assert_within_bound(run_general(x, f, SIMPLE), acc, mag, f"simple kernel {shape}")
+    print(f"max err / mag = {ratio:.2e} over {C * F * F} terms", flush=True)
+    if F > 11:
+        assert_within_bound(run_general(x, f, AUTO), acc, mag, f"automatic choice {shape}")
+
+
 def test_config_G2_whole_output():
     w = wl.G2
     x, f = wl.make_inputs(w)
