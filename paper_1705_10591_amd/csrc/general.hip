@@ -151,7 +151,17 @@ namespace {
 //   schedule 0: by shape, 1: whole tiles only, 2: tiles cut over channels wherever the even
 //            split of the work falls, 3: the same on a grid of 7 workgroups (so that small
 //            test shapes exercise every way a tile can be shared)
-constexpr int kShapes = 3, kSchedules = 4;
+//   write-back: configurations 0 to 11 store straight from the accumulators, 12 to 23 are the
+//            same twelve with tiles written back in whole 128-byte lines through LDS (the
+//            reorganisation through on-chip memory that the paper leaves open, Sec. 4.2).
+//            Measured against each other (paper_1705_10591_amd.tune writeback): the second is
+//            never faster, so no shape gets it by itself.  Outputs that fit the 256 MB
+//            memory-side cache do not care about line alignment at all; larger ones of narrow
+//            maps break even at best, because every accumulator then passes the register file's
+//            ports three times (to LDS, back, to memory) instead of once, and those ports are
+//            what stores compete for with the matrix cores; wide maps lose up to 40 %, because
+//            column strips cut every row into segments whose ends are partial lines anyway.
+constexpr int kShapes = 3, kSchedules = 4, kWriteBacks = 2;
 
 int launch_any(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st,
                int tile_cfg, const GenSched& sched, bool dry)
@@ -182,6 +192,16 @@ int shape_for(const Shape& s)
 {
     const int64_t px = (int64_t)s.N * s.Ho * s.Wo;
     if (s.K <= 32) return 2;
+    // Few multiply-adds per output element (up to sixteen channels of 3x3 filters): a tile is over
+    // after a few dozen steps and the time goes to its stores, which the vector memory pipe of
+    // a CU takes slowly while its matrix cores are busy.  The small tile, three workgroups per
+    // CU and 32 store instructions per wave and tile, then reaches the sum of arithmetic and
+    // store time; the larger ones, with 64 stores per wave in one burst, fall 25 to 60 % short
+    // of it (measured on 56^2 to 224^2 maps with 0.75 GB of output and more; outputs that the
+    // 256 MB memory-side cache absorbs are stored fast enough by every tile shape).  1x1 filters
+    // keep the rule below: their chunks are short and the small tile stages twice per
+    // matrix-core step.
+    if (s.F >= 2 && s.C * s.F * s.F <= 160 && px * s.K >= 100000000LL) return 0;
     if (s.K <= 64) {
         const int64_t wide_tiles = (px + 255) / 256;
         const int64_t chunks = ((int64_t)s.C * s.F * s.F + 35) / 36;
@@ -192,13 +212,13 @@ int shape_for(const Shape& s)
 
 }  // namespace
 
-int general_tile_configs() { return kShapes * kSchedules; }
+int general_tile_configs() { return kShapes * kSchedules * kWriteBacks; }
 
 namespace {
 
 bool whole_batch_supported(const Shape& s)
 {
-    const GenSched sched{0, 0, false, false};
+    const GenSched sched{0, 0, false, false, 0};
     return launch_any(nullptr, nullptr, nullptr, s, nullptr, shape_for(s), sched, true) == DCONV_OK ||
            launch_any(nullptr, nullptr, nullptr, s, nullptr, 0, sched, true) == DCONV_OK;
 }
@@ -223,7 +243,7 @@ bool general_tiled_supports(const Shape& s)
 int launch_general_tiled(const float* in, const float* filt, float* out, const Shape& s,
                          hipStream_t st, int cfg, bool static_ws)
 {
-    if (cfg >= kShapes * kSchedules) return DCONV_UNSUPPORTED;
+    if (cfg >= kShapes * kSchedules * kWriteBacks) return DCONV_UNSUPPORTED;
     Shape one;
     if (!whole_batch_supported(s) && per_image_supported(s, &one)) {
         const int64_t in_image = (int64_t)s.C * s.H * s.W, out_image = (int64_t)s.K * s.Ho * s.Wo;
@@ -235,14 +255,15 @@ int launch_general_tiled(const float* in, const float* filt, float* out, const S
         return DCONV_OK;
     }
     if (cfg < 0) {
-        const GenSched sched{0, 0, false, static_ws};
+        const GenSched sched{0, 0, false, static_ws, 0};
         int rc = launch_any(in, filt, out, s, st, shape_for(s), sched, false);
         if (rc == DCONV_UNSUPPORTED)
             rc = launch_any(in, filt, out, s, st, 0, sched, false);
         return rc;
     }
-    const int schedule = cfg / kShapes;
-    const GenSched sched{schedule == 3 ? 2 : schedule, schedule == 3 ? 7 : 0, false, static_ws};
+    const int schedule = cfg / kShapes % kSchedules;
+    const int wb = cfg / (kShapes * kSchedules) + 1;
+    const GenSched sched{schedule == 3 ? 2 : schedule, schedule == 3 ? 7 : 0, false, static_ws, wb};
     return launch_any(in, filt, out, s, st, cfg % kShapes, sched, false);
 }
 

@@ -86,6 +86,8 @@ struct GenParams {
     int tiles;       // all tiles: ((nstrips - 1) * pt_full + pt_last) * KB
     int G;           // workgroups launched
     int split;       // 1: ranges are cut in units (tiles may be shared), 0: in whole tiles
+    int aligned;     // 1: tiles are written back through LDS in whole 128-byte lines
+    int pad_words;   // LDS words added to every slot so that it can hold a tile on its way out
     FastDiv d_strip; // by pt_full * KB
     FastDiv d_kb;    // by KB
     FastDiv d_wsf;   // by bw, the width of a full strip
@@ -174,9 +176,9 @@ general_tiled_kernel(GenParams p)
     const int img_words = CSH * PL;             // a multiple of four: LS is
     // one LDS slot: filter block [TROWS][LDK], image block [CSH][RS][LS] on a 16-byte boundary,
     // a zero word (and three spare ones), four trash words
-    const int zero_word = IOFF + img_words;
+    const int zero_word = IOFF + img_words + p.pad_words;
     const int trash_word = zero_word + 4;
-    const int BUF = IOFF + img_words + 8;
+    const int BUF = zero_word + 8;
 
     // Workgroups are handed to the 8 XCDs round-robin by their id; give each XCD one contiguous
     // stretch of the unit list so that neighbouring tiles share its L2.
@@ -411,6 +413,101 @@ general_tiled_kernel(GenParams p)
             }
         }
     };
+    // Line-aligned write-back (the reorganisation through on-chip memory that the paper leaves
+    // open for this kernel, Sec. 4.2).  HBM runs at full rate only when every 128-byte line is
+    // written whole by one store instruction; straight from the accumulators, 32 lanes write 32
+    // consecutive pixels of one map, which start anywhere in a line.  Here the tile goes through
+    // LDS, GR filters at a time: every wave parks the accumulator registers of those filters
+    // (rows of NT pixels, one row per filter), and after a barrier every half-wave takes its
+    // share of the rows and stores them line by line: lane l of a half-wave always writes word
+    // l of a line.  A tile's pixels are contiguous in memory only within a segment (one image
+    // when the strip is the whole row, one row of the strip otherwise); each segment of each
+    // filter has its own offset within a line, so only its first and last line may be partial.
+    // Two regions alternate, one barrier per group: `r0` is the LDS slot of the chunk consumed
+    // last and `r1` the slot that the chunk after next will go to (with two slots: the second
+    // half of r0); nobody refills either before the next chunk's barrier.
+    constexpr int kWbRows = NBUF == 3 ? (NT == 128 ? 32 : 16) : 8;     // GR
+    constexpr int kWbStride = NT + 8;          // row stride: the two halves of a wave on different banks
+    auto store_out_aligned = [&](int tile, float* r0, float* r1) __attribute__((always_inline)) {
+        static_assert(WM == 1, "every wave holds all the tile's filters");
+        constexpr int GR = kWbRows, RSW = kWbStride;
+        constexpr int NGRP = MT / GR, RPH = GR / 8;  // groups per tile, rows per half-wave and group
+        const int strip = min(fdiv(tile, p.d_strip), p.nstrips - 1);
+        const int rem = tile - strip * per_strip;
+        const int ptile = fdiv(rem, p.d_kb), kb = rem - ptile * p.KB;
+        const int x0 = strip * p.bw;
+        const int ws = min(p.bw, p.Wo - x0);
+        const bool last_strip = strip == p.nstrips - 1;
+        const FastDiv d_ws{last_strip ? p.d_wsl.m : p.d_wsf.m, last_strip ? p.d_wsl.sh : p.d_wsf.sh, ws};
+        const int total_p = p.N * p.Ho * ws;
+        const int p0 = ptile * NT;
+        const int ntv = min(NT, total_p - p0);       // valid pixels of the tile
+        const int n_first = fdiv(fdiv(p0, d_ws), p.d_ho);
+        const int k0 = kb * MT;
+        const uint32_t kplane = (uint32_t)p.K * (uint32_t)plane;
+        // (tiny maps would cut the tile into many short segments: not worth the detour)
+        if ((p.nstrips == 1 ? p.Ho * ws : ws) < 32) { store_out(); return; }       // uniform
+        const int pm = (int)(plane & 31);
+        const int abase = (int)(((uintptr_t)obase_t >> 2) & 31);
+        const int hw = 2 * wave + h;                 // this half-wave's first filter row within a group
+        auto park = [&](int g) __attribute__((always_inline)) {
+            float* rg = (g & 1) ? r1 : r0;
+#pragma unroll
+            for (int q8 = 0; q8 < GR / 8; ++q8) {    // blocks of eight filters: one register quad each
+                const int f8 = g * (GR / 8) + q8, mt = f8 / 4, gq = f8 % 4;
+#pragma unroll
+                for (int jq = 0; jq < 4; ++jq)
+#pragma unroll
+                    for (int nt = 0; nt < NW; ++nt)
+                        rg[(8 * q8 + 4 * h + jq) * RSW + (wn * NW + nt) * 32 + l32] = acc[mt][nt][4 * gq + jq];
+            }
+        };
+        __syncthreads();                             // everyone has consumed the slots' chunks
+        park(0);
+        // (one copy of the store code: the groups are a run-time loop, and only the parking,
+        // which names accumulator registers, is selected group by group)
+#pragma unroll 1
+        for (int g = 0; g < NGRP; ++g) {
+            __syncthreads();                         // group g is parked; group g-1 has been read
+#pragma unroll
+            for (int c = 1; c < NGRP; ++c)
+                if (g + 1 == c) park(c);             // uniform
+            const float* rg = (g & 1) ? r1 : r0;
+#pragma unroll 1
+            for (int rr = 0; rr < RPH; ++rr) {
+                const int rowi = hw + 8 * rr;
+                const int kk = GR * g + rowi;        // filter, from the tile's first
+                const bool kvalid = k0 + kk < p.K;
+                float* ob = obase_t + (int64_t)kk * plane;
+                const int ak = abase + kk * pm;
+                const float* row = rg + rowi * RSW;
+                int pix = 0;                         // first pixel of the segment, from p0
+                while (pix < ntv) {                  // uniform
+                    const int pp = p0 + pix;
+                    const int Q = fdiv(pp, d_ws), xl = pp - Q * ws;
+                    const int n = fdiv(Q, p.d_ho), y = Q - n * p.Ho;
+                    const int seg_end = p.nstrips == 1 ? (n + 1) * p.Ho * ws : (Q + 1) * ws;
+                    const int len = min(seg_end, p0 + ntv) - pp;
+                    // word offset of the segment's start from out[n_first][k][0][0]
+                    const uint32_t oseg = (uint32_t)(n - n_first) * kplane + (uint32_t)(y * p.Wo + x0 + xl);
+                    const int shift = (ak + (int)(oseg & 31u)) & 31;   // of that start within a line
+                    const int t0 = l32 - shift;      // lane l writes word l of each line
+                    float* dst = ob + oseg + t0;
+                    const float* src = row + pix + t0;
+                    const int nlines = (len + 62) >> 5;       // at most: a start at word 31 of a line
+#pragma unroll
+                    for (int q = 0; q <= NT / 32; ++q) {
+                        if (q >= nlines) break;      // uniform
+                        const int t = t0 + 32 * q;
+                        if (kvalid && (unsigned)t < (unsigned)len) dst[32 * q] = src[32 * q];
+                    }
+                    pix += len;
+                }
+            }
+        }
+        if (NBUF == 2) __syncthreads();              // the slot is refilled right away
+    };
+
     // A partial tile in the workspace: per wave, per block, per accumulator register, one word
     // per lane, so that every store and load is 256 B contiguous per wave.  The words are
     // written and read with device-scope accesses, which pass through the per-XCD L2 to the
@@ -422,8 +519,12 @@ general_tiled_kernel(GenParams p)
     };
     // The tile whose chunks [.., last] this workgroup has just summed is complete if the
     // workgroup also summed its first chunk; otherwise it is shared with its neighbours.
-    auto finish_tile = [&](int tile, bool whole) __attribute__((always_inline)) {
-        if (whole) { store_out(); return; }
+    auto finish_tile = [&](int tile, bool whole, float* r0, float* r1) __attribute__((always_inline)) {
+        auto emit = [&]() __attribute__((always_inline)) {
+            if (p.aligned) store_out_aligned(tile, r0, r1);
+            else store_out();
+        };
+        if (whole) { emit(); return; }
         const int t0u = tile * nch;
         const int first = unit_owner(t0u, U, G), last = unit_owner(t0u + nch - 1, U, G);
         const int m = last - first + 1;
@@ -470,7 +571,7 @@ general_tiled_kernel(GenParams p)
                     __builtin_amdgcn_sched_barrier(0);   // one block's loads in flight at a time
                 }
         }
-        store_out();
+        emit();
     };
 
     // ---- prologue: constant LDS words, first unit into slot 0, second unit into registers ------
@@ -552,7 +653,8 @@ general_tiled_kernel(GenParams p)
         if (NBUF == 2) __syncthreads();      // unit u+1 is in LDS; everyone is done with unit u
 
         if (tile_ends) {
-            finish_tile(tile, from_first && chunk == nch - 1);
+            finish_tile(tile, from_first && chunk == nch - 1, lds + bi * BUF,
+                        NBUF == 3 ? lds + (bi == 0 ? 2 : bi - 1) * BUF : lds + bi * BUF + kWbRows * kWbStride);
             if (has1) {
                 ++tile; chunk = 0; from_first = true;
                 setup_compute(tile);
@@ -614,6 +716,7 @@ struct GenSched {
     int force_G;       // > 0: this many workgroups (tests), 0: what the chip holds
     bool widest_only;  // refuse shapes whose image block needs narrower column strips
     bool static_ws;    // shared tiles meet in the library's static device array: nothing is allocated
+    int wb;            // write-back: 0 by shape, 1 straight from the accumulators, 2 in whole lines through LDS
 };
 
 // Workspace of one (device, stream): grown on demand by the dispatcher.
@@ -640,7 +743,21 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     const GenPlan pl = make_gen_plan(s, NT, CSH, IMAX, RG, sched.widest_only);
     if (!pl.ok) return DCONV_UNSUPPORTED;
     const int64_t img_words = (int64_t)CSH * pl.RS * pl.LS;
-    const int64_t buf_words = Gm::IOFF + img_words + 8;
+    // The line-aligned write-back parks a tile in the LDS slots that are free when a tile ends,
+    // some filter rows of NT + 8 words at a time in two alternating regions; a slot too small
+    // for a region (for both, where there are only two slots) is padded.  It runs only when asked
+    // for: measured, it never beats the stores straight from the accumulators (see the
+    // dispatcher).
+    const bool want_aligned = sched.wb == 2;
+    constexpr int kWbWords = (NBUF == 3 ? (NT == 128 ? 32 : 16) : 16) * (NT + 8);   // see store_out_aligned
+    int64_t pad_words = want_aligned ? std::max<int64_t>(0, kWbWords - (Gm::IOFF + img_words)) : 0;
+    pad_words = (pad_words + 3) & ~(int64_t)3;
+    if (NBUF * 4 * (Gm::IOFF + img_words + pad_words + 8) > kGenLdsLimit) {
+        if (sched.wb == 2 && NBUF * 4 * (Gm::IOFF + img_words + 8) <= kGenLdsLimit) return DCONV_UNSUPPORTED;
+        pad_words = 0;
+    }
+    const int aligned = want_aligned && kWbWords <= Gm::IOFF + img_words + pad_words ? 1 : 0;
+    const int64_t buf_words = Gm::IOFF + img_words + pad_words + 8;
     const int64_t lds_bytes = NBUF * 4 * buf_words;
     if (lds_bytes > kGenLdsLimit) return DCONV_UNSUPPORTED;
     const int KB = (s.K + MT - 1) / MT;
@@ -717,7 +834,7 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
         if (!ws.part || !ws.cnt) return DCONV_LAUNCH_FAILED;
     }
     GenParams p{in, filt, out, ws.part, ws.cnt, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo,
-                pl.bw, pl.nstrips, pl.LS, pl.RS, pl.pt_full, KB, nch, (int)tiles, G, split,
+                pl.bw, pl.nstrips, pl.LS, pl.RS, pl.pt_full, KB, nch, (int)tiles, G, split, aligned, (int)pad_words,
                 make_fastdiv(pl.pt_full * KB), make_fastdiv(KB), make_fastdiv(pl.bw),
                 make_fastdiv(s.Wo - (pl.nstrips - 1) * pl.bw), make_fastdiv(s.Ho), make_fastdiv(s.Ho + RG - 1),
                 make_fastdiv(nch), s.Ho + RG - 1};

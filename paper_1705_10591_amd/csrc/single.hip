@@ -14,7 +14,9 @@ namespace {
 // 32 filters (one filter block, rows dealt to the waves) the smallest, 128 x 4.  Configuration 5
 // is that tile with passes of 64 instead of 128 pixels, for images 128 to 199 pixels wide, and
 // configuration 6 with passes of 32 pixels, for images 96 to 127 wide.
-constexpr int kSingleConfigs = 7;
+// Configuration 7 is configuration 0 with a unit of one word instead of four on the way out (strip
+// reads and stores): the width-matching ablation, never chosen by shape.
+constexpr int kSingleConfigs = 8;
 
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
@@ -66,6 +68,7 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
     case 4: return launch_cfg<F, 128, 4, 4, WS>(img, filt, out, s, st);
     case 5: return launch_cfg<F, 128, 4, 2, WS>(img, filt, out, s, st);
     case 6: return launch_cfg<F, 128, 4, 1, WS>(img, filt, out, s, st);
+    case 7: return launch_cfg<F, 512, 4, 4, 3, 1, 1>(img, filt, out, s, st);
     default: return launch_cfg<F, 512, 4, 4, 3>(img, filt, out, s, st);
     }
 }

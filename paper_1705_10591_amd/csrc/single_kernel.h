@@ -68,7 +68,10 @@ enum : int { kPlain = 0, kTail = 1, kEdge = 2 };
 // (img [N][C][H][W], filt [K][C][F][F]; C*F*F taps instead of F*F, the tile staged per channel)
 // are the same kernel: such shapes are bound by the output stream just the same, and the
 // general-case kernel does not write whole lines.
-template <int F, int TW, int TR, int NBW, int WPE, int C = 1>
+// UNIT: words a lane moves per instruction on the way out (strip read and store): 4 (16 bytes),
+// or 1 for the ablation of the paper's width-matching experiment (Sec. 5.1: the unit a thread
+// reads from on-chip memory against the width the hardware serves best).
+template <int F, int TW, int TR, int NBW, int WPE, int C = 1, int UNIT = 4>
 __global__ void __launch_bounds__(kThreads, WPE)
 single_tiled_kernel(SingleParams p)
 {
@@ -187,6 +190,7 @@ single_tiled_kernel(SingleParams p)
     struct PassOut {
         int tw, tr, trn;       // per-lane shift seeds of the pass's output row and of the next row
         float* orow;           // out[kb][y][X], wave-uniform
+        int c0, c0n;           // the same seeds without their per-lane parts (uniform)
         int X;                 // first output column of the pass
         int kind;              // kPlain, kTail or kEdge
         bool head;             // kEdge only: also write the pixels before the first boundary
@@ -207,6 +211,32 @@ single_tiled_kernel(SingleParams p)
                 asm volatile("" : "+v"(word));
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) sh[word + nb * 32] = A[nb][q];
+            }
+            if constexpr (UNIT == 1) {
+                // One word per lane: a wave instruction reads 64 pixels of one filter row from the
+                // strip and stores them, four times the instructions of the 16-byte unit.
+                static_assert(PASS % 64 == 0, "the one-word unit is compiled for passes of whole waves");
+#pragma unroll
+                for (int r8 = 0; r8 < 8; ++r8) {
+                    const int kofs = (kb + 8 * g + r8) * pm;
+                    const int sk = (-(pd.c0 + kofs)) & 31;
+                    const int skn = (-(pd.c0n + kofs)) & 31;
+                    float* ub = pd.orow + (8 * g + r8) * plane;     // out[kb + 8g + r8][y][X]
+                    const bool kvalid = kb + 8 * g + r8 < p.K;
+#pragma unroll
+                    for (int ip = 0; ip < PASS / 64; ++ip) {
+                        const int col = 64 * ip + lane;
+                        const float v = stg[r8 * SW + 32 + col];
+                        const int px = pd.X + sk + col;
+                        float* dst = ub + (sk + col);
+                        if (pd.kind == kPlain) __builtin_nontemporal_store(v, dst);
+                        else if (pd.kind == kTail) { if (px < p.Wo + skn) __builtin_nontemporal_store(v, dst); }
+                        else if (kvalid && px < p.Wo) *dst = v;
+                    }
+                    if (pd.kind == kEdge && pd.head && kvalid && lane < sk && lane < p.Wo)
+                        (ub - pd.X)[lane] = stg[r8 * SW + 32 - sk + lane];
+                }
+                continue;
             }
             v4f held[ITS];
 #pragma unroll
@@ -328,12 +358,12 @@ single_tiled_kernel(SingleParams p)
         if (ch > 0) compute(std::true_type{}, acc, base);
         else compute(std::false_type{}, acc, base);
         const PassOut pd{tw_lane + c0, tr_lane + c0, tr_lane + c0n,
-                         out + kb * plane + rowoff + X, X, kind, needs_head};
+                         out + kb * plane + rowoff + X, c0, c0n, X, kind, needs_head};
         write_back(acc, pd);
     }
 }
 
-template <int F, int TW, int TR, int NBW, int WPE, int C = 1>
+template <int F, int TW, int TR, int NBW, int WPE, int C = 1, int UNIT = 4>
 int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
     if (s.C != C) return DCONV_UNSUPPORTED;
@@ -355,7 +385,7 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
     begin_launch();
-    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE, C>),
+    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE, C, UNIT>),
                        dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
     return launch_status();
 }

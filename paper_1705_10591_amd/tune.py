@@ -16,6 +16,11 @@ that the rules can be checked or re-derived on another chip.
                                                                    kernel next to the general kernel)
     python -m paper_1705_10591_amd.tune table single|general|bf16|bf16-blocked
                                                                   (the shapes the rules were set on)
+    python -m paper_1705_10591_amd.tune units                     (special case: 16-byte against 4-byte units
+                                                                   on the way out, the width-matching ablation)
+    python -m paper_1705_10591_amd.tune writeback                 (general case: stores straight from the
+                                                                   accumulators against the line-aligned
+                                                                   write-back through LDS, per tile shape)
 """
 from __future__ import annotations
 
@@ -48,7 +53,11 @@ def _time(fn, warm_ms: float = 40.0, steps: int = 20) -> float:
 def _config_count(kind: str) -> int:
     # the short-data-type kernel: 64 filters x 256 pixels and 128 x 512 staged through registers,
     # the same two staged directly into LDS
-    return 4 if kind.startswith("bf16") else dconv.tile_config_count(kind in ("single", "special"))
+    if kind.startswith("bf16"):
+        return 4
+    # general case: configurations 0..11 (12..23 repeat them with the line-aligned write-back,
+    # see `writeback`)
+    return 12 if kind == "general" else dconv.tile_config_count(kind in ("single", "special"))
 
 
 def tune(kind: str, dims, steps: int = 20):
@@ -109,7 +118,19 @@ TABLE_GENERAL = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (64, 3, 224
                  (64, 128, 28, 28, 128, 3), (16, 512, 14, 14, 512, 3), (32, 192, 13, 13, 384, 3),
                  (8, 3, 224, 224, 32, 3), (32, 16, 64, 64, 32, 5), (128, 64, 32, 32, 128, 3),
                  (32, 64, 56, 56, 64, 5), (32, 64, 56, 56, 64, 7), (32, 64, 56, 56, 256, 3),
-                 (8, 128, 112, 112, 128, 3), (64, 512, 7, 7, 512, 3)]
+                 (8, 128, 112, 112, 128, 3), (64, 512, 7, 7, 512, 3),
+                 # few multiply-adds per output: the output stream is a large part of the time
+                 (64, 8, 224, 224, 64, 3), (256, 8, 112, 112, 64, 3), (256, 16, 112, 112, 64, 3),
+                 (512, 8, 56, 56, 128, 3), (256, 32, 112, 112, 64, 1)]
+
+# Shapes for the comparison of the two write-backs: few multiply-adds per output element, maps
+# narrower and wider than a column strip, outputs below and above the 256 MB memory-side cache;
+# and the three benchmark shapes of the general case.
+TABLE_WRITEBACK = [(64, 8, 224, 224, 64, 3), (64, 16, 224, 224, 64, 3), (64, 8, 130, 130, 64, 3),
+                   (64, 16, 130, 130, 64, 3), (128, 8, 56, 56, 64, 3), (64, 16, 112, 112, 64, 3),
+                   (256, 8, 112, 112, 64, 3), (256, 16, 112, 112, 64, 3), (512, 8, 56, 56, 128, 3),
+                   (256, 32, 112, 112, 64, 1), (512, 64, 56, 56, 128, 1),
+                   (64, 3, 224, 224, 64, 11), (32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3)]
 
 
 TABLE_BF16 = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (32, 128, 56, 56, 128, 3),
@@ -138,7 +159,66 @@ def table(kind: str) -> None:
               flush=True)
 
 
+def writeback_table() -> None:
+    """Per shape: the library's choice, the three tile shapes with stores straight from the
+    accumulators (configurations 0..2) and with the line-aligned write-back (12..14)."""
+    print("# general case, microseconds per launch: library choice | 64x128, 64x256, 32x256 tiles straight "
+          "from the accumulators | the same through LDS in whole lines | bound = max(flops / 157.3 TFLOP/s, "
+          "bytes / 8 TB/s) | output MB | best straight / best aligned")
+    for sh in TABLE_WRITEBACK:
+        N, C, H, W, K, F = sh
+        gen = torch.Generator(device="cuda").manual_seed(1705)
+        x = torch.rand(N, C, H, W, device="cuda", generator=gen)
+        f = (torch.rand(K, C, F, F, device="cuda", generator=gen) - 0.5) * 0.1
+        out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda")
+        t = [_time(lambda: dconv.dconv_general(x, f, out=out, variant=v))
+             for v in [dconv.VARIANT_AUTO] + [dconv.VARIANT_TILED_CFG0 + i for i in (0, 1, 2, 12, 13, 14)]]
+        flops = 2.0 * out.numel() * C * F * F
+        byts = 4.0 * (x.numel() + f.numel() + out.numel())
+        bound = max(flops / 157.3e12, byts / 8e12) * 1e6
+        print(f"{'x'.join(map(str, sh)):24s} {t[0] * 1e3:7.1f} | " + " ".join(f"{v * 1e3:7.1f}" for v in t[1:4]) + " | " +
+              " ".join(f"{v * 1e3:7.1f}" for v in t[4:7]) + f" | {bound:7.1f} | {out.numel() * 4 / 1e6:6.0f} | "
+              f"{min(t[1:4]) / min(t[4:7]):4.2f}", flush=True)
+        del x, f, out
+        torch.cuda.empty_cache()
+
+
+def unit_table() -> None:
+    """The paper's matched-against-unmatched experiment (Sec. 5.1: its 3x3 kernel is 19 % slower
+    when a thread moves units narrower than the hardware serves best) inside the special-case
+    kernel: tile configuration 0 moves 16 bytes per lane from the write-back strips to memory,
+    configuration 7 is the same kernel moving 4 bytes per lane."""
+    print("# special case, 64 filters, milliseconds per launch: 16-byte unit | 4-byte unit | ratio")
+    for H, W, K, F in [(4096, 4096, 64, 1), (4096, 4096, 64, 3), (4096, 4096, 64, 5), (4096, 4096, 64, 7),
+                       (2048, 2048, 64, 3)]:
+        gen = torch.Generator(device="cuda").manual_seed(1705)
+        x = torch.rand(H, W, device="cuda", generator=gen)
+        f = torch.rand(K, F, F, device="cuda", generator=gen) - 0.5
+        out = torch.empty(K, H - F + 1, W - F + 1, device="cuda")
+        t = {}
+        for rep in range(2):        # alternate, so that neither gets the warmer chip
+            for name, cfg in (("16", 0), ("4", 7)):
+                ms = _time(lambda: dconv.dconv_single_channel(x, f, out=out, variant=dconv.VARIANT_TILED_CFG0 + cfg),
+                           warm_ms=60.0, steps=30)
+                t[name] = min(ms, t.get(name, ms))
+        print(f"{H}x{W}x{K}x{F:<3d} {t['16']:8.4f} | {t['4']:8.4f} | {t['4'] / t['16']:5.3f}", flush=True)
+        del x, f, out
+        torch.cuda.empty_cache()
+
+
 def main(argv):
+    if argv == ["units"]:
+        if not torch.cuda.is_available():
+            print("tune needs a GPU", file=sys.stderr)
+            return 2
+        unit_table()
+        return 0
+    if argv == ["writeback"]:
+        if not torch.cuda.is_available():
+            print("tune needs a GPU", file=sys.stderr)
+            return 2
+        writeback_table()
+        return 0
     if len(argv) == 2 and argv[0] == "table" and argv[1] in KINDS:
         if not torch.cuda.is_available():
             print("tune needs a GPU", file=sys.stderr)
