@@ -15,8 +15,10 @@ namespace {
 // is that tile with passes of 64 instead of 128 pixels, for images 128 to 199 pixels wide, and
 // configuration 6 with passes of 32 pixels, for images 96 to 127 wide.
 // Configuration 7 is configuration 0 with a unit of one word instead of four on the way out (strip
-// reads and stores): the width-matching ablation, never chosen by shape.
-constexpr int kSingleConfigs = 8;
+// reads and stores): the width-matching ablation, never chosen by shape.  Configuration 8 is a
+// 64 x 4 tile with passes of 32 pixels, for images so small that 128-pixel tiles would leave
+// CUs without a workgroup: every wave then has half the passes in its chain of latencies.
+constexpr int kSingleConfigs = 9;
 
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
@@ -32,7 +34,12 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
-        if (s.Wo >= 96 && s.Wo < 200) {
+        if (items(128, 4) <= 320 && items(64, 4) > items(128, 4)) {
+            // so few 128-pixel tiles that CUs would stay without a workgroup (up to about 384 x 384
+            // with one filter group): 64-pixel tiles, twice the workgroups, half the passes per wave
+            // (256 x 256, 16 filters of 3 x 3: 7.1 -> 5.8 us per launch replayed from a graph)
+            cfg = 8;
+        } else if (s.Wo >= 96 && s.Wo < 200) {
             // rows too short for a 160-pixel pass to complete their ends across rows: passes of
             // 64 pixels (from 128 pixels of width on) or of 32, whichever computes fewer blocks
             // per row (1.2 to 1.7 times faster than the wider passes there)
@@ -41,8 +48,9 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
             // one filter block: the four waves of a workgroup take one row each, and on images up
             // to about 768^2 (1080p for a full block of small filters) the smallest tile is the
             // shortest chain of latencies; with passes of 64 pixels the stores of a wave begin
-            // earlier still (5 to 16 % over passes of 128)
-            cfg = 5;
+            // earlier still (5 to 16 % over passes of 128); with up to 16 filters or from 5x5 on,
+            // passes of 32 pixels are a few per cent faster again
+            cfg = (s.K <= 16 || F >= 5) ? 6 : 5;
         } else if (s.K <= 32 && F < 8 && s.Wo < 3072) {
             cfg = 0;
         } else if (F <= 4) {
@@ -69,6 +77,7 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
     case 5: return launch_cfg<F, 128, 4, 2, WS>(img, filt, out, s, st);
     case 6: return launch_cfg<F, 128, 4, 1, WS>(img, filt, out, s, st);
     case 7: return launch_cfg<F, 512, 4, 4, 3, 1, 1>(img, filt, out, s, st);
+    case 8: return launch_cfg<F, 64, 4, 1, WS>(img, filt, out, s, st);
     default: return launch_cfg<F, 512, 4, 4, 3>(img, filt, out, s, st);
     }
 }

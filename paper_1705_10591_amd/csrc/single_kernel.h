@@ -201,6 +201,7 @@ single_tiled_kernel(SingleParams p)
     auto write_back = [&](const v16f (&A)[NB], const PassOut& pd) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
+            if (kb + 8 * g >= p.K) break;        // (uniform) no filter of this group exists
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int q = 4 * g + j;
