@@ -153,7 +153,7 @@ int dconv_general_bf16(const void *in, int N, int C, int H, int W,
  * DCONV_VARIANT_TILED_CFG0 + i to force a tile configuration of the matrix-core
  * kernel, for tests and tuning (0: 64 filters x 256 pixels, 1: 128 x 512, both
  * with chunks staged through registers; 2 and 3: the same tiles staged by loads
- * that write LDS directly). */
+ * that write LDS directly; 4: 128 x 384, staged directly). */
 int dconv_general_half_v(const void *in, int N, int C, int H, int W,
                          const void *filt, int K, int F,
                          float *out, int dtype, int variant, void *stream);

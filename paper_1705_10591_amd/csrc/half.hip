@@ -64,9 +64,14 @@ int preferred_config(const Shape& s, int dtype, bool blocked)
         cus = 256;
     const int64_t px = (int64_t)s.N * s.Ho * s.Wo;
     const int64_t large = ((px + 511) / 512) * ((s.K + 127) / 128);
+    const int64_t mid = ((px + 383) / 384) * ((s.K + 127) / 128);
     const int64_t small = ((px + 255) / 256) * ((s.K + 63) / 64);
     const double large_cost = (double)((large + cus - 1) / cus) * 2.95;
+    // (the mid tile: three quarters of the large one's work at the same rate, a little more for
+    // its five operand reads per six matrix-core instructions instead of six per eight)
+    const double mid_cost = (double)((mid + cus - 1) / cus) * 2.3;
     const double small_cost = (double)((small + cus - 1) / cus);
+    if (!short_chunks && mid_cost < large_cost && mid_cost < small_cost) return 4;
     if (large_cost >= small_cost) return small_cfg;
     return short_chunks ? 1 : 3;
 }

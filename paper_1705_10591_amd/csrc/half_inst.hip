@@ -37,6 +37,7 @@ int half_launch_for_F<DCONV_F>(const void* in, const void* filt, float* out, con
     case 1: return launch_dtype<HalfTileLarge, false>(in, filt, out, s, st, dtype, blocked, dry);
     case 2: return launch_dtype<HalfTileSmall, true>(in, filt, out, s, st, dtype, blocked, dry);
     case 3: return launch_dtype<HalfTileLarge, true>(in, filt, out, s, st, dtype, blocked, dry);
+    case 4: return launch_dtype<HalfTileMid, true>(in, filt, out, s, st, dtype, blocked, dry);
     default: return DCONV_UNSUPPORTED;
     }
 }

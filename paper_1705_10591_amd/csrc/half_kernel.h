@@ -114,8 +114,12 @@ struct HalfTile {
     static constexpr int THREADS = kWave * WM * WN;
     static constexpr int MT = 32 * MW * WM, NT = 32 * NW * WN;
 };
+//   mid:   128 filters x 384 pixels, 2 x 4 waves with 2 x 3 blocks each: the large tile with a
+//          quarter fewer pixels, for shapes whose large tiles would leave a third of the CUs
+//          without one (five operand reads per six instructions)
 using HalfTileSmall = HalfTile<2, 2, 1, 4, 6>;
 using HalfTileLarge = HalfTile<2, 4, 2, 4, 4>;
+using HalfTileMid = HalfTile<2, 3, 2, 4, 4>;
 
 // RG: filter rows per chunk (the last group of a filter may be shorter).
 // DIRECT: how a chunk travels from HBM to LDS.
@@ -552,8 +556,8 @@ int half_try_launch(const void* in, const void* filt, float* out, const Shape& s
 
 // Tile configurations of the short-data-type kernel (DCONV_VARIANT_TILED_CFG0 + i forces one):
 // 0: small tile, 1: large tile, both staged through registers; 2: small tile, 3: large tile,
-// both staged directly into LDS.
-constexpr int kHalfConfigs = 4;
+// 4: mid tile, all three staged directly into LDS.
+constexpr int kHalfConfigs = 5;
 
 // Implemented once per filter side, each in its own translation unit.
 template <int F>

@@ -52,9 +52,9 @@ def _time(fn, warm_ms: float = 40.0, steps: int = 20) -> float:
 
 def _config_count(kind: str) -> int:
     # the short-data-type kernel: 64 filters x 256 pixels and 128 x 512 staged through registers,
-    # the same two staged directly into LDS
+    # the same two and 128 x 384 staged directly into LDS
     if kind.startswith("bf16"):
-        return 4
+        return 5
     # general case: configurations 0..11 (12..23 repeat them with the line-aligned write-back,
     # see `writeback`)
     return 12 if kind == "general" else dconv.tile_config_count(kind in ("single", "special"))

@@ -18,8 +18,10 @@ SIMPLE, TILED, AUTO = dconv.VARIANT_SIMPLE, dconv.VARIANT_TILED, dconv.VARIANT_A
 TORCH_TYPE = {"f16": torch.float16, "bf16": torch.bfloat16}
 # the matrix-core kernel with its tile shape forced: 64 filters x 256 pixels, 128 x 512
 # small and large tile staged through registers, small and large tile staged directly into LDS
-TILE_SMALL, TILE_LARGE, TILE_SMALL_DIRECT, TILE_LARGE_DIRECT = (dconv.VARIANT_TILED_CFG0 + i for i in range(4))
-TILES = (TILE_SMALL, TILE_LARGE, TILE_SMALL_DIRECT, TILE_LARGE_DIRECT)
+# and a mid tile, 128 x 384, staged directly
+TILE_SMALL, TILE_LARGE, TILE_SMALL_DIRECT, TILE_LARGE_DIRECT, TILE_MID_DIRECT = \
+    (dconv.VARIANT_TILED_CFG0 + i for i in range(5))
+TILES = (TILE_SMALL, TILE_LARGE, TILE_SMALL_DIRECT, TILE_LARGE_DIRECT, TILE_MID_DIRECT)
 KERNELS = [TILED, SIMPLE, *TILES]
 
 
@@ -147,7 +149,7 @@ def test_half_output_guard_bands_stay_untouched():
 
 
 @pytest.mark.parametrize("variant", [TILED, *TILES],
-                         ids=["auto", "small", "large", "small-direct", "large-direct"])
+                         ids=["auto", "small", "large", "small-direct", "large-direct", "mid-direct"])
 @pytest.mark.parametrize("kind", ["f16", "bf16"])
 @pytest.mark.parametrize("name", ["G2", "G3"])
 def test_half_config_shapes_sampled(name, kind, variant):
@@ -227,7 +229,7 @@ def test_int8_extreme_values_do_not_overflow_early():
 
 
 @pytest.mark.parametrize("variant", [TILED, *TILES],
-                         ids=["auto", "small", "large", "small-direct", "large-direct"])
+                         ids=["auto", "small", "large", "small-direct", "large-direct", "mid-direct"])
 @pytest.mark.parametrize("name", ["G2", "G3"])
 def test_int8_config_shapes_sampled(name, variant):
     w = wl.CONFIGS[name]

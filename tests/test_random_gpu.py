@@ -92,7 +92,7 @@ def test_short_data_types_random_shapes_layouts_and_configurations():
                 xd = torch.from_numpy(xs.view(np.int16)).view(tt).cuda()
                 fd = torch.from_numpy(fs.view(np.int16)).view(tt).cuda()
             fn = dconv.dconv_general_i8 if kind == "i8" else dconv.dconv_general_half
-            for v in [dconv.VARIANT_AUTO] + [dconv.VARIANT_TILED_CFG0 + i for i in range(4)]:
+            for v in [dconv.VARIANT_AUTO] + [dconv.VARIANT_TILED_CFG0 + i for i in range(5)]:
                 what = f"{kind} N,C,H,W,K,F={(N, C, H, W, K, F)} blocked={bl} variant {v:#x}"
                 print(what, flush=True)
                 try:
