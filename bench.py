@@ -69,6 +69,7 @@ def measured_peaks():
     try:
         return {"hbm_fill_gbs": val["fill, 16 B per lane"], "hbm_read_gbs": val["read, 16 B per lane"],
                 "fp32_mfma_tflops": val["no other vector instructions"],
+                "bf16_mfma_tflops": val["bf16, operands from LDS every step"],
                 "source": "paper_1705_10591_amd/hw_bench --quick, same box, before the timed runs"}
     except KeyError:
         return None
@@ -419,12 +420,20 @@ def main():
         half.append(e)
         del r
         torch.cuda.empty_cache()
+        if peaks:
+            for e in half:
+                if not e["name"].endswith("i8") and not e["name"].endswith("i8_blocked"):
+                    e["frac_bf16_mfma_measured"] = round(e["gflops"] / 1e3 / peaks["bf16_mfma_tflops"], 4)
         result["per_config_short_types"] = half
         best = max((e for e in half if e["name"].endswith("f16")), key=lambda e: e["gflops"])
         result["roofline_16bit"] = {"bound": "mfma", "kernel": best["kernel"], "workload": best["name"],
                                     "achieved": round(best["gflops"] / 1e3, 3), "peak": MFMA16_PEAK_TFLOPS,
                                     "unit": "TFLOP/s", "frac": best["frac_mfma_peak"],
-                                    "traffic": read_traffic(f"{best['kernel']}_{best['name']}")}
+                                    "traffic": read_traffic(f"{best['kernel']}_{best['name']}"),
+                                    "traffic_source": f"profiles/{best['kernel']}_{best['name']}_hbm_traffic.txt (earlier run)"}
+        if peaks:
+            result["roofline_16bit"]["peak_measured"] = peaks["bf16_mfma_tflops"]
+            result["roofline_16bit"]["frac_measured"] = round(best["gflops"] / 1e3 / peaks["bf16_mfma_tflops"], 4)
 
     if args.paper_sweep:
         sweep = []

@@ -57,7 +57,7 @@ int preferred_config(const Shape& s, int dtype, bool blocked)
     const int rg = half_row_group(s.F);
     const int chunks = s.C / (kHalfChunkBytes / elem_bytes(dtype)) * ((s.F + rg - 1) / rg);
     const bool short_chunks = rg * s.F <= 2;
-    if (s.K < 96 || chunks < 8 || (blocked && short_chunks)) return small_cfg;
+    if (s.K < 96 || chunks < 4 || (blocked && short_chunks)) return small_cfg;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
@@ -66,12 +66,14 @@ int preferred_config(const Shape& s, int dtype, bool blocked)
     const int64_t large = ((px + 511) / 512) * ((s.K + 127) / 128);
     const int64_t mid = ((px + 383) / 384) * ((s.K + 127) / 128);
     const int64_t small = ((px + 255) / 256) * ((s.K + 63) / 64);
-    const double large_cost = (double)((large + cus - 1) / cus) * 2.95;
-    // (the mid tile: three quarters of the large one's work at the same rate, a little more for
-    // its five operand reads per six matrix-core instructions instead of six per eight)
-    const double mid_cost = (double)((mid + cus - 1) / cus) * 2.3;
+    // rounds of tiles over the CUs x time per tile, in units of a small tile's time (measured over
+    // the twelve shapes of the search table in both layouts).  The mid tile does three quarters of
+    // the large one's work per chunk and has less to do before and after its chunks, which
+    // counts for more the fewer chunks a tile has; the large tile needs eight chunks to pay.
+    const double large_cost = chunks >= 8 ? (double)((large + cus - 1) / cus) * 2.95 : 1e30;
+    const double mid_cost = short_chunks ? 1e30 : (double)((mid + cus - 1) / cus) * (chunks >= 12 ? 2.45 : 2.1);
     const double small_cost = (double)((small + cus - 1) / cus);
-    if (!short_chunks && mid_cost < large_cost && mid_cost < small_cost) return 4;
+    if (mid_cost < large_cost && mid_cost < small_cost) return 4;
     if (large_cost >= small_cost) return small_cfg;
     return short_chunks ? 1 : 3;
 }

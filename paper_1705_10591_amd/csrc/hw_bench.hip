@@ -8,8 +8,11 @@
 //      v_mfma_f32_32x32x2_f32) bare and with 8, 16, 32 integer vector-ALU instructions added per
 //      four matrix-core instructions: what an ordinary vector instruction costs the matrix cores.
 //
-// `hw_bench --quick` runs only the three rates that bench.py quotes as measured achievable
-// peaks beside the published ones: fill, read, and the bare matrix-core loop.
+//   3. the bf16 matrix-core loop (v_mfma_f32_32x32x16_bf16) with operands in registers and fed
+//      from LDS, 16 bytes per lane and operand: what the chip sustains of its 16-bit peak.
+//
+// `hw_bench --quick` runs only the rates that bench.py quotes as measured achievable peaks
+// beside the published ones: fill, read, and the bare fp32 and bf16 matrix-core loops.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstring>
@@ -102,6 +105,47 @@ __global__ void __launch_bounds__(256, 2) mfma_loop(float* o, int trips) {
     o[blockIdx.x * 256 + threadIdx.x] = r;
 }
 
+// ---- 3. the 16-bit matrix-core loop ----------------------------------------------------------------
+
+typedef __bf16 v8b __attribute__((ext_vector_type(8)));
+// 2 x 2 blocks of v_mfma_f32_32x32x16_bf16 per wave; FEED: operands re-read from LDS every step
+// (16 bytes per lane and operand, the next step's requested before this step's arithmetic) or
+// kept in registers.  36 steps between barriers.
+template <bool FEED>
+__global__ void __launch_bounds__(256, 2) mfma16_loop(float* o, int trips) {
+    __shared__ __attribute__((aligned(16))) float sh[12288];
+    for (int i = threadIdx.x; i < 12288; i += 256) sh[i] = i * 0.001f;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v16f acc[4];
+    for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+    const v4f* q = reinterpret_cast<const v4f*>(sh) + lane + (wave & 1) * 64;   // 16-byte pieces
+    for (int t = 0; t < trips; ++t) {
+        v4f a0 = q[0], a1 = q[128], b0 = q[256], b1 = q[384];
+#pragma unroll
+        for (int s = 0; s < 36; ++s) {
+            v4f na0 = a0, na1 = a1, nb0 = b0, nb1 = b1;
+            if (FEED && s + 1 < 36) {
+                na0 = q[((s + 1) % 4) * 512];
+                na1 = q[((s + 1) % 4) * 512 + 128];
+                nb0 = q[((s + 1) % 4) * 512 + 256];
+                nb1 = q[((s + 1) % 4) * 512 + 384];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a0), __builtin_bit_cast(v8b, b0), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a0), __builtin_bit_cast(v8b, b1), acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a1), __builtin_bit_cast(v8b, b0), acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a1), __builtin_bit_cast(v8b, b1), acc[3], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+        }
+        __syncthreads();
+    }
+    float r = 0.f;
+    for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) r += acc[n][i];
+    o[blockIdx.x * 256 + threadIdx.x] = r;
+}
+
 template <class L>
 int time_ms(L launch, int reps, float* ms) {
     hipEvent_t a, b;
@@ -152,6 +196,15 @@ int main(int argc, char** argv) {
     const double flop = (double)blocks * 4 * trips * 36 * 4 * 4096.0;
     if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<0>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
     printf("no other vector instructions:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    {
+        printf("# bf16 matrix-core loop (v_mfma_f32_32x32x16_bf16), 2 workgroups of 4 waves per CU, 2 x 2 blocks per wave\n");
+        const int trips16 = 4000;
+        const double flop16 = (double)blocks * 4 * trips16 * 36 * 4 * 32768.0;
+        if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<false>, dim3(blocks), dim3(256), 0, 0, b, trips16); }, 2, &ms)) return 1;
+        printf("bf16, operands in registers:                %7.3f ms  %6.1f TFLOP/s\n", ms, flop16 / ms / 1e9);
+        if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<true>, dim3(blocks), dim3(256), 0, 0, b, trips16); }, 2, &ms)) return 1;
+        printf("bf16, operands from LDS every step:         %7.3f ms  %6.1f TFLOP/s\n", ms, flop16 / ms / 1e9);
+    }
     if (quick) {
         CHECK(hipFree(a));
         CHECK(hipFree(b));

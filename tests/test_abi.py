@@ -182,6 +182,6 @@ def test_hardware_rate_microbenchmark_runs():
     assert r.returncode == 0, r.stderr
     val = {m.group(1).strip(): float(m.group(2))
            for m in re.finditer(r"^([^#\n][^:]*):\s+[\d.]+ ms\s+([\d.]+) (?:GB/s|TFLOP/s)", r.stdout, re.M)}
-    assert len(val) == 11, r.stdout
+    assert len(val) == 13, r.stdout
     assert val["128 B runs, rows of 4092 floats"] < 0.8 * val["128 B runs, rows of 4096 floats"]
     assert val["+ 32 integer VALU per 4 MFMA"] < 0.8 * val["no other vector instructions"]
