@@ -10,6 +10,8 @@
 //
 //   3. the bf16 matrix-core loop (v_mfma_f32_32x32x16_bf16) with operands in registers and fed
 //      from LDS, 16 bytes per lane and operand: what the chip sustains of its 16-bit peak.
+//   4. fp32 matrix-core waves and store waves on the same SIMD: the two do not overlap -- the
+//      stores advance only in the gaps the matrix-core instruction stream leaves.
 //
 // `hw_bench --quick` runs only the rates that bench.py quotes as measured achievable peaks
 // beside the published ones: fill, read, and the bare fp32 and bf16 matrix-core loops.
@@ -146,6 +148,39 @@ __global__ void __launch_bounds__(256, 2) mfma16_loop(float* o, int trips) {
     o[blockIdx.x * 256 + threadIdx.x] = r;
 }
 
+// ---- 4. matrix cores and a store stream on the same SIMD ------------------------------------------
+
+// Eight waves per workgroup, one workgroup per CU: waves 0-3 (one per SIMD) issue fp32
+// matrix-core instructions back to back, four independent chains, with GAP idle slots of 16
+// clocks after every four; waves 4-7 (the second wave of each SIMD) store `n4` 16-byte pieces
+// from a uniform base with a constant lane offset, so that a store costs no vector-ALU
+// instruction.  mode: 1 = only the matrix-core waves work, 2 = only the store waves, 3 = both.
+template <int GAP>
+__global__ void __launch_bounds__(512, 1) mfma_and_stores(float* o, v4f* big, size_t n4, int iters, int mode) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (wave < 4) {
+        if (!(mode & 1)) return;
+        float a = lane * 0.1f, b = 1.5f;
+        v16f acc[4];
+        for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int q = 0; q < GAP; ++q) asm volatile("s_nop 15");
+#pragma unroll
+            for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[n], 0, 0, 0);
+        }
+        float r = 0.f;
+        for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) r += acc[n][i];
+        o[blockIdx.x * 256 + threadIdx.x] = r;
+    } else {
+        if (!(mode & 2)) return;
+        const int uw = __builtin_amdgcn_readfirstlane(wave);
+        const size_t stp = (size_t)gridDim.x * 4 * 64;
+        const v4f v = {1, 2, 3, 4};
+        for (size_t i = ((size_t)blockIdx.x * 4 + (uw - 4)) * 64; i + 64 <= n4; i += stp) big[i + lane] = v;
+    }
+}
+
 template <class L>
 int time_ms(L launch, int reps, float* ms) {
     hipEvent_t a, b;
@@ -196,6 +231,14 @@ int main(int argc, char** argv) {
     const double flop = (double)blocks * 4 * trips * 36 * 4 * 4096.0;
     if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<0>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
     printf("no other vector instructions:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    if (!quick) {
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<8>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    printf("+ 8 integer VALU per 4 MFMA:                %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<16>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    printf("+ 16 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<32>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    printf("+ 32 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    }
     {
         printf("# bf16 matrix-core loop (v_mfma_f32_32x32x16_bf16), 2 workgroups of 4 waves per CU, 2 x 2 blocks per wave\n");
         const int trips16 = 4000;
@@ -210,12 +253,23 @@ int main(int argc, char** argv) {
         CHECK(hipFree(b));
         return 0;
     }
-    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<8>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
-    printf("+ 8 integer VALU per 4 MFMA:                %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
-    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<16>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
-    printf("+ 16 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
-    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<32>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
-    printf("+ 32 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
+    printf("# fp32 matrix-core waves and store waves sharing every SIMD (one of each), 4 GiB stored, 12000 matrix-core instructions per wave\n");
+    {
+        const int iters = 3000;
+        for (int gap = 0; gap < 3; ++gap) {
+            float t[3];
+            for (int mode = 1; mode <= 3; ++mode) {
+                auto go = [&] {
+                    if (gap == 0) hipLaunchKernelGGL(mfma_and_stores<0>, dim3(cus), dim3(512), 0, 0, a, (v4f*)b, n16, iters, mode);
+                    else if (gap == 1) hipLaunchKernelGGL(mfma_and_stores<2>, dim3(cus), dim3(512), 0, 0, a, (v4f*)b, n16, iters, mode);
+                    else hipLaunchKernelGGL(mfma_and_stores<8>, dim3(cus), dim3(512), 0, 0, a, (v4f*)b, n16, iters, mode);
+                };
+                if (time_ms(go, 3, &t[mode - 1])) return 1;
+            }
+            printf("%3d idle clocks per 4 MFMA: matrix cores alone %6.3f ms, stores alone %6.3f ms, together %6.3f ms\n",
+                   gap == 0 ? 0 : gap == 1 ? 32 : 128, t[0], t[1], t[2]);
+        }
+    }
     CHECK(hipFree(a));
     CHECK(hipFree(b));
     return 0;

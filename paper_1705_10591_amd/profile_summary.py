@@ -25,6 +25,11 @@ def _bench_line(path):
     return json.loads(lines[-1])
 
 
+def _name(b):
+    """The workload's name as bench.py --only takes it."""
+    return b["config"]["workload"].split(":")[0]
+
+
 def _dispatches(d):
     rows = []
     for f in glob.glob(d + "/**/*kernel_trace.csv", recursive=True):
@@ -53,7 +58,7 @@ def trace(d, bench_json):
     out = [
         f"# rocprofv3 kernel trace: {r['kernel']} on workload {b['config']['workload']}",
         "# command (from /tmp, TMPDIR=/tmp): rocprofv3 --kernel-trace --stats -d <dir> --output-format csv -- "
-        f"python3 bench.py --only <workload> --steps {steps} --warmup {b['warmup']} --no-cpu-baseline",
+        f"python3 bench.py --only {_name(b)} --steps {steps} --warmup {b['warmup']} --no-cpu-baseline",
         "# summary: python -m paper_1705_10591_amd.profile_summary trace <dir> <bench.json>",
         f"# bench.py line of the same run (HIP events over the {steps} timed launches): kernel_ms={r['kernel_ms']} "
         f"value={b['value']} {b['unit']} roofline={r['bound']} achieved={r['achieved']} {r['unit']} "
@@ -66,10 +71,7 @@ def trace(d, bench_json):
         out.append(f"warm-up launches before them (not part of any figure): {len(warm)} dispatches | "
                    f"median {statistics.median(warm) / 1e3:.2f} us | max {max(warm) / 1e3:.2f} us")
     med_ms = statistics.median(timed) / 1e6
-    if r["unit"] == "GB/s":
-        ach = r["achieved"] * r["kernel_ms"] / med_ms
-    else:
-        ach = r["achieved"] * r["kernel_ms"] / med_ms
+    ach = r["achieved"] * r["kernel_ms"] / med_ms      # (the line's rate is work / kernel_ms)
     out.append(f"from the median: achieved {ach:.1f} {r['unit']} = {ach / r['peak']:.4f} of the published peak "
                f"({r['peak']} {r['unit']})")
     others = {}
@@ -95,9 +97,9 @@ def traffic(fetch_dir, write_dir, bench_json):
     out = [
         f"# HBM traffic of {r['kernel']} on workload {b['config']['workload']} from rocprofv3 counters (KiB per dispatch)",
         "# commands (from /tmp, TMPDIR=/tmp): rocprofv3 --pmc FETCH_SIZE -d <fetch dir> --output-format csv -- python3 bench.py "
-        "--only <workload> --steps 5 --warmup 2 --no-cpu-baseline --copy-calibration",
+        f"--only {_name(b)} --steps 5 --warmup 2 --no-cpu-baseline --copy-calibration",
         "#                                    rocprofv3 --pmc WRITE_SIZE -d <write dir> --output-format csv -- python3 bench.py "
-        "--only <workload> --steps 5 --warmup 2 --no-cpu-baseline --copy-calibration",
+        f"--only {_name(b)} --steps 5 --warmup 2 --no-cpu-baseline --copy-calibration",
         "# summary: python -m paper_1705_10591_amd.profile_summary traffic <fetch dir> <write dir> <bench.json>",
         "# calibration: a plain device-to-device copy of 2^28 floats (1 GiB = 1048576 KiB read, the same written), "
         "the copy kernel torch launches for Tensor.copy_",
