@@ -11,7 +11,8 @@
 //   3. the bf16 matrix-core loop (v_mfma_f32_32x32x16_bf16) with operands in registers and fed
 //      from LDS, 16 bytes per lane and operand: what the chip sustains of its 16-bit peak.
 //   4. fp32 matrix-core waves and store waves on the same SIMD: the two do not overlap -- the
-//      stores advance only in the gaps the matrix-core instruction stream leaves.
+//      stores advance only in the gaps the matrix-core instruction stream leaves -- while a
+//      wave's own stores between its own matrix-core instructions do.
 //
 // `hw_bench --quick` runs only the rates that bench.py quotes as measured achievable peaks
 // beside the published ones: fill, read, and the bare fp32 and bf16 matrix-core loops.
@@ -181,6 +182,38 @@ __global__ void __launch_bounds__(512, 1) mfma_and_stores(float* o, v4f* big, si
     }
 }
 
+// The same two streams in ONE wave per SIMD: after every four matrix-core instructions the wave
+// issues SPM of its stores.  mode as above.
+template <int SPM>
+__global__ void __launch_bounds__(256, 1) mfma_own_stores(float* o, v4f* big, size_t n4, int iters, int mode) {
+    const int lane = threadIdx.x & 63;
+    const int uw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float a = lane * 0.1f, b = 1.5f;
+    v16f acc[4];
+    for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+    const size_t stp = (size_t)gridDim.x * 4 * 64;
+    size_t i = ((size_t)blockIdx.x * 4 + uw) * 64;
+    const v4f v = {1, 2, 3, 4};
+    for (int it = 0; it < iters; ++it) {
+        if (mode & 1) {
+#pragma unroll
+            for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[n], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (mode & 2) {
+#pragma unroll
+            for (int q = 0; q < SPM; ++q) {
+                if (i + 64 <= n4) big[i + lane] = v;
+                i += stp;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float r = 0.f;
+    for (int n = 0; n < 4; ++n) for (int q = 0; q < 16; ++q) r += acc[n][q];
+    o[blockIdx.x * 256 + threadIdx.x] = r;
+}
+
 template <class L>
 int time_ms(L launch, int reps, float* ms) {
     hipEvent_t a, b;
@@ -269,6 +302,16 @@ int main(int argc, char** argv) {
             printf("%3d idle clocks per 4 MFMA: matrix cores alone %6.3f ms, stores alone %6.3f ms, together %6.3f ms\n",
                    gap == 0 ? 0 : gap == 1 ? 32 : 128, t[0], t[1], t[2]);
         }
+    }
+    printf("# the same in ONE wave per SIMD: its own stores between its matrix-core instructions, 4 GiB stored\n");
+    {
+        float t[3];
+        for (int mode = 1; mode <= 3; ++mode)
+            if (time_ms([&] { hipLaunchKernelGGL(mfma_own_stores<1>, dim3(cus), dim3(256), 0, 0, a, (v4f*)b, n16, 4096, mode); }, 3, &t[mode - 1])) return 1;
+        printf("1 store per 4 MFMA:  matrix cores alone %6.3f ms, stores alone %6.3f ms, interleaved %6.3f ms\n", t[0], t[1], t[2]);
+        for (int mode = 1; mode <= 3; ++mode)
+            if (time_ms([&] { hipLaunchKernelGGL(mfma_own_stores<2>, dim3(cus), dim3(256), 0, 0, a, (v4f*)b, n16, 2048, mode); }, 3, &t[mode - 1])) return 1;
+        printf("2 stores per 4 MFMA: matrix cores alone %6.3f ms, stores alone %6.3f ms, interleaved %6.3f ms\n", t[0], t[1], t[2]);
     }
     CHECK(hipFree(a));
     CHECK(hipFree(b));

@@ -185,3 +185,11 @@ def test_hardware_rate_microbenchmark_runs():
     assert len(val) == 13, r.stdout
     assert val["128 B runs, rows of 4092 floats"] < 0.8 * val["128 B runs, rows of 4096 floats"]
     assert val["+ 32 integer VALU per 4 MFMA"] < 0.8 * val["no other vector instructions"]
+    # matrix-core waves and store waves on one SIMD take the sum of their times; a wave's own
+    # stores between its own matrix-core instructions overlap
+    m = re.search(r"^\s*0 idle clocks per 4 MFMA: matrix cores alone\s+([\d.]+) ms, stores alone\s+([\d.]+) ms, "
+                  r"together\s+([\d.]+) ms", r.stdout, re.M)
+    assert m and float(m.group(3)) > 0.85 * (float(m.group(1)) + float(m.group(2))), r.stdout
+    m = re.search(r"^1 store per 4 MFMA:\s+matrix cores alone\s+([\d.]+) ms, stores alone\s+([\d.]+) ms, "
+                  r"interleaved\s+([\d.]+) ms", r.stdout, re.M)
+    assert m and float(m.group(3)) < 0.8 * (float(m.group(1)) + float(m.group(2))), r.stdout
