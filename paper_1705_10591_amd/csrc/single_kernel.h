@@ -289,10 +289,7 @@ single_tiled_kernel(SingleParams p)
         constexpr bool CARRY = decltype(carry_tag)::value;
         constexpr int NB0 = CARRY ? 1 : 0;
         if (CARRY) A[0] = A[NB - 1];
-#pragma unroll
-        for (int nb = NB0; nb < NB; ++nb)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) A[nb][q] = 0.f;
+        // (the other blocks start from a zero accumulator operand in step 0: no clearing)
         // pixel operands of step s; those of step s+1 are requested before the matrix-core
         // instructions of step s are issued, so the wave does not wait for LDS with the
         // matrix pipe idle
@@ -319,7 +316,7 @@ single_tiled_kernel(SingleParams p)
             if (s + 1 < S) load_b(s + 1, (s & 1) ? b0 : b1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nb = NB0; nb < NB; ++nb) A[nb] = mfma_32x32x2(a[s], b[nb], A[nb]);
+            for (int nb = NB0; nb < NB; ++nb) A[nb] = mfma_32x32x2(a[s], b[nb], s == 0 ? v16f{} : A[nb]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
