@@ -65,11 +65,12 @@ def measured_peaks():
     if r.returncode != 0:
         return None
     val = {m.group(1).strip(): float(m.group(2))
-           for m in re.finditer(r"^([^#\n][^:]*):\s+[\d.]+ ms\s+([\d.]+) (?:GB/s|TFLOP/s)", r.stdout, re.M)}
+           for m in re.finditer(r"^([^#\n][^:]*):\s+[\d.]+ ms\s+([\d.]+) (?:GB/s|TFLOP/s|TOP/s)", r.stdout, re.M)}
     try:
         return {"hbm_fill_gbs": val["fill, 16 B per lane"], "hbm_read_gbs": val["read, 16 B per lane"],
                 "fp32_mfma_tflops": val["no other vector instructions"],
                 "bf16_mfma_tflops": val["bf16, operands from LDS every step"],
+                "int8_mfma_tops": val["int8, operands from LDS every step"],
                 "source": "paper_1705_10591_amd/hw_bench --quick, same box, before the timed runs"}
     except KeyError:
         return None
@@ -422,7 +423,9 @@ def main():
         torch.cuda.empty_cache()
         if peaks:
             for e in half:
-                if not e["name"].endswith("i8") and not e["name"].endswith("i8_blocked"):
+                if e["name"].endswith("i8") or e["name"].endswith("i8_blocked"):
+                    e["frac_int8_mfma_measured"] = round(e["gflops"] / 1e3 / peaks["int8_mfma_tops"], 4)
+                else:
                     e["frac_bf16_mfma_measured"] = round(e["gflops"] / 1e3 / peaks["bf16_mfma_tflops"], 4)
         result["per_config_short_types"] = half
         best = max((e for e in half if e["name"].endswith("f16")), key=lambda e: e["gflops"])

@@ -114,7 +114,15 @@ typedef __bf16 v8b __attribute__((ext_vector_type(8)));
 // 2 x 2 blocks of v_mfma_f32_32x32x16_bf16 per wave; FEED: operands re-read from LDS every step
 // (16 bytes per lane and operand, the next step's requested before this step's arithmetic) or
 // kept in registers.  36 steps between barriers.
-template <bool FEED>
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+template <bool I8>
+__device__ __forceinline__ v16f mfma_short(v4f a, v4f b, v16f c) {
+    if (I8) return __builtin_bit_cast(v16f, __builtin_amdgcn_mfma_i32_32x32x32_i8(
+        __builtin_bit_cast(v4i, a), __builtin_bit_cast(v4i, b), __builtin_bit_cast(v16i, c), 0, 0, 0));
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
+}
+template <bool FEED, bool I8 = false>
 __global__ void __launch_bounds__(256, 2) mfma16_loop(float* o, int trips) {
     __shared__ __attribute__((aligned(16))) float sh[12288];
     for (int i = threadIdx.x; i < 12288; i += 256) sh[i] = i * 0.001f;
@@ -135,10 +143,10 @@ __global__ void __launch_bounds__(256, 2) mfma16_loop(float* o, int trips) {
                 nb1 = q[((s + 1) % 4) * 512 + 384];
             }
             __builtin_amdgcn_sched_barrier(0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a0), __builtin_bit_cast(v8b, b0), acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a0), __builtin_bit_cast(v8b, b1), acc[1], 0, 0, 0);
-            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a1), __builtin_bit_cast(v8b, b0), acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a1), __builtin_bit_cast(v8b, b1), acc[3], 0, 0, 0);
+            acc[0] = mfma_short<I8>(a0, b0, acc[0]);
+            acc[1] = mfma_short<I8>(a0, b1, acc[1]);
+            acc[2] = mfma_short<I8>(a1, b0, acc[2]);
+            acc[3] = mfma_short<I8>(a1, b1, acc[3]);
             __builtin_amdgcn_sched_barrier(0);
             a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
         }
@@ -280,6 +288,9 @@ int main(int argc, char** argv) {
         printf("bf16, operands in registers:                %7.3f ms  %6.1f TFLOP/s\n", ms, flop16 / ms / 1e9);
         if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<true>, dim3(blocks), dim3(256), 0, 0, b, trips16); }, 2, &ms)) return 1;
         printf("bf16, operands from LDS every step:         %7.3f ms  %6.1f TFLOP/s\n", ms, flop16 / ms / 1e9);
+        // (the 8-bit instruction does twice the operations per instruction)
+        if (time_ms([&] { hipLaunchKernelGGL((mfma16_loop<true, true>), dim3(blocks), dim3(256), 0, 0, b, trips16); }, 2, &ms)) return 1;
+        printf("int8, operands from LDS every step:         %7.3f ms  %6.1f TOP/s\n", ms, 2.0 * flop16 / ms / 1e9);
     }
     if (quick) {
         CHECK(hipFree(a));
