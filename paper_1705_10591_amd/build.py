@@ -55,13 +55,21 @@ def build(verbose: bool = False) -> Path:
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr[-4000:]}")
     os.replace(tmp, LIB)
+    # The microbenchmarks are no part of the library: bench.py quotes hw_bench's rates as measured
+    # peaks when it is there, and the tests that run them skip when they are not.  A failure to
+    # build one is reported and does not fail the library's build.
+    built = []
     for exe in (LDS_BENCH, HW_BENCH):
         cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], str(CSRC / (exe.name + ".hip")), "-o", str(exe)]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed for {exe.name}.hip:\n{r.stderr[-4000:]}")
+            exe.unlink(missing_ok=True)
+            print(f"warning: hipcc failed for {exe.name}.hip (the library is built):\n{r.stderr[-2000:]}",
+                  file=sys.stderr)
+        else:
+            built.append(exe.name)
     if verbose:
-        print(f"built {LIB}, {LDS_BENCH.name} and {HW_BENCH.name}")
+        print(f"built {LIB}" + "".join(f", {n}" for n in built))
     return LIB
 
 
