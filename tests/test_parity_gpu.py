@@ -148,6 +148,43 @@ def test_general_every_tile_configuration(shape):
         np.testing.assert_array_equal(run_general(xi, fi, variant), o32)
 
 
+# shapes for the line-aligned write-back of the general kernel (tile configurations 12 to 23): maps
+# smaller than a line (direct stores instead), tiles that span two and three images (a segment
+# per image), column strips (a segment per strip row), filter counts that leave groups of eight
+# incomplete, one output row
+ALIGNED_SHAPES = [(6, 4, 7, 7, 20, 3), (5, 8, 16, 16, 37, 3), (9, 4, 14, 14, 70, 3), (2, 3, 30, 300, 13, 5),
+                  (1, 8, 12, 500, 64, 3), (3, 16, 3, 90, 65, 3), (2, 2, 40, 41, 130, 11), (4, 16, 20, 20, 9, 1)]
+
+
+@pytest.mark.parametrize("shape", ALIGNED_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_general_line_aligned_write_back(shape):
+    """Whole tiles and tiles shared between workgroups, every tile shape, into an output buffer
+    that starts mid-line between NaN guard bands; integer inputs bit for bit."""
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(1300 + C + K, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    xi, fi = wl.integer_case(1350 + C + K, N, C, H, W, K, F)
+    _, _, o32, _ = oracle.general(xi, fi, want32=True)
+    Ho, Wo = H - F + 1, W - F + 1
+    n_out, guard = N * K * Ho * Wo, 77
+    xd, fd, xid, fid = dev(x), dev(f), dev(xi), dev(fi)
+    for schedule in (0, 2, 3):
+        for tile in range(3):
+            variant = dconv.VARIANT_TILED_CFG0 + 12 + 3 * schedule + tile
+            buf = torch.full((n_out + 2 * guard,), float("nan"), device="cuda")
+            out = buf[guard:guard + n_out].view(N, K, Ho, Wo)
+            print(f"aligned write-back {shape} variant {variant:#x}", flush=True)
+            dconv.dconv_general(xd, fd, out=out, variant=variant)
+            torch.cuda.synchronize()
+            host = buf.cpu().numpy()
+            assert np.isnan(host[:guard]).all() and np.isnan(host[guard + n_out:]).all(), "guard bands touched"
+            assert_within_bound(host[guard:guard + n_out].reshape(N, K, Ho, Wo), acc, mag,
+                                f"aligned write-back {shape} variant {variant:#x}")
+            got = dconv.dconv_general(xid, fid, variant=variant)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(got.cpu().numpy(), o32)
+
+
 @pytest.mark.parametrize("shape", [(9, 24, 9, 35, 96, 3), (4, 64, 28, 28, 128, 3)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_general_shared_tiles_repeat_exactly(shape):
