@@ -17,6 +17,7 @@
 // `hw_bench --quick` runs only the rates that bench.py quotes as measured achievable peaks
 // beside the published ones: fill, read, and the bare fp32 and bf16 matrix-core loops.
 #include <hip/hip_runtime.h>
+#include <string>
 #include <cstdio>
 #include <cstring>
 
@@ -66,11 +67,27 @@ __global__ void store_runs(float* o, int w, int rows) {
 
 // ---- 2. matrix cores next to vector-ALU work ----------------------------------------------------
 
+// What the LDS operands of the matrix-core loops hold.  0: a ramp (neighbouring words differ in
+// a few low bits), 1: zeros, 2: pseudo-random bits in sign and mantissa, exponents of about one
+// (as fp32 words; as pairs of bf16 values in the 16-bit loop).  The instruction stream is the
+// same for all three; how fast it runs is not (section 5).
+__device__ __forceinline__ float operand_word(int i, int fill, bool halves) {
+    if (fill == 0) return i * 0.001f;
+    if (fill == 1) return 0.f;
+    unsigned x = (unsigned)i * 2654435761u;
+    x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
+    if (halves) {
+        const unsigned lo = 0x3F80u | (x & 0x807Fu), hi = 0x3F80u | ((x >> 16) & 0x807Fu);
+        return __uint_as_float((hi << 16) | lo);
+    }
+    return __uint_as_float(0x3F800000u | (x & 0x807FFFFFu));
+}
+
 // NV integer vector instructions per four matrix-core instructions; 36 steps between barriers.
 template <int NV>
-__global__ void __launch_bounds__(256, 2) mfma_loop(float* o, int trips) {
+__global__ void __launch_bounds__(256, 2) mfma_loop(float* o, int trips, int fill) {
     __shared__ float sh[12288];
-    for (int i = threadIdx.x; i < 12288; i += 256) sh[i] = i * 0.001f;
+    for (int i = threadIdx.x; i < 12288; i += 256) sh[i] = operand_word(i, fill, false);
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int busy[8];
@@ -123,9 +140,9 @@ __device__ __forceinline__ v16f mfma_short(v4f a, v4f b, v16f c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
 }
 template <bool FEED, bool I8 = false>
-__global__ void __launch_bounds__(256, 2) mfma16_loop(float* o, int trips) {
+__global__ void __launch_bounds__(256, 2) mfma16_loop(float* o, int trips, int fill) {
     __shared__ __attribute__((aligned(16))) float sh[12288];
-    for (int i = threadIdx.x; i < 12288; i += 256) sh[i] = i * 0.001f;
+    for (int i = threadIdx.x; i < 12288; i += 256) sh[i] = operand_word(i, fill, !I8);
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     v16f acc[4];
@@ -270,26 +287,26 @@ int main(int argc, char** argv) {
     printf("# fp32 matrix-core loop fed from LDS, 2 workgroups of 4 waves per CU, 36 steps per barrier\n");
     const int blocks = 2 * cus, trips = 2000;
     const double flop = (double)blocks * 4 * trips * 36 * 4 * 4096.0;
-    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<0>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<0>, dim3(blocks), dim3(256), 0, 0, b, trips, 0); }, 2, &ms)) return 1;
     printf("no other vector instructions:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
     if (!quick) {
-    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<8>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<8>, dim3(blocks), dim3(256), 0, 0, b, trips, 0); }, 2, &ms)) return 1;
     printf("+ 8 integer VALU per 4 MFMA:                %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
-    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<16>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<16>, dim3(blocks), dim3(256), 0, 0, b, trips, 0); }, 2, &ms)) return 1;
     printf("+ 16 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
-    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<32>, dim3(blocks), dim3(256), 0, 0, b, trips); }, 2, &ms)) return 1;
+    if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<32>, dim3(blocks), dim3(256), 0, 0, b, trips, 0); }, 2, &ms)) return 1;
     printf("+ 32 integer VALU per 4 MFMA:               %7.3f ms  %6.1f TFLOP/s\n", ms, flop / ms / 1e9);
     }
     {
         printf("# bf16 matrix-core loop (v_mfma_f32_32x32x16_bf16), 2 workgroups of 4 waves per CU, 2 x 2 blocks per wave\n");
         const int trips16 = 4000;
         const double flop16 = (double)blocks * 4 * trips16 * 36 * 4 * 32768.0;
-        if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<false>, dim3(blocks), dim3(256), 0, 0, b, trips16); }, 2, &ms)) return 1;
+        if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<false>, dim3(blocks), dim3(256), 0, 0, b, trips16, 0); }, 2, &ms)) return 1;
         printf("bf16, operands in registers:                %7.3f ms  %6.1f TFLOP/s\n", ms, flop16 / ms / 1e9);
-        if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<true>, dim3(blocks), dim3(256), 0, 0, b, trips16); }, 2, &ms)) return 1;
+        if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<true>, dim3(blocks), dim3(256), 0, 0, b, trips16, 0); }, 2, &ms)) return 1;
         printf("bf16, operands from LDS every step:         %7.3f ms  %6.1f TFLOP/s\n", ms, flop16 / ms / 1e9);
         // (the 8-bit instruction does twice the operations per instruction)
-        if (time_ms([&] { hipLaunchKernelGGL((mfma16_loop<true, true>), dim3(blocks), dim3(256), 0, 0, b, trips16); }, 2, &ms)) return 1;
+        if (time_ms([&] { hipLaunchKernelGGL((mfma16_loop<true, true>), dim3(blocks), dim3(256), 0, 0, b, trips16, 0); }, 2, &ms)) return 1;
         printf("int8, operands from LDS every step:         %7.3f ms  %6.1f TOP/s\n", ms, 2.0 * flop16 / ms / 1e9);
     }
     if (quick) {
@@ -323,6 +340,23 @@ int main(int argc, char** argv) {
         for (int mode = 1; mode <= 3; ++mode)
             if (time_ms([&] { hipLaunchKernelGGL(mfma_own_stores<2>, dim3(cus), dim3(256), 0, 0, a, (v4f*)b, n16, 2048, mode); }, 3, &t[mode - 1])) return 1;
         printf("2 stores per 4 MFMA: matrix cores alone %6.3f ms, stores alone %6.3f ms, interleaved %6.3f ms\n", t[0], t[1], t[2]);
+    }
+    {
+        // 5. the same matrix-core loops on other operand VALUES: the chip's clock is managed by
+        // power, and what a multiplier array draws depends on the bits it is fed.  Ten launches
+        // each (some 150 ms), so that the clock has settled.
+        printf("# the matrix-core loops of sections 2 and 3 by what their operands hold (same instructions; 10 launches each)\n");
+        const int trips16 = 4000;
+        const double flop16 = (double)blocks * 4 * trips16 * 36 * 4 * 32768.0;
+        const char* names[3] = {"a ramp", "zeros", "random bits"};
+        for (int fill = 1; fill <= 2; ++fill) {
+            if (time_ms([&] { hipLaunchKernelGGL(mfma_loop<0>, dim3(blocks), dim3(256), 0, 0, b, trips, fill); }, 10, &ms)) return 1;
+            printf("fp32 loop, operands %-12s           %7.3f ms  %6.1f TFLOP/s\n", (std::string(names[fill]) + ":").c_str(), ms, flop / ms / 1e9);
+        }
+        for (int fill = 1; fill <= 2; ++fill) {
+            if (time_ms([&] { hipLaunchKernelGGL(mfma16_loop<true>, dim3(blocks), dim3(256), 0, 0, b, trips16, fill); }, 10, &ms)) return 1;
+            printf("bf16 loop, operands %-12s           %7.3f ms  %6.1f TFLOP/s\n", (std::string(names[fill]) + ":").c_str(), ms, flop16 / ms / 1e9);
+        }
     }
     CHECK(hipFree(a));
     CHECK(hipFree(b));

@@ -21,6 +21,9 @@ that the rules can be checked or re-derived on another chip.
     python -m paper_1705_10591_amd.tune writeback                 (general case: stores straight from the
                                                                    accumulators against the line-aligned
                                                                    write-back through LDS, per tile shape)
+    python -m paper_1705_10591_amd.tune operands                  (the benchmark shapes on random inputs against
+                                                                   the same launches on an input of zeros: what
+                                                                   the chip's power management takes)
 """
 from __future__ import annotations
 
@@ -206,7 +209,57 @@ def unit_table() -> None:
         torch.cuda.empty_cache()
 
 
+def operand_table() -> None:
+    """The same launch on an input of zeros: instructions, addresses and memory traffic are those of
+    the random input, what the matrix cores and the memory draw is not, and the clock follows."""
+    print("# milliseconds per launch, random filters: random input | input of zeros | ratio")
+    rows = [("S2 F=%d" % F, (4096, 4096, 64, F)) for F in (3, 5, 7, 9, 11)]
+    rows += [("G1", (64, 3, 224, 224, 64, 11)), ("G2", (32, 64, 56, 56, 64, 3)), ("G3", (32, 256, 28, 28, 512, 3)),
+             ("G3 bf16", (32, 256, 28, 28, 512, 3)), ("G3 int8", (32, 256, 28, 28, 512, 3))]
+    for name, sh in rows:
+        gen = torch.Generator(device="cuda").manual_seed(1705)
+        if len(sh) == 4:
+            H, W, K, F = sh
+            xs = [torch.rand(H, W, device="cuda", generator=gen), torch.zeros(H, W, device="cuda")]
+            f = torch.rand(K, F, F, device="cuda", generator=gen) - 0.5
+            out = torch.empty(K, H - F + 1, W - F + 1, device="cuda")
+            call = lambda x: dconv.dconv_single_channel(x, f, out=out)
+        else:
+            N, C, H, W, K, F = sh
+            if name.endswith("bf16") or name.endswith("int8"):
+                if name.endswith("bf16"):
+                    x = (torch.rand(N, H, W, C, device="cuda", generator=gen) - 0.5).to(torch.bfloat16)
+                    f = (torch.rand(K, F, F, C, device="cuda", generator=gen) - 0.5).to(torch.bfloat16)
+                    out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda")
+                    call = lambda x: dconv.dconv_general_half(x, f, out=out)
+                else:
+                    x = torch.randint(-128, 128, (N, H, W, C), device="cuda", generator=gen, dtype=torch.int8)
+                    f = torch.randint(-128, 128, (K, F, F, C), device="cuda", generator=gen, dtype=torch.int8)
+                    out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda", dtype=torch.int32)
+                    call = lambda x: dconv.dconv_general_i8(x, f, out=out)
+                xs = [x, torch.zeros_like(x)]
+            else:
+                xs = [torch.rand(N, C, H, W, device="cuda", generator=gen), torch.zeros(N, C, H, W, device="cuda")]
+                f = (torch.rand(K, C, F, F, device="cuda", generator=gen) - 0.5) * 0.1
+                out = torch.empty(N, K, H - F + 1, W - F + 1, device="cuda")
+                call = lambda x: dconv.dconv_general(x, f, out=out)
+        t = [None, None]
+        for rep in range(2):        # alternate, so that neither gets the warmer chip
+            for i in (0, 1):
+                ms = _time(lambda: call(xs[i]), warm_ms=80.0, steps=30)
+                t[i] = ms if t[i] is None else min(t[i], ms)
+        print(f"{name:10s} {t[0]:8.4f} | {t[1]:8.4f} | {t[0] / t[1]:5.3f}", flush=True)
+        del xs, f, out
+        torch.cuda.empty_cache()
+
+
 def main(argv):
+    if argv == ["operands"]:
+        if not torch.cuda.is_available():
+            print("tune needs a GPU", file=sys.stderr)
+            return 2
+        operand_table()
+        return 0
     if argv == ["units"]:
         if not torch.cuda.is_available():
             print("tune needs a GPU", file=sys.stderr)
