@@ -67,6 +67,7 @@ int general_tile_configs();
 int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st);
 bool single_few_supports(const Shape& s);      // the few-filters kernel can run the shape
 bool single_few_preferred(const Shape& s);     // ... and is the better choice for it
+bool single_blocks16_preferred(const Shape& s);   // up to 16 filters: matrix-core blocks of 16 filters are the better choice
 bool single_tiled_supports(const Shape& s);
 bool single_batch_preferred(const Shape& s);   // dconv_general with up to four channels: the special-case kernel is the better choice
 bool general_tiled_supports(const Shape& s);

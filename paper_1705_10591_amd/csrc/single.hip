@@ -18,7 +18,10 @@ namespace {
 // reads and stores): the width-matching ablation, never chosen by shape.  Configuration 8 is a
 // 64 x 4 tile with passes of 32 pixels, for images so small that 128-pixel tiles would leave
 // CUs without a workgroup: every wave then has half the passes in its chain of latencies.
-constexpr int kSingleConfigs = 9;
+// Configurations 9 and 10 compute with matrix-core blocks of 16 filters (v_mfma_f32_16x16x4_f32)
+// instead of 32, on 512 x 4 tiles and on 128 x 4 tiles with passes of 32 pixels: for up to 16
+// filters (single_blocks16_preferred below).
+constexpr int kSingleConfigs = 11;
 
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
@@ -34,7 +37,12 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
-        if (items(128, 4) <= 320 && items(64, 4) > items(128, 4)) {
+        if (single_blocks16_preferred(s)) {
+            // (the small tile with short passes for 3x3 on mid-sized images, as for 32-filter
+            // blocks, and where 512-pixel tile columns would overhang the image by 15 % or more)
+            const bool overhang = (int64_t)((s.Wo + 511) / 512) * 512 * 100 >= (int64_t)s.Wo * 115;
+            cfg = ((s.F == 3 && (int64_t)s.Ho * s.Wo < 3000000) || overhang) ? 10 : 9;
+        } else if (items(128, 4) <= 320 && items(64, 4) > items(128, 4)) {
             // so few 128-pixel tiles that CUs would stay without a workgroup (up to about 384 x 384
             // with one filter group): 64-pixel tiles, twice the workgroups, half the passes per wave
             // (256 x 256, 16 filters of 3 x 3: 7.1 -> 5.8 us per launch replayed from a graph)
@@ -78,11 +86,41 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
     case 6: return launch_cfg<F, 128, 4, 1, WS>(img, filt, out, s, st);
     case 7: return launch_cfg<F, 512, 4, 4, 3, 1, 1>(img, filt, out, s, st);
     case 8: return launch_cfg<F, 64, 4, 1, WS>(img, filt, out, s, st);
+    case 9: return launch_cfg<F, 512, 4, 4, 3, 1, 4, 16>(img, filt, out, s, st);
+    case 10: return launch_cfg<F, 128, 4, 1, 3, 1, 4, 16>(img, filt, out, s, st);
     default: return launch_cfg<F, 512, 4, 4, 3>(img, filt, out, s, st);
     }
 }
 
 }  // namespace
+
+// Five to sixteen filters on one image (paper Sec. 5.1: few filters are the method's weak spot).
+// A 32-filter matrix-core block would be half padding or more, and the vector-ALU kernel
+// (single_fewfilters.hip) computes filter by filter, its time growing with K * F * F, on units
+// of half the matrix cores' rate, and does not write whole lines.  Configurations 9 and 10
+// compute with 16-filter blocks.  Measured on 720 x 1280 .. 4096 x 4096 images, 5 to 16 filters,
+// 3x3 .. 7x7, against the better of the other two:
+//  * 13 to 16 filters: 5-30 % faster throughout (the vector-ALU kernel is out of its range),
+//    except 3x3 filters on 2048 x 2048, where the 32-filter blocks are 4 % ahead;
+//  * 8 to 12 filters of 3x3: faster (5-25 %) only where the output outgrows the memory-side
+//    cache and the vector-ALU kernel's misaligned rows cost, or where that kernel has too few
+//    tiles to be chosen; 4x4: 5-30 % faster throughout;
+//  * from 5x5 on, 7 to 12 filters: faster (15-25 %) where the vector-ALU kernel's 256 x 32 tiles
+//    do not cover the chip twice (up to about 1536 x 1536), slower beyond; 5 and 6 filters only
+//    where that kernel is not chosen at all.
+bool single_blocks16_preferred(const Shape& s)
+{
+    if (s.C != 1 || s.N != 1 || s.K > 16 || s.K < 5 || s.F < 3 || s.F > 11 || s.Wo < 256) return false;
+    const int64_t px = (int64_t)s.Ho * s.Wo;
+    if (px < 500000 || px >= (1LL << 29)) return false;
+    if (s.K > 12) return s.F > 3 || px < 3000000 || px * s.K >= 70000000LL;
+    const bool few = single_few_preferred(s);
+    if (s.F == 3) return s.K >= 8 && (px * s.K >= 70000000LL || !few);
+    if (s.F == 4) return s.K >= 8;
+    if (s.K <= 6) return !few;
+    const int64_t few_tiles = (int64_t)((s.Wo + 255) / 256) * ((s.Ho + 31) / 32);
+    return few_tiles < 400 || !few;
+}
 
 bool single_tiled_supports(const Shape& s)
 {

@@ -71,24 +71,33 @@ enum : int { kPlain = 0, kTail = 1, kEdge = 2 };
 // UNIT: words a lane moves per instruction on the way out (strip read and store): 4 (16 bytes),
 // or 1 for the ablation of the paper's width-matching experiment (Sec. 5.1: the unit a thread
 // reads from on-chip memory against the width the hardware serves best).
-template <int F, int TW, int TR, int NBW, int WPE, int C = 1, int UNIT = 4>
+// FB: filters of a matrix-core block.  32: v_mfma_f32_32x32x2_f32, 32 filters x 32 pixels, two
+// taps per instruction.  16: v_mfma_f32_16x16x4_f32, 16 filters x 16 pixels, four taps per
+// instruction: with up to 16 filters (the paper's weak spot, Sec. 5.1) half of a 32-filter block
+// would be padding, and from 5x5 filters on that padding bounds the time.
+template <int F, int TW, int TR, int NBW, int WPE, int C = 1, int UNIT = 4, int FB = 32>
 __global__ void __launch_bounds__(kThreads, WPE)
 single_tiled_kernel(SingleParams p)
 {
+    static_assert(FB == 32 || (FB == 16 && UNIT == 4), "filter blocks of 32 or 16");
     constexpr int FF = F * F;
     constexpr int T = C * FF;                   // taps: (channel, filter row, filter column)
-    constexpr int TP = T + (T & 1);
-    constexpr int S = TP / 2;                   // matrix-core steps per 32x32 block
+    constexpr int TPM = FB == 32 ? 2 : 4;       // taps per matrix-core instruction
+    constexpr int S = (T + TPM - 1) / TPM;      // matrix-core steps per block
+    constexpr int BW = FB == 32 ? 32 : 16;      // pixels of a block
     constexpr int PC0 = TW + 32 + F - 1;        // first column of the next-row patch
     constexpr int PW = 32 + F - 1;              // its width: the head of the next row
     constexpr int LS = PC0 + PW;                // LDS row stride of the image tile
     constexpr int ROWS = TR + F - 1;            // staged image rows per channel; after the last
                                                 // channel one more row, of zeros, follows
     constexpr int CHS = ROWS * LS;              // LDS words of one channel of the tile
-    constexpr int NB = NBW + 1;                 // blocks computed per pass
+    constexpr int NBP = NBW + 1;                // 32-pixel columns computed per pass
+    constexpr int NB = 32 * NBP / BW;           // blocks computed per pass
+    constexpr int CB = 32 / BW;                 // blocks a pass takes over from the one before
+    using acc_t = typename std::conditional<FB == 32, v16f, v4f>::type;
     constexpr int PASS = 32 * NBW;              // pixels written per pass
     constexpr int CHUNKS = TW / PASS;
-    constexpr int SW = 32 * NB + 32;            // row stride of the write-back strip
+    constexpr int SW = 32 * NBP + 32;           // row stride of the write-back strip
     constexpr int LPR = PASS / 4;               // lanes that cover one filter's window, 16 B each
     constexpr int RPI = kWave / LPR;            // filter rows stored per instruction
     constexpr int ITS = 8 / RPI;                // store instructions per group of 8 filters
@@ -103,7 +112,13 @@ single_tiled_kernel(SingleParams p)
     const int lane = tid & 63;
     // uniform: lets wave-level index math run on the scalar unit
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // 32-filter blocks: lane half h takes the odd tap of a pair, lane l32 one filter / pixel.
+    // 16-filter blocks: lane quarter q4 takes one tap of four, lane l16 one filter / pixel; of
+    // its quarter's four filters, hh says whether they are the lower or upper four of a group
+    // of eight.  (The write-back below is written once, in terms of hh and lp.)
     const int h = lane >> 5, l32 = lane & 31;
+    const int q4 = lane >> 4, l16 = lane & 15;
+    const int hh = FB == 32 ? h : (q4 & 1), lp = FB == 32 ? l32 : l16;
     float* stg = sh + IMG_WORDS + wave * (8 * SW);
 
     // Workgroups are handed to the 8 XCDs round-robin by their linear id.  Give each XCD one
@@ -126,10 +141,10 @@ single_tiled_kernel(SingleParams p)
     // ---- this wave's filter operands: a[s] = filt[k][tap 2s + h], zero beyond K / F*F --
     float a[S];
     {
-        const int k = fb * 32 + l32;
+        const int k = fb * FB + lp;
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            const int t = 2 * s + h;
+            const int t = FB == 32 ? 2 * s + h : 4 * s + q4;
             a[s] = (k < p.K && t < T) ? p.filt[(int64_t)k * T + t] : 0.f;
         }
     }
@@ -172,16 +187,30 @@ single_tiled_kernel(SingleParams p)
     const int rows_here = min(TR, p.Ho - y0);
     const int dY = h * (LS - (F - 1));          // second tap of a pair sits on the next row
     const int dZ = h * (CHS - (F - 1) * LS - (F - 1));    // ... or is the first tap of the next channel
-    const int kb = fb * 32;
-    const bool full_block = kb + 32 <= p.K;
+    const int kb = fb * FB;
+    // The write-back goes by groups of eight filters and skips the groups beyond K, so windows
+    // can be stored without a test per filter wherever the block's filters fill whole groups.
+    const bool whole_groups = kb + FB <= p.K || (p.K - kb) % 8 == 0;
     const int rrow = lane / LPR, c4 = lane % LPR;          // read phase: strip row and 16 B column
     const int rdofs = rrow * SW + 32 + 4 * c4;
     // The shift of filter k in output row y is s = -(k*pm + c0(y)) mod 32.  k*pm is split into
     // a per-lane part (one register) and a wave-uniform part per accumulator register / store.
-    const int wl = 4 * h * SW + 32 + l32;                  // strip word of (q % 4 == 0, block 0, s = 0)
-    const int tw_lane = (kb + 4 * h) * pm;
+    const int wl = 4 * hh * SW + 32 + lp;                  // strip word of (q % 4 == 0, block 0, s = 0)
+    const int tw_lane = (kb + 4 * hh) * pm;
     const unsigned gl = (unsigned)(rrow * (int)plane + 4 * c4);
     const int tr_lane = (kb + rrow) * pm;
+
+    // sixteen-filter blocks: where tap 4s + q4 lies in the tile, from the lane's pixel
+    int toff[FB == 16 ? S : 1];
+    if (FB == 16) {
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const int t = min(4 * s + q4, T - 1);
+            const int tc = t / FF, i = (t % FF) / F, j = t % F;
+            toff[s] = tc * CHS + i * LS + j;
+        }
+    }
+    bool contiguous = true;                // (per pass) the pass's pixels lie side by side in LDS
 
     // ---- the write-back of one pass ---------------------------------------------------------
     // Per group g of eight filters: park one accumulator register of every block in the strip
@@ -198,20 +227,23 @@ single_tiled_kernel(SingleParams p)
     auto store4 = [&](float* dst, const v4f& v) {
         __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(dst));
     };
-    auto write_back = [&](const v16f (&A)[NB], const PassOut& pd) {
+    auto write_back = [&](const acc_t (&A)[NB], const PassOut& pd) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
+        for (int g = 0; g < FB / 8; ++g) {
             if (kb + 8 * g >= p.K) break;        // (uniform) no filter of this group exists
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int q = 4 * g + j;
+                // the accumulator register that holds filter 8g + 4hh + j of the block: with
+                // 32-filter blocks in every lane, with 16-filter blocks in lane half g
+                const int q = FB == 32 ? 4 * g + j : j;
                 const int sk = (-(pd.tw + (8 * g + j) * pm)) & 31;
                 // the strip word as one opaque register: the stores then pair up with offsets of
                 // 0..4 blocks and need no further address arithmetic on the vector ALU
                 int word = (int)(stg - sh) + (wl - sk) + j * SW;
                 asm volatile("" : "+v"(word));
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) sh[word + nb * 32] = A[nb][q];
+                for (int nb = 0; nb < NB; ++nb)
+                    if (FB == 32 || h == g) sh[word + nb * BW] = A[nb][q];
             }
             if constexpr (UNIT == 1) {
                 // One word per lane: a wave instruction reads 64 pixels of one filter row from the
@@ -285,10 +317,50 @@ single_tiled_kernel(SingleParams p)
     // ---- the matrix-core steps of one pass ---------------------------------------------------
     // Block 0 of a pass covers the same 32 pixels as block NB-1 of the pass before it on the
     // same row; when CARRY is set those sums are taken over instead of being formed again.
-    auto compute = [&](auto carry_tag, v16f (&A)[NB], const int (&base)[NB]) {
+    auto compute = [&](auto carry_tag, acc_t (&A)[NB], const int (&base)[NB]) {
         constexpr bool CARRY = decltype(carry_tag)::value;
-        constexpr int NB0 = CARRY ? 1 : 0;
-        if (CARRY) A[0] = A[NB - 1];
+        constexpr int NB0 = CARRY ? CB : 0;
+        if (CARRY) {
+#pragma unroll
+            for (int nb = 0; nb < CB; ++nb) A[nb] = A[NB - CB + nb];
+        }
+        if constexpr (FB == 16) {
+            // Sixteen-filter blocks: lane quarter q4 brings tap 4s + q4 of step s, whose place in
+            // the tile (toff) differs from lane to lane, so it cannot be an immediate; where the
+            // pass's pixels are contiguous in LDS (every pass but the one that runs over the row
+            // end into the next row's head), one addition per step gives the address of block 0
+            // and the other blocks follow at immediate offsets.  A pad tap (beyond the last
+            // one) reads the row of zeros; its weight is zero as well.
+            auto load_b = [&](int s, float (&b)[NB]) {
+                const bool pad = 4 * s + q4 >= T;                    // (only in the last step)
+                if (contiguous) {
+                    int addr = base[0] + toff[s];
+                    if (4 * s + 3 >= T) addr = pad ? C * ROWS * LS + l16 : addr;
+#pragma unroll
+                    for (int nb = NB0; nb < NB; ++nb) b[nb] = sh[addr + nb * 16];
+                } else {
+#pragma unroll
+                    for (int nb = NB0; nb < NB; ++nb) {
+                        int addr = base[nb] + toff[s];
+                        if (4 * s + 3 >= T) addr = pad ? C * ROWS * LS + l16 : addr;
+                        b[nb] = sh[addr];
+                    }
+                }
+            };
+            float b0[NB], b1[NB];
+            load_b(0, b0);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                float (&b)[NB] = (s & 1) ? b1 : b0;
+                if (s + 1 < S) load_b(s + 1, (s & 1) ? b0 : b1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int nb = NB0; nb < NB; ++nb)
+                    A[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[nb], s == 0 ? v4f{} : A[nb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            return;
+        }
         // (the other blocks start from a zero accumulator operand in step 0: no clearing)
         // pixel operands of step s; those of step s+1 are requested before the matrix-core
         // instructions of step s are issued, so the wave does not wait for LDS with the
@@ -316,7 +388,9 @@ single_tiled_kernel(SingleParams p)
             if (s + 1 < S) load_b(s + 1, (s & 1) ? b0 : b1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nb = NB0; nb < NB; ++nb) A[nb] = mfma_32x32x2(a[s], b[nb], s == 0 ? v16f{} : A[nb]);
+            for (int nb = NB0; nb < NB; ++nb) {
+                if constexpr (FB == 32) A[nb] = mfma_32x32x2(a[s], b[nb], s == 0 ? v16f{} : A[nb]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -326,7 +400,7 @@ single_tiled_kernel(SingleParams p)
     const int rows_mine = rows_here > row_start ? (rows_here - row_start + row_step - 1) / row_step : 0;
     const int npass = rows_mine * ch_mine;
 
-    v16f acc[NB];
+    acc_t acc[NB];
     int ri = 0, ci = 0;                    // row and chunk counters of the next pass
 #pragma unroll 1
     for (int q = 0; q < npass; ++q) {
@@ -343,14 +417,15 @@ single_tiled_kernel(SingleParams p)
         int base[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            const int x = X + nb * 32 + l32;
+            const int x = X + nb * BW + lp;
             // lanes beyond the row end compute the head of the next row from the patch
             base[nb] = r * LS + ((wrap_tile && x >= p.Wo) ? PC0 + min(x - p.Wo, 31) : x - x0);
         }
         const bool reaches_end = X + 32 + PASS > p.Wo;                // a window may cross Wo
-        const bool needs_head = X == 0 && (y == 0 || !p.wrap || !full_block);
+        contiguous = !(wrap_tile && reaches_end);                     // no lane reads the next row's head
+        const bool needs_head = X == 0 && (y == 0 || !p.wrap || !whole_groups);
         int kind = kPlain;
-        if (!full_block || needs_head) kind = kEdge;
+        if (!whole_groups || needs_head) kind = kEdge;
         else if (reaches_end) kind = (p.wrap && y < p.Ho - 1) ? kTail : kEdge;
         // every pass but the first of a row continues the previous pass of this wave
         if (ch > 0) compute(std::true_type{}, acc, base);
@@ -361,7 +436,7 @@ single_tiled_kernel(SingleParams p)
     }
 }
 
-template <int F, int TW, int TR, int NBW, int WPE, int C = 1, int UNIT = 4>
+template <int F, int TW, int TR, int NBW, int WPE, int C = 1, int UNIT = 4, int FB = 32>
 int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)
 {
     if (s.C != C) return DCONV_UNSUPPORTED;
@@ -371,7 +446,7 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     p.H = s.H; p.W = s.W; p.K = s.K; p.Ho = s.Ho; p.Wo = s.Wo;
     p.tiles_x = (s.Wo + TW - 1) / TW;
     p.tiles_y = (s.Ho + TR - 1) / TR;
-    const int fblocks = (s.K + 31) / 32;
+    const int fblocks = (s.K + FB - 1) / FB;
     p.fbw = fblocks >= 4 ? 4 : fblocks >= 2 ? 2 : 1;
     p.fgroups = (fblocks + p.fbw - 1) / p.fbw;
     // Completing row ends with the next row's head needs a pass to span at most one row end,
@@ -383,7 +458,7 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     if (items > 2000000000LL) return DCONV_UNSUPPORTED;
     p.per_xcd = (int)((items + 7) / 8);
     begin_launch();
-    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE, C, UNIT>),
+    hipLaunchKernelGGL((single_tiled_kernel<F, TW, TR, NBW, WPE, C, UNIT, FB>),
                        dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
     return launch_status();
 }

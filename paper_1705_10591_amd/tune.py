@@ -114,7 +114,11 @@ TABLE_SINGLE = [(4096, 4096, 64, 5), (4096, 4096, 64, 3), (4096, 4096, 64, 7), (
                 (720, 1280, 96, 5),
                 # up to 32 filters: one filter block, rows dealt to the waves
                 (256, 256, 32, 5), (512, 512, 32, 3), (768, 768, 16, 3), (768, 768, 32, 5),
-                (1024, 1024, 16, 3), (1024, 1024, 16, 5), (1024, 1024, 32, 7), (2048, 2048, 16, 3)]
+                (1024, 1024, 16, 3), (1024, 1024, 16, 5), (1024, 1024, 32, 7), (2048, 2048, 16, 3),
+                # up to 16 filters: blocks of 16 filters (configurations 9 and 10); where the library
+                # picks the vector-ALU kernel for few filters, its time is the first column's
+                (4096, 4096, 16, 5), (4096, 4096, 8, 3), (2048, 2048, 16, 7), (1536, 1536, 8, 4),
+                (1080, 1920, 12, 7), (720, 1280, 16, 5), (3000, 3000, 8, 5)]
 TABLE_GENERAL = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (64, 3, 224, 224, 64, 11),
                  (32, 128, 56, 56, 128, 3), (32, 256, 14, 14, 256, 3), (16, 64, 112, 112, 128, 3),
                  (64, 32, 32, 32, 32, 3), (32, 96, 27, 27, 256, 5), (16, 64, 224, 224, 64, 3),

@@ -830,3 +830,48 @@ def test_special_case_kernel_widths_around_the_row_end_rule(W):
             torch.cuda.synchronize()
             np.testing.assert_array_equal(out.cpu().numpy(), acc.astype(np.float32))
             assert torch.isnan(buf[:1001]).all() and torch.isnan(buf[1001 + total:]).all()
+
+
+@pytest.mark.parametrize("K", [1, 4, 7, 8, 9, 12, 15, 16, 17, 24, 31, 32, 33, 40, 48])
+def test_special_case_kernel_filter_counts_around_group_and_block_limits(K):
+    """The write-back goes by groups of eight filters and by blocks of 32 or 16: filter counts on both
+    sides of those limits (whole groups are stored without a test per filter, partial ones with),
+    every tile configuration and the library's own choice, wide rows completed across row ends
+    and narrow ones, exact results between guard bands that start mid-line."""
+    for (H, W, F) in ((11, 700, 3), (9, 230, 5), (12, 90, 4)):
+        x, f = wl.integer_case(900 + K + F, 1, 1, H, W, K, F)
+        acc, _, _ = oracle.general(x, f)
+        want = acc.astype(np.float32)[0]
+        total = want.size
+        img, flt = dev(x[0, 0]), dev(f[:, 0])
+        for variant in [dconv.VARIANT_AUTO] + _tile_variants(True):
+            print(f"special-case kernel K={K} H,W,F={(H, W, F)} variant {variant:#x}", flush=True)
+            buf = torch.full((total + 2048,), float("nan"), device="cuda")
+            out = buf[1003:1003 + total].view(want.shape)
+            dconv.dconv_single_channel(img, flt, out=out, variant=variant)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out.cpu().numpy(), want)
+            assert torch.isnan(buf[:1003]).all() and torch.isnan(buf[1003 + total:]).all()
+
+
+def test_sixteen_filter_blocks_where_the_library_picks_them():
+    """Shapes the dispatcher sends to the 16-filter matrix-core blocks (13 to 16 filters; 8 to 12 on
+    images whose vector-ALU tiles do not cover the chip), at full size on sampled outputs, and the
+    same launch with the configuration forced, bit for bit."""
+    for (H, W, K, F) in ((1080, 1920, 12, 7), (1024, 1024, 16, 5), (720, 1280, 14, 4)):
+        x, f = wl.random_case(1600 + K, 1, 1, H, W, K, F)
+        img, flt = dev(x[0, 0]), dev(f[:, 0])
+        got = dconv.dconv_single_channel(img, flt)
+        forced = [dconv.dconv_single_channel(img, flt, variant=dconv.VARIANT_TILED_CFG0 + c) for c in (9, 10)]
+        torch.cuda.synchronize()
+        assert any(torch.equal(got, o) for o in forced), "the library's choice is one of the 16-filter configurations"
+        rng = np.random.default_rng(K)
+        Ho, Wo = H - F + 1, W - F + 1
+        ks, ys, xs = rng.integers(0, K, 4000), rng.integers(0, Ho, 4000), rng.integers(0, Wo, 4000)
+        xs[:200] = Wo - 1 - (xs[:200] % 40)                # row ends
+        xs[200:400] = xs[200:400] % 40                     # row starts
+        idx = ((ks * Ho + ys) * Wo + xs).astype(np.int64)
+        acc, mag = oracle.general_at(x, f, idx)
+        for o in [got] + forced:
+            vals = o.cpu().numpy().reshape(-1)[idx]
+            assert_within_bound(vals, acc, mag, f"16-filter blocks {(H, W, K, F)}")
