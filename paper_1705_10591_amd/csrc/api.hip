@@ -38,8 +38,7 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
     };
     switch (variant) {
     case DCONV_VARIANT_AUTO:
-        if (single && dconv::single_few_preferred(s) && !dconv::single_blocks16_preferred(s))
-            return dconv::launch_single_few(in, filt, out, s, st);
+        if (single && dconv::single_few_preferred(s)) return dconv::launch_single_few(in, filt, out, s, st);
         return tiled_ok ? tiled(-1) : dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_FEW_FILTERS:
         if (!single || !dconv::single_few_supports(s)) return DCONV_UNSUPPORTED;

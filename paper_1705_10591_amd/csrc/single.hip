@@ -95,31 +95,16 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
 }  // namespace
 
 // Five to sixteen filters on one image (paper Sec. 5.1: few filters are the method's weak spot).
-// A 32-filter matrix-core block would be half padding or more, and the vector-ALU kernel
-// (single_fewfilters.hip) computes filter by filter, its time growing with K * F * F, on units
-// of half the matrix cores' rate, and does not write whole lines.  Configurations 9 and 10
-// compute with 16-filter blocks.  Measured on 720 x 1280 .. 4096 x 4096 images, 5 to 16 filters,
-// 3x3 .. 7x7, against the better of the other two:
-//  * 13 to 16 filters: 5-30 % faster throughout (the vector-ALU kernel is out of its range),
-//    except 3x3 filters on 2048 x 2048, where the 32-filter blocks are 4 % ahead;
-//  * 8 to 12 filters of 3x3: faster (5-25 %) only where the output outgrows the memory-side
-//    cache and the vector-ALU kernel's misaligned rows cost, or where that kernel has too few
-//    tiles to be chosen; 4x4: 5-30 % faster throughout;
-//  * from 5x5 on, 7 to 12 filters: faster (15-25 %) where the vector-ALU kernel's 256 x 32 tiles
-//    do not cover the chip twice (up to about 1536 x 1536), slower beyond; 5 and 6 filters only
-//    where that kernel is not chosen at all.
+// A 32-filter matrix-core block would be half padding or more; configurations 9 and 10 compute
+// with 16-filter blocks and are 5-30 % faster than the 32-filter blocks from 3x3 on (720 x 1280 ..
+// 4096 x 4096 images; 4096 x 4096, 16 filters of 5x5: 0.31 -> 0.26 ms).  Where the vector-ALU
+// kernel is faster still is its own rule (single_few_preferred in single_fewfilters.hip).
 bool single_blocks16_preferred(const Shape& s)
 {
     if (s.C != 1 || s.N != 1 || s.K > 16 || s.K < 5 || s.F < 3 || s.F > 11 || s.Wo < 256) return false;
     const int64_t px = (int64_t)s.Ho * s.Wo;
     if (px < 500000 || px >= (1LL << 29)) return false;
-    if (s.K > 12) return s.F > 3 || px < 3000000 || px * s.K >= 70000000LL;
-    const bool few = single_few_preferred(s);
-    if (s.F == 3) return s.K >= 8 && (px * s.K >= 70000000LL || !few);
-    if (s.F == 4) return s.K >= 8;
-    if (s.K <= 6) return !few;
-    const int64_t few_tiles = (int64_t)((s.Wo + 255) / 256) * ((s.Ho + 31) / 32);
-    return few_tiles < 400 || !few;
+    return !single_few_preferred(s);
 }
 
 bool single_tiled_supports(const Shape& s)

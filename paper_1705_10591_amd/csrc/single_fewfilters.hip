@@ -21,7 +21,12 @@
 // workgroups share a CU and overlap each other's loads); the window does not
 // shift, the row loop is unrolled so that the ring index is a compile-time
 // constant; the filters are the outer loop, so a filter's weights are fetched
-// once per wave and tile (one load, issued a filter ahead).
+// once per wave and tile (one load, issued a filter ahead).  The tile goes from
+// global memory straight into LDS (buffer loads with the LDS bit, 64 words per
+// wave instruction, a row's five instructions with a scalar base and no
+// vector-ALU work): all of a wave's loads are in flight at once, where a loop of
+// load, wait, LDS store per word paid one memory latency per trip and, with one
+// filter, took longer than the arithmetic.
 #include <type_traits>
 #include "common.h"
 #include "../../include/dconv.h"
@@ -56,9 +61,11 @@ single_few_kernel(FewParams p)
     constexpr int FF = F * F;
     constexpr int WIN = 4 + F - 1;                 // window columns of a lane
     constexpr int NV = (WIN + 3) / 4;              // 16-byte LDS reads per window row
-    constexpr int LS = kFewTW + 4 * NV - 4;        // LDS row stride: the last lane's reads stay in the row
+    constexpr int SEGS = (kFewTW + 4 * NV - 4 + kWave - 1) / kWave;   // 64-word pieces of a row
+    constexpr int LS = SEGS * kWave;               // LDS row stride: the last lane's reads stay in the row
     constexpr int ROWS = kFewTR + F - 1;
     static_assert(LS % 4 == 0, "16-byte aligned rows");
+    static_assert(ROWS * LS * 4 <= 64 * 1024, "the tile fits a static LDS array");
 
     __shared__ __attribute__((aligned(16))) float sh[ROWS * LS];
 
@@ -72,15 +79,28 @@ single_few_kernel(FewParams p)
     const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
     const int x0 = tx * kFewTW, y0 = ty * kFewTR;
 
-    // ---- stage the tile (zeros outside the image), coalesced along rows -------------------
+    // ---- stage the tile: the waves take rows in turn, 64 words per instruction, straight into
+    // LDS.  A row's descriptor starts at the row's first pixel in the tile and ends with the
+    // image: lanes beyond that write zeros (rows below the image), lanes beyond the row's end
+    // but inside the image bring pixels of the next row, which only outputs beyond the row's end
+    // would use, and those are not stored.
     {
-        const int cols = min(LS, p.W - x0);
-        const int rows = min(ROWS, p.H - y0);
-        const float* src = p.img + (int64_t)y0 * p.W + x0;
-        for (int e = tid; e < ROWS * LS; e += kThreads) {
-            const int r = e / LS, c = e - r * LS;
-            sh[e] = (r < rows && c < cols) ? src[(int64_t)r * p.W + c] : 0.f;
+        typedef __attribute__((address_space(3))) void* lds_ptr;
+        constexpr int kRsrcFlags = 0x00020000;     // raw buffer of 32-bit words
+        const int64_t img_words = (int64_t)p.H * p.W;
+        int voff[SEGS];
+#pragma unroll
+        for (int j = 0; j < SEGS; ++j) voff[j] = 4 * (lane + kWave * j);
+        for (int r = wave; r < ROWS; r += 4) {     // (uniform)
+            const int64_t first = (int64_t)(y0 + r) * p.W + x0;
+            const int64_t left = (img_words - first) * 4;
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(p.img + first), 0, (int)(left < 0 ? 0 : left > 0x7FFFFFFF ? 0x7FFFFFFF : left), kRsrcFlags);
+#pragma unroll
+            for (int j = 0; j < SEGS; ++j)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(sh + r * LS + kWave * j), 4, voff[j], 0, 0, 0);
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's pieces are in LDS
     }
     __syncthreads();
 
@@ -179,15 +199,31 @@ bool single_few_supports(const Shape& s)
     return s.N == 1 && s.C == 1 && s.F >= 1 && s.F <= 7;
 }
 
-// Worth it (measured against the matrix-core kernel on 4096 x 4096, 1920 x 1080 and 1024 x 1024
-// images): few enough filters that a 32-filter matrix-core block would be mostly empty -- up
-// to 12, up to 20 from 5x5 filters on, where the padding of the block costs more -- and enough
-// tiles to cover the chip.
+// Worth it (measured against the matrix-core kernel with blocks of 32 and of 16 filters on
+// 512^2 .. 4096^2 images, 3 to 20 filters, 3x3 .. 7x7).  Its time grows with K * F * F, the
+// matrix-core kernel's hardly at all up to a block's filters, so there is a filter count up to
+// which it wins; that count is lower where its tiles (256 x 16 or 256 x 32 pixels, one per
+// workgroup) do not cover the chip, because a launch then takes as long as one tile:
+//  * up to four filters: always (from about 100 tiles on; below, the matrix-core kernel's small
+//    tiles cover the chip better);
+//  * up to 3x3: as long as the output fits the memory-side cache (under 110 M outputs; beyond,
+//    its rows, written at any alignment, cost, and the matrix-core kernel's whole lines win);
+//  * from 4x4 on: up to 6 filters with fewer than 200 tiles, 8 with fewer than 400, else 10
+//    filters of 4x4 (16 while the output fits the memory-side cache) and 13 of 5x5 and
+//    larger; 17 to 20 filters (two 16-filter blocks or a 32-filter block with padding) from
+//    5x5 on images of at least 512 tiles.
 bool single_few_preferred(const Shape& s)
 {
+    if (!single_few_supports(s) || s.K > 20) return false;
     const int tr = 4 * few_rpw(s.F, s.K);
     const int64_t tiles = (int64_t)((s.Wo + kFewTW - 1) / kFewTW) * ((s.Ho + tr - 1) / tr);
-    return single_few_supports(s) && s.K <= (s.F <= 4 ? 12 : 20) && tiles >= (s.K <= 8 ? 256 : 512);
+    if (tiles < 100) return false;
+    if (s.K <= 4) return true;
+    const int64_t outputs = (int64_t)s.K * s.Ho * s.Wo;
+    if (s.F <= 3) return outputs < 110000000LL;
+    if (s.K > 16) return s.F >= 5 && tiles >= 512;
+    const int kmax = tiles < 200 ? 6 : tiles < 400 ? 8 : s.F > 4 ? 13 : outputs < 70000000LL ? 16 : 10;
+    return s.K <= kmax;
 }
 
 int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st)

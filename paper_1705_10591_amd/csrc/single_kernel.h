@@ -188,9 +188,8 @@ single_tiled_kernel(SingleParams p)
     const int dY = h * (LS - (F - 1));          // second tap of a pair sits on the next row
     const int dZ = h * (CHS - (F - 1) * LS - (F - 1));    // ... or is the first tap of the next channel
     const int kb = fb * FB;
-    // The write-back goes by groups of eight filters and skips the groups beyond K, so windows
-    // can be stored without a test per filter wherever the block's filters fill whole groups.
-    const bool whole_groups = kb + FB <= p.K || (p.K - kb) % 8 == 0;
+    // (The write-back goes by groups of eight filters and skips the groups beyond K; in a last
+    // group that is not full, the lanes of the missing filters store nothing.)
     const int rrow = lane / LPR, c4 = lane % LPR;          // read phase: strip row and 16 B column
     const int rdofs = rrow * SW + 32 + 4 * c4;
     // The shift of filter k in output row y is s = -(k*pm + c0(y)) mod 32.  k*pm is split into
@@ -262,8 +261,8 @@ single_tiled_kernel(SingleParams p)
                         const float v = stg[r8 * SW + 32 + col];
                         const int px = pd.X + sk + col;
                         float* dst = ub + (sk + col);
-                        if (pd.kind == kPlain) __builtin_nontemporal_store(v, dst);
-                        else if (pd.kind == kTail) { if (px < p.Wo + skn) __builtin_nontemporal_store(v, dst); }
+                        if (pd.kind == kPlain) { if (kvalid) __builtin_nontemporal_store(v, dst); }
+                        else if (pd.kind == kTail) { if (kvalid && px < p.Wo + skn) __builtin_nontemporal_store(v, dst); }
                         else if (kvalid && px < p.Wo) *dst = v;
                     }
                     if (pd.kind == kEdge && pd.head && kvalid && lane < sk && lane < p.Wo)
@@ -275,22 +274,24 @@ single_tiled_kernel(SingleParams p)
 #pragma unroll
             for (int it = 0; it < ITS; ++it)
                 held[it] = *reinterpret_cast<const v4f*>(stg + rdofs + it * RPI * SW);
+            const int rows_left = p.K - kb - 8 * g;            // (uniform) filters of this group and beyond
 #pragma unroll
             for (int it = 0; it < ITS; ++it) {
+                const bool row_ok = rows_left >= 8 || it * RPI + rrow < rows_left;
                 const int kofs = (8 * g + it * RPI) * pm;
                 const int sk = (-(pd.tr + kofs)) & 31;
                 float* ub = pd.orow + (8 * g + it * RPI) * plane;     // out[kb + 8g + it*RPI][y][X]
                 float* dst = ub + (gl + (unsigned)sk);                // this lane's four pixels
                 const int px = pd.X + sk + 4 * c4;
                 if (pd.kind == kPlain) {
-                    store4(dst, held[it]);
+                    if (row_ok) store4(dst, held[it]);
                 } else if (pd.kind == kTail) {
                     // The window runs over the end of the row into the head of the next one; it
                     // stops at the first line boundary of the next row, where that row's own
                     // passes begin.  Both limits are multiples of 16 B away from px.
                     const int skn = (-(pd.trn + kofs)) & 31;
-                    if (px < p.Wo + skn) store4(dst, held[it]);
-                } else if (kb + 8 * g + it * RPI + rrow < p.K) {
+                    if (row_ok && px < p.Wo + skn) store4(dst, held[it]);
+                } else if (row_ok) {
                     // Same window, clipped to the row; whole 16 B pieces wherever they fit.
                     if (px + 3 < p.Wo) {
                         store4(dst, held[it]);
@@ -423,9 +424,9 @@ single_tiled_kernel(SingleParams p)
         }
         const bool reaches_end = X + 32 + PASS > p.Wo;                // a window may cross Wo
         contiguous = !(wrap_tile && reaches_end);                     // no lane reads the next row's head
-        const bool needs_head = X == 0 && (y == 0 || !p.wrap || !whole_groups);
+        const bool needs_head = X == 0 && (y == 0 || !p.wrap);
         int kind = kPlain;
-        if (!whole_groups || needs_head) kind = kEdge;
+        if (needs_head) kind = kEdge;
         else if (reaches_end) kind = (p.wrap && y < p.Ho - 1) ? kTail : kEdge;
         // every pass but the first of a row continues the previous pass of this wave
         if (ch > 0) compute(std::true_type{}, acc, base);
