@@ -875,3 +875,42 @@ def test_sixteen_filter_blocks_where_the_library_picks_them():
         for o in [got] + forced:
             vals = o.cpu().numpy().reshape(-1)[idx]
             assert_within_bound(vals, acc, mag, f"16-filter blocks {(H, W, K, F)}")
+
+
+@pytest.mark.parametrize("side", [24000, 23100])
+def test_single_channel_huge_images_sampled(side):
+    """One 24000 x 24000 image (2.3 GB: input rows beyond 2 GiB, more than 4 GiB of output) on the
+    few-filters kernel, whose row descriptors start at each row and are clamped to 31 bits; the
+    matrix-core kernel addresses an output plane with 32-bit lane offsets and refuses it.  One
+    23100 x 23100 image (2.13 GB, the largest it takes) on 32- and 16-filter blocks.  Sampled
+    outputs, whole rows at the far end and at the seam between the maps."""
+    H = W = side
+    K, F = 2, 3
+    rng = np.random.default_rng(side)
+    img = rng.standard_normal((H, W), dtype=np.float32)
+    flt = rng.standard_normal((K, F, F), dtype=np.float32)
+    x4, f4 = img.reshape(1, 1, H, W), flt.reshape(K, 1, F, F)
+    Ho, Wo = H - F + 1, W - F + 1
+    total = K * Ho * Wo
+    idx = np.unique(np.concatenate([wl.sample_indices(2401, total, 20000),
+                                    np.arange(total - 2 * Wo, total),                  # the last rows, whole
+                                    np.arange(Ho * Wo - 3000, Ho * Wo + 3000),         # the seam between the maps
+                                    # around the input row whose byte offset crosses 2 GiB (if any)
+                                    min((1 << 29) // W, Ho - 2) * Wo + np.arange(-3000, 3000)]))
+    acc, mag = oracle.general_at(x4, f4, idx)
+    xd, fd = dev(img), dev(flt)
+    sel = torch.from_numpy(idx).to("cuda")
+    if side == 24000:
+        variants = (("few-filters kernel", dconv.VARIANT_FEW_FILTERS), ("library's choice", dconv.VARIANT_AUTO))
+        with pytest.raises(dconv.DconvError) as e:
+            dconv.dconv_single_channel(xd, fd, variant=dconv.VARIANT_TILED)
+        assert e.value.status == dconv.STATUS_UNSUPPORTED
+    else:
+        variants = (("32-filter blocks", dconv.VARIANT_TILED_CFG0 + 0), ("16-filter blocks", dconv.VARIANT_TILED_CFG0 + 9),
+                    ("library's choice", dconv.VARIANT_AUTO))
+    for name, variant in variants:
+        print(f"{side} x {side} image, {name}", flush=True)
+        out = dconv.dconv_single_channel(xd, fd, variant=variant)
+        torch.cuda.synchronize()
+        assert_within_bound(out.view(-1)[sel].cpu().numpy(), acc, mag, f"{side}^2 image, {name}")
+        del out
