@@ -61,8 +61,9 @@ enum {
                               /* single-channel case only, F <= 7: vector-ALU
                                  kernel with a sliding register window (the
                                  paper's Algorithm 1 as it stands); what AUTO
-                                 picks for up to 12 filters (20 from 5x5 on) on
-                                 large images                                    */
+                                 picks for few filters (at most 20; how many
+                                 depends on filter and image size) where it
+                                 beats the matrix-core kernel                    */
     DCONV_VARIANT_SPECIAL_CASE = 4,
                               /* dconv_general with C = 1 (any filter up to
                                  11x11) or C <= 4 (filters up to 5x5) only: the
