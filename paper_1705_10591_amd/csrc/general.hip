@@ -192,16 +192,13 @@ int shape_for(const Shape& s)
 {
     const int64_t px = (int64_t)s.N * s.Ho * s.Wo;
     if (s.K <= 32) return 2;
-    // Few multiply-adds per output element (up to sixteen channels of 3x3 filters): a tile is over
-    // after a few dozen steps and the time goes to its stores, which the vector memory pipe of
-    // a CU takes slowly while its matrix cores are busy.  The small tile, three workgroups per
-    // CU and 32 store instructions per wave and tile, then reaches the sum of arithmetic and
-    // store time; the larger ones, with 64 stores per wave in one burst, fall 25 to 60 % short
-    // of it (measured on 56^2 to 224^2 maps with 0.75 GB of output and more; outputs that the
-    // 256 MB memory-side cache absorbs are stored fast enough by every tile shape).  1x1 filters
-    // keep the rule below: their chunks are short and the small tile stages twice per
-    // matrix-core step.
-    if (s.F >= 2 && s.C * s.F * s.F <= 160 && px * s.K >= 100000000LL) return 0;
+    // 2x2 filters with few multiply-adds per output element (up to 40 channels) and more output
+    // than the memory-side cache absorbs: a tile is over after a few dozen steps, its image block
+    // of eight channels holds narrow column strips only, and the 64 x 256 tile's 64 stores per
+    // wave in one burst drain slowly; the small tile, three workgroups per CU, is 15 % faster on
+    // 224-wide maps.  (From 3x3 on such shapes run on the kernels with the large image block,
+    // whose wide strips favour the 64 x 256 tile by 7-17 %: general_inst.hip.)
+    if (s.F == 2 && s.C * s.F * s.F <= 160 && px * s.K >= 100000000LL) return 0;
     if (s.K <= 64) {
         const int64_t wide_tiles = (px + 255) / 256;
         const int64_t chunks = ((int64_t)s.C * s.F * s.F + 35) / 36;

@@ -25,8 +25,8 @@ constexpr int kRowGroup = F <= 5 ? F : F == 6 ? 3 : F == 9 ? 3 : F == 10 ? 5 : 4
 // larger filters have a second set of kernels with sixteen for shapes (tiny maps, where a
 // tile spans many images) whose image block does not fit in eight
 constexpr int kImaxF = F == 1 ? 16 : 8;
-// (3x3 filters: for few channels only, see launch_tile)
-constexpr bool kSecondImax = F >= 5 || F == 3;
+// (3x3 and 4x4 filters: for few channels only, see launch_tile)
+constexpr bool kSecondImax = F >= 3;
 
 // Three LDS slots when three chunks with the largest image block fit twice on a CU (or at
 // least once, for chunks with enough steps); two otherwise.
@@ -64,13 +64,15 @@ int launch_tile(const float* in, const float* filt, float* out, const Shape& s, 
                 int tile_cfg, const GenSched& sched, bool dry)
 {
     if (!kSecondImax) return launch_tile_imax<CSH, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
-    // 3x3 filters on maps wider than a 128-column strip: with eight words per thread the image
-    // block of four channels holds strips of some 56 columns only (222-wide maps: four strips),
-    // and every strip row is a run of its own in the output.  With up to about 80 multiply-adds
-    // per output element the stores bound such shapes and the wider strips of the large image
-    // block pay (64 images of 224 x 224, 8 channels, 64 filters: 0.49 -> 0.43 ms); with more
-    // channels its LDS costs a workgroup per CU and more than it saves (16 channels: 6 % slower).
-    if (F < 5 && s.C * F * F > 80) return launch_tile_imax<CSH, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
+    // 3x3 and 4x4 filters with few channels.  With eight words per thread the image block of a
+    // chunk holds narrow column strips only (four channels of 3x3 on 222-wide maps: four strips
+    // of 56 columns under a 128-pixel tile, and a 256-pixel tile cannot even keep a 110-wide map
+    // whole), and every strip row is a run of its own in the output.  With up to 160
+    // multiply-adds per output element the stores bound such shapes and the wide strips of the
+    // large image block pay, most of all under the 64 x 256 tile (256 images of 112 x 112, 8
+    // channels, 64 filters: 0.42 -> 0.35 ms; 64 of 224 x 224: 0.49 -> 0.37 ms; 16 channels:
+    // 0.63 -> 0.58 ms); with more channels its LDS costs a workgroup per CU and more than it saves.
+    if (F < 5 && s.C * F * F > 160) return launch_tile_imax<CSH, kImaxF>(in, filt, out, s, st, tile_cfg, sched, dry);
     GenSched widest = sched;
     widest.widest_only = true;
     int rc = launch_tile_imax<CSH, kImaxF>(in, filt, out, s, st, tile_cfg, widest, dry);
