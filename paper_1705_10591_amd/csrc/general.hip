@@ -192,6 +192,13 @@ int shape_for(const Shape& s)
 {
     const int64_t px = (int64_t)s.N * s.Ho * s.Wo;
     if (s.K <= 32) return 2;
+    // 1x1 filters: a chunk is sixteen channels, eight matrix-core steps and a barrier, whatever
+    // the tile, and the 64 x 128 tile's three workgroups per CU hide that better than the four
+    // matrix-core instructions per step of the 64 x 256 tile pay: 10-80 % faster from 128
+    // channels on and on maps up to 64 wide (14 x 14 .. 224 x 224 maps, 32 to 512 channels, 64
+    // to 256 filters); with fewer channels on wider maps the large tile's fewer, longer output
+    // runs win by up to 30 %.
+    if (s.F == 1) return (s.C >= 128 || s.Wo <= 64) ? 0 : 1;
     // 2x2 filters with few multiply-adds per output element (up to 40 channels) and more output
     // than the memory-side cache absorbs: a tile is over after a few dozen steps, its image block
     // of eight channels holds narrow column strips only, and the 64 x 256 tile's 64 stores per

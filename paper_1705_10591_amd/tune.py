@@ -128,7 +128,10 @@ TABLE_GENERAL = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (64, 3, 224
                  (8, 128, 112, 112, 128, 3), (64, 512, 7, 7, 512, 3),
                  # few multiply-adds per output: the output stream is a large part of the time
                  (64, 8, 224, 224, 64, 3), (256, 8, 112, 112, 64, 3), (256, 16, 112, 112, 64, 3),
-                 (512, 8, 56, 56, 128, 3), (256, 32, 112, 112, 64, 1)]
+                 (512, 8, 56, 56, 128, 3), (256, 32, 112, 112, 64, 1),
+                 # 1x1 layers
+                 (128, 256, 28, 28, 256, 1), (64, 512, 14, 14, 512, 1), (512, 64, 56, 56, 128, 1),
+                 (58, 64, 112, 112, 128, 1), (7, 256, 112, 112, 256, 1)]
 
 # Shapes for the comparison of the two write-backs: few multiply-adds per output element, maps
 # narrower and wider than a column strip, outputs below and above the 256 MB memory-side cache;
