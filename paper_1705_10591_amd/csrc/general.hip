@@ -195,10 +195,10 @@ int shape_for(const Shape& s)
     // 1x1 filters: a chunk is sixteen channels, eight matrix-core steps and a barrier, whatever
     // the tile, and the 64 x 128 tile's three workgroups per CU hide that better than the four
     // matrix-core instructions per step of the 64 x 256 tile pay: 10-80 % faster from 128
-    // channels on and on maps up to 64 wide (14 x 14 .. 224 x 224 maps, 32 to 512 channels, 64
-    // to 256 filters); with fewer channels on wider maps the large tile's fewer, longer output
-    // runs win by up to 30 %.
-    if (s.F == 1) return (s.C >= 128 || s.Wo <= 64) ? 0 : 1;
+    // channels on, and from 64 on maps up to 64 wide (14 x 14 .. 224 x 224 maps, 32 to 512
+    // channels, 64 to 512 filters); with fewer channels or on wider maps the large tile's
+    // fewer, longer output runs win by up to 30 %.
+    if (s.F == 1) return (s.C >= 128 || (s.C >= 64 && s.Wo <= 64)) ? 0 : 1;
     // Tiny maps (under a hundred outputs per image): a 256-pixel tile reaches over several
     // images, each with its halo rows in the image block; the 128-pixel tile is 20-35 % faster
     // (7 x 7 outputs, 64 to 512 channels and filters, hundreds of images).

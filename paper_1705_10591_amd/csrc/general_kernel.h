@@ -812,11 +812,16 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     else {
         // ... when a last round would leave much of the chip idle and a tile is long enough
         // (about 60 us with the workgroups of a CU sharing its matrix cores) for the saving to
-        // outweigh the cost of meeting in the workspace (measured: some 25 us per launch)
+        // outweigh the cost of meeting in the workspace; or, with shorter tiles in two rounds
+        // or more, when the time the last round leaves the chip idle (its empty part times a
+        // tile's time) exceeds that cost (some 12 us).  64 images of 14 x 14 with 512 channels
+        // and 512 1x1 filters: 784 tiles of 41 us on 768 slots, 96 us whole, 74 us shared.
         const int64_t rounds = (tiles + chip - 1) / chip;
         const double tile_us = (double)nch * Gm::S * (MW * NW) * 64.0 * OCC / 2400.0;
-        split = (nch >= 2 && tile_us >= 60.0 && tiles < 8LL * chip &&
-                 (double)tiles < 0.93 * (double)(rounds * chip)) ? 1 : 0;
+        const double idle_us = ((double)rounds - (double)tiles / (double)chip) * tile_us;
+        const bool long_tiles = tile_us >= 60.0 && (double)tiles < 0.93 * (double)(rounds * chip);
+        const bool idle_round = rounds >= 2 && tile_us >= 20.0 && idle_us >= 12.0;
+        split = (nch >= 2 && tiles < 8LL * chip && (long_tiles || idle_round)) ? 1 : 0;
     }
     const int64_t U = split ? tiles * nch : tiles;
     G = sched.force_G > 0 ? sched.force_G : chip;
