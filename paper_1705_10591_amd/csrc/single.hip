@@ -2,6 +2,9 @@
 // kernel in single_kernel.h and the rules that pick one.
 #include "single_kernel.h"
 
+#include <algorithm>
+#include <cmath>
+
 namespace dconv {
 
 namespace {
@@ -35,13 +38,39 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
         auto items = [&](int tw, int tr) {
             return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
         };
+        // Imbalance of a tile shape: the workgroups of the fullest CU over the mean per CU, tiles
+        // counted by their passes (the last tile column may hold fewer than the others).  The
+        // hardware deals workgroups evenly, so a launch of 534 wide tiles takes as long as one of
+        // 768 (a handful of tiles beyond a multiple of the CUs is not counted as a round: those
+        // run on CUs that have little else left).  `round_up` says how much of the last,
+        // partly filled round counts: all of it for the wide tiles, less for the small ones,
+        // which are dealt as slots fall free.  For filters bound by the matrix cores this factor
+        // predicts the measured time per pixel of 512-pixel tiles on 720 x 1280 .. 3000 x 3000
+        // images within a few per cent.
+        auto imbalance = [&](int tw, int tr, int pass, double round_up) {
+            constexpr double kCUs = 256;
+            const int64_t cols = (s.Wo + tw - 1) / tw, rows = (s.Ho + tr - 1) / tr;
+            const int64_t per_tile = tw / pass;
+            const int64_t last = (s.Wo - tw * (cols - 1) + pass - 1) / pass;
+            const double mean = (double)(rows * fgroups * (per_tile * (cols - 1) + last)) /
+                                ((double)per_tile * kCUs);
+            const double per_cu = std::max(1.0, (double)(cols * rows * fgroups) / kCUs);
+            const double full = std::max(1.0, std::ceil(per_cu - 0.05));
+            return (full > per_cu ? per_cu + round_up * (full - per_cu) : full) / mean;
+        };
+        // (128 x 4 with passes of 32 pixels, or 256 x 2: whichever divides the image more evenly)
+        auto small_tile = [&](double bias) {
+            return imbalance(128, 4, 32, 0.0) < bias * imbalance(256, 2, 128, 0.75) ? 6 : 3;
+        };
         // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
         const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
         if (single_blocks16_preferred(s)) {
             // (the small tile with short passes for 3x3 on mid-sized images, as for 32-filter
-            // blocks, and where 512-pixel tile columns would overhang the image by 15 % or more)
+            // blocks, where 512-pixel tile columns would overhang the image by 15 % or more, and
+            // where there are too few wide tiles for the CUs: 600 x 1000, 5x5: 20 -> 17 us)
             const bool overhang = (int64_t)((s.Wo + 511) / 512) * 512 * 100 >= (int64_t)s.Wo * 115;
-            cfg = ((s.F == 3 && (int64_t)s.Ho * s.Wo < 3000000) || overhang) ? 10 : 9;
+            const bool uneven = imbalance(512, 4, 128, 1.0) > 1.5;
+            cfg = ((s.F == 3 && (int64_t)s.Ho * s.Wo < 3000000) || overhang || uneven) ? 10 : 9;
         } else if (items(128, 4) <= 320 && items(64, 4) > items(128, 4)) {
             // so few 128-pixel tiles that CUs would stay without a workgroup (up to about 384 x 384
             // with one filter group): 64-pixel tiles, twice the workgroups, half the passes per wave
@@ -60,18 +89,36 @@ int launch_F(const float* img, const float* filt, float* out, const Shape& s, hi
             // passes of 32 pixels are a few per cent faster again
             cfg = (s.K <= 16 || F >= 5) ? 6 : 5;
         } else if (s.K <= 32 && F < 8 && s.Wo < 3072) {
-            cfg = 0;
+            cfg = (F >= 5 && imbalance(512, 4, 128, 1.0) > 1.25) ? 6 : 0;
         } else if (F <= 4) {
             // (mid-sized problems: 256 x 2, or with up to 64 filters 128 x 4 with short passes)
             cfg = items(512, 4) < 1280 ? (s.K <= 64 ? 5 : 3) : 0;
         } else if (items(512, 4) < 384) {
-            cfg = 3;
+            cfg = small_tile(1.0);
         } else if (F >= 8) {
-            cfg = items(512, 8) >= 512 ? 2 : 0;
+            // bound by the matrix cores: the time of a tile shape is its cost per pixel (relative
+            // to 512 x 4, measured on 3000 x 3000 images) times its imbalance.  The taller tile
+            // pays only with several workgroups per CU and, with more than one filter block, must
+            // win by a margin: its model is the least exact there.
+            const double wide = imbalance(512, 4, 128, 1.0);
+            const bool one_block = s.K <= 32;  // (each wave then takes whole rows of the tile)
+            double tall = 1e9, small;
+            if (one_block) {
+                if (items(512, 8) >= 380) tall = 0.95 * imbalance(512, 8, 128, 1.0);
+                small = F == 8 ? 1.40 : F >= 11 ? 1.30 : 1.25;
+            } else {
+                if (items(512, 8) >= 920)
+                    tall = 1.05 * (F == 8 ? 0.99 : 0.95) * imbalance(512, 8, 128, 1.0);
+                small = F == 8 ? 1.30 : F >= 11 ? 1.25 : 1.20;
+            }
+            if (small < wide && small < tall) cfg = F >= 11 ? 5 : 6;
+            else cfg = tall < wide ? 2 : 0;
         } else {
-            // 5x5 .. 7x7: the small tile keeps its lead over a wide range of mid-sized problems
+            // 5x5 .. 7x7: a small tile where the wide one would leave CUs idle (7x7 is bound by
+            // the matrix cores and tolerates a little more)
             const int64_t it = items(512, 4);
-            cfg = (it >= 520 && it < 4200) ? 3 : 0;
+            const bool mid = it >= 520 && it < (F == 7 ? 4200 : 2000);
+            cfg = (mid && imbalance(512, 4, 128, 1.0) > (F == 7 ? 1.25 : 1.20)) ? small_tile(0.95) : 0;
         }
     }
     // (the small tiles keep three waves per SIMD in registers up to 8x8; beyond, the filter
@@ -103,7 +150,9 @@ bool single_blocks16_preferred(const Shape& s)
 {
     if (s.C != 1 || s.N != 1 || s.K > 16 || s.K < 5 || s.F < 3 || s.F > 11 || s.Wo < 256) return false;
     const int64_t px = (int64_t)s.Ho * s.Wo;
-    if (px < 500000 || px >= (1LL << 29)) return false;
+    // (from about 560 x 560 on for 5x5 and larger: 5 to 20 % there; smaller launches are all
+    // latency)
+    if (px < (s.F >= 5 ? 300000 : 500000) || px >= (1LL << 29)) return false;
     return !single_few_preferred(s);
 }
 

@@ -207,7 +207,8 @@ bool single_few_supports(const Shape& s)
 //  * up to four filters: always (from about 100 tiles on; below, the matrix-core kernel's small
 //    tiles cover the chip better);
 //  * up to 3x3: as long as the output fits the memory-side cache (under 110 M outputs; beyond,
-//    its rows, written at any alignment, cost, and the matrix-core kernel's whole lines win);
+//    its rows, written at any alignment, cost, and the matrix-core kernel's whole lines win)
+//    and the image is not too small for the filter count (18 filters per million pixels);
 //  * from 4x4 on: up to 6 filters with fewer than 200 tiles, 8 with fewer than 400, else 10
 //    filters of 4x4 (16 while the output fits the memory-side cache) and 13 of 5x5 and
 //    larger; 17 to 20 filters (two 16-filter blocks or a 32-filter block with padding) from
@@ -220,7 +221,10 @@ bool single_few_preferred(const Shape& s)
     if (tiles < 100) return false;
     if (s.K <= 4) return true;
     const int64_t outputs = (int64_t)s.K * s.Ho * s.Wo;
-    if (s.F <= 3) return outputs < 110000000LL;
+    // (up to 3x3: its time grows with the filter count while the matrix-core kernel on a small
+    // image takes the time of its latencies whatever the count: 768 x 768, 16 filters of 3x3:
+    // 19 against 14 us; about 18 filters per million output pixels is where they meet)
+    if (s.F <= 3) return outputs < 110000000LL && (int64_t)s.K * 1000000 <= 18 * (int64_t)s.Ho * s.Wo;
     if (s.K > 16) return s.F >= 5 && tiles >= 512;
     const int kmax = tiles < 200 ? 6 : tiles < 400 ? 8 : s.F > 4 ? 13 : outputs < 70000000LL ? 16 : 10;
     return s.K <= kmax;

@@ -112,6 +112,9 @@ TABLE_SINGLE = [(4096, 4096, 64, 5), (4096, 4096, 64, 3), (4096, 4096, 64, 7), (
                 (1024, 1024, 64, 3), (512, 512, 64, 3), (1080, 1920, 32, 3), (1080, 1920, 64, 7),
                 (256, 256, 16, 3), (1536, 1536, 128, 3), (3000, 3000, 64, 5), (2048, 2048, 256, 5),
                 (720, 1280, 96, 5),
+                # images that 512-pixel tiles divide unevenly over the CUs
+                (720, 1280, 64, 9), (1080, 1920, 64, 9), (1536, 1536, 64, 9), (1800, 1800, 64, 7),
+                (1280, 1280, 32, 8), (900, 1600, 128, 11), (600, 800, 64, 7), (720, 1280, 32, 5),
                 # up to 32 filters: one filter block, rows dealt to the waves
                 (256, 256, 32, 5), (512, 512, 32, 3), (768, 768, 16, 3), (768, 768, 32, 5),
                 (1024, 1024, 16, 3), (1024, 1024, 16, 5), (1024, 1024, 32, 7), (2048, 2048, 16, 3),
