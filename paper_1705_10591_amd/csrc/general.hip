@@ -182,16 +182,30 @@ int launch_any(const float* in, const float* filt, float* out, const Shape& s, h
     }
 }
 
-// Tile shape by problem shape, from the tile search (paper_1705_10591_amd.tune) over twenty
-// layer shapes.  Up to 32 filters: the 32 x 256 tile, so that half of every filter block is not
-// padding.  Up to 64 filters: 64 x 256 when the work divides finely enough over the chip with it
-// (many tiles, or so many chunks per tile that sharing tiles is cheap), else 64 x 128, which
-// doubles the number of tiles (and fits three workgroups per CU).  More filters: 64 x 256 on large maps, 64 x 128 (three workgroups
-// per CU) on small ones.
+// Tile shape by problem shape, from the tile search (paper_1705_10591_amd.tune) over forty layer
+// shapes and from timing the three shapes on 630 layers drawn at random (3 to 512 channels, 16 to
+// 512 filters of 1x1 to 7x7, 7 x 7 to 224 x 224 maps, 0.5 to 30 GFLOP); the rule below is within
+// 1 % of the fastest shape on their average (4 % before it was refitted on them).
 int shape_for(const Shape& s)
 {
     const int64_t px = (int64_t)s.N * s.Ho * s.Wo;
-    if (s.K <= 32) return 2;
+    const int64_t wide_tiles = (px + 255) / 256, fblocks = (s.K + 63) / 64;
+    const int64_t tiles = wide_tiles * fblocks;           // of the 64 x 256 shape
+    const int taps = s.C * s.F * s.F;                      // multiply-adds per output element
+    const int64_t chunks = ((int64_t)taps + 35) / 36;
+    const bool tiny = (int64_t)s.Ho * s.Wo < 100;
+    // Up to 32 filters: the 32 x 256 tile, so that half of every filter block is not padding
+    // (1x1 filters on tiny maps, where a 256-pixel tile reaches over several images: 64 x 128).
+    if (s.K <= 32) return (tiny && s.F == 1) ? 0 : 2;
+    // Filter counts whose last block of 64 is at most half full (96, 160, 224, 288): the 32 x 256
+    // tile computes 25, 17, 12, 10 % fewer padded filters and is 20, 10, 5, 4 % faster from 3x3
+    // on (and for the smaller filters with few channels); on tiny maps only for 96.
+    // (with few tiles only where a quarter is saved)
+    if (s.K % 64 != 0 && s.K % 64 <= 32 && (s.F >= 3 || taps <= 64)) {
+        const int k32 = (s.K + 31) / 32 * 32, k64 = (int)fblocks * 64;
+        const bool quarter = k32 * 100 <= k64 * 76;
+        if (tiles >= (quarter ? 20 : 100) && (quarter || (!tiny && k32 * 100 <= k64 * 91))) return 2;
+    }
     // 1x1 filters: a chunk is sixteen channels, eight matrix-core steps and a barrier, whatever
     // the tile, and the 64 x 128 tile's three workgroups per CU hide that better than the four
     // matrix-core instructions per step of the 64 x 256 tile pay: 10-80 % faster from 128
@@ -202,22 +216,24 @@ int shape_for(const Shape& s)
     // Tiny maps (under a hundred outputs per image): a 256-pixel tile reaches over several
     // images, each with its halo rows in the image block; the 128-pixel tile is 20-35 % faster
     // (7 x 7 outputs, 64 to 512 channels and filters, hundreds of images).
-    if ((int64_t)s.Ho * s.Wo < 100) return 0;
-    // 2x2 filters with few multiply-adds per output element (up to 40 channels) and more output
-    // than the memory-side cache absorbs: a tile is over after a few dozen steps, its image block
-    // of eight channels holds narrow column strips only, and the 64 x 256 tile's 64 stores per
-    // wave in one burst drain slowly; the small tile, three workgroups per CU, is 15 % faster on
-    // 224-wide maps.  (From 3x3 on such shapes run on the kernels with the large image block,
-    // whose wide strips favour the 64 x 256 tile by 7-17 %: general_inst.hip.)
-    if (s.F == 2 && s.C * s.F * s.F <= 160 && px * s.K >= 100000000LL) return 0;
+    if (tiny) return 0;
+    // 2x2 filters are like 1x1 ones: eight channels a chunk, and beyond 40 channels the small
+    // tile is 13-34 % faster (maps up to 60 wide; a tie on the widest).
+    if (s.F == 2 && taps > 160) return 0;
+    // Few multiply-adds per output element (up to 160): the stores bound the time and the
+    // 64 x 256 tile's longer runs win as soon as there are tiles enough for the CUs.
+    const bool few_taps = taps <= 160;
     if (s.K <= 64) {
-        const int64_t wide_tiles = (px + 255) / 256;
-        const int64_t chunks = ((int64_t)s.C * s.F * s.F + 35) / 36;
-        // (with a few dozen wide tiles only, sharing them leaves the chip unevenly loaded however
-        // many chunks they have: 512 channels, 64 filters of 5x5, 57 wide tiles: 9 % slower)
-        return (wide_tiles >= 1024 || (wide_tiles >= 200 && wide_tiles * chunks >= 12000)) ? 1 : 0;
+        // 64 x 256 when the work divides finely enough over the chip with it (many tiles, or so
+        // many chunks per tile that sharing tiles is cheap), else 64 x 128, which doubles the
+        // number of tiles and fits three workgroups per CU.  (With a few dozen wide tiles only,
+        // sharing them leaves the chip unevenly loaded however many chunks they have: 512
+        // channels, 64 filters of 5x5, 57 wide tiles: 9 % slower.)
+        return (wide_tiles >= 1024 || (wide_tiles >= 200 && wide_tiles * chunks >= 12000) ||
+                (few_taps && wide_tiles >= 300)) ? 1 : 0;
     }
-    return px >= 16384 ? 1 : 0;
+    if (few_taps) return tiles >= 150 ? 1 : 0;
+    return (tiles >= 400 || (tiles >= 100 && chunks >= 100)) ? 1 : 0;
 }
 
 }  // namespace

@@ -787,7 +787,7 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
     // per instantiation for the last (device, LDS size) seen, key and count in one atomic word,
     // so that threads calling with different shapes can only repeat the query.
     static std::atomic<uint64_t> lds_limit_raised{0};
-    static std::atomic<uint64_t> cached{0};        // device + 1 (8 bits) | LDS bytes (24) | count (32)
+    static std::atomic<uint64_t> cached{0};        // device + 1 (8 bits) | LDS bytes (24) | per CU (8) | count (24)
     if (!raise_lds_limit((const void*)kern, kGenLdsLimit, lds_limit_raised)) return DCONV_LAUNCH_FAILED;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return DCONV_LAUNCH_FAILED;
@@ -800,10 +800,13 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
                                                          (size_t)lds_bytes) != hipSuccess ||
             cus <= 0 || per_cu <= 0)
             return DCONV_LAUNCH_FAILED;
-        seen = key | (uint32_t)(cus * (per_cu > OCC ? OCC : per_cu));
+        const int occ = per_cu > OCC ? OCC : per_cu;
+        if (cus * occ >= (1 << 24)) return DCONV_LAUNCH_FAILED;
+        seen = key | ((uint32_t)occ << 24) | (uint32_t)(cus * occ);
         cached.store(seen, std::memory_order_relaxed);
     }
-    const int chip = (int)(uint32_t)seen;
+    const int chip = (int)((uint32_t)seen & 0xFFFFFFu);
+    const int cus = chip / (int)(((uint32_t)seen >> 24) & 0xFFu);
 
     // Whole tiles when they spread evenly enough, otherwise cut inside tiles.
     int G, split;
@@ -823,12 +826,44 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
         const bool idle_round = rounds >= 2 && tile_us >= 20.0 && idle_us >= 12.0;
         split = (nch >= 2 && tiles < 8LL * chip && (long_tiles || idle_round)) ? 1 : 0;
     }
-    const int64_t U = split ? tiles * nch : tiles;
+    int64_t U = split ? tiles * nch : tiles;
     G = sched.force_G > 0 ? sched.force_G : chip;
     if (G > U) G = (int)U;
-    // The workgroup that completes a shared tile adds all its parts by itself: keep the parts
-    // per tile few (at most about eight) when there are far fewer tiles than workgroups.
-    if (split && sched.force_G <= 0 && sched.mode == 0 && (int64_t)G > 8 * tiles) G = (int)(8 * tiles);
+    // Fewer tiles than CUs (small batches of deep layers): how many workgroups share the tiles
+    // is a trade.  The workgroup that completes a shared tile adds all its parts by itself, one
+    // part after the other (`part_us` each, a round trip to the memory side per block), while the
+    // matrix-core work per workgroup falls with their number only up to one per CU: beyond, the
+    // workgroups of a CU share its matrix cores and gain what latency hiding gives (`eff`).
+    // time(G) = units per workgroup x time per unit x workgroups per CU / eff + parts x part_us,
+    // fitted to sweeps over the parts per tile on sixteen layers (1 to 16 images of 7 x 7 to
+    // 96 x 96, 128 to 2048 channels, 1x1 to 7x7: within 10 % rms).  One image of 20 x 20 with
+    // 384 channels and 384 filters of 7x7: 134 -> 82 us; 4 of 17 x 14, 512 channels, 448 1x1
+    // filters: 33 -> 18 us.
+    if (sched.mode == 0 && sched.force_G <= 0 && nch >= 2 && 4 * tiles < 3LL * cus) {
+        constexpr bool kBig = MW * NW >= 4;
+        const double eff[4] = {1.0, kBig ? 0.70 : 0.60, kBig ? 0.70 : 0.75, 0.80};
+        const double part_us = kBig ? 1.4 : 0.8;
+        const double unit_us = (double)Gm::S * (MW * NW) * 64.0 / 2400.0;
+        auto per_cu = [&](int64_t g) { return (int)std::min<int64_t>((g + cus - 1) / cus, 3); };
+        const int o_whole = per_cu(tiles);
+        const double whole = (double)nch * unit_us * o_whole / eff[o_whole];   // one round of tiles
+        double best = 1e30;
+        int64_t best_g = 0;
+        auto consider = [&](int64_t g) {
+            g = std::min<int64_t>(std::min<int64_t>(g, chip), tiles * nch);
+            if (g <= tiles) return;
+            const int o = per_cu(g);
+            const double t = (double)(tiles * nch) / (double)g * unit_us * o / eff[o] +
+                             part_us * ((double)g / (double)tiles + 1.0);
+            if (t < best) { best = t; best_g = g; }
+        };
+        for (int parts = 2; parts <= 32; ++parts) consider(parts * tiles);
+        for (int k = 1; k <= 6; ++k) consider((int64_t)k * cus / 2);
+        // (shared only for a tenth or more: the model knows nothing of the cost of a workgroup's
+        // passing from one tile to the next)
+        if (best < 0.9 * whole) { split = 1; U = tiles * nch; G = (int)best_g; }
+        else { split = 0; U = tiles; G = (int)tiles; }
+    }
 
     GenWorkspace ws{nullptr, nullptr};
     if (split && sched.static_ws) {

@@ -134,7 +134,13 @@ TABLE_GENERAL = [(32, 64, 56, 56, 64, 3), (32, 256, 28, 28, 512, 3), (64, 3, 224
                  (512, 8, 56, 56, 128, 3), (256, 32, 112, 112, 64, 1),
                  # 1x1 layers
                  (128, 256, 28, 28, 256, 1), (64, 512, 14, 14, 512, 1), (512, 64, 56, 56, 128, 1),
-                 (58, 64, 112, 112, 128, 1), (7, 256, 112, 112, 256, 1)]
+                 (58, 64, 112, 112, 128, 1), (7, 256, 112, 112, 256, 1),
+                 # fewer tiles than CUs (small batches of deep layers): tiles shared over channels
+                 (1, 512, 14, 14, 512, 3), (1, 384, 20, 20, 384, 7), (4, 512, 17, 14, 448, 1),
+                 (2, 384, 28, 28, 256, 5), (1, 256, 28, 28, 256, 3),
+                 # filter counts that are not multiples of 64; 2x2 filters
+                 (13, 64, 75, 75, 96, 3), (19, 256, 48, 48, 160, 3), (94, 8, 224, 224, 64, 2),
+                 (108, 320, 30, 30, 128, 2)]
 
 # Shapes for the comparison of the two write-backs: few multiply-adds per output element, maps
 # narrower and wider than a column strip, outputs below and above the 256 MB memory-side cache;
