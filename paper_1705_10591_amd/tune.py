@@ -16,6 +16,9 @@ that the rules can be checked or re-derived on another chip.
                                                                    kernel next to the general kernel)
     python -m paper_1705_10591_amd.tune table single|general|bf16|bf16-blocked
                                                                   (the shapes the rules were set on)
+    python -m paper_1705_10591_amd.tune random single|general SEED COUNT
+                                                                  (shapes drawn at random: the check of the rules
+                                                                   on shapes they were not set on)
     python -m paper_1705_10591_amd.tune units                     (special case: 16-byte against 4-byte units
                                                                    on the way out, the width-matching ablation)
     python -m paper_1705_10591_amd.tune writeback                 (general case: stores straight from the
@@ -178,6 +181,61 @@ def table(kind: str) -> None:
               flush=True)
 
 
+def random_shapes(kind: str, seed: int, count: int):
+    """Shapes drawn at random (Python's own generator, so the same seed gives the same shapes
+    anywhere): images 400 to 3000 pixels on a side with 24 to 200 filters of 3x3 to 11x11 for
+    the special case; layers of 3 to 512 channels, 16 to 512 filters of 1x1 to 7x7 on 7 x 7 to
+    224 x 224 maps, 0.5 to 30 GFLOP, for the general case."""
+    import random
+    rng = random.Random(seed)
+    shapes = []
+    while len(shapes) < count:
+        if kind == "single":
+            H, W = rng.randint(400, 3000), rng.randint(400, 3000)
+            K = rng.choice((24, 32, 48, 64, 96, 128, 200))
+            F = rng.choice((3, 4, 5, 6, 7, 8, 9, 10, 11))
+            if K * H * W * 4 <= 3e9:
+                shapes.append((H, W, K, F))
+            continue
+        C = rng.choice((3, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 160, 192, 256, 320, 384, 512))
+        K = rng.choice((16, 32, 48, 64, 80, 96, 112, 128, 160, 192, 224, 256, 288, 320, 384, 448, 512))
+        F = rng.choice((1, 2, 3, 3, 3, 4, 5, 5, 7))
+        H = rng.choice((7, 8, 10, 13, 14, 17, 20, 24, 28, 30, 35, 40, 48, 56, 60, 64, 75, 96, 112,
+                        128, 150, 224))
+        W = H if rng.random() < 0.7 else rng.choice((14, 28, 40, 56, 80, 112, 160))
+        if F > min(H, W):
+            continue
+        Ho, Wo = H - F + 1, W - F + 1
+        N = max(1, min(512, int(rng.choice((0.5e9, 2e9, 8e9, 30e9)) / (2.0 * C * K * F * F * Ho * Wo))))
+        if N * C * H * W * 4 <= 2e9 and N * K * Ho * Wo * 4 <= 2e9:
+            shapes.append((N, C, H, W, K, F))
+    return shapes
+
+
+def random_table(kind: str, seed: int, count: int) -> None:
+    """The library's choice against every tile configuration on shapes drawn at random; the
+    lines of the shapes where the choice is 8 % or more above the fastest, and a summary."""
+    n = _config_count(kind)
+    print(f"# {kind}, {count} random shapes (seed {seed}): microseconds per launch; the library's choice and "
+          f"the fastest of configurations 0..{n - 1} (the ablation excluded); shapes listed where the choice "
+          "is 8 % or more above the fastest")
+    ratios = []
+    for sh in random_shapes(kind, seed, count):
+        rows = tune(kind, sh, steps=6)
+        lib = rows[0][1]
+        cfgs = [None if (kind == "single" and i == 7) else ms for i, (_, ms) in enumerate(rows[1:])]
+        best = min(ms for ms in cfgs if ms is not None)
+        ratios.append(lib / best)
+        if lib / best >= 1.08:
+            print(f"{'x'.join(map(str, sh)):28s} {lib * 1e3:8.1f} {best * 1e3:8.1f}  configuration "
+                  f"{cfgs.index(best):2d}  {lib / best:5.2f}", flush=True)
+    ratios.sort()
+    m = len(ratios)
+    print(f"# library / fastest over {m} shapes: mean {sum(ratios) / m:.3f}, median {ratios[m // 2]:.3f}, "
+          f"90th percentile {ratios[(9 * m) // 10]:.3f}, worst {ratios[-1]:.2f}; "
+          f"{sum(r >= 1.06 for r in ratios)} shapes 6 % or more above the fastest")
+
+
 def writeback_table() -> None:
     """Per shape: the library's choice, the three tile shapes with stores straight from the
     accumulators (configurations 0..2) and with the line-aligned write-back (12..14)."""
@@ -287,6 +345,12 @@ def main(argv):
             print("tune needs a GPU", file=sys.stderr)
             return 2
         writeback_table()
+        return 0
+    if len(argv) == 4 and argv[0] == "random" and argv[1] in ("single", "general"):
+        if not torch.cuda.is_available():
+            print("tune needs a GPU", file=sys.stderr)
+            return 2
+        random_table(argv[1], int(argv[2]), int(argv[3]))
         return 0
     if len(argv) == 2 and argv[0] == "table" and argv[1] in KINDS:
         if not torch.cuda.is_available():
