@@ -203,6 +203,28 @@ int dconv_general_lowp(const void *in, int N, int C, int H, int W,
 int dconv_tile_config_count(int single_channel);
 
 /*
+ * What DCONV_VARIANT_AUTO picks for a shape, decided on the host from the shape
+ * alone: nothing is launched and no GPU is needed.  For tuners, and for tests
+ * that pin the dispatcher's rules (the rules are where the paper's per-device
+ * design-space exploration, Sec. 5 and Table 1, ends up in this library).
+ *   single_channel != 0: the shape of dconv_single_channel (N and C must be 1);
+ *   single_channel == 0: the shape of dconv_general.
+ * Returns the tile configuration i (as in DCONV_VARIANT_TILED_CFG0 + i) of that
+ * entry point's tiled kernel -- for dconv_general the tile shape only, 0 to 2:
+ * how its tiles are shared between workgroups is decided at launch from the
+ * device's CU count -- or one of the negative values below.
+ */
+enum dconv_choice {
+    DCONV_CHOICE_FEW_FILTERS = -1,  /* special case: the vector-ALU kernel for few filters */
+    DCONV_CHOICE_SPECIAL_CASE = -2, /* dconv_general hands the shape to the special-case
+                                       kernel (one channel, or a few with small filters)   */
+    DCONV_CHOICE_SIMPLE = -3,       /* the one-thread-per-output kernel                    */
+    DCONV_CHOICE_INVALID = -4       /* not a valid shape (the entry point would return
+                                       DCONV_BAD_SHAPE)                                    */
+};
+int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int F);
+
+/*
  * HIP graph capture.  Every entry point only enqueues kernels on `stream` (no
  * synchronisation, no host-side reads), so calls can be captured into a graph
  * and replayed.  The one exception is the workspace of dconv_general described

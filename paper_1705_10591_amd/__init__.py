@@ -26,7 +26,7 @@ STATUS_OK, STATUS_NULL_POINTER, STATUS_BAD_SHAPE, STATUS_UNSUPPORTED, STATUS_LAU
 
 EXPORTS = ("dconv_single_channel", "dconv_general", "dconv_single_channel_v",
            "dconv_general_v", "dconv_status_string", "dconv_version",
-           "dconv_tile_config_count", "dconv_release_workspace",
+           "dconv_tile_config_count", "dconv_tile_choice", "dconv_release_workspace",
            "dconv_general_f16", "dconv_general_bf16", "dconv_general_half_v",
            "dconv_general_i8", "dconv_general_i8_v", "dconv_general_lowp", "dconv_general_noalloc")
 DTYPE_F16, DTYPE_BF16, DTYPE_I8 = 0, 1, 2
@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
             getattr(lib, name).restype = i
         lib.dconv_tile_config_count.argtypes = [i]
         lib.dconv_tile_config_count.restype = i
+        lib.dconv_tile_choice.argtypes = [i] * 7
+        lib.dconv_tile_choice.restype = i
         lib.dconv_status_string.argtypes = [i]
         lib.dconv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -83,6 +85,15 @@ def status_string(status: int) -> str:
 def tile_config_count(single_channel: bool) -> int:
     """Number of tile configurations of the tiled kernel (see VARIANT_TILED_CFG0)."""
     return int(load_library().dconv_tile_config_count(1 if single_channel else 0))
+
+
+CHOICE_FEW_FILTERS, CHOICE_SPECIAL_CASE, CHOICE_SIMPLE, CHOICE_INVALID = -1, -2, -3, -4
+
+
+def tile_choice(single_channel: bool, N: int, C: int, H: int, W: int, K: int, F: int) -> int:
+    """What VARIANT_AUTO picks for a shape: a tile configuration (>= 0) or a CHOICE_* value.
+    Host arithmetic only: works without a GPU."""
+    return int(load_library().dconv_tile_choice(1 if single_channel else 0, N, C, H, W, K, F))
 
 
 def release_workspace() -> None:

@@ -189,6 +189,26 @@ int dconv_tile_config_count(int single_channel)
     return single_channel ? dconv::single_tile_configs() : dconv::general_tile_configs();
 }
 
+int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int F)
+{
+    Shape s;
+    const int dummy = 0;       // (validate only tests its pointers against null)
+    if (validate(&dummy, &dummy, &dummy, N, C, H, W, K, F, &s) != DCONV_OK ||
+        (single_channel && (N != 1 || C != 1)))
+        return DCONV_CHOICE_INVALID;
+    // the routing of general_entry and dispatch for DCONV_VARIANT_AUTO
+    const bool special = single_channel || (N == 1 && C == 1) || dconv::single_batch_preferred(s) ||
+                         (dconv::single_tiled_supports(s) && !dconv::general_tiled_supports(s));
+    if (special) {
+        if (dconv::single_few_preferred(s)) return DCONV_CHOICE_FEW_FILTERS;
+        if (!dconv::single_tiled_supports(s)) return DCONV_CHOICE_SIMPLE;
+        if (!single_channel) return DCONV_CHOICE_SPECIAL_CASE;
+        return dconv::single_auto_config(s);
+    }
+    if (!dconv::general_tiled_supports(s)) return DCONV_CHOICE_SIMPLE;
+    return dconv::general_auto_shape(s);
+}
+
 int dconv_release_workspace(void)
 {
     dconv::release_general_workspaces();

@@ -64,6 +64,10 @@ int launch_general_tiled(const float* in, const float* filt, float* out, const S
                          hipStream_t st, int cfg, bool static_ws);
 int single_tile_configs();
 int general_tile_configs();
+// what the dispatchers pick by shape: the special case's tile configuration, the general case's
+// tile shape (pure host arithmetic)
+int single_auto_config(const Shape& s);
+int general_auto_shape(const Shape& s);
 int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st);
 bool single_few_supports(const Shape& s);      // the few-filters kernel can run the shape
 bool single_few_preferred(const Shape& s);     // ... and is the better choice for it

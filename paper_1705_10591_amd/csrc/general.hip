@@ -240,6 +240,8 @@ int shape_for(const Shape& s)
 
 int general_tile_configs() { return kShapes * kSchedules * kWriteBacks; }
 
+int general_auto_shape(const Shape& s) { return shape_for(s); }
+
 namespace {
 
 bool whole_batch_supported(const Shape& s)

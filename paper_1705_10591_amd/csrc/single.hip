@@ -26,101 +26,107 @@ namespace {
 // filters (single_blocks16_preferred below).
 constexpr int kSingleConfigs = 11;
 
+// The configuration by shape (what launch_F runs when none is forced).
+int auto_config(const Shape& s)
+{
+    int cfg;
+    // (work items of all images count: a batch of small images fills the chip like one
+    // large image)
+    const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4 * s.N;
+    auto items = [&](int tw, int tr) {
+        return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
+    };
+    // Imbalance of a tile shape: the workgroups of the fullest CU over the mean per CU, tiles
+    // counted by their passes (the last tile column may hold fewer than the others).  The
+    // hardware deals workgroups evenly, so a launch of 534 wide tiles takes as long as one of
+    // 768 (a handful of tiles beyond a multiple of the CUs is not counted as a round: those
+    // run on CUs that have little else left).  `round_up` says how much of the last,
+    // partly filled round counts: all of it for the wide tiles, less for the small ones,
+    // which are dealt as slots fall free.  For filters bound by the matrix cores this factor
+    // predicts the measured time per pixel of 512-pixel tiles on 720 x 1280 .. 3000 x 3000
+    // images within a few per cent.
+    auto imbalance = [&](int tw, int tr, int pass, double round_up) {
+        constexpr double kCUs = 256;
+        const int64_t cols = (s.Wo + tw - 1) / tw, rows = (s.Ho + tr - 1) / tr;
+        const int64_t per_tile = tw / pass;
+        const int64_t last = (s.Wo - tw * (cols - 1) + pass - 1) / pass;
+        const double mean = (double)(rows * fgroups * (per_tile * (cols - 1) + last)) /
+                            ((double)per_tile * kCUs);
+        const double per_cu = std::max(1.0, (double)(cols * rows * fgroups) / kCUs);
+        const double full = std::max(1.0, std::ceil(per_cu - 0.05));
+        return (full > per_cu ? per_cu + round_up * (full - per_cu) : full) / mean;
+    };
+    // (128 x 4 with passes of 32 pixels, or 256 x 2: whichever divides the image more evenly)
+    auto small_tile = [&](double bias) {
+        return imbalance(128, 4, 32, 0.0) < bias * imbalance(256, 2, 128, 0.75) ? 6 : 3;
+    };
+    // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
+    const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
+    if (single_blocks16_preferred(s)) {
+        // (the small tile with short passes for 3x3 on mid-sized images, as for 32-filter
+        // blocks, where 512-pixel tile columns would overhang the image by 15 % or more, and
+        // where there are too few wide tiles for the CUs: 600 x 1000, 5x5: 20 -> 17 us)
+        const bool overhang = (int64_t)((s.Wo + 511) / 512) * 512 * 100 >= (int64_t)s.Wo * 115;
+        const bool uneven = imbalance(512, 4, 128, 1.0) > 1.5;
+        cfg = ((s.F == 3 && (int64_t)s.Ho * s.Wo < 3000000) || overhang || uneven) ? 10 : 9;
+    } else if (items(128, 4) <= 320 && items(64, 4) > items(128, 4)) {
+        // so few 128-pixel tiles that CUs would stay without a workgroup (up to about 384 x 384
+        // with one filter group): 64-pixel tiles, twice the workgroups, half the passes per wave
+        // (256 x 256, 16 filters of 3 x 3: 7.1 -> 5.8 us per launch replayed from a graph)
+        cfg = 8;
+    } else if (s.Wo >= 96 && s.Wo < 200) {
+        // rows too short for a 160-pixel pass to complete their ends across rows: passes of
+        // 64 pixels (from 128 pixels of width on) or of 32, whichever computes fewer blocks
+        // per row (1.2 to 1.7 times faster than the wider passes there)
+        cfg = short_pass_config(s.Wo);
+    } else if (s.K <= 32 && t128 < ((s.F <= 4 && s.K > 16) ? 8192 : 1536)) {
+        // one filter block: the four waves of a workgroup take one row each, and on images up
+        // to about 768^2 (1080p for a full block of small filters) the smallest tile is the
+        // shortest chain of latencies; with passes of 64 pixels the stores of a wave begin
+        // earlier still (5 to 16 % over passes of 128); with up to 16 filters or from 5x5 on,
+        // passes of 32 pixels are a few per cent faster again
+        cfg = (s.K <= 16 || s.F >= 5) ? 6 : 5;
+    } else if (s.K <= 32 && s.F < 8 && s.Wo < 3072) {
+        cfg = (s.F >= 5 && imbalance(512, 4, 128, 1.0) > 1.25) ? 6 : 0;
+    } else if (s.F <= 4) {
+        // (mid-sized problems: 256 x 2, or with up to 64 filters 128 x 4 with short passes)
+        cfg = items(512, 4) < 1280 ? (s.K <= 64 ? 5 : 3) : 0;
+    } else if (items(512, 4) < 384) {
+        cfg = small_tile(1.0);
+    } else if (s.F >= 8) {
+        // bound by the matrix cores: the time of a tile shape is its cost per pixel (relative
+        // to 512 x 4, measured on 3000 x 3000 images) times its imbalance.  The taller tile
+        // pays only with several workgroups per CU and, with more than one filter block, must
+        // win by a margin: its model is the least exact there.
+        const double wide = imbalance(512, 4, 128, 1.0);
+        const bool one_block = s.K <= 32;  // (each wave then takes whole rows of the tile)
+        double tall = 1e9, small;
+        if (one_block) {
+            if (items(512, 8) >= 380) tall = 0.95 * imbalance(512, 8, 128, 1.0);
+            small = s.F == 8 ? 1.40 : s.F >= 11 ? 1.30 : 1.25;
+        } else {
+            if (items(512, 8) >= 920)
+                tall = 1.05 * (s.F == 8 ? 0.99 : 0.95) * imbalance(512, 8, 128, 1.0);
+            small = s.F == 8 ? 1.30 : s.F >= 11 ? 1.25 : 1.20;
+        }
+        if (small < wide && small < tall) cfg = s.F >= 11 ? 5 : 6;
+        else cfg = tall < wide ? 2 : 0;
+    } else {
+        // 5x5 .. 7x7: a small tile where the wide one would leave CUs idle (7x7 is bound by
+        // the matrix cores and tolerates a little more)
+        const int64_t it = items(512, 4);
+        const bool mid = it >= 520 && it < (s.F == 7 ? 4200 : 2000);
+        cfg = (mid && imbalance(512, 4, 128, 1.0) > (s.F == 7 ? 1.25 : 1.20)) ? small_tile(0.95) : 0;
+    }
+    return cfg;
+}
+
 template <int F>
 int launch_F(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st,
              int cfg)
 {
     if (cfg >= kSingleConfigs) return DCONV_UNSUPPORTED;
-    if (cfg < 0) {
-        // (work items of all images count: a batch of small images fills the chip like one
-        // large image)
-        const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4 * s.N;
-        auto items = [&](int tw, int tr) {
-            return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
-        };
-        // Imbalance of a tile shape: the workgroups of the fullest CU over the mean per CU, tiles
-        // counted by their passes (the last tile column may hold fewer than the others).  The
-        // hardware deals workgroups evenly, so a launch of 534 wide tiles takes as long as one of
-        // 768 (a handful of tiles beyond a multiple of the CUs is not counted as a round: those
-        // run on CUs that have little else left).  `round_up` says how much of the last,
-        // partly filled round counts: all of it for the wide tiles, less for the small ones,
-        // which are dealt as slots fall free.  For filters bound by the matrix cores this factor
-        // predicts the measured time per pixel of 512-pixel tiles on 720 x 1280 .. 3000 x 3000
-        // images within a few per cent.
-        auto imbalance = [&](int tw, int tr, int pass, double round_up) {
-            constexpr double kCUs = 256;
-            const int64_t cols = (s.Wo + tw - 1) / tw, rows = (s.Ho + tr - 1) / tr;
-            const int64_t per_tile = tw / pass;
-            const int64_t last = (s.Wo - tw * (cols - 1) + pass - 1) / pass;
-            const double mean = (double)(rows * fgroups * (per_tile * (cols - 1) + last)) /
-                                ((double)per_tile * kCUs);
-            const double per_cu = std::max(1.0, (double)(cols * rows * fgroups) / kCUs);
-            const double full = std::max(1.0, std::ceil(per_cu - 0.05));
-            return (full > per_cu ? per_cu + round_up * (full - per_cu) : full) / mean;
-        };
-        // (128 x 4 with passes of 32 pixels, or 256 x 2: whichever divides the image more evenly)
-        auto small_tile = [&](double bias) {
-            return imbalance(128, 4, 32, 0.0) < bias * imbalance(256, 2, 128, 0.75) ? 6 : 3;
-        };
-        // measured with the tile search (paper_1705_10591_amd.tune) on 256^2 .. 4096^2 images
-        const int64_t t128 = (int64_t)((s.Wo + 127) / 128) * ((s.Ho + 3) / 4) * s.N;
-        if (single_blocks16_preferred(s)) {
-            // (the small tile with short passes for 3x3 on mid-sized images, as for 32-filter
-            // blocks, where 512-pixel tile columns would overhang the image by 15 % or more, and
-            // where there are too few wide tiles for the CUs: 600 x 1000, 5x5: 20 -> 17 us)
-            const bool overhang = (int64_t)((s.Wo + 511) / 512) * 512 * 100 >= (int64_t)s.Wo * 115;
-            const bool uneven = imbalance(512, 4, 128, 1.0) > 1.5;
-            cfg = ((s.F == 3 && (int64_t)s.Ho * s.Wo < 3000000) || overhang || uneven) ? 10 : 9;
-        } else if (items(128, 4) <= 320 && items(64, 4) > items(128, 4)) {
-            // so few 128-pixel tiles that CUs would stay without a workgroup (up to about 384 x 384
-            // with one filter group): 64-pixel tiles, twice the workgroups, half the passes per wave
-            // (256 x 256, 16 filters of 3 x 3: 7.1 -> 5.8 us per launch replayed from a graph)
-            cfg = 8;
-        } else if (s.Wo >= 96 && s.Wo < 200) {
-            // rows too short for a 160-pixel pass to complete their ends across rows: passes of
-            // 64 pixels (from 128 pixels of width on) or of 32, whichever computes fewer blocks
-            // per row (1.2 to 1.7 times faster than the wider passes there)
-            cfg = short_pass_config(s.Wo);
-        } else if (s.K <= 32 && t128 < ((F <= 4 && s.K > 16) ? 8192 : 1536)) {
-            // one filter block: the four waves of a workgroup take one row each, and on images up
-            // to about 768^2 (1080p for a full block of small filters) the smallest tile is the
-            // shortest chain of latencies; with passes of 64 pixels the stores of a wave begin
-            // earlier still (5 to 16 % over passes of 128); with up to 16 filters or from 5x5 on,
-            // passes of 32 pixels are a few per cent faster again
-            cfg = (s.K <= 16 || F >= 5) ? 6 : 5;
-        } else if (s.K <= 32 && F < 8 && s.Wo < 3072) {
-            cfg = (F >= 5 && imbalance(512, 4, 128, 1.0) > 1.25) ? 6 : 0;
-        } else if (F <= 4) {
-            // (mid-sized problems: 256 x 2, or with up to 64 filters 128 x 4 with short passes)
-            cfg = items(512, 4) < 1280 ? (s.K <= 64 ? 5 : 3) : 0;
-        } else if (items(512, 4) < 384) {
-            cfg = small_tile(1.0);
-        } else if (F >= 8) {
-            // bound by the matrix cores: the time of a tile shape is its cost per pixel (relative
-            // to 512 x 4, measured on 3000 x 3000 images) times its imbalance.  The taller tile
-            // pays only with several workgroups per CU and, with more than one filter block, must
-            // win by a margin: its model is the least exact there.
-            const double wide = imbalance(512, 4, 128, 1.0);
-            const bool one_block = s.K <= 32;  // (each wave then takes whole rows of the tile)
-            double tall = 1e9, small;
-            if (one_block) {
-                if (items(512, 8) >= 380) tall = 0.95 * imbalance(512, 8, 128, 1.0);
-                small = F == 8 ? 1.40 : F >= 11 ? 1.30 : 1.25;
-            } else {
-                if (items(512, 8) >= 920)
-                    tall = 1.05 * (F == 8 ? 0.99 : 0.95) * imbalance(512, 8, 128, 1.0);
-                small = F == 8 ? 1.30 : F >= 11 ? 1.25 : 1.20;
-            }
-            if (small < wide && small < tall) cfg = F >= 11 ? 5 : 6;
-            else cfg = tall < wide ? 2 : 0;
-        } else {
-            // 5x5 .. 7x7: a small tile where the wide one would leave CUs idle (7x7 is bound by
-            // the matrix cores and tolerates a little more)
-            const int64_t it = items(512, 4);
-            const bool mid = it >= 520 && it < (F == 7 ? 4200 : 2000);
-            cfg = (mid && imbalance(512, 4, 128, 1.0) > (F == 7 ? 1.25 : 1.20)) ? small_tile(0.95) : 0;
-        }
-    }
+    if (cfg < 0) cfg = auto_config(s);
     // (the small tiles keep three waves per SIMD in registers up to 8x8; beyond, the filter
     // operands of all taps would spill)
     constexpr int WS = F >= 9 ? 2 : 3;
@@ -188,6 +194,8 @@ bool single_batch_preferred(const Shape& s)
 }
 
 int single_tile_configs() { return kSingleConfigs; }
+
+int single_auto_config(const Shape& s) { return auto_config(s); }
 
 int launch_single_tiled(const float* img, const float* filt, float* out, const Shape& s,
                         hipStream_t st, int cfg)

@@ -877,6 +877,51 @@ def test_sixteen_filter_blocks_where_the_library_picks_them():
             assert_within_bound(vals, acc, mag, f"16-filter blocks {(H, W, K, F)}")
 
 
+def _variant_of_choice(c):
+    return {dconv.CHOICE_FEW_FILTERS: dconv.VARIANT_FEW_FILTERS, dconv.CHOICE_SPECIAL_CASE: dconv.VARIANT_SPECIAL_CASE,
+            dconv.CHOICE_SIMPLE: dconv.VARIANT_SIMPLE}.get(c, dconv.VARIANT_TILED_CFG0 + c)
+
+
+def test_the_reported_choice_is_what_the_library_runs():
+    """dconv_tile_choice names, on the host, the kernel and configuration the plain entry points
+    launch: forcing what it names gives the plain call's output bit for bit (every kernel sums in
+    an order that its configuration fixes), and the outputs are within the bound of the oracle.
+    One shape for every branch of the dispatchers' rules that a small problem can reach."""
+    single = [(256, 256, 16, 3), (300, 420, 3, 5), (700, 900, 12, 5), (600, 800, 64, 7), (720, 1280, 40, 9),
+              (150, 2000, 64, 3), (512, 512, 32, 3), (640, 640, 128, 5), (96, 96, 8, 13), (1100, 1100, 8, 3),
+              (800, 800, 96, 5), (1024, 1024, 16, 5)]
+    general = [(2, 64, 30, 30, 64, 3), (3, 32, 20, 20, 32, 3), (2, 64, 40, 40, 96, 3), (1, 256, 14, 14, 256, 3),
+               (1, 128, 20, 20, 128, 7), (4, 128, 17, 14, 192, 1), (8, 8, 60, 60, 64, 2), (2, 64, 30, 30, 128, 2),
+               (40, 16, 7, 7, 64, 3), (2, 2, 200, 200, 16, 3), (1, 1, 200, 200, 64, 3), (2, 16, 20, 20, 8, 12),
+               (16, 8, 96, 96, 64, 3)]
+    seen = set()
+    for i, (H, W, K, F) in enumerate(single):
+        x, f = wl.random_case(3100 + i, 1, 1, H, W, K, F)
+        c = dconv.tile_choice(True, 1, 1, H, W, K, F)
+        seen.add(("single", min(c, 0) if c < 0 else c))
+        got = dconv.dconv_single_channel(dev(x[0, 0]), dev(f[:, 0]))
+        forced = dconv.dconv_single_channel(dev(x[0, 0]), dev(f[:, 0]), variant=_variant_of_choice(c))
+        torch.cuda.synchronize()
+        assert torch.equal(got, forced), f"single-channel {(H, W, K, F)}: choice {c}"
+        acc, mag, _ = oracle.general(x, f)
+        assert_within_bound(got.cpu().numpy(), acc[0], mag[0], f"single-channel {(H, W, K, F)}")
+    for i, (N, C, H, W, K, F) in enumerate(general):
+        x, f = wl.random_case(3200 + i, N, C, H, W, K, F)
+        c = dconv.tile_choice(False, N, C, H, W, K, F)
+        seen.add(("general", c))
+        got = dconv.dconv_general(dev(x), dev(f))
+        forced = dconv.dconv_general(dev(x), dev(f), variant=_variant_of_choice(c))
+        torch.cuda.synchronize()
+        assert torch.equal(got, forced), f"general {(N, C, H, W, K, F)}: choice {c}"
+        acc, mag, _ = oracle.general(x, f)
+        assert_within_bound(got.cpu().numpy(), acc, mag, f"general {(N, C, H, W, K, F)}")
+    # the shapes reach the three tile shapes and the other kernels of both entry points
+    assert {("general", 0), ("general", 1), ("general", 2), ("general", dconv.CHOICE_SPECIAL_CASE),
+            ("general", dconv.CHOICE_SIMPLE), ("single", dconv.CHOICE_FEW_FILTERS),
+            ("single", dconv.CHOICE_SIMPLE)} <= seen, seen
+    assert len({c for k, c in seen if k == "single" and c >= 0}) >= 5, seen
+
+
 @pytest.mark.parametrize("side", [24000, 23100])
 def test_single_channel_huge_images_sampled(side):
     """One 24000 x 24000 image (2.3 GB: input rows beyond 2 GiB, more than 4 GiB of output) on the
