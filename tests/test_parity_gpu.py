@@ -877,6 +877,31 @@ def test_sixteen_filter_blocks_where_the_library_picks_them():
             assert_within_bound(vals, acc, mag, f"16-filter blocks {(H, W, K, F)}")
 
 
+@pytest.mark.parametrize("shape", [(1, 512, 14, 14, 512, 3), (1, 384, 20, 20, 192, 7), (4, 512, 17, 14, 448, 1),
+                                   (2, 256, 9, 31, 96, 5), (1, 192, 12, 50, 160, 2), (3, 128, 28, 28, 64, 3),
+                                   (1, 96, 33, 47, 320, 4), (2, 64, 10, 12, 256, 9)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_fewer_tiles_than_cus_integer_inputs_bit_exact(shape):
+    """Small batches of deep layers: fewer tiles than CUs, so the launch shares every tile between a
+    number of workgroups that it picks from the shape (ranges of chunks that start and end inside
+    tiles, parts summed by the workgroup that arrives last).  Integer inputs, so every order of
+    summation gives the same bits as the oracle; guard bands; each launch twice, because the
+    counters of the shared tiles have to be back at zero for the next launch."""
+    N, C, H, W, K, F = shape
+    x, f = wl.integer_case(4100 + C + K, N, C, H, W, K, F)
+    acc, _, _ = oracle.general(x, f)
+    want = acc.astype(np.float32)
+    xd, fd = dev(x), dev(f)
+    for v in [dconv.VARIANT_AUTO] + [dconv.VARIANT_TILED_CFG0 + i for i in range(3)]:
+        for rep in range(2):
+            buf = torch.full((want.size + 2048,), float("nan"), device="cuda")
+            out = buf[1024:1024 + want.size].view(want.shape)
+            dconv.dconv_general(xd, fd, out=out, variant=v)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want), f"{shape} variant {v:#x} launch {rep}"
+            assert torch.isnan(buf[:1024]).all() and torch.isnan(buf[1024 + want.size:]).all(), f"{shape}: guard bands"
+
+
 def _variant_of_choice(c):
     return {dconv.CHOICE_FEW_FILTERS: dconv.VARIANT_FEW_FILTERS, dconv.CHOICE_SPECIAL_CASE: dconv.VARIANT_SPECIAL_CASE,
             dconv.CHOICE_SIMPLE: dconv.VARIANT_SIMPLE}.get(c, dconv.VARIANT_TILED_CFG0 + c)
