@@ -215,6 +215,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1010; }
+int dconv_version(void) { return 1011; }
 
 }  // extern "C"
