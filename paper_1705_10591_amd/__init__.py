@@ -87,7 +87,7 @@ def tile_config_count(single_channel: bool) -> int:
     return int(load_library().dconv_tile_config_count(1 if single_channel else 0))
 
 
-CHOICE_FEW_FILTERS, CHOICE_SPECIAL_CASE, CHOICE_SIMPLE, CHOICE_INVALID = -1, -2, -3, -4
+CHOICE_FEW_FILTERS, CHOICE_SPECIAL_CASE, CHOICE_SIMPLE, CHOICE_INVALID, CHOICE_GENERAL_CASE = -1, -2, -3, -4, -5
 
 
 def tile_choice(single_channel: bool, N: int, C: int, H: int, W: int, K: int, F: int) -> int:

@@ -19,7 +19,7 @@ BUILD = PKG / "_build"
 SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", [], "single"), ("single_fewfilters.hip", [], "single_fewfilters"),
            *[("single_multi_inst.hip", [f"-DDCONV_C={c}"], f"single_c{c}") for c in (2, 3, 4)],
            ("general.hip", [], "general")] + \
-          [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 12)] + \
+          [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 33)] + \
           [("half.hip", [], "half")] + \
           [("half_inst.hip", [f"-DDCONV_F={f}"], f"half_f{f}") for f in range(1, 12)]
 

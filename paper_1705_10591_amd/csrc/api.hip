@@ -39,6 +39,9 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
     switch (variant) {
     case DCONV_VARIANT_AUTO:
         if (single && dconv::single_few_preferred(s)) return dconv::launch_single_few(in, filt, out, s, st);
+        // (filters beyond the special case's 11 x 11: the general kernel takes one channel too)
+        if (single && !tiled_ok && dconv::general_tiled_supports(s))
+            return dconv::launch_general_tiled(in, filt, out, s, st, -1, static_ws);
         return tiled_ok ? tiled(-1) : dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_FEW_FILTERS:
         if (!single || !dconv::single_few_supports(s)) return DCONV_UNSUPPORTED;
@@ -201,7 +204,8 @@ int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int
                          (dconv::single_tiled_supports(s) && !dconv::general_tiled_supports(s));
     if (special) {
         if (dconv::single_few_preferred(s)) return DCONV_CHOICE_FEW_FILTERS;
-        if (!dconv::single_tiled_supports(s)) return DCONV_CHOICE_SIMPLE;
+        if (!dconv::single_tiled_supports(s))
+            return dconv::general_tiled_supports(s) ? DCONV_CHOICE_GENERAL_CASE : DCONV_CHOICE_SIMPLE;
         if (!single_channel) return DCONV_CHOICE_SPECIAL_CASE;
         return dconv::single_auto_config(s);
     }

@@ -178,6 +178,27 @@ int launch_any(const float* in, const float* filt, float* out, const Shape& s, h
     case 9: return gen_launch_for_F<9>(in, filt, out, s, st, tile_cfg, sched, dry);
     case 10: return gen_launch_for_F<10>(in, filt, out, s, st, tile_cfg, sched, dry);
     case 11: return gen_launch_for_F<11>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 12: return gen_launch_for_F<12>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 13: return gen_launch_for_F<13>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 14: return gen_launch_for_F<14>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 15: return gen_launch_for_F<15>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 16: return gen_launch_for_F<16>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 17: return gen_launch_for_F<17>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 18: return gen_launch_for_F<18>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 19: return gen_launch_for_F<19>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 20: return gen_launch_for_F<20>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 21: return gen_launch_for_F<21>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 22: return gen_launch_for_F<22>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 23: return gen_launch_for_F<23>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 24: return gen_launch_for_F<24>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 25: return gen_launch_for_F<25>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 26: return gen_launch_for_F<26>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 27: return gen_launch_for_F<27>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 28: return gen_launch_for_F<28>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 29: return gen_launch_for_F<29>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 30: return gen_launch_for_F<30>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 31: return gen_launch_for_F<31>(in, filt, out, s, st, tile_cfg, sched, dry);
+    case 32: return gen_launch_for_F<32>(in, filt, out, s, st, tile_cfg, sched, dry);
     default: return DCONV_UNSUPPORTED;
     }
 }

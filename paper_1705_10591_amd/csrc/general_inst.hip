@@ -19,7 +19,7 @@ constexpr int F = DCONV_F;
 constexpr int kChunkBig = F == 1 ? 16 : F == 2 ? 8 : F == 3 ? 4 : F == 4 ? 2 : 1;
 constexpr int kChunkSmall = F == 1 ? 4 : F == 2 ? 2 : F == 3 ? 3 : 1;   // 3: RGB inputs
 // filter rows per chunk: whole filters up to 5x5, groups of rows above (see GenGeom)
-constexpr int kRowGroup = F <= 5 ? F : F == 6 ? 3 : F == 9 ? 3 : F == 10 ? 5 : 4;
+constexpr int kRowGroup = F <= 5 ? F : F == 6 ? 3 : F == 9 ? 3 : F == 10 ? 5 : F <= 12 ? 4 : F <= 16 ? 3 : F <= 24 ? 2 : 1;
 // image words a thread stages per chunk: eight cover a 256-pixel tile of the widest column
 // strips with its halo rows; 1x1 filters (sixteen channels per chunk) take sixteen, and the
 // larger filters have a second set of kernels with sixteen for shapes (tiny maps, where a

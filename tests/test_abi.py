@@ -69,7 +69,7 @@ def test_unknown_variant_and_unsupported_tiled_shape():
     lib = dconv.load_library()
     assert lib.dconv_general_v(FAKE, 1, 1, 8, 8, FAKE, 1, 3, FAKE, 99, None) == dconv.STATUS_UNSUPPORTED
     # filter side above the largest compiled tiled kernel
-    assert lib.dconv_general_v(FAKE, 1, 1, 32, 32, FAKE, 1, 13, FAKE, dconv.VARIANT_TILED, None) \
+    assert lib.dconv_general_v(FAKE, 1, 1, 64, 64, FAKE, 1, 33, FAKE, dconv.VARIANT_TILED, None) \
         == dconv.STATUS_UNSUPPORTED
     assert lib.dconv_single_channel_v(FAKE, 32, 32, FAKE, 1, 13, FAKE, dconv.VARIANT_TILED, None) \
         == dconv.STATUS_UNSUPPORTED
@@ -107,7 +107,7 @@ def test_two_threads_in_the_dispatcher_at_once():
             N, C, H, W, K, F = shapes[(rep + t) % len(shapes)]
             seen[t].add(lib.dconv_general(FAKE, N, C, H, W, FAKE, K, F, FAKE, None))
             seen[t].add(10 + lib.dconv_general(FAKE, N, C, F - 1, W, FAKE, K, F, FAKE, None))
-            seen[t].add(20 + lib.dconv_general_v(FAKE, N, C, H, W, FAKE, K, 13, FAKE, dconv.VARIANT_TILED, None))
+            seen[t].add(20 + lib.dconv_general_v(FAKE, N, C, 64, 64, FAKE, K, 33, FAKE, dconv.VARIANT_TILED, None))
 
     threads = [threading.Thread(target=worker, args=(t,)) for t in range(2)]
     for th in threads:

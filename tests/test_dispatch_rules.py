@@ -75,8 +75,10 @@ def test_other_kernels_by_shape():
     assert choice(True, 1, 1, 2048, 2048, 8, 3) == dconv.CHOICE_FEW_FILTERS
     assert choice(True, 1, 1, 768, 768, 16, 3) >= 0            # too small an image for sixteen
     # filters beyond the compiled sides
-    assert choice(True, 1, 1, 512, 512, 8, 13) == dconv.CHOICE_SIMPLE
-    assert choice(False, 4, 64, 56, 56, 64, 13) == dconv.CHOICE_SIMPLE
+    assert choice(True, 1, 1, 512, 512, 8, 13) == dconv.CHOICE_GENERAL_CASE
+    assert choice(True, 1, 1, 512, 512, 8, 33) == dconv.CHOICE_SIMPLE
+    assert choice(False, 4, 64, 56, 56, 64, 13) >= 0
+    assert choice(False, 4, 64, 56, 56, 64, 33) == dconv.CHOICE_SIMPLE
     # dconv_general with one channel, or a few with small filters and a large output
     assert choice(False, 1, 1, 512, 512, 64, 3) == dconv.CHOICE_SPECIAL_CASE
     assert choice(False, 16, 1, 512, 512, 64, 3) == dconv.CHOICE_SPECIAL_CASE
@@ -95,18 +97,19 @@ def test_invalid_shapes(args):
 
 def test_every_answer_is_a_configuration_or_a_named_choice():
     rng = random.Random(1705)
-    named = {dconv.CHOICE_FEW_FILTERS, dconv.CHOICE_SPECIAL_CASE, dconv.CHOICE_SIMPLE}
+    named = {dconv.CHOICE_FEW_FILTERS, dconv.CHOICE_SPECIAL_CASE, dconv.CHOICE_SIMPLE, dconv.CHOICE_GENERAL_CASE}
     n_single, n_general = dconv.tile_config_count(True), dconv.tile_config_count(False)
     for _ in range(3000):
         H, W = rng.randint(1, 5000), rng.randint(1, 5000)
-        K, F = rng.randint(1, 300), rng.randint(1, 13)
+        K, F = rng.randint(1, 300), rng.randint(1, 36)
         c = choice(True, 1, 1, H, W, K, F)
         if F > min(H, W) or K * (H - F + 1) * (W - F + 1) > 2**31 - 1:
             assert c == dconv.CHOICE_INVALID
         else:
             assert c in named - {dconv.CHOICE_SPECIAL_CASE} or 0 <= c < n_single, (H, W, K, F, c)
             assert c != 7              # the width-matching ablation is never chosen by shape
-            assert (c == dconv.CHOICE_SIMPLE) == (F > 11), (H, W, K, F, c)
+            assert (c in (dconv.CHOICE_SIMPLE, dconv.CHOICE_GENERAL_CASE)) == (F > 11), (H, W, K, F, c)
+            assert (c == dconv.CHOICE_SIMPLE) <= (F > 32), (H, W, K, F, c)
         N, C = rng.randint(1, 64), rng.randint(1, 600)
         H, W = rng.randint(1, 300), rng.randint(1, 300)
         c = choice(False, N, C, H, W, K, F)
@@ -121,8 +124,10 @@ def test_rules_that_hold_for_every_shape():
     rng = random.Random(10591)
     for _ in range(2000):
         N, C = rng.randint(1, 64), rng.randint(5, 600)
-        H, W = rng.randint(12, 200), rng.randint(12, 200)
-        K, F = rng.randint(1, 600), rng.randint(2, 11)
+        H, W = rng.randint(12, 200), rng.randint(12, 200)   # (some too small for the filter drawn below)
+        K, F = rng.randint(1, 600), rng.randint(2, 32)
+        if F > min(H, W):
+            continue
         c = choice(False, N, C, H, W, K, F)
         assert c >= 0, (N, C, H, W, K, F, c)
         if K <= 32:

@@ -272,14 +272,14 @@ def test_single_channel_integer_inputs_are_bit_exact(shape):
 
 
 def test_filter_side_without_a_tiled_kernel_falls_back():
-    x, f = wl.random_case(3, 1, 2, 20, 20, 3, 13)
+    x, f = wl.random_case(3, 1, 2, 40, 40, 3, 33)        # the tiled kernels end at 32 x 32
     acc, mag, _ = oracle.general(x, f)
-    assert_within_bound(run_general(x, f, AUTO), acc, mag, "F=13 auto")
+    assert_within_bound(run_general(x, f, AUTO), acc, mag, "F=33 auto")
     with pytest.raises(dconv.DconvError) as e:
         run_general(x, f, TILED)
     assert e.value.status == dconv.STATUS_UNSUPPORTED
     acc, mag, _ = oracle.single_channel(x[0, 0], f[:, 0])
-    assert_within_bound(run_single(x[0, 0], f[:, 0], AUTO), acc, mag, "F=13 single auto")
+    assert_within_bound(run_single(x[0, 0], f[:, 0], AUTO), acc, mag, "F=33 single auto")
 
 
 def test_single_channel_agrees_with_general_on_one_image_one_channel():
@@ -902,6 +902,42 @@ def test_fewer_tiles_than_cus_integer_inputs_bit_exact(shape):
             assert torch.isnan(buf[:1024]).all() and torch.isnan(buf[1024 + want.size:]).all(), f"{shape}: guard bands"
 
 
+LARGE_FILTER_SHAPES = [(2, 3, 30, 40, 70, 13), (1, 8, 20, 50, 33, 12), (2, 16, 18, 18, 64, 16), (1, 2, 40, 41, 130, 14),
+                       (3, 5, 15, 140, 9, 15), (1, 64, 16, 16, 40, 16), (1, 1, 70, 300, 24, 13), (4, 1, 33, 29, 5, 12),
+                       (1, 3, 40, 60, 33, 17), (2, 4, 30, 70, 20, 21), (1, 2, 45, 50, 64, 24), (1, 1, 64, 200, 12, 25),
+                       (1, 8, 36, 36, 70, 31), (2, 1, 40, 90, 16, 32), (1, 16, 34, 34, 8, 32), (1, 1, 50, 50, 3, 19)]
+
+
+@pytest.mark.parametrize("shape", LARGE_FILTER_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_filters_of_12_to_32_on_the_general_kernel(shape):
+    """Filters beyond 11 x 11 (up to 32 x 32) run on the general-case kernel, one to four filter
+    rows of one channel per chunk: every tile shape and schedule against the oracle, integer inputs
+    bit for bit, guard bands; with one channel and one image also through dconv_single_channel,
+    which hands such filters to the same kernel."""
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(5200 + F + K, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    xi, fi = wl.integer_case(5300 + F + K, N, C, H, W, K, F)
+    want = oracle.general(xi, fi)[0].astype(np.float32)
+    assert dconv.tile_choice(False, N, C, H, W, K, F) >= 0 or (N == 1 and C == 1)
+    for v in [AUTO, dconv.VARIANT_TILED] + [dconv.VARIANT_TILED_CFG0 + i for i in range(12)]:
+        assert_within_bound(run_general(x, f, v), acc, mag, f"general {shape} variant {v:#x}")
+        buf = torch.full((want.size + 2048,), float("nan"), device="cuda")
+        out = buf[1024:1024 + want.size].view(want.shape)
+        dconv.dconv_general(dev(xi), dev(fi), out=out, variant=v)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want), f"{shape} variant {v:#x}: integer inputs"
+        assert torch.isnan(buf[:1024]).all() and torch.isnan(buf[1024 + want.size:]).all(), f"{shape}: guard bands"
+    if N == 1 and C == 1:
+        assert dconv.tile_choice(True, 1, 1, H, W, K, F) == dconv.CHOICE_GENERAL_CASE
+        got = run_single(x[0, 0], f[:, 0], AUTO)
+        assert_within_bound(got, acc[0], mag[0], f"single-channel {shape}")
+        assert np.array_equal(run_single(xi[0, 0], fi[:, 0], AUTO), want[0])
+        with pytest.raises(dconv.DconvError) as e:          # the special case's own kernels end at 11 x 11
+            run_single(x[0, 0], f[:, 0], dconv.VARIANT_TILED)
+        assert e.value.status == dconv.STATUS_UNSUPPORTED
+
+
 def _variant_of_choice(c):
     return {dconv.CHOICE_FEW_FILTERS: dconv.VARIANT_FEW_FILTERS, dconv.CHOICE_SPECIAL_CASE: dconv.VARIANT_SPECIAL_CASE,
             dconv.CHOICE_SIMPLE: dconv.VARIANT_SIMPLE}.get(c, dconv.VARIANT_TILED_CFG0 + c)
@@ -913,19 +949,22 @@ def test_the_reported_choice_is_what_the_library_runs():
     an order that its configuration fixes), and the outputs are within the bound of the oracle.
     One shape for every branch of the dispatchers' rules that a small problem can reach."""
     single = [(256, 256, 16, 3), (300, 420, 3, 5), (700, 900, 12, 5), (600, 800, 64, 7), (720, 1280, 40, 9),
-              (150, 2000, 64, 3), (512, 512, 32, 3), (640, 640, 128, 5), (96, 96, 8, 13), (1100, 1100, 8, 3),
+              (150, 2000, 64, 3), (512, 512, 32, 3), (640, 640, 128, 5), (96, 96, 8, 33), (1100, 1100, 8, 3), (120, 150, 8, 13),
               (800, 800, 96, 5), (1024, 1024, 16, 5)]
     general = [(2, 64, 30, 30, 64, 3), (3, 32, 20, 20, 32, 3), (2, 64, 40, 40, 96, 3), (1, 256, 14, 14, 256, 3),
                (1, 128, 20, 20, 128, 7), (4, 128, 17, 14, 192, 1), (8, 8, 60, 60, 64, 2), (2, 64, 30, 30, 128, 2),
-               (40, 16, 7, 7, 64, 3), (2, 2, 200, 200, 16, 3), (1, 1, 200, 200, 64, 3), (2, 16, 20, 20, 8, 12),
+               (40, 16, 7, 7, 64, 3), (2, 2, 200, 200, 16, 3), (1, 1, 200, 200, 64, 3), (2, 16, 40, 40, 8, 33),
                (16, 8, 96, 96, 64, 3)]
     seen = set()
     for i, (H, W, K, F) in enumerate(single):
         x, f = wl.random_case(3100 + i, 1, 1, H, W, K, F)
         c = dconv.tile_choice(True, 1, 1, H, W, K, F)
-        seen.add(("single", min(c, 0) if c < 0 else c))
+        seen.add(("single", c))
         got = dconv.dconv_single_channel(dev(x[0, 0]), dev(f[:, 0]))
-        forced = dconv.dconv_single_channel(dev(x[0, 0]), dev(f[:, 0]), variant=_variant_of_choice(c))
+        if c == dconv.CHOICE_GENERAL_CASE:     # (the general kernel's own entry point, one image of one channel)
+            forced = dconv.dconv_general(dev(x), dev(f), variant=dconv.VARIANT_TILED)[0]
+        else:
+            forced = dconv.dconv_single_channel(dev(x[0, 0]), dev(f[:, 0]), variant=_variant_of_choice(c))
         torch.cuda.synchronize()
         assert torch.equal(got, forced), f"single-channel {(H, W, K, F)}: choice {c}"
         acc, mag, _ = oracle.general(x, f)
@@ -943,7 +982,7 @@ def test_the_reported_choice_is_what_the_library_runs():
     # the shapes reach the three tile shapes and the other kernels of both entry points
     assert {("general", 0), ("general", 1), ("general", 2), ("general", dconv.CHOICE_SPECIAL_CASE),
             ("general", dconv.CHOICE_SIMPLE), ("single", dconv.CHOICE_FEW_FILTERS),
-            ("single", dconv.CHOICE_SIMPLE)} <= seen, seen
+            ("single", dconv.CHOICE_SIMPLE), ("single", dconv.CHOICE_GENERAL_CASE)} <= seen, seen
     assert len({c for k, c in seen if k == "single" and c >= 0}) >= 5, seen
 
 
