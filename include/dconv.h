@@ -145,8 +145,10 @@ int dconv_general_v(const float *in, int N, int C, int H, int W,
  *   out[n][k][y][x] = sum_i sum_j sum_c in[n][y+i][x+j][c] * filt[k][i][j][c]
  * Products of two 16-bit values are exact in fp32; sums are fp32 in
  * unspecified order.  The matrix-core kernel needs C to be a multiple of 16,
- * F <= 11 and 16-byte aligned inputs; other shapes run on a
- * one-thread-per-output kernel (any valid shape, 2-byte alignment).
+ * F <= 32 (and, beyond 27 x 27, an image block small enough for a filter row
+ * of a chunk to fit in LDS beside it) and 16-byte aligned inputs; other
+ * shapes run on a one-thread-per-output kernel (any valid shape, 2-byte
+ * alignment), which is some thousand times slower: pad the channels.
  * Errors as for dconv_general; a base pointer that is not 2-byte aligned ->
  * DCONV_BAD_SHAPE.
  */
@@ -172,7 +174,7 @@ int dconv_general_half_v(const void *in, int N, int C, int H, int W,
  * (|sum| <= C*F*F*2^14 must fit int32, which it does for every shape the
  * 2^31-1 element limits admit with C*F*F < 2^17; larger reductions wrap as
  * int32 arithmetic does).  The matrix-core kernel needs C to be a multiple of
- * 32, F <= 11 and 16-byte aligned inputs; other shapes run on the
+ * 32, F <= 32 (as above) and 16-byte aligned inputs; other shapes run on the
  * one-thread-per-output kernel.  variant as for dconv_general_half_v.
  */
 int dconv_general_i8(const void *in, int N, int C, int H, int W,

@@ -21,7 +21,7 @@ SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", 
            ("general.hip", [], "general")] + \
           [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 33)] + \
           [("half.hip", [], "half")] + \
-          [("half_inst.hip", [f"-DDCONV_F={f}"], f"half_f{f}") for f in range(1, 12)]
+          [("half_inst.hip", [f"-DDCONV_F={f}"], f"half_f{f}") for f in range(1, 33)]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed fp32 VALU forms are switched off for all device code (the host pass

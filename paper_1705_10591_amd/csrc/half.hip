@@ -21,6 +21,27 @@ int launch_tiled(const void* in, const void* filt, float* out, const Shape& s, h
     case 9: return half_launch_for_F<9>(in, filt, out, s, st, dtype, config, blocked, dry);
     case 10: return half_launch_for_F<10>(in, filt, out, s, st, dtype, config, blocked, dry);
     case 11: return half_launch_for_F<11>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 12: return half_launch_for_F<12>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 13: return half_launch_for_F<13>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 14: return half_launch_for_F<14>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 15: return half_launch_for_F<15>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 16: return half_launch_for_F<16>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 17: return half_launch_for_F<17>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 18: return half_launch_for_F<18>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 19: return half_launch_for_F<19>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 20: return half_launch_for_F<20>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 21: return half_launch_for_F<21>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 22: return half_launch_for_F<22>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 23: return half_launch_for_F<23>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 24: return half_launch_for_F<24>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 25: return half_launch_for_F<25>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 26: return half_launch_for_F<26>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 27: return half_launch_for_F<27>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 28: return half_launch_for_F<28>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 29: return half_launch_for_F<29>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 30: return half_launch_for_F<30>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 31: return half_launch_for_F<31>(in, filt, out, s, st, dtype, config, blocked, dry);
+    case 32: return half_launch_for_F<32>(in, filt, out, s, st, dtype, config, blocked, dry);
     default: return DCONV_UNSUPPORTED;
     }
 }

@@ -328,3 +328,39 @@ def test_half_large_image_sampled():
         acc, mag = oracle.general_at(xr, fr, idx)
         assert_within_bound(got, acc, mag, f"half bf16 large image variant {variant}")
         del out
+
+
+# ---- filters beyond 11 x 11: one filter row of a block of channels per chunk ----------------
+
+LARGE_FILTER_HALF_SHAPES = [(1, 16, 20, 40, 64, 13), (2, 32, 34, 36, 9, 32), (1, 48, 30, 30, 70, 21),
+                            (1, 16, 26, 90, 130, 17), (3, 32, 14, 60, 33, 12), (1, 64, 40, 40, 16, 25)]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("shape", LARGE_FILTER_HALF_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_short_types_filters_of_12_to_32(shape, kind):
+    """The matrix-core kernel of the short data types is compiled for every filter side up to 32.
+    Integer inputs, so every kernel must give the oracle's sums bit for bit; a forced tile whose
+    filter block does not fit in LDS refuses the shape, the small register-staged tile and the
+    library's own choice never do."""
+    N, C, H, W, K, F = shape
+    if kind == "i8":
+        C = (C + 31) // 32 * 32
+        x, f = int8_case(40 + F, (N, C, H, W, K, F))
+        want = exact_i8(x, f)
+        run = lambda v: run_i8(x, f, v).astype(np.int64)
+    else:
+        xr, fr, xb, fb = rounded_case(40 + F, shape, kind, integer=True)
+        want = oracle.general(xr, fr, want32=True)[2]
+        run = lambda v: run_half(xb, fb, kind, v)
+    ran = 0
+    for variant in KERNELS:
+        try:
+            got = run(variant)
+        except dconv.DconvError as e:
+            assert e.status == dconv.STATUS_UNSUPPORTED and variant not in (TILED, SIMPLE, TILE_SMALL), variant
+            continue
+        np.testing.assert_array_equal(got, want)
+        ran += 1
+    assert ran >= 3
+    np.testing.assert_array_equal(run(AUTO), want)
