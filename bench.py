@@ -327,8 +327,17 @@ def main():
         roof = {"bound": "hbm", "achieved": entry["algorithmic_gbs"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(entry["algorithmic_gbs"] / HBM_PEAK_GBS, 4)}
     else:
-        roof = {"bound": "mfma", "achieved": round(entry["gflops"] / 1e3, 3), "peak": FP32_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(entry["gflops"] / 1e3 / FP32_PEAK_TFLOPS, 4)}
+        # the few-filters kernels compute on the vector ALU: same published fp32 peak (it counts
+        # the packed forms, which this build switches off: plain multiply-adds reach half of it)
+        import paper_1705_10591_amd as dconv
+        sh = entry["shape"]
+        on_alu = dconv.tile_choice(single, sh["N"], sh["C"], sh["H"], sh["W"], sh["K"], sh["F"]) == dconv.CHOICE_FEW_FILTERS
+        roof = {"bound": "alu" if on_alu else "mfma", "achieved": round(entry["gflops"] / 1e3, 3),
+                "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(entry["gflops"] / 1e3 / FP32_PEAK_TFLOPS, 4)}
+        if on_alu:
+            roof["peak_plain_fma"] = FP32_PEAK_TFLOPS / 2
+            roof["frac_plain_fma"] = round(entry["gflops"] / 1e3 / (FP32_PEAK_TFLOPS / 2), 4)
     roof["kernel"] = entry["kernel"]
     roof["kernel_ms"] = round(ms, 5)
     roof["traffic"] = read_traffic(f"{entry['kernel']}_{head.name}")

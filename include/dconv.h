@@ -58,12 +58,18 @@ enum {
     DCONV_VARIANT_TILED = 2,  /* LDS-staged, matrix-core tiled kernel, tile
                                  configuration picked by shape                   */
     DCONV_VARIANT_FEW_FILTERS = 3,
-                              /* single-channel case only, F <= 7: vector-ALU
-                                 kernel with a sliding register window (the
-                                 paper's Algorithm 1 as it stands); what AUTO
-                                 picks for few filters (at most 20; how many
-                                 depends on filter and image size) where it
-                                 beats the matrix-core kernel                    */
+                              /* F <= 7: vector-ALU kernels with a sliding
+                                 register window and wave-uniform weights.
+                                 dconv_single_channel_v: the paper's Algorithm 1
+                                 as it stands; what AUTO picks for few filters
+                                 (at most 20; how many depends on filter and
+                                 image size) where it beats the matrix-core
+                                 kernel.  dconv_general_v: the paper's
+                                 Algorithm 2 with all filters in a thread's
+                                 register tile, K <= 8 only; what AUTO picks for
+                                 such layers where the launch covers the chip
+                                 and a 32-filter matrix-core block would be
+                                 mostly padding                                  */
     DCONV_VARIANT_SPECIAL_CASE = 4,
                               /* dconv_general with C = 1 (any filter up to
                                  11x11) or C <= 4 (filters up to 5x5) only: the
@@ -224,7 +230,7 @@ int dconv_tile_config_count(int single_channel);
  * device's CU count -- or one of the negative values below.
  */
 enum dconv_choice {
-    DCONV_CHOICE_FEW_FILTERS = -1,  /* special case: the vector-ALU kernel for few filters */
+    DCONV_CHOICE_FEW_FILTERS = -1,  /* the vector-ALU kernel for few filters of that entry point */
     DCONV_CHOICE_SPECIAL_CASE = -2, /* dconv_general hands the shape to the special-case
                                        kernel (one channel, or a few with small filters)   */
     DCONV_CHOICE_SIMPLE = -3,       /* the one-thread-per-output kernel                    */

@@ -18,7 +18,8 @@ BUILD = PKG / "_build"
 # (source, extra flags, object name); the general-case kernels are compiled once per filter side
 SOURCES = [("api.hip", [], "api"), ("simple.hip", [], "simple"), ("single.hip", [], "single"), ("single_fewfilters.hip", [], "single_fewfilters"),
            *[("single_multi_inst.hip", [f"-DDCONV_C={c}"], f"single_c{c}") for c in (2, 3, 4)],
-           ("general.hip", [], "general")] + \
+           ("general.hip", [], "general"), ("general_fewfilters.hip", [], "general_fewfilters")] + \
+          [("general_few_inst.hip", [f"-DDCONV_F={f}"], f"general_few_f{f}") for f in range(1, 8)] + \
           [("general_inst.hip", [f"-DDCONV_F={f}"], f"general_f{f}") for f in range(1, 33)] + \
           [("half.hip", [], "half")] + \
           [("half_inst.hip", [f"-DDCONV_F={f}"], f"half_f{f}") for f in range(1, 33)]

@@ -42,9 +42,11 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
         // (filters beyond the special case's 11 x 11: the general kernel takes one channel too)
         if (single && !tiled_ok && dconv::general_tiled_supports(s))
             return dconv::launch_general_tiled(in, filt, out, s, st, -1, static_ws);
+        if (!single && dconv::general_few_preferred(s)) return dconv::launch_general_few(in, filt, out, s, st);
         return tiled_ok ? tiled(-1) : dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_FEW_FILTERS:
-        if (!single || !dconv::single_few_supports(s)) return DCONV_UNSUPPORTED;
+        if (!single) return dconv::launch_general_few(in, filt, out, s, st);   // (refuses what it cannot run)
+        if (!dconv::single_few_supports(s)) return DCONV_UNSUPPORTED;
         return dconv::launch_single_few(in, filt, out, s, st);
     case DCONV_VARIANT_SIMPLE:
         return dconv::launch_simple(in, filt, out, s, st);
@@ -209,6 +211,7 @@ int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int
         if (!single_channel) return DCONV_CHOICE_SPECIAL_CASE;
         return dconv::single_auto_config(s);
     }
+    if (dconv::general_few_preferred(s)) return DCONV_CHOICE_FEW_FILTERS;
     if (!dconv::general_tiled_supports(s)) return DCONV_CHOICE_SIMPLE;
     return dconv::general_auto_shape(s);
 }

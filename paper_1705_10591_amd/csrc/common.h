@@ -69,6 +69,10 @@ int general_tile_configs();
 int single_auto_config(const Shape& s);
 int general_auto_shape(const Shape& s);
 int launch_single_few(const float* img, const float* filt, float* out, const Shape& s, hipStream_t st);
+// the general case with up to eight filters on the vector ALU (general_fewfilters.hip)
+int launch_general_few(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st);
+bool general_few_supports(const Shape& s);
+bool general_few_preferred(const Shape& s);
 bool single_few_supports(const Shape& s);      // the few-filters kernel can run the shape
 bool single_few_preferred(const Shape& s);     // ... and is the better choice for it
 bool single_blocks16_preferred(const Shape& s);   // up to 16 filters: matrix-core blocks of 16 filters are the better choice

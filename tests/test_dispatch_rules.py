@@ -84,6 +84,12 @@ def test_other_kernels_by_shape():
     assert choice(False, 16, 1, 512, 512, 64, 3) == dconv.CHOICE_SPECIAL_CASE
     assert choice(False, 16, 3, 512, 512, 64, 3) == dconv.CHOICE_SPECIAL_CASE
     assert choice(False, 16, 3, 512, 512, 64, 7) >= 0
+    # a few filters on many channels: the vector-ALU kernel of the general case, where it covers the chip
+    assert choice(False, 8, 64, 224, 224, 3, 3) == dconv.CHOICE_FEW_FILTERS
+    assert choice(False, 8, 16, 224, 224, 1, 7) == dconv.CHOICE_FEW_FILTERS
+    assert choice(False, 1, 256, 128, 128, 3, 3) == 2            # too few tiles
+    assert choice(False, 64, 256, 38, 38, 4, 1) == 2             # a barrier per channel for very little work
+    assert choice(False, 8, 64, 224, 224, 9, 3) == 2             # nine filters
 
 
 @pytest.mark.parametrize("args", [
@@ -129,8 +135,8 @@ def test_rules_that_hold_for_every_shape():
         if F > min(H, W):
             continue
         c = choice(False, N, C, H, W, K, F)
-        assert c >= 0, (N, C, H, W, K, F, c)
-        if K <= 32:
+        assert c >= 0 or (c == dconv.CHOICE_FEW_FILTERS and K <= 8 and F <= 7), (N, C, H, W, K, F, c)
+        if K <= 32 and c >= 0:
             assert c == 2          # no 64-filter block that is half padding
         if K % 64 == 0:
             assert c != 2          # nothing to save with 32-filter blocks

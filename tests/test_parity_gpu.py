@@ -902,6 +902,74 @@ def test_fewer_tiles_than_cus_integer_inputs_bit_exact(shape):
             assert torch.isnan(buf[:1024]).all() and torch.isnan(buf[1024 + want.size:]).all(), f"{shape}: guard bands"
 
 
+# ---- the few-filters kernel of the general case -------------------------------------------
+
+# (N, C, H, W, K, F): every tile shape of the kernel (256, 128 and 64 columns wide; four, two and
+# one row per band: the tall bands need many tiles, hence the batches of small images), every
+# compiled filter count, filter sides 1..7, ragged tiles, a filter as large as the image
+GENERAL_FEW_SHAPES = [(400, 2, 20, 260, 3, 3), (200, 3, 20, 300, 7, 2), (3, 5, 40, 500, 4, 5), (800, 2, 12, 100, 1, 3),
+                      (5, 4, 30, 120, 6, 4), (800, 2, 10, 60, 2, 3), (7, 8, 33, 40, 8, 7), (2, 16, 9, 700, 5, 1),
+                      (1, 3, 50, 257, 3, 6), (2, 37, 7, 7, 2, 7), (1, 2, 130, 258, 1, 5)]
+
+
+@pytest.mark.parametrize("shape", GENERAL_FEW_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_general_few_filters_kernel(shape):
+    """Algorithm 2 with all filters in a thread's register tile, on the vector ALU: against the
+    oracle within the bound, integer inputs bit for bit, guard bands, twice in a row."""
+    N, C, H, W, K, F = shape
+    x, f = wl.random_case(6100 + K + F, N, C, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    assert_within_bound(run_general(x, f, FEW), acc, mag, f"general few-filters {shape}")
+    xi, fi = wl.integer_case(6200 + K + F, N, C, H, W, K, F)
+    want = oracle.general(xi, fi)[0].astype(np.float32)
+    for rep in range(2):
+        buf = torch.full((want.size + 2048,), float("nan"), device="cuda")
+        out = buf[1024 + rep:1024 + rep + want.size].view(want.shape)      # (any 4-byte alignment)
+        dconv.dconv_general(dev(xi), dev(fi), out=out, variant=FEW)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want), f"{shape}: integer inputs"
+        assert torch.isnan(buf[:1024 + rep]).all() and torch.isnan(buf[1024 + rep + want.size:]).all(), f"{shape}: guard bands"
+
+
+def test_general_few_filters_kernel_limits_and_non_finite_inputs():
+    x, f = wl.random_case(6300, 2, 3, 20, 70, 9, 3)
+    with pytest.raises(dconv.DconvError) as e:              # nine filters
+        run_general(x, f, FEW)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
+    x, f = wl.random_case(6301, 1, 2, 20, 70, 2, 8)
+    with pytest.raises(dconv.DconvError) as e:              # 8 x 8 filters
+        run_general(x, f, FEW)
+    assert e.value.status == dconv.STATUS_UNSUPPORTED
+    # a NaN pixel reaches exactly the windows that hold it, a NaN weight its own map only
+    N, C, H, W, K, F = 2, 3, 24, 300, 4, 3
+    x, f = wl.random_case(6302, N, C, H, W, K, F)
+    x[1, 2, 10, 150] = np.nan
+    got = run_general(x, f, FEW)
+    bad = np.isnan(got)
+    want = np.zeros_like(bad)
+    want[1, :, 8:11, 148:151] = True
+    assert np.array_equal(bad, want)
+    x, f = wl.random_case(6303, N, C, H, W, K, F)
+    f[2, 1, 0, 1] = np.inf
+    got = run_general(x, f, FEW)
+    assert np.isfinite(got[:, [0, 1, 3]]).all() and not np.isfinite(got[:, 2]).any()
+
+
+def test_general_few_filters_where_the_library_picks_it():
+    """Layers with one to eight filters that cover the chip, at full size on sampled outputs; the
+    plain call and the forced kernel agree bit for bit."""
+    for (N, C, H, W, K, F) in ((8, 16, 224, 224, 3, 5), (64, 32, 56, 56, 1, 3), (4, 32, 300, 512, 8, 3)):
+        assert dconv.tile_choice(False, N, C, H, W, K, F) == dconv.CHOICE_FEW_FILTERS
+        x, f = wl.random_case(6400 + K, N, C, H, W, K, F)
+        got = dconv.dconv_general(dev(x), dev(f))
+        forced = dconv.dconv_general(dev(x), dev(f), variant=FEW)
+        torch.cuda.synchronize()
+        assert torch.equal(got, forced)
+        idx = wl.sample_indices(6400 + K, got.numel(), 20000)
+        acc, mag = oracle.general_at(x, f, idx)
+        assert_within_bound(got.cpu().numpy().reshape(-1)[idx], acc, mag, f"general few-filters {(N, C, H, W, K, F)}")
+
+
 LARGE_FILTER_SHAPES = [(2, 3, 30, 40, 70, 13), (1, 8, 20, 50, 33, 12), (2, 16, 18, 18, 64, 16), (1, 2, 40, 41, 130, 14),
                        (3, 5, 15, 140, 9, 15), (1, 64, 16, 16, 40, 16), (1, 1, 70, 300, 24, 13), (4, 1, 33, 29, 5, 12),
                        (1, 3, 40, 60, 33, 17), (2, 4, 30, 70, 20, 21), (1, 2, 45, 50, 64, 24), (1, 1, 64, 200, 12, 25),

@@ -102,6 +102,9 @@ PAPER_SWEEP = {w.name: w for w in (
     # three channels, small filters: still bound by the output stream (a first layer on RGB images)
     _mk("A_C3_N16_512_F3", "general", 16, 3, 512, 512, 64, 3, "u01", "he", 41),
     _mk("A_C3_N64_224_F3", "general", 64, 3, 224, 224, 64, 3, "u01", "he", 42),
+    # few filters in the general case (the weak spot of Sec. 5 carried over: a last layer to RGB, one map)
+    _mk("B_K3_F3", "general", 8, 64, 224, 224, 3, 3, "u01", "he", 43),
+    _mk("B_K1_F7", "general", 8, 16, 224, 224, 1, 7, "u01", "he", 44),
 )}
 
 
