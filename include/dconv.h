@@ -119,7 +119,9 @@ int dconv_single_channel(const float *img, int H, int W,
  * With C = 1 this is the special case of Sec. 3 applied to N images: the
  * automatic choice runs them on the single-channel kernel (all images in one
  * launch) where that is the faster one, and likewise two to four channels
- * with small filters, see DCONV_VARIANT_SPECIAL_CASE.
+ * with small filters, see DCONV_VARIANT_SPECIAL_CASE.  With up to eight
+ * filters the automatic choice is the vector-ALU kernel of
+ * DCONV_VARIANT_FEW_FILTERS wherever it is the faster one.
  * The tiled kernel is compiled for filters up to 32 x 32; larger ones (and
  * shapes beyond its 32-bit index limits) run on the one-thread-per-output
  * kernel.

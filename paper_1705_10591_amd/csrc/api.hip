@@ -42,7 +42,6 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
         // (filters beyond the special case's 11 x 11: the general kernel takes one channel too)
         if (single && !tiled_ok && dconv::general_tiled_supports(s))
             return dconv::launch_general_tiled(in, filt, out, s, st, -1, static_ws);
-        if (!single && dconv::general_few_preferred(s)) return dconv::launch_general_few(in, filt, out, s, st);
         return tiled_ok ? tiled(-1) : dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_FEW_FILTERS:
         if (!single) return dconv::launch_general_few(in, filt, out, s, st);   // (refuses what it cannot run)
@@ -81,6 +80,10 @@ int general_entry(const float* in, int N, int C, int H, int W, const float* filt
     }
     // (the same kernel takes two to four channels with small filters: such shapes are bound by
     // the output stream like the one-channel case)
+    // (with up to eight filters the vector-ALU kernel of the general case goes first: it is 2 to
+    // 10 times faster than a mostly padded matrix-core block of either kernel)
+    if (variant == DCONV_VARIANT_AUTO && !(N == 1 && C == 1) && dconv::general_few_preferred(s))
+        return dconv::launch_general_few(in, filt, out, s, (hipStream_t)stream);
     if (variant == DCONV_VARIANT_AUTO &&
         ((N == 1 && C == 1) || dconv::single_batch_preferred(s) ||
          (dconv::single_tiled_supports(s) && !dconv::general_tiled_supports(s))))
@@ -202,6 +205,7 @@ int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int
         (single_channel && (N != 1 || C != 1)))
         return DCONV_CHOICE_INVALID;
     // the routing of general_entry and dispatch for DCONV_VARIANT_AUTO
+    if (!single_channel && !(N == 1 && C == 1) && dconv::general_few_preferred(s)) return DCONV_CHOICE_FEW_FILTERS;
     const bool special = single_channel || (N == 1 && C == 1) || dconv::single_batch_preferred(s) ||
                          (dconv::single_tiled_supports(s) && !dconv::general_tiled_supports(s));
     if (special) {
@@ -211,7 +215,6 @@ int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int
         if (!single_channel) return DCONV_CHOICE_SPECIAL_CASE;
         return dconv::single_auto_config(s);
     }
-    if (dconv::general_few_preferred(s)) return DCONV_CHOICE_FEW_FILTERS;
     if (!dconv::general_tiled_supports(s)) return DCONV_CHOICE_SIMPLE;
     return dconv::general_auto_shape(s);
 }

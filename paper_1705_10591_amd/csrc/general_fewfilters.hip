@@ -27,7 +27,8 @@ bool general_few_supports(const Shape& s)
 // three 3x3 filters: 139 -> 53 us; eight: 139 -> 116 us).
 bool general_few_preferred(const Shape& s)
 {
-    if (!general_few_supports(s) || s.C < 2) return false;
+    // (one image of one channel is the special case proper, which has its own few-filters kernel)
+    if (!general_few_supports(s) || (s.C == 1 && s.N == 1)) return false;
     const GfTile t = gf_tile_for(s);
     const double tiles = (double)gf_tiles(s, t.lpr, t.rpw);
     if (tiles < 32) return false;
