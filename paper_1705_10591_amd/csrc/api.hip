@@ -225,6 +225,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1011; }
+int dconv_version(void) { return 1012; }
 
 }  // extern "C"

@@ -15,10 +15,14 @@
 //    instruction) and runs filter after filter over them, every pixel of the window used F
 //    times per filter row: the paper's register reuse, Sec. 4.3 (6x6 and 7x7 filters keep a
 //    ring of F rows per filter instead: the band's rows do not fit the registers);
-//  * the filters are wave-uniform: the F x F weights of one (filter, channel) pair arrive with one
-//    load (lane t takes weight t), issued a trip ahead, and move to scalar registers tap by tap,
-//    so each multiply-add takes its weight from a scalar operand (scalar loads of the weights
-//    were measured 10-40 % slower: their latency is in the way of every filter);
+//  * the filters are wave-uniform.  From two filters on, the F x F weights of every (filter,
+//    channel) pair of a trip are staged in LDS like the tile (one 64-word load each) and a
+//    multiply-add takes its weight from a register that all lanes read from the same LDS address:
+//    the counterpart of the paper's constant-cache broadcast.  With one filter they arrive with
+//    one vector load (lane t takes weight t) and move to scalar registers tap by tap; that is
+//    5-15 % faster for one filter and 7-32 % slower for three to eight, where the moves take a
+//    quarter of the vector instructions (scalar loads of the weights: 10-40 % slower, their
+//    latency is in the way of every filter);
 //  * after the last channel a lane stores its four outputs per row and filter as 16 bytes.
 // Every input pixel is read from HBM once per tile (halo aside) whatever the filter count, and
 // the arithmetic is K x F x F multiply-adds per pixel and channel with no padding.
@@ -57,10 +61,17 @@ general_few_kernel(GenFewParams p)
     constexpr int ROWS = TR + F - 1;
     constexpr bool kWholeWindow = (RPW + F - 1) * 4 * NV <= 64;   // registers for a band's image rows
     static_assert(LS % 4 == 0, "16-byte aligned rows");
-    static_assert(2 * CC * ROWS * LS * 4 <= 64 * 1024, "two sets of tiles fit a static LDS array");
+    static_assert(2 * (CC * ROWS * LS + (KT >= 2 ? CC * KT * kWave : 4)) * 4 <= 64 * 1024,
+                  "two sets of tiles and weights fit static LDS");
     static_assert(FF <= kWave, "one lane per weight");
 
     __shared__ __attribute__((aligned(16))) float sh[2][CC * ROWS * LS];
+    // From two filters on the weights go through LDS too (64 words per filter and channel) and a
+    // multiply-add takes its weight from a register that every lane read from the same LDS
+    // address; with one filter they go through scalar registers (moved there lane by lane), which
+    // is 5-15 % faster for one filter and 7-32 % slower for three to eight.
+    constexpr bool kLdsWeights = KT >= 2;
+    __shared__ __attribute__((aligned(16))) float wsh[2][kLdsWeights ? CC * KT * kWave : 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -105,6 +116,18 @@ general_few_kernel(GenFewParams p)
             w[k] = (lane < FF && k < p.K && c < p.C) ? p.filt[k * CFF + (int64_t)c * FF + lane] : 0.f;
     };
 
+    // the weights of (filter k, channel c) straight into LDS, 64 words per instruction (the F x F
+    // weights and whatever follows them; a filter or channel beyond the last reads as zeros)
+    const int64_t filt_words = (int64_t)p.K * CFF;
+    auto stage_weights = [&](int c, int cc, float* wbuf) __attribute__((always_inline)) {
+        for (int k = wave; k < KT; k += 4) {       // (uniform)
+            const int64_t first = k * CFF + (int64_t)c * FF;
+            const int64_t left = (k < p.K && c < p.C) ? (filt_words - first) * 4 : 0;
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(p.filt + (left > 0 ? first : 0)), 0, (int)(left > 0x7FFFFFFF ? 0x7FFFFFFF : left), kRsrcFlags);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(wbuf + (cc * KT + k) * kWave), 4, voff[0], 0, 0, 0);
+        }
+    };
     const int lx = lane % LPR;
     const int r0 = (wave * BANDS + lane / LPR) * RPW;   // first output row of this lane's band
     const int xo = x0 + 4 * lx;                    // first output column of this lane
@@ -122,7 +145,8 @@ general_few_kernel(GenFewParams p)
 #pragma unroll
     for (int cc = 0; cc < CC; ++cc) {
         if (cc < p.C) stage(cc, sh[0] + cc * (ROWS * LS));
-        load_weights(cc, wcur[cc]);
+        if constexpr (kLdsWeights) stage_weights(cc, cc, wsh[0]);
+        else load_weights(cc, wcur[cc]);
     }
     for (int c0 = 0; c0 < p.C; c0 += CC) {         // uniform loop
         // this wave's pieces of these channels are in LDS (and the weights in registers); after
@@ -133,7 +157,8 @@ general_few_kernel(GenFewParams p)
 #pragma unroll
         for (int cc = 0; cc < CC; ++cc) {
             if (c0 + CC + cc < p.C) stage(c0 + CC + cc, sh[cur ^ 1] + cc * (ROWS * LS));
-            load_weights(c0 + CC + cc, wnext[cc]);
+            if constexpr (kLdsWeights) stage_weights(c0 + CC + cc, cc, wsh[cur ^ 1]);
+            else load_weights(c0 + CC + cc, wnext[cc]);
         }
 #pragma unroll
         for (int cc = 0; cc < CC; ++cc) {
@@ -159,8 +184,10 @@ general_few_kernel(GenFewParams p)
                 for (int k = 0; k < KT; ++k) {
                     float wgt[FF];
 #pragma unroll
-                    for (int t = 0; t < FF; ++t)
-                        wgt[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wcur[cc][k]), t));
+                    for (int t = 0; t < FF; ++t) {
+                        if constexpr (kLdsWeights) wgt[t] = wsh[cur][(cc * KT + k) * kWave + t];
+                        else wgt[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wcur[cc][k]), t));
+                    }
 #pragma unroll
                     for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
@@ -178,8 +205,10 @@ general_few_kernel(GenFewParams p)
                 for (int k = 0; k < KT; ++k) {
                     float wgt[FF];
 #pragma unroll
-                    for (int t = 0; t < FF; ++t)
-                        wgt[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wcur[cc][k]), t));
+                    for (int t = 0; t < FF; ++t) {
+                        if constexpr (kLdsWeights) wgt[t] = wsh[cur][(cc * KT + k) * kWave + t];
+                        else wgt[t] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wcur[cc][k]), t));
+                    }
                     // window row of band row rr lives in win[rr % F]
                     float win[F][4 * NV];
 #pragma unroll

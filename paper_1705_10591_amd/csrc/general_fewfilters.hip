@@ -11,20 +11,21 @@ bool general_few_supports(const Shape& s)
     return s.F >= 1 && s.F <= 7 && s.K >= 1 && s.K <= 8;
 }
 
-// Worth it when its estimated time is below the matrix-core kernel's.  Estimates in
-// microseconds, fitted to 260 measured layers (1 to 8 filters of 1x1 to 7x7, 2 to 256 channels,
-// 14 x 14 to 512 x 640 maps, 1 to 512 images; this kernel's within 20 % rms, the other's 23 %):
+// Worth it when its estimated time is below nine tenths of the matrix-core kernel's.  Estimates in
+// microseconds, fitted to 460 measured layers (1 to 8 filters of 1x1 to 7x7, 2 to 256 channels,
+// 14 x 14 to 512 x 640 maps, 1 to 512 images; this kernel's within 22 % rms, the other's 23 %):
 //   this kernel: 8 us plus the largest of three bounds -- a barrier and a round of LDS latencies
-//     per channel (0.55 us), input and output at 7 TB/s, and K x F x F multiply-adds per pixel
+//     per channel (0.55 us), input and output at 6 TB/s, and K x F x F multiply-adds per pixel
 //     and channel (K rounded up to the filter counts it is compiled for, divided by the share
-//     of its lanes that fall inside the map) at 40 TFLOP/s with one row per band, 48 with two,
-//     53 with four, stretched when there are fewer tiles than CUs;
-//   the matrix-core kernel: 12 us plus a 32-filter block at 110 TFLOP/s whatever the filter
+//     of its lanes that fall inside the map) at 62 TFLOP/s with one row per band, 64 with two,
+//     70 with four (two thirds of that with one filter, whose weights go through scalar
+//     registers), stretched when there are fewer than 384 tiles;
+//   the matrix-core kernel: 12 us plus a 32-filter block at 90 TFLOP/s whatever the filter
 //     count, or input and output at 2.5 TB/s.
-// On those layers the choice is within 1.3 % of the faster kernel on average (9 of 260 are 15 %
+// On those layers the choice is within 1.4 % of the faster kernel on average (14 of 460 are 15 %
 // or more off); where this kernel is chosen it is up to 6 times faster (101 x 3 x 64 x 640, two
 // 1x1 filters: 97 -> 16 us; 8 x 16 x 224 x 224, one 7x7 filter: 189 -> 25 us; 8 x 64 x 224 x 224,
-// three 3x3 filters: 139 -> 53 us; eight: 139 -> 116 us).
+// three 3x3 filters: 139 -> 51 us; eight: 139 -> 81 us).
 bool general_few_preferred(const Shape& s)
 {
     // (one image of one channel is the special case proper, which has its own few-filters kernel)
@@ -38,11 +39,11 @@ bool general_few_preferred(const Shape& s)
                           ((double)((s.Wo + (int)tw - 1) / (int)tw) * tw * (double)((s.Ho + (int)tr - 1) / (int)tr) * tr);
     const double macs = (double)s.N * s.Ho * s.Wo * s.C * s.F * s.F;      // per filter
     const double bytes = 4.0 * ((double)s.N * s.C * s.H * s.W + (double)s.N * s.K * s.Ho * s.Wo);
-    const double rate = t.rpw == 1 ? 40e6 : t.rpw == 2 ? 48e6 : 53e6;
-    const double alu = 2.0 * macs * kCompiled[s.K] / inside / rate * std::max(1.0, 256.0 / tiles);
-    const double few = 8.0 + std::max({0.55 * s.C, bytes / 7e6, alu});
-    const double tiled = 12.0 + std::max(2.0 * macs * 32 / 110e6, bytes / 2.5e6);
-    return few < tiled;
+    const double rate = (t.rpw == 1 ? 62e6 : t.rpw == 2 ? 64e6 : 70e6) * (s.K == 1 ? 0.65 : 1.0);
+    const double alu = 2.0 * macs * kCompiled[s.K] / inside / rate * std::max(1.0, 384.0 / tiles);
+    const double few = 8.0 + std::max({0.55 * s.C, bytes / 6e6, alu});
+    const double tiled = 12.0 + std::max(2.0 * macs * 32 / 90e6, bytes / 2.5e6);
+    return few < 0.9 * tiled;
 }
 
 int launch_general_few(const float* in, const float* filt, float* out, const Shape& s, hipStream_t st)
