@@ -66,10 +66,11 @@ enum {
                                  image size) where it beats the matrix-core
                                  kernel.  dconv_general_v: the paper's
                                  Algorithm 2 with all filters in a thread's
-                                 register tile, K <= 8 only; what AUTO picks for
+                                 register tile, K <= 16 only; what AUTO picks for
                                  such layers where the launch covers the chip
                                  and a 32-filter matrix-core block would be
-                                 mostly padding                                  */
+                                 mostly padding (from nine filters on: layers of
+                                 few channels)                                   */
     DCONV_VARIANT_SPECIAL_CASE = 4,
                               /* dconv_general with C = 1 (any filter up to
                                  11x11) or C <= 4 (filters up to 5x5) only: the
@@ -119,7 +120,7 @@ int dconv_single_channel(const float *img, int H, int W,
  * With C = 1 this is the special case of Sec. 3 applied to N images: the
  * automatic choice runs them on the single-channel kernel (all images in one
  * launch) where that is the faster one, and likewise two to four channels
- * with small filters, see DCONV_VARIANT_SPECIAL_CASE.  With up to eight
+ * with small filters, see DCONV_VARIANT_SPECIAL_CASE.  With up to sixteen
  * filters the automatic choice is the vector-ALU kernel of
  * DCONV_VARIANT_FEW_FILTERS wherever it is the faster one.
  * The tiled kernel is compiled for filters up to 32 x 32; larger ones (and

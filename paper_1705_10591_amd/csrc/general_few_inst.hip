@@ -19,6 +19,8 @@ int gf_launch_for_F<DCONV_F>(const float* in, const float* filt, float* out, con
     case 4: return launch_gf_K<F, 4>(in, filt, out, s, st);
     case 5: case 6: return launch_gf_K<F, 6>(in, filt, out, s, st);
     case 7: case 8: return launch_gf_K<F, 8>(in, filt, out, s, st);
+    case 9: case 10: case 11: case 12: return launch_gf_K<F, 12>(in, filt, out, s, st);
+    case 13: case 14: case 15: case 16: return launch_gf_K<F, 16>(in, filt, out, s, st);
     default: return DCONV_UNSUPPORTED;
     }
 }

@@ -1,7 +1,7 @@
 // General-case direct convolution for VERY FEW filters (paper Sec. 4, Algorithm 2), gfx950.
 //
-// With up to eight filters the matrix-core kernel of general_kernel.h computes a 32-filter block
-// that is three quarters padding or more, and the layer is bound by reading its input.  This
+// With up to sixteen filters the matrix-core kernel of general_kernel.h computes a 32-filter block
+// that is half padding or more, and with a few filters the layer is bound by reading its input.  This
 // kernel is the paper's general-case scheme taken almost literally, on the vector ALU, with the
 // thread's filter tile F_T = all K filters:
 //  * the output is cut into tiles of one image (256 x 4 to 64 x 32 outputs, by map size and
@@ -42,8 +42,8 @@ struct GenFewParams {
     int per_xcd;     // tiles per XCD (the grid has 8 * per_xcd workgroups)
 };
 
-// KT:  filters a lane sums at once (K rounded up to 1, 2, 3, 4, 6 or 8; filters beyond K have
-//      zero weights and are not stored).
+// KT:  filters a lane sums at once (K rounded up to 1, 2, 3, 4, 6, 8, 12 or 16; filters beyond K
+//      have zero weights and are not stored).
 // LPR: lanes side by side in a row of the tile (64, 32 or 16: tiles 256, 128 or 64 columns wide);
 //      a wave holds 64 / LPR bands of rows, one below the other.
 // RPW: output rows per band.  A tile is 4 * LPR columns x 4 * (64 / LPR) * RPW rows.
@@ -237,21 +237,24 @@ general_few_kernel(GenFewParams p)
     typedef float v4f_a4 __attribute__((ext_vector_type(4), aligned(4)));
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
-        if (k >= p.K) break;                       // uniform
-        float* plane_k = p.out + ((int64_t)n * p.K + k) * plane;
+        // (a uniform branch per filter, not a loop exit: with an early exit the compiler leaves
+        // loops of more than eight trips rolled, and the sums would live in scratch memory)
+        if (k < p.K) {
+            float* plane_k = p.out + ((int64_t)n * p.K + k) * plane;
 #pragma unroll
-        for (int rr = 0; rr < RPW; ++rr) {
-            const int y = y0 + r0 + rr;
-            if (y < p.Ho) {
-                float* dst = plane_k + (int64_t)y * p.Wo + xo;
-                // 16 bytes at once where they fit (rows start at any 4-byte offset: the store
-                // is declared 4-byte aligned), single words at the row end
-                if (xo + 3 < p.Wo) {
-                    *reinterpret_cast<v4f_a4*>(dst) = (v4f_a4){acc[rr][k][0], acc[rr][k][1], acc[rr][k][2], acc[rr][k][3]};
-                } else {
+            for (int rr = 0; rr < RPW; ++rr) {
+                const int y = y0 + r0 + rr;
+                if (y < p.Ho) {
+                    float* dst = plane_k + (int64_t)y * p.Wo + xo;
+                    // 16 bytes at once where they fit (rows start at any 4-byte offset: the store
+                    // is declared 4-byte aligned), single words at the row end
+                    if (xo + 3 < p.Wo) {
+                        *reinterpret_cast<v4f_a4*>(dst) = (v4f_a4){acc[rr][k][0], acc[rr][k][1], acc[rr][k][2], acc[rr][k][3]};
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (xo + e < p.Wo) dst[e] = acc[rr][k][e];
+                        for (int e = 0; e < 4; ++e)
+                            if (xo + e < p.Wo) dst[e] = acc[rr][k][e];
+                    }
                 }
             }
         }
@@ -275,7 +278,7 @@ inline GfTile gf_tile_for(const Shape& s)
         const int64_t padded = (int64_t)((s.Wo + 4 * l - 1) / (4 * l)) * (4 * l);
         if (padded * 10 < best * 9) { best = padded; lpr = l; }
     }
-    const int rmax = s.K > 4 ? 2 : lpr == 64 ? 4 : 2;
+    const int rmax = s.K > 8 ? 1 : s.K > 4 ? 2 : lpr == 64 ? 4 : 2;
     int rpw = rmax;
     while (rpw > 1 && gf_tiles(s, lpr, rpw) < 768) rpw /= 2;
     return {lpr, rpw};
@@ -293,8 +296,9 @@ int launch_gf(const float* in, const float* filt, float* out, const Shape& s, hi
     p.per_xcd = (int)((tiles + 7) / 8);
     begin_launch();
     // (one row per band is so little work per channel that two channels share a barrier:
-    // 8 x 64 x 224 x 224, 1x1 filters: 29 -> 23 us)
-    constexpr int CC = RPW == 1 ? 2 : 1;
+    // 8 x 64 x 224 x 224, 1x1 filters: 29 -> 23 us; not with twelve or sixteen filters, which
+    // are work enough and whose weights take the LDS a second channel would need)
+    constexpr int CC = (RPW == 1 && KT <= 8) ? 2 : 1;
     hipLaunchKernelGGL((general_few_kernel<F, KT, RPW, LPR, CC>), dim3((unsigned)(p.per_xcd * 8)), dim3(kThreads), 0, st, p);
     return launch_status();
 }
@@ -304,18 +308,24 @@ int launch_gf_K(const float* in, const float* filt, float* out, const Shape& s, 
 {
     const GfTile t = gf_tile_for(s);
     // (six and eight filters: at most two rows per band, so that the sums and a 7x7 window fit
-    // the registers of two waves per SIMD)
-    if (t.lpr == 64) {
-        if (KT <= 4 && t.rpw == 4) return launch_gf<F, KT, (KT <= 4 ? 4 : 2), 64>(in, filt, out, s, st);
-        if (t.rpw >= 2) return launch_gf<F, KT, 2, 64>(in, filt, out, s, st);
-        return launch_gf<F, KT, 1, 64>(in, filt, out, s, st);
+    // the registers of two waves per SIMD; twelve and sixteen: one row)
+    if constexpr (KT > 8) {
+        if (t.lpr == 64) return launch_gf<F, KT, 1, 64>(in, filt, out, s, st);
+        if (t.lpr == 32) return launch_gf<F, KT, 1, 32>(in, filt, out, s, st);
+        return launch_gf<F, KT, 1, 16>(in, filt, out, s, st);
+    } else {
+        if (t.lpr == 64) {
+            if (KT <= 4 && t.rpw == 4) return launch_gf<F, KT, (KT <= 4 ? 4 : 2), 64>(in, filt, out, s, st);
+            if (t.rpw >= 2) return launch_gf<F, KT, 2, 64>(in, filt, out, s, st);
+            return launch_gf<F, KT, 1, 64>(in, filt, out, s, st);
+        }
+        if (t.lpr == 32) {
+            if (t.rpw >= 2) return launch_gf<F, KT, 2, 32>(in, filt, out, s, st);
+            return launch_gf<F, KT, 1, 32>(in, filt, out, s, st);
+        }
+        if (t.rpw >= 2) return launch_gf<F, KT, 2, 16>(in, filt, out, s, st);
+        return launch_gf<F, KT, 1, 16>(in, filt, out, s, st);
     }
-    if (t.lpr == 32) {
-        if (t.rpw >= 2) return launch_gf<F, KT, 2, 32>(in, filt, out, s, st);
-        return launch_gf<F, KT, 1, 32>(in, filt, out, s, st);
-    }
-    if (t.rpw >= 2) return launch_gf<F, KT, 2, 16>(in, filt, out, s, st);
-    return launch_gf<F, KT, 1, 16>(in, filt, out, s, st);
 }
 
 // Implemented once per filter side, each in its own translation unit.

@@ -5,10 +5,10 @@
 
 namespace dconv {
 
-// Filter sides with a window that fits the register file comfortably, up to eight filters.
+// Filter sides with a window that fits the register file comfortably, up to sixteen filters.
 bool general_few_supports(const Shape& s)
 {
-    return s.F >= 1 && s.F <= 7 && s.K >= 1 && s.K <= 8;
+    return s.F >= 1 && s.F <= 7 && s.K >= 1 && s.K <= 16;
 }
 
 // Worth it when its estimated time is below nine tenths of the matrix-core kernel's.  Estimates in
@@ -26,6 +26,13 @@ bool general_few_supports(const Shape& s)
 // or more off); where this kernel is chosen it is up to 6 times faster (101 x 3 x 64 x 640, two
 // 1x1 filters: 97 -> 16 us; 8 x 16 x 224 x 224, one 7x7 filter: 189 -> 25 us; 8 x 64 x 224 x 224,
 // three 3x3 filters: 139 -> 51 us; eight: 139 -> 81 us).
+// Nine to sixteen filters (compiled for twelve and sixteen, one row per band, one channel per
+// barrier) pay off on layers of few channels, where the matrix-core kernel is bound by its
+// write-back: the same estimate with 58 TFLOP/s stretched below 512 tiles, 1.5 us per channel and
+// 4 TB/s, chosen where it is below the other's.  On 280 further measured layers of 9 to 16 filters
+// that choice is within 2 % of the faster kernel on average (10 of 280 are 15 % or more off; 18 %
+// with the matrix-core kernel alone), and up to 2.8 times faster (512 x 3 x 28 x 320, ten 1x1
+// filters: 108 -> 38 us; 21 x 8 x 96 x 640, twelve 5x5: 174 -> 80 us).
 bool general_few_preferred(const Shape& s)
 {
     // (one image of one channel is the special case proper, which has its own few-filters kernel)
@@ -33,16 +40,20 @@ bool general_few_preferred(const Shape& s)
     const GfTile t = gf_tile_for(s);
     const double tiles = (double)gf_tiles(s, t.lpr, t.rpw);
     if (tiles < 32) return false;
-    static const int kCompiled[9] = {0, 1, 2, 3, 4, 6, 6, 8, 8};
+    static const int kCompiled[17] = {0, 1, 2, 3, 4, 6, 6, 8, 8, 12, 12, 12, 12, 16, 16, 16, 16};
     const double tw = 4.0 * t.lpr, tr = 4.0 * (kWave / t.lpr) * t.rpw;
     const double inside = (double)s.Wo * s.Ho /
                           ((double)((s.Wo + (int)tw - 1) / (int)tw) * tw * (double)((s.Ho + (int)tr - 1) / (int)tr) * tr);
     const double macs = (double)s.N * s.Ho * s.Wo * s.C * s.F * s.F;      // per filter
     const double bytes = 4.0 * ((double)s.N * s.C * s.H * s.W + (double)s.N * s.K * s.Ho * s.Wo);
+    const double tiled = 12.0 + std::max(2.0 * macs * 32 / 90e6, bytes / 2.5e6);
+    if (s.K > 8) {
+        const double alu = 2.0 * macs * kCompiled[s.K] / inside / 58e6 * std::max(1.0, 512.0 / tiles);
+        return 8.0 + std::max({1.5 * s.C, bytes / 4e6, alu}) < tiled;
+    }
     const double rate = (t.rpw == 1 ? 62e6 : t.rpw == 2 ? 64e6 : 70e6) * (s.K == 1 ? 0.65 : 1.0);
     const double alu = 2.0 * macs * kCompiled[s.K] / inside / rate * std::max(1.0, 384.0 / tiles);
     const double few = 8.0 + std::max({0.55 * s.C, bytes / 6e6, alu});
-    const double tiled = 12.0 + std::max(2.0 * macs * 32 / 90e6, bytes / 2.5e6);
     return few < 0.9 * tiled;
 }
 

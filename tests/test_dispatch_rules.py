@@ -89,7 +89,10 @@ def test_other_kernels_by_shape():
     assert choice(False, 8, 16, 224, 224, 1, 7) == dconv.CHOICE_FEW_FILTERS
     assert choice(False, 1, 256, 128, 128, 3, 3) == 2            # too few tiles
     assert choice(False, 64, 256, 38, 38, 4, 1) == 2             # a barrier per channel for very little work
-    assert choice(False, 8, 64, 224, 224, 9, 3) == 2             # nine filters
+    assert choice(False, 21, 8, 96, 640, 12, 5) == dconv.CHOICE_FEW_FILTERS      # (nine to sixteen filters: few channels)
+    assert choice(False, 15, 3, 384, 384, 10, 3) == dconv.CHOICE_FEW_FILTERS
+    assert choice(False, 8, 64, 224, 224, 16, 3) == 2            # sixteen filters on many channels
+    assert choice(False, 8, 64, 224, 224, 17, 3) == 2            # seventeen filters
 
 
 @pytest.mark.parametrize("args", [
@@ -135,7 +138,7 @@ def test_rules_that_hold_for_every_shape():
         if F > min(H, W):
             continue
         c = choice(False, N, C, H, W, K, F)
-        assert c >= 0 or (c == dconv.CHOICE_FEW_FILTERS and K <= 8 and F <= 7), (N, C, H, W, K, F, c)
+        assert c >= 0 or (c == dconv.CHOICE_FEW_FILTERS and K <= 16 and F <= 7), (N, C, H, W, K, F, c)
         if K <= 32 and c >= 0:
             assert c == 2          # no 64-filter block that is half padding
         if K % 64 == 0:

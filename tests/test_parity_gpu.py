@@ -909,7 +909,10 @@ def test_fewer_tiles_than_cus_integer_inputs_bit_exact(shape):
 # compiled filter count, filter sides 1..7, ragged tiles, a filter as large as the image
 GENERAL_FEW_SHAPES = [(400, 2, 20, 260, 3, 3), (200, 3, 20, 300, 7, 2), (3, 5, 40, 500, 4, 5), (800, 2, 12, 100, 1, 3),
                       (5, 4, 30, 120, 6, 4), (800, 2, 10, 60, 2, 3), (7, 8, 33, 40, 8, 7), (2, 16, 9, 700, 5, 1),
-                      (1, 3, 50, 257, 3, 6), (2, 37, 7, 7, 2, 7), (1, 2, 130, 258, 1, 5)]
+                      (1, 3, 50, 257, 3, 6), (2, 37, 7, 7, 2, 7), (1, 2, 130, 258, 1, 5),
+                      # nine to sixteen filters (compiled for twelve and sixteen, one row per band)
+                      (3, 4, 37, 300, 9, 3), (2, 3, 50, 130, 13, 7), (5, 6, 21, 70, 16, 5), (2, 7, 33, 257, 12, 1),
+                      (3, 2, 30, 90, 11, 2), (1, 5, 40, 64, 15, 6), (2, 3, 35, 200, 10, 4), (1, 9, 16, 16, 14, 3)]
 
 
 @pytest.mark.parametrize("shape", GENERAL_FEW_SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -932,8 +935,8 @@ def test_general_few_filters_kernel(shape):
 
 
 def test_general_few_filters_kernel_limits_and_non_finite_inputs():
-    x, f = wl.random_case(6300, 2, 3, 20, 70, 9, 3)
-    with pytest.raises(dconv.DconvError) as e:              # nine filters
+    x, f = wl.random_case(6300, 2, 3, 20, 70, 17, 3)
+    with pytest.raises(dconv.DconvError) as e:              # seventeen filters
         run_general(x, f, FEW)
     assert e.value.status == dconv.STATUS_UNSUPPORTED
     x, f = wl.random_case(6301, 1, 2, 20, 70, 2, 8)
@@ -956,9 +959,10 @@ def test_general_few_filters_kernel_limits_and_non_finite_inputs():
 
 
 def test_general_few_filters_where_the_library_picks_it():
-    """Layers with one to eight filters that cover the chip, at full size on sampled outputs; the
+    """Layers with one to sixteen filters that cover the chip, at full size on sampled outputs; the
     plain call and the forced kernel agree bit for bit."""
-    for (N, C, H, W, K, F) in ((8, 16, 224, 224, 3, 5), (64, 32, 56, 56, 1, 3), (4, 32, 300, 512, 8, 3)):
+    for (N, C, H, W, K, F) in ((8, 16, 224, 224, 3, 5), (64, 32, 56, 56, 1, 3), (4, 32, 300, 512, 8, 3),
+                               (15, 3, 384, 384, 10, 3), (21, 8, 96, 640, 12, 5), (64, 3, 128, 128, 16, 2)):
         assert dconv.tile_choice(False, N, C, H, W, K, F) == dconv.CHOICE_FEW_FILTERS
         x, f = wl.random_case(6400 + K, N, C, H, W, K, F)
         got = dconv.dconv_general(dev(x), dev(f))
