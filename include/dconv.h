@@ -99,10 +99,11 @@ enum {
  * Errors: NULL img/filt/out -> DCONV_NULL_POINTER; H, W, K, F <= 0, F > H or
  * F > W, or more than 2^31-1 elements in img or in the whole output
  * [K][Ho][Wo] -> DCONV_BAD_SHAPE.
- * Filters up to 11 x 11 run on the kernels of the special case; 12 x 12 to
- * 32 x 32 on the general-case kernel with one channel (which may allocate its
- * workspace, see dconv_release_workspace); larger ones on the
- * one-thread-per-output kernel.
+ * Filters up to 11 x 11 run on the kernels of the special case, or, where
+ * that is the faster one (narrow or short images, large filters: the choice is
+ * made from the shape), on the general-case kernel with one channel; 12 x 12
+ * to 32 x 32 always on the latter (it may allocate its workspace, see
+ * dconv_release_workspace); larger ones on the one-thread-per-output kernel.
  */
 int dconv_single_channel(const float *img, int H, int W,
                          const float *filt, int K, int F,
@@ -239,8 +240,10 @@ enum dconv_choice {
     DCONV_CHOICE_SIMPLE = -3,       /* the one-thread-per-output kernel                    */
     DCONV_CHOICE_INVALID = -4,      /* not a valid shape (the entry point would return
                                        DCONV_BAD_SHAPE)                                    */
-    DCONV_CHOICE_GENERAL_CASE = -5  /* one channel with filters beyond the special-case
-                                       kernel's 11 x 11: the general-case kernel           */
+    DCONV_CHOICE_GENERAL_CASE = -5  /* one channel on the general-case kernel: filters
+                                       beyond the special-case kernel's 11 x 11, and
+                                       shapes where it is the faster one (narrow or short
+                                       images, large filters)                              */
 };
 int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int F);
 
@@ -261,8 +264,8 @@ int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int
  * hipMalloc, what the largest launch on that device can need (256 KiB of
  * partial sums and four counters per compute unit: 64 MiB + 4 KiB on a 256-CU
  * chip) and clears the counters on that stream; no other entry point
- * allocates (dconv_single_channel with filters of 12 x 12 to 32 x 32 counts
- * as dconv_general here: it runs on the same kernel), and no call
+ * allocates (dconv_single_channel counts as dconv_general here where it runs
+ * on the same kernel, see there), and no call
  * synchronises.  The block keeps its address from then
  * on: later calls on the stream, whatever their shape, use the same block (they
  * run in order, so they share it safely; calls on different streams use

@@ -39,8 +39,9 @@ int dispatch(bool single, const float* in, const float* filt, float* out,
     switch (variant) {
     case DCONV_VARIANT_AUTO:
         if (single && dconv::single_few_preferred(s)) return dconv::launch_single_few(in, filt, out, s, st);
-        // (filters beyond the special case's 11 x 11: the general kernel takes one channel too)
-        if (single && !tiled_ok && dconv::general_tiled_supports(s))
+        // (filters beyond the special case's 11 x 11: the general kernel takes one channel too;
+        // so do narrow or short images and large filters, where it is the faster one)
+        if (single && (!tiled_ok || dconv::single_general_preferred(s)) && dconv::general_tiled_supports(s))
             return dconv::launch_general_tiled(in, filt, out, s, st, -1, static_ws);
         return tiled_ok ? tiled(-1) : dconv::launch_simple(in, filt, out, s, st);
     case DCONV_VARIANT_FEW_FILTERS:
@@ -211,8 +212,11 @@ int dconv_tile_choice(int single_channel, int N, int C, int H, int W, int K, int
                          (dconv::single_tiled_supports(s) && !dconv::general_tiled_supports(s));
     if (special) {
         if (dconv::single_few_preferred(s)) return DCONV_CHOICE_FEW_FILTERS;
-        if (!dconv::single_tiled_supports(s))
-            return dconv::general_tiled_supports(s) ? DCONV_CHOICE_GENERAL_CASE : DCONV_CHOICE_SIMPLE;
+        if (!dconv::general_tiled_supports(s) && !dconv::single_tiled_supports(s)) return DCONV_CHOICE_SIMPLE;
+        // (one channel on the general-case kernel: dconv_general names the tile shape it runs with)
+        if (dconv::general_tiled_supports(s) &&
+            (!dconv::single_tiled_supports(s) || dconv::single_general_preferred(s)))
+            return single_channel ? DCONV_CHOICE_GENERAL_CASE : dconv::general_auto_shape(s);
         if (!single_channel) return DCONV_CHOICE_SPECIAL_CASE;
         return dconv::single_auto_config(s);
     }
@@ -226,6 +230,6 @@ int dconv_release_workspace(void)
     return DCONV_OK;
 }
 
-int dconv_version(void) { return 1013; }
+int dconv_version(void) { return 1014; }
 
 }  // extern "C"

@@ -26,6 +26,31 @@ namespace {
 // filters (single_blocks16_preferred below).
 constexpr int kSingleConfigs = 11;
 
+// Imbalance of a tile shape: the workgroups of the fullest CU over the mean per CU, tiles
+// counted by their passes (the last tile column may hold fewer than the others).  The
+// hardware deals workgroups evenly, so a launch of 534 wide tiles takes as long as one of
+// 768 (a handful of tiles beyond a multiple of the CUs is not counted as a round: those
+// run on CUs that have little else left).  `round_up` says how much of the last,
+// partly filled round counts: all of it for the wide tiles, less for the small ones,
+// which are dealt as slots fall free.  For filters bound by the matrix cores this factor
+// predicts the measured time per pixel of 512-pixel tiles on 720 x 1280 .. 3000 x 3000
+// images within a few per cent.
+double tile_imbalance(const Shape& s, int tw, int tr, int pass, double round_up)
+{
+    constexpr double kCUs = 256;
+    // (work items of all images count: a batch of small images fills the chip like one
+    // large image)
+    const int64_t fgroups = (((s.K + 31) / 32) + 3) / 4 * s.N;
+    const int64_t cols = (s.Wo + tw - 1) / tw, rows = (s.Ho + tr - 1) / tr;
+    const int64_t per_tile = tw / pass;
+    const int64_t last = (s.Wo - tw * (cols - 1) + pass - 1) / pass;
+    const double mean = (double)(rows * fgroups * (per_tile * (cols - 1) + last)) /
+                        ((double)per_tile * kCUs);
+    const double per_cu = std::max(1.0, (double)(cols * rows * fgroups) / kCUs);
+    const double full = std::max(1.0, std::ceil(per_cu - 0.05));
+    return (full > per_cu ? per_cu + round_up * (full - per_cu) : full) / mean;
+}
+
 // The configuration by shape (what launch_F runs when none is forced).
 int auto_config(const Shape& s)
 {
@@ -36,25 +61,8 @@ int auto_config(const Shape& s)
     auto items = [&](int tw, int tr) {
         return (int64_t)((s.Wo + tw - 1) / tw) * ((s.Ho + tr - 1) / tr) * fgroups;
     };
-    // Imbalance of a tile shape: the workgroups of the fullest CU over the mean per CU, tiles
-    // counted by their passes (the last tile column may hold fewer than the others).  The
-    // hardware deals workgroups evenly, so a launch of 534 wide tiles takes as long as one of
-    // 768 (a handful of tiles beyond a multiple of the CUs is not counted as a round: those
-    // run on CUs that have little else left).  `round_up` says how much of the last,
-    // partly filled round counts: all of it for the wide tiles, less for the small ones,
-    // which are dealt as slots fall free.  For filters bound by the matrix cores this factor
-    // predicts the measured time per pixel of 512-pixel tiles on 720 x 1280 .. 3000 x 3000
-    // images within a few per cent.
     auto imbalance = [&](int tw, int tr, int pass, double round_up) {
-        constexpr double kCUs = 256;
-        const int64_t cols = (s.Wo + tw - 1) / tw, rows = (s.Ho + tr - 1) / tr;
-        const int64_t per_tile = tw / pass;
-        const int64_t last = (s.Wo - tw * (cols - 1) + pass - 1) / pass;
-        const double mean = (double)(rows * fgroups * (per_tile * (cols - 1) + last)) /
-                            ((double)per_tile * kCUs);
-        const double per_cu = std::max(1.0, (double)(cols * rows * fgroups) / kCUs);
-        const double full = std::max(1.0, std::ceil(per_cu - 0.05));
-        return (full > per_cu ? per_cu + round_up * (full - per_cu) : full) / mean;
+        return tile_imbalance(s, tw, tr, pass, round_up);
     };
     // (128 x 4 with passes of 32 pixels, or 256 x 2: whichever divides the image more evenly)
     auto small_tile = [&](double bias) {
@@ -191,6 +199,35 @@ bool single_batch_preferred(const Shape& s)
     if (outputs < 100000000LL) return false;
     if (s.C == 1) return (s.F <= 5 && s.Wo >= 96) || (s.F <= 8 && s.Wo >= 256);
     return (s.F == 1 && s.Wo >= 96) || (s.F <= 3 && s.Wo >= 104) || (s.C == 2 && s.Wo >= 400);
+}
+
+// One image of one channel on the GENERAL-case kernel (Sec. 4 with C = 1): the special case's
+// kernel spends its store time and its matrix-core time one after the other and cuts the image
+// into row strips, which suits large images with small filters (the paper's sweep: output-bound,
+// whole rows per strip); the general kernel overlaps the two and tiles the flattened pixels, which
+// suits everything narrow, short or heavy in arithmetic.  A linear rule in the filter side and the
+// logarithms of the sizes, with three flags: fewer than 32 filters (the special case's 16-filter
+// blocks and small tiles are hard to beat), filter blocks left over beyond groups of four (a
+// leftover group of one or two blocks runs with the tile shape chosen for the full groups, which
+// suits it badly: 160 filters cost the special case's kernel almost what 256 do), and a large
+// image that the special case's wide tiles divide evenly over the CUs (there it is at its best:
+// 1024^2, 2048^2 and 3000^2 with 64 filters of 9x9 .. 11x11 are 6-8 % faster on it).  Fitted to
+// 960 measured shapes (64^2 .. 4096^2, 9 to 512 filters of 1x1 .. 11x11; fitted on two thirds and
+// checked on the third, in turn): within 2-2.5 % of the faster kernel on average, against 26 %
+// with the special case's kernels alone and 17 % with the general one alone (64 x 64 with 128
+// 8x8 filters: 32 -> 11 us; 384 x 384, 192 11x11: 140 -> 75 us; 768 x 768, 192 8x8: 247 -> 166 us;
+// 1536 x 1280, 96 11x11: 643 -> 471 us).  The 4096 x 4096 shapes of the paper's sweep stay on the
+// special case's kernel for every filter side.
+bool single_general_preferred(const Shape& s)
+{
+    if (s.N != 1 || s.C != 1 || s.K < 9) return false;
+    const int blocks = (s.K + 31) / 32;
+    const bool leftover = blocks > 2 && blocks % 4 != 0;
+    const bool even = s.Wo >= 900 && tile_imbalance(s, 512, 4, 128, 1.0) <= 1.06;
+    const double score = 0.63 * s.F - 0.20 * std::log2((double)s.K) - 0.70 * std::log2((double)s.Ho) -
+                         1.12 * std::log2((double)s.Wo) - (s.K < 32 ? 2.62 : 0.0) +
+                         (leftover ? 1.17 : 0.0) - (even ? 1.57 : 0.0) + 15.06;
+    return score > 0.0;
 }
 
 int single_tile_configs() { return kSingleConfigs; }

@@ -53,8 +53,10 @@ struct SingleParams {
     int N;           // images (each convolved with the same filters); img and out are dense over n
     int H, W, K, Ho, Wo;
     int tiles_x, tiles_y;
-    int fbw;         // 32-filter blocks handled by one workgroup: 1, 2 or 4
-    int fgroups;     // filter groups (of 32*fbw filters); work items = N * tiles * fgroups
+    int nfull;       // filter groups of four 32-filter blocks (one block per wave, every tile row)
+    int rem;         // blocks left over (0..3): a group of two (two waves per block, every other
+                     // row each) and / or a group of one (the four waves share its rows)
+    int fgroups;     // filter groups: nfull + (rem == 3 ? 2 : rem ? 1 : 0); work items = N * tiles * fgroups
     int per_xcd;     // work items per XCD (the chip has 8), see the mapping in the kernel
     int wrap;        // 1: row ends are completed with the head of the next row (wide images)
 };
@@ -131,11 +133,21 @@ single_tiled_kernel(SingleParams p)
     if (n >= p.N) return;                                  // uniform: before any barrier
     const float* img = p.img + (int64_t)n * C * p.H * p.W;
     float* out = p.out + (int64_t)n * p.K * p.Ho * p.Wo;
-    const int fgroup = item / ntiles, tile = item - fgroup * ntiles;
+    // (the filter groups of a tile are neighbours in the order of work items: every XCD gets
+    // the same mix of full and leftover groups, and its L2 serves a tile's pixels to all of them)
+    const int tile = item / p.fgroups, fgroup = item - tile * p.fgroups;
     const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
     const int x0 = tx * TW, y0 = ty * TR;
-    const int fb = fgroup * p.fbw + wave % p.fbw;          // this wave's 32-filter block
-    const int row_start = wave / p.fbw, row_step = 4 / p.fbw;   // its share of the tile rows
+    // this group's blocks: four, or what is left over as two and / or one (no wave works on a
+    // block of padding: 160 filters are a group of four blocks and a group of one)
+    int fbw = 4, fb0 = 4 * fgroup;
+    if (fgroup >= p.nfull) {
+        const bool second = fgroup > p.nfull;              // (only with three blocks left over)
+        fbw = p.rem == 3 ? (second ? 1 : 2) : p.rem;
+        fb0 = 4 * p.nfull + (second ? 2 : 0);
+    }
+    const int fb = fb0 + wave % fbw;                       // this wave's 32-filter block
+    const int row_start = wave / fbw, row_step = 4 / fbw;  // its share of the tile rows
     const bool wrap_tile = p.wrap && tx == p.tiles_x - 1;
 
     // ---- this wave's filter operands: a[s] = filt[k][tap 2s + h], zero beyond K / F*F --
@@ -448,8 +460,9 @@ int launch_cfg(const float* img, const float* filt, float* out, const Shape& s, 
     p.tiles_x = (s.Wo + TW - 1) / TW;
     p.tiles_y = (s.Ho + TR - 1) / TR;
     const int fblocks = (s.K + FB - 1) / FB;
-    p.fbw = fblocks >= 4 ? 4 : fblocks >= 2 ? 2 : 1;
-    p.fgroups = (fblocks + p.fbw - 1) / p.fbw;
+    p.nfull = fblocks / 4;
+    p.rem = fblocks % 4;
+    p.fgroups = p.nfull + (p.rem == 3 ? 2 : p.rem ? 1 : 0);
     // Completing row ends with the next row's head needs a pass to span at most one row end,
     // and every pass that reaches the row end to lie in the last tile column.
     // (a pass computes 32 * NBW + 32 pixels from a multiple of 32 * NBW on: it crosses one row

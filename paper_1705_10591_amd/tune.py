@@ -19,6 +19,9 @@ that the rules can be checked or re-derived on another chip.
     python -m paper_1705_10591_amd.tune random single|general SEED COUNT
                                                                   (shapes drawn at random: the check of the rules
                                                                    on shapes they were not set on)
+    python -m paper_1705_10591_amd.tune route SEED COUNT          (one image of one channel on shapes drawn at
+                                                                   random: the library's choice, the special
+                                                                   case's kernel and the general-case kernel)
     python -m paper_1705_10591_amd.tune units                     (special case: 16-byte against 4-byte units
                                                                    on the way out, the width-matching ablation)
     python -m paper_1705_10591_amd.tune writeback                 (general case: stores straight from the
@@ -171,7 +174,8 @@ def table(kind: str) -> None:
               "bf16-blocked": TABLE_BF16}[kind]
     n = _config_count(kind)
     print(f"# {kind}: microseconds per launch; columns: library choice, configurations 0..{n - 1} "
-          "(n/a = cannot hold the shape), fastest configuration, library / fastest")
+          "(n/a = cannot hold the shape), fastest configuration, library / fastest (below 1 where the "
+          "library runs the shape on another kernel than the one whose configurations are listed)")
     for sh in shapes:
         rows = tune(kind, sh)
         lib, cfgs = rows[0][1], [ms for _, ms in rows[1:]]
@@ -217,8 +221,9 @@ def random_table(kind: str, seed: int, count: int) -> None:
     lines of the shapes where the choice is 8 % or more above the fastest, and a summary."""
     n = _config_count(kind)
     print(f"# {kind}, {count} random shapes (seed {seed}): microseconds per launch; the library's choice and "
-          f"the fastest of configurations 0..{n - 1} (the ablation excluded); shapes listed where the choice "
-          "is 8 % or more above the fastest")
+          f"the fastest of configurations 0..{n - 1} (the ablation excluded; where the library runs a shape on "
+          "another kernel than the one with these configurations its time can be below the fastest); shapes "
+          "listed where the choice is 8 % or more above the fastest")
     ratios = []
     for sh in random_shapes(kind, seed, count):
         rows = tune(kind, sh, steps=6)
@@ -234,6 +239,54 @@ def random_table(kind: str, seed: int, count: int) -> None:
     print(f"# library / fastest over {m} shapes: mean {sum(ratios) / m:.3f}, median {ratios[m // 2]:.3f}, "
           f"90th percentile {ratios[(9 * m) // 10]:.3f}, worst {ratios[-1]:.2f}; "
           f"{sum(r >= 1.06 for r in ratios)} shapes 6 % or more above the fastest")
+
+
+def route_table(seed: int, count: int) -> None:
+    """One image of one channel: the library's choice against the special case's kernel (its own
+    tile choice) and the general-case kernel (its own tile choice) on shapes drawn at random --
+    images 64 to 4096 pixels on a side, 9 to 512 filters of 1x1 to 11x11.  Lists the shapes where
+    the choice is 10 % or more above the faster of the two, and a summary."""
+    import random
+    rng = random.Random(seed)
+    print(f"# one channel, {count} random shapes (seed {seed}): microseconds per launch of the library's choice, "
+          "the special case's kernel and the general-case kernel; shapes listed where the choice is 10 % or "
+          "more above the faster kernel")
+    lib_r, special_r, general_r = [], [], []
+    gen = torch.Generator(device="cuda").manual_seed(1705)
+    done = 0
+    while done < count:
+        K = rng.choice((9, 12, 16, 17, 24, 32, 32, 40, 48, 64, 64, 80, 96, 128, 128, 160, 192, 224, 256, 320, 512))
+        F = rng.randint(1, 11)
+        H = rng.choice((64, 96, 128, 150, 224, 256, 384, 512, 768, 1024, 1536, 2048, 3000, 4096))
+        W = H if rng.random() < 0.7 else rng.choice((100, 160, 320, 640, 1280, 1920))
+        if F > min(H, W):
+            continue
+        Ho, Wo = H - F + 1, W - F + 1
+        if K * Ho * Wo * 4 > 4.5e9 or K * Ho * Wo < 2e5:
+            continue
+        x = torch.rand(1, 1, H, W, device="cuda", generator=gen) * 2 - 1
+        f = torch.rand(K, 1, F, F, device="cuda", generator=gen) * 2 - 1
+        out = torch.empty(1, K, Ho, Wo, device="cuda")
+        x1, f1, out1 = x[0, 0], f[:, 0], out[0]
+        # (interleaved and repeated: the clock settles differently after a long and a short launch)
+        t = [1e30, 1e30, 1e30]
+        for _ in range(2):
+            t[0] = min(t[0], _time(lambda: dconv.dconv_single_channel(x1, f1, out=out1), 8, 6))
+            t[1] = min(t[1], _time(lambda: dconv.dconv_single_channel(x1, f1, out=out1, variant=dconv.VARIANT_TILED), 8, 6))
+            t[2] = min(t[2], _time(lambda: dconv.dconv_general(x, f, out=out, variant=dconv.VARIANT_TILED), 8, 6))
+        best = min(t[1:])
+        lib_r.append(t[0] / best); special_r.append(t[1] / best); general_r.append(t[2] / best)
+        if t[0] / best >= 1.10:
+            print(f"{H}x{W}x{K}x{F:<3d} {t[0] * 1e3:9.1f} {t[1] * 1e3:9.1f} {t[2] * 1e3:9.1f}  choice "
+                  f"{dconv.tile_choice(True, 1, 1, H, W, K, F):3d}  {t[0] / best:5.2f}", flush=True)
+        del x, f, out, x1, f1, out1
+        done += 1
+    m = len(lib_r)
+    mean = lambda r: sum(r) / len(r)
+    print(f"# time / faster kernel's time over {m} shapes: library's choice mean {mean(lib_r):.3f} "
+          f"({sum(r >= 1.10 for r in lib_r)} shapes 10 % or more above), special case's kernel alone {mean(special_r):.3f} "
+          f"({sum(r >= 1.10 for r in special_r)}), general-case kernel alone {mean(general_r):.3f} "
+          f"({sum(r >= 1.10 for r in general_r)})")
 
 
 def writeback_table() -> None:
@@ -351,6 +404,12 @@ def main(argv):
             print("tune needs a GPU", file=sys.stderr)
             return 2
         random_table(argv[1], int(argv[2]), int(argv[3]))
+        return 0
+    if len(argv) == 3 and argv[0] == "route":
+        if not torch.cuda.is_available():
+            print("tune needs a GPU", file=sys.stderr)
+            return 2
+        route_table(int(argv[1]), int(argv[2]))
         return 0
     if len(argv) == 2 and argv[0] == "table" and argv[1] in KINDS:
         if not torch.cuda.is_available():

@@ -23,23 +23,31 @@ SINGLE_PINS = [
     ((4096, 4096, 64, 7), 0),
     ((4096, 4096, 64, 11), 2),    # 512 x 8: fewer halo rows per output row for the largest filters
     ((2048, 2048, 64, 9), 2),
-    ((1536, 1536, 64, 9), 0),     # 573 tall tiles would load the CUs unevenly
-    ((1080, 1920, 64, 9), 6),     # 1072 wide tiles on 256 CUs: five on some, four on most
-    ((720, 1280, 64, 9), 6),
+    ((2400, 1600, 128, 9), 6),    # wide tiles would load the CUs unevenly
+    ((1440, 1600, 128, 8), 6),
     ((1024, 1024, 64, 9), 0),     # 508 wide tiles: two per CU, even
     ((1800, 1800, 64, 7), 0),
     ((256, 256, 16, 3), 8),       # 64 x 4 tiles: a workgroup for every CU
-    ((256, 256, 32, 5), 8),
     ((768, 768, 32, 5), 6),       # one filter block: the smallest tile, passes of 32 pixels
     ((1024, 1024, 32, 7), 0),
-    ((600, 800, 64, 7), 6),       # 128 x 4 divides the image more evenly than 256 x 2
-    ((900, 1600, 128, 11), 5),
-    ((1280, 1280, 32, 8), 2),
+    ((640, 640, 128, 5), 6),      # 128 x 4 divides the image more evenly than 256 x 2
+    ((3000, 3000, 32, 8), 2),
     ((720, 1280, 32, 5), 6),
     ((4096, 4096, 16, 5), 9),     # 16-filter matrix-core blocks
     ((720, 1280, 16, 5), 10),
     ((512, 512, 32, 3), 5),
 ]
+
+# (H, W, K, F): one image of one channel that runs on the general-case kernel (narrow or short
+# images, large filters: measured 8 to 38 % faster there; 12 x 12 and beyond always)
+SINGLE_ON_THE_GENERAL_KERNEL = [(1536, 1536, 64, 11), (1080, 1920, 64, 9), (720, 1280, 64, 9), (256, 256, 32, 5),
+                                (600, 800, 64, 7), (900, 1600, 128, 11), (1280, 1280, 32, 8), (768, 768, 64, 8),
+                                (1536, 1280, 96, 11), (64, 64, 128, 8), (224, 224, 64, 3), (512, 512, 8, 13)]
+# ... and shapes that stay on the special case's kernels: the paper's sweep, large images that
+# its wide tiles divide evenly, few filters
+SINGLE_ON_ITS_OWN_KERNELS = [(4096, 4096, 64, 1), (4096, 4096, 64, 11), (2048, 2048, 64, 11), (3000, 3000, 64, 11),
+                             (1024, 1024, 64, 9), (1024, 1024, 32, 7), (2048, 2048, 64, 5), (512, 512, 64, 3),
+                             (256, 256, 8, 7), (1920, 1080, 32, 3)]
 
 # (N, C, H, W, K, F) -> tile shape of the general kernel (0: 64 x 128, 1: 64 x 256, 2: 32 x 256)
 GENERAL_PINS = [
@@ -64,6 +72,16 @@ def test_special_case_configuration_by_shape(dims, cfg):
     assert choice(True, 1, 1, H, W, K, F) == cfg
 
 
+def test_one_channel_on_the_general_kernel_by_shape():
+    for (H, W, K, F) in SINGLE_ON_THE_GENERAL_KERNEL:
+        assert choice(True, 1, 1, H, W, K, F) == dconv.CHOICE_GENERAL_CASE, (H, W, K, F)
+        # (dconv_general with one image of one channel takes the same route and names the tile shape)
+        assert 0 <= choice(False, 1, 1, H, W, K, F) < 3, (H, W, K, F)
+    for (H, W, K, F) in SINGLE_ON_ITS_OWN_KERNELS:
+        assert choice(True, 1, 1, H, W, K, F) >= 0, (H, W, K, F)
+        assert choice(False, 1, 1, H, W, K, F) == dconv.CHOICE_SPECIAL_CASE, (H, W, K, F)
+
+
 @pytest.mark.parametrize("dims,shape", GENERAL_PINS)
 def test_general_tile_shape_by_shape(dims, shape):
     assert choice(False, *dims) == shape
@@ -80,7 +98,7 @@ def test_other_kernels_by_shape():
     assert choice(False, 4, 64, 56, 56, 64, 13) >= 0
     assert choice(False, 4, 64, 56, 56, 64, 33) == dconv.CHOICE_SIMPLE
     # dconv_general with one channel, or a few with small filters and a large output
-    assert choice(False, 1, 1, 512, 512, 64, 3) == dconv.CHOICE_SPECIAL_CASE
+    assert choice(False, 1, 1, 1024, 1024, 64, 3) == dconv.CHOICE_SPECIAL_CASE
     assert choice(False, 16, 1, 512, 512, 64, 3) == dconv.CHOICE_SPECIAL_CASE
     assert choice(False, 16, 3, 512, 512, 64, 3) == dconv.CHOICE_SPECIAL_CASE
     assert choice(False, 16, 3, 512, 512, 64, 7) >= 0
@@ -117,8 +135,9 @@ def test_every_answer_is_a_configuration_or_a_named_choice():
         else:
             assert c in named - {dconv.CHOICE_SPECIAL_CASE} or 0 <= c < n_single, (H, W, K, F, c)
             assert c != 7              # the width-matching ablation is never chosen by shape
-            assert (c in (dconv.CHOICE_SIMPLE, dconv.CHOICE_GENERAL_CASE)) == (F > 11), (H, W, K, F, c)
-            assert (c == dconv.CHOICE_SIMPLE) <= (F > 32), (H, W, K, F, c)
+            assert (F > 11) <= (c in (dconv.CHOICE_SIMPLE, dconv.CHOICE_GENERAL_CASE)), (H, W, K, F, c)
+            assert (c == dconv.CHOICE_SIMPLE) == (F > 32), (H, W, K, F, c)
+            assert (c == dconv.CHOICE_GENERAL_CASE) <= (K >= 9 or F > 11), (H, W, K, F, c)
         N, C = rng.randint(1, 64), rng.randint(1, 600)
         H, W = rng.randint(1, 300), rng.randint(1, 300)
         c = choice(False, N, C, H, W, K, F)

@@ -854,6 +854,59 @@ def test_special_case_kernel_filter_counts_around_group_and_block_limits(K):
             assert torch.isnan(buf[:1003]).all() and torch.isnan(buf[1003 + total:]).all()
 
 
+@pytest.mark.parametrize("K", [65, 96, 129, 160, 161, 192, 200, 225, 288, 353])
+def test_special_case_kernel_leftover_filter_blocks(K):
+    """Filter blocks beyond whole groups of four form a group of two and / or a group of one (three,
+    five, six, seven ... blocks), and the groups of a tile are neighbouring work items: every tile
+    configuration, one image and a batch with two to four channels, exact results between guard
+    bands."""
+    for (N, C, H, W, F) in ((1, 1, 9, 600, 3), (1, 1, 14, 140, 7), (2, 3, 10, 300, 3), (3, 1, 8, 70, 5), (2, 4, 7, 200, 2)):
+        x, f = wl.integer_case(950 + K + F, N, C, H, W, K, F)
+        want = oracle.general(x, f)[0].astype(np.float32)
+        for variant in [dconv.VARIANT_SPECIAL_CASE] + [dconv.VARIANT_SPECIAL_CASE_CFG0 + i
+                                                      for i in range(dconv.tile_config_count(True))]:
+            print(f"special-case kernel K={K} {(N, C, H, W, F)} variant {variant:#x}", flush=True)
+            buf = torch.full((want.size + 2048,), float("nan"), device="cuda")
+            out = buf[1003:1003 + want.size].view(want.shape)
+            try:
+                dconv.dconv_general(dev(x), dev(f), out=out, variant=variant)
+            except dconv.DconvError as e:          # (a configuration that cannot hold the shape)
+                assert e.status == dconv.STATUS_UNSUPPORTED
+                continue
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out.cpu().numpy(), want)
+            assert torch.isnan(buf[:1003]).all() and torch.isnan(buf[1003 + want.size:]).all()
+
+
+ONE_CHANNEL_ON_THE_GENERAL_KERNEL = [(64, 64, 128, 8), (150, 150, 96, 5), (100, 333, 40, 11), (37, 700, 64, 9),
+                                     (224, 224, 64, 3), (300, 61, 200, 6)]
+
+
+@pytest.mark.parametrize("shape", ONE_CHANNEL_ON_THE_GENERAL_KERNEL, ids=lambda s: "x".join(map(str, s)))
+def test_one_channel_where_the_library_runs_the_general_kernel(shape):
+    """dconv_single_channel on shapes that the general-case kernel runs faster (narrow or short
+    images, large filters): the same bits as dconv_general with one image of one channel, within
+    the bound of the oracle, integer inputs exact, guard bands."""
+    H, W, K, F = shape
+    assert dconv.tile_choice(True, 1, 1, H, W, K, F) == dconv.CHOICE_GENERAL_CASE
+    x, f = wl.random_case(7100 + K + F, 1, 1, H, W, K, F)
+    acc, mag, _ = oracle.general(x, f)
+    got = dconv.dconv_single_channel(dev(x[0, 0]), dev(f[:, 0]))
+    same = dconv.dconv_general(dev(x), dev(f), variant=dconv.VARIANT_TILED)[0]
+    plain = dconv.dconv_general(dev(x), dev(f))[0]
+    torch.cuda.synchronize()
+    assert torch.equal(got, same) and torch.equal(got, plain)
+    assert_within_bound(got.cpu().numpy(), acc[0], mag[0], f"one channel on the general kernel {shape}")
+    xi, fi = wl.integer_case(7200 + K + F, 1, 1, H, W, K, F)
+    want = oracle.general(xi, fi)[0].astype(np.float32)[0]
+    buf = torch.full((want.size + 2048,), float("nan"), device="cuda")
+    out = buf[1001:1001 + want.size].view(want.shape)
+    dconv.dconv_single_channel(dev(xi[0, 0]), dev(fi[:, 0]), out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+    assert torch.isnan(buf[:1001]).all() and torch.isnan(buf[1001 + want.size:]).all()
+
+
 def test_sixteen_filter_blocks_where_the_library_picks_them():
     """Shapes the dispatcher sends to the 16-filter matrix-core blocks (13 to 16 filters; 8 to 12 on
     images whose vector-ALU tiles do not cover the chip), at full size on sampled outputs, and the
@@ -1026,7 +1079,7 @@ def test_the_reported_choice_is_what_the_library_runs():
     general = [(2, 64, 30, 30, 64, 3), (3, 32, 20, 20, 32, 3), (2, 64, 40, 40, 96, 3), (1, 256, 14, 14, 256, 3),
                (1, 128, 20, 20, 128, 7), (4, 128, 17, 14, 192, 1), (8, 8, 60, 60, 64, 2), (2, 64, 30, 30, 128, 2),
                (40, 16, 7, 7, 64, 3), (2, 2, 200, 200, 16, 3), (1, 1, 200, 200, 64, 3), (2, 16, 40, 40, 8, 33),
-               (16, 8, 96, 96, 64, 3)]
+               (16, 8, 96, 96, 64, 3), (1, 1, 700, 900, 64, 3)]
     seen = set()
     for i, (H, W, K, F) in enumerate(single):
         x, f = wl.random_case(3100 + i, 1, 1, H, W, K, F)
