@@ -115,6 +115,18 @@ def test_variants_without_shared_tiles_and_errors():
     assert lib.dconv_general_noalloc(fake, 1, 2, 8, 8, fake, 2, 3, fake, 99, None) == dconv.STATUS_UNSUPPORTED
 
 
+def test_one_image_of_one_channel_that_the_general_kernel_runs():
+    """One channel is the special case, but this shape runs on the general-case kernel (few tiles,
+    shared between workgroups: the static array is in use), then a smaller one."""
+    for i, (H, W, K, F) in enumerate(((64, 64, 128, 8), (50, 60, 96, 8))):
+        assert dconv.tile_choice(False, 1, 1, H, W, K, F) >= 0
+        x, f = wl.random_case(612 + i, 1, 1, H, W, K, F)
+        acc, mag, _ = oracle.general(x, f)
+        got, ref = both(dev(x), dev(f), dconv.VARIANT_AUTO, "one channel")
+        assert torch.equal(got, ref)
+        assert_within_bound(got.cpu().numpy(), acc, mag, f"noalloc one channel {(H, W, K, F)}")
+
+
 def test_nothing_is_allocated_on_a_fresh_stream():
     """On a stream the library has never seen, dconv_general_v allocates its workspace (64 MiB on
     this chip); dconv_general_noalloc leaves the device's free memory as it is."""
