@@ -200,15 +200,22 @@ bool single_few_supports(const Shape& s)
 }
 
 // Worth it (measured against the matrix-core kernel with blocks of 32 and of 16 filters on
-// 512^2 .. 4096^2 images, 3 to 20 filters, 3x3 .. 7x7).  Its time grows with K * F * F, the
+// 128^2 .. 4096^2 images, 1 to 20 filters, 1x1 .. 7x7).  Its time grows with K * F * F, the
 // matrix-core kernel's hardly at all up to a block's filters, so there is a filter count up to
 // which it wins; that count is lower where its tiles (256 x 16 or 256 x 32 pixels, one per
 // workgroup) do not cover the chip, because a launch then takes as long as one tile:
-//  * up to four filters: always (from about 100 tiles on; below, the matrix-core kernel's small
-//    tiles cover the chip better);
-//  * up to 3x3: as long as the output fits the memory-side cache (under 110 M outputs; beyond,
-//    its rows, written at any alignment, cost, and the matrix-core kernel's whole lines win)
-//    and the image is not too small for the filter count (18 filters per million pixels);
+//  * fewer than 100 tiles (kernel time from replayed graphs, 2.5 to 20 us): both kernels take
+//    the time of their chains of latencies, this one's grows with K * F * F, the other's with
+//    the image: one to three 1x1 filters or one or two filters up to 5x5 on the smallest images
+//    (under 120 k outputs per filter; 256 x 256, one 3x3 filter: 4.5 -> 3.2 us), four filters
+//    up to 3x3 and two beyond up to 350 k, four from there on (640 x 640, one 7x7 filter:
+//    22 -> 7 us);
+//  * up to four filters: always from 100 tiles on;
+//  * up to 3x3: as long as the output fits the memory-side cache (under 110 M outputs; under
+//    70 M for 1x1 and 2x2, which have no arithmetic to hide behind: beyond, its rows, written
+//    at any alignment, cost, and the matrix-core kernel's whole lines win; 3000 x 3000, twelve
+//    2x2 filters: 121 -> 90 us) and the image is not too small for the filter count (20 filters
+//    per million pixels);
 //  * from 4x4 on: up to 6 filters with fewer than 200 tiles, 8 with fewer than 400, else 10
 //    filters of 4x4 (16 while the output fits the memory-side cache) and 13 of 5x5 and
 //    larger; 17 to 20 filters (two 16-filter blocks or a 32-filter block with padding) from
@@ -218,13 +225,19 @@ bool single_few_preferred(const Shape& s)
     if (!single_few_supports(s) || s.K > 20) return false;
     const int tr = 4 * few_rpw(s.F, s.K);
     const int64_t tiles = (int64_t)((s.Wo + kFewTW - 1) / kFewTW) * ((s.Ho + tr - 1) / tr);
-    if (tiles < 100) return false;
+    if (tiles < 100) {
+        const int64_t px = (int64_t)s.Ho * s.Wo;
+        const int kmax = px < 120000 ? (s.F == 1 ? 3 : s.F <= 5 ? 2 : 0) : px < 350000 ? (s.F <= 3 ? 4 : 2) : 4;
+        return s.K <= kmax;
+    }
     if (s.K <= 4) return true;
     const int64_t outputs = (int64_t)s.K * s.Ho * s.Wo;
     // (up to 3x3: its time grows with the filter count while the matrix-core kernel on a small
     // image takes the time of its latencies whatever the count: 768 x 768, 16 filters of 3x3:
-    // 19 against 14 us; about 18 filters per million output pixels is where they meet)
-    if (s.F <= 3) return outputs < 110000000LL && (int64_t)s.K * 1000000 <= 18 * (int64_t)s.Ho * s.Wo;
+    // 19 against 14 us; about 20 filters per million output pixels is where they meet)
+    if (s.F <= 3)
+        return outputs < (s.F == 3 ? 110000000LL : 70000000LL) &&
+               (int64_t)s.K * 1000000 <= 20 * (int64_t)s.Ho * s.Wo;
     if (s.K > 16) return s.F >= 5 && tiles >= 512;
     const int kmax = tiles < 200 ? 6 : tiles < 400 ? 8 : s.F > 4 ? 13 : outputs < 70000000LL ? 16 : 10;
     return s.K <= kmax;

@@ -92,6 +92,16 @@ def test_other_kernels_by_shape():
     assert choice(True, 1, 1, 4096, 4096, 1, 3) == dconv.CHOICE_FEW_FILTERS
     assert choice(True, 1, 1, 2048, 2048, 8, 3) == dconv.CHOICE_FEW_FILTERS
     assert choice(True, 1, 1, 768, 768, 16, 3) >= 0            # too small an image for sixteen
+    assert choice(True, 1, 1, 3000, 3000, 12, 2) >= 0          # an output beyond the memory-side cache, no arithmetic
+    assert choice(True, 1, 1, 3000, 3000, 6, 2) == dconv.CHOICE_FEW_FILTERS
+    # small images (its tiles do not cover the chip): one or two filters, more on mid-sized images
+    assert choice(True, 1, 1, 256, 256, 1, 3) == dconv.CHOICE_FEW_FILTERS
+    assert choice(True, 1, 1, 128, 128, 2, 5) == dconv.CHOICE_FEW_FILTERS
+    assert choice(True, 1, 1, 256, 256, 1, 7) >= 0
+    assert choice(True, 1, 1, 256, 256, 4, 3) >= 0
+    assert choice(True, 1, 1, 512, 512, 4, 3) == dconv.CHOICE_FEW_FILTERS
+    assert choice(True, 1, 1, 512, 512, 3, 5) >= 0
+    assert choice(True, 1, 1, 640, 640, 1, 7) == dconv.CHOICE_FEW_FILTERS
     # filters beyond the compiled sides
     assert choice(True, 1, 1, 512, 512, 8, 13) == dconv.CHOICE_GENERAL_CASE
     assert choice(True, 1, 1, 512, 512, 8, 33) == dconv.CHOICE_SIMPLE

@@ -1075,7 +1075,7 @@ def test_the_reported_choice_is_what_the_library_runs():
     One shape for every branch of the dispatchers' rules that a small problem can reach."""
     single = [(256, 256, 16, 3), (300, 420, 3, 5), (700, 900, 12, 5), (600, 800, 64, 7), (720, 1280, 40, 9),
               (150, 2000, 64, 3), (512, 512, 32, 3), (640, 640, 128, 5), (96, 96, 8, 33), (1100, 1100, 8, 3), (120, 150, 8, 13),
-              (800, 800, 96, 5), (1024, 1024, 16, 5)]
+              (800, 800, 96, 5), (1024, 1024, 16, 5), (256, 256, 1, 3), (500, 520, 2, 7)]
     general = [(2, 64, 30, 30, 64, 3), (3, 32, 20, 20, 32, 3), (2, 64, 40, 40, 96, 3), (1, 256, 14, 14, 256, 3),
                (1, 128, 20, 20, 128, 7), (4, 128, 17, 14, 192, 1), (8, 8, 60, 60, 64, 2), (2, 64, 30, 30, 128, 2),
                (40, 16, 7, 7, 64, 3), (2, 2, 200, 200, 16, 3), (1, 1, 200, 200, 64, 3), (2, 16, 40, 40, 8, 33),
