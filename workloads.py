@@ -105,6 +105,10 @@ PAPER_SWEEP = {w.name: w for w in (
     # few filters in the general case (the weak spot of Sec. 5 carried over: a last layer to RGB, one map)
     _mk("B_K3_F3", "general", 8, 64, 224, 224, 3, 3, "u01", "he", 43),
     _mk("B_K1_F7", "general", 8, 16, 224, 224, 1, 7, "u01", "he", 44),
+    # one channel where the general-case kernel is the faster one: a mid-sized image with many large
+    # filters, a small image
+    _mk("A_768_K192_F8", "single", 1, 1, 768, 768, 192, 8, "u11", "u11", 45),
+    _mk("A_64_K128_F8", "single", 1, 1, 64, 64, 128, 8, "u11", "u11", 46),
 )}
 
 
