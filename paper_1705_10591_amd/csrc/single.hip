@@ -220,7 +220,12 @@ bool single_batch_preferred(const Shape& s)
 // special case's kernel for every filter side.
 bool single_general_preferred(const Shape& s)
 {
-    if (s.N != 1 || s.C != 1 || s.K < 9) return false;
+    if (s.N != 1 || s.C != 1) return false;
+    // (fewer than nine filters: only small images with large filters, where both kernels take the
+    // time of their chains of latencies and the general one's is the shorter -- kernel times from
+    // replayed graphs, 96^2 .. 2048^2, 2 to 8 filters: 224 x 320, eight 10x10 filters 15.3 -> 11.4 us;
+    // from 512 x 512 on the special case's 16-filter blocks win, up to 1.8 times)
+    if (s.K < 9) return s.F >= 6 && (int64_t)s.Ho * s.Wo <= 200000;
     const int blocks = (s.K + 31) / 32;
     const bool leftover = blocks > 2 && blocks % 4 != 0;
     const bool even = s.Wo >= 900 && tile_imbalance(s, 512, 4, 128, 1.0) <= 1.06;
