@@ -32,20 +32,27 @@ def test_captured_graph_replays_match_eager_calls():
     xg, fg = wl.random_case(32, 2, 8, 30, 30, 70, 3)
     xs, fsh = wl.random_case(33, 3, 16, 28, 28, 130, 3)
     xh, fh = wl.random_case(34, 2, 32, 20, 23, 40, 3)
+    x1g, f1g = wl.random_case(35, 1, 1, 64, 64, 128, 8)      # one channel that the general-case kernel runs
+    xf, ff = wl.random_case(36, 3, 5, 40, 300, 3, 3)         # three filters: the few-filters kernel
+    assert dconv.tile_choice(True, 1, 1, 64, 64, 128, 8) == dconv.CHOICE_GENERAL_CASE
     xhr, xhb = wl.to_16bit(xh, "bf16")              # rounded values for the oracle, bits for the device
     fhr, fhb = wl.to_16bit(fh, "bf16")
 
     d_img, d_fs, d_xg, d_fg, d_xs, d_fsh = map(dev, (img, fs, xg, fg, xs, fsh))
     d_xh, d_fh = (torch.from_numpy(np.ascontiguousarray(np.moveaxis(b, 1, -1)).view(np.int16))
                   .view(torch.bfloat16).to("cuda") for b in (xhb, fhb))       # channels last
+    d_x1g, d_f1g, d_xf, d_ff = dev(x1g[0, 0]), dev(f1g[:, 0]), dev(xf), dev(ff)
     outs = [torch.empty(16, 198, 298, device="cuda"), torch.empty(2, 70, 28, 28, device="cuda"),
-            torch.empty(3, 130, 26, 26, device="cuda"), torch.empty(2, 40, 18, 21, device="cuda")]
+            torch.empty(3, 130, 26, 26, device="cuda"), torch.empty(2, 40, 18, 21, device="cuda"),
+            torch.empty(128, 57, 57, device="cuda"), torch.empty(3, 3, 38, 298, device="cuda")]
 
     def enqueue():
         dconv.dconv_single_channel(d_img, d_fs, out=outs[0])
         dconv.dconv_general(d_xg, d_fg, out=outs[1])
         dconv.dconv_general(d_xs, d_fsh, out=outs[2], variant=shared)
         dconv.dconv_general_half(d_xh, d_fh, out=outs[3])
+        dconv.dconv_single_channel(d_x1g, d_f1g, out=outs[4])
+        dconv.dconv_general(d_xf, d_ff, out=outs[5], variant=dconv.VARIANT_FEW_FILTERS)
 
     torch.cuda.synchronize()
     s = torch.cuda.Stream()
@@ -54,7 +61,7 @@ def test_captured_graph_replays_match_eager_calls():
     s.synchronize()
     eager = [o.clone() for o in outs]
 
-    print("capturing four launches into one graph", flush=True)
+    print("capturing six launches into one graph", flush=True)
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=s):
         enqueue()
@@ -74,7 +81,9 @@ def test_captured_graph_replays_match_eager_calls():
 
     acc, mag, _ = oracle.single_channel(img, fs)
     assert_within_bound(eager[0].cpu().numpy(), acc, mag, "single channel")
-    for (x, f), e, what in (((xg, fg), eager[1], "general"), ((xs, fsh), eager[2], "general, shared tiles")):
+    for (x, f), e, what in (((xg, fg), eager[1], "general"), ((xs, fsh), eager[2], "general, shared tiles"),
+                            ((x1g, f1g), eager[4][None], "one channel on the general kernel"),
+                            ((xf, ff), eager[5], "general, few filters")):
         acc, mag, _ = oracle.general(x, f)
         assert_within_bound(e.cpu().numpy(), acc, mag, what)
     acc, mag, _ = oracle.general(xhr, fhr)
