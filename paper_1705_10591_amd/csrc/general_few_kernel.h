@@ -278,7 +278,10 @@ inline GfTile gf_tile_for(const Shape& s)
         const int64_t padded = (int64_t)((s.Wo + 4 * l - 1) / (4 * l)) * (4 * l);
         if (padded * 10 < best * 9) { best = padded; lpr = l; }
     }
-    const int rmax = s.K > 8 ? 1 : s.K > 4 ? 2 : lpr == 64 ? 4 : 2;
+    // (nine to sixteen filters: two rows per band only for 1x1 filters, 10-20 % faster there;
+    // with larger filters the registers of two rows cost more waves per SIMD than the rows save:
+    // measured 15-30 % slower from 2x2 on)
+    const int rmax = s.K > 8 ? (s.F == 1 ? 2 : 1) : s.K > 4 ? 2 : lpr == 64 ? 4 : 2;
     int rpw = rmax;
     while (rpw > 1 && gf_tiles(s, lpr, rpw) < 768) rpw /= 2;
     return {lpr, rpw};
@@ -308,11 +311,12 @@ int launch_gf_K(const float* in, const float* filt, float* out, const Shape& s, 
 {
     const GfTile t = gf_tile_for(s);
     // (six and eight filters: at most two rows per band, so that the sums and a 7x7 window fit
-    // the registers of two waves per SIMD; twelve and sixteen: one row)
+    // the registers of two waves per SIMD; twelve and sixteen: one row, two for 1x1 filters)
     if constexpr (KT > 8) {
-        if (t.lpr == 64) return launch_gf<F, KT, 1, 64>(in, filt, out, s, st);
-        if (t.lpr == 32) return launch_gf<F, KT, 1, 32>(in, filt, out, s, st);
-        return launch_gf<F, KT, 1, 16>(in, filt, out, s, st);
+        constexpr int R2 = F == 1 ? 2 : 1;
+        if (t.lpr == 64) return t.rpw >= 2 ? launch_gf<F, KT, R2, 64>(in, filt, out, s, st) : launch_gf<F, KT, 1, 64>(in, filt, out, s, st);
+        if (t.lpr == 32) return t.rpw >= 2 ? launch_gf<F, KT, R2, 32>(in, filt, out, s, st) : launch_gf<F, KT, 1, 32>(in, filt, out, s, st);
+        return t.rpw >= 2 ? launch_gf<F, KT, R2, 16>(in, filt, out, s, st) : launch_gf<F, KT, 1, 16>(in, filt, out, s, st);
     } else {
         if (t.lpr == 64) {
             if (KT <= 4 && t.rpw == 4) return launch_gf<F, KT, (KT <= 4 ? 4 : 2), 64>(in, filt, out, s, st);
