@@ -77,6 +77,7 @@ bool single_few_supports(const Shape& s);      // the few-filters kernel can run
 bool single_few_preferred(const Shape& s);     // ... and is the better choice for it
 bool single_blocks16_preferred(const Shape& s);   // up to 16 filters: matrix-core blocks of 16 filters are the better choice
 bool single_tiled_supports(const Shape& s);
+int single_split_filters(const Shape& s);      // filters of the first of two launches of the special-case kernel, 0 for one launch
 bool single_general_preferred(const Shape& s); // one image of one channel: the general-case kernel is the better choice
 bool single_batch_preferred(const Shape& s);   // dconv_general with up to four channels: the special-case kernel is the better choice
 bool general_tiled_supports(const Shape& s);

@@ -207,9 +207,9 @@ bool single_batch_preferred(const Shape& s)
 // whole rows per strip); the general kernel overlaps the two and tiles the flattened pixels, which
 // suits everything narrow, short or heavy in arithmetic.  A linear rule in the filter side and the
 // logarithms of the sizes, with three flags: fewer than 32 filters (the special case's 16-filter
-// blocks and small tiles are hard to beat), filter blocks left over beyond groups of four (a
-// leftover group of one or two blocks runs with the tile shape chosen for the full groups, which
-// suits it badly: 160 filters cost the special case's kernel almost what 256 do), and a large
+// blocks and small tiles are hard to beat), filter blocks left over beyond groups of four that
+// do not get a launch of their own (single_split_filters below: a leftover group of one or two
+// blocks runs with the tile shape chosen for the full groups, which suits it badly), and a large
 // image that the special case's wide tiles divide evenly over the CUs (there it is at its best:
 // 1024^2, 2048^2 and 3000^2 with 64 filters of 9x9 .. 11x11 are 6-8 % faster on it).  Fitted to
 // 960 measured shapes (64^2 .. 4096^2, 9 to 512 filters of 1x1 .. 11x11; fitted on two thirds and
@@ -227,7 +227,7 @@ bool single_general_preferred(const Shape& s)
     // from 512 x 512 on the special case's 16-filter blocks win, up to 1.8 times)
     if (s.K < 9) return s.F >= 6 && (int64_t)s.Ho * s.Wo <= 200000;
     const int blocks = (s.K + 31) / 32;
-    const bool leftover = blocks > 2 && blocks % 4 != 0;
+    const bool leftover = blocks > 2 && blocks % 4 != 0 && single_split_filters(s) == 0;
     const bool even = s.Wo >= 900 && tile_imbalance(s, 512, 4, 128, 1.0) <= 1.06;
     const double score = 0.63 * s.F - 0.20 * std::log2((double)s.K) - 0.70 * std::log2((double)s.Ho) -
                          1.12 * std::log2((double)s.Wo) - (s.K < 32 ? 2.62 : 0.0) +
@@ -239,10 +239,42 @@ int single_tile_configs() { return kSingleConfigs; }
 
 int single_auto_config(const Shape& s) { return auto_config(s); }
 
+// Filter blocks left over beyond groups of four, run as a launch of their own: a leftover group
+// inside one launch works with the tile shape chosen for the full groups, which suits it badly
+// where the matrix cores set the pace (160 filters of 9x9 on 2048 x 2048: 1532 us, against
+// 788 us for 128 filters plus 217 us for 32: 1029 us in two launches; 96 filters of 11x11 on
+// 3000 x 3000: 2436 -> 1929 us as 64 + 32).  Worth it from 5x5 on with one block left over
+// (or three blocks in all: 64 + 32), from 7x7 with two, from 9x9 with three after full groups
+// (128 + 64 + 32); with small filters the output stream sets the pace and one launch is as good
+// (measured on 1024^2 .. 3000^2 images, 96 to 224 filters of 1x1 .. 11x11).  Returns the filters
+// of the first launch, 0 for one launch.
+int single_split_filters(const Shape& s)
+{
+    if (s.N != 1 || s.C != 1) return 0;
+    const int blocks = (s.K + 31) / 32, full = blocks / 4, rem = blocks % 4;
+    if (blocks <= 2 || rem == 0) return 0;
+    const int fmin = (rem == 1 || full == 0) ? 5 : rem == 2 ? 7 : 9;
+    if (s.F < fmin) return 0;
+    return full > 0 ? 128 * full : 64;
+}
+
 int launch_single_tiled(const float* img, const float* filt, float* out, const Shape& s,
                         hipStream_t st, int cfg)
 {
     if (!single_tiled_supports(s)) return DCONV_UNSUPPORTED;
+    if (cfg < 0) {
+        // (each part with the configuration of its own shape; a forced configuration runs the
+        // whole layer in one launch)
+        if (const int first = single_split_filters(s)) {
+            Shape a = s, b = s;
+            a.K = first;
+            b.K = s.K - first;
+            const int rc = launch_single_tiled(img, filt, out, a, st, -1);
+            if (rc != DCONV_OK) return rc;
+            return launch_single_tiled(img, filt + (int64_t)first * s.F * s.F,
+                                       out + (int64_t)first * s.Ho * s.Wo, b, st, -1);
+        }
+    }
     switch (s.C) {
     case 1: break;
     case 2: return single_multi_launch_for_C<2>(img, filt, out, s, st, cfg);
