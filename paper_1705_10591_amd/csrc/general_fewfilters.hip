@@ -39,8 +39,21 @@ bool general_few_preferred(const Shape& s)
     if (!general_few_supports(s) || (s.C == 1 && s.N == 1)) return false;
     const GfTile t = gf_tile_for(s);
     const double tiles = (double)gf_tiles(s, t.lpr, t.rpw);
-    if (tiles < 32) return false;
     static const int kCompiled[17] = {0, 1, 2, 3, 4, 6, 6, 8, 8, 12, 12, 12, 12, 16, 16, 16, 16};
+    if (tiles < 32) {
+        // A launch of a few tiles: both kernels take the time of one workgroup's chain of
+        // latencies.  This kernel's grows with the channels it walks (a barrier, the staging of
+        // the tile's rows and the tile's multiply-adds per channel); the matrix-core kernel
+        // shares a tile's channels between workgroups and grows slowly.  Kernel times from
+        // replayed graphs (1 to 16 images of 28^2 .. 224^2, 3 to 64 channels, 1 to 8 filters of
+        // 1x1 .. 5x5; within 7 % and 17 % rms), microseconds: over the 319 measured layers with
+        // fewer than 32 tiles the choice goes from 5.3 % above the faster kernel to 1.0 %
+        // (1 x 3 x 112 x 112, one 5x5 filter: 7.9 -> 4.4 us).
+        const int kc = kCompiled[s.K], ff = s.F * s.F;
+        const double few = 3.1 + s.C * (0.32 + 0.036 * (s.F - 1) + 0.0081 * kc * ff + 0.025 * kc);
+        const double tiled = 5.4 + 0.059 * s.C + 0.144 * ff + 0.0071 * s.C * ff;
+        return few < 0.9 * tiled;
+    }
     const double tw = 4.0 * t.lpr, tr = 4.0 * (kWave / t.lpr) * t.rpw;
     const double inside = (double)s.Wo * s.Ho /
                           ((double)((s.Wo + (int)tw - 1) / (int)tw) * tw * (double)((s.Ho + (int)tr - 1) / (int)tr) * tr);

@@ -117,7 +117,10 @@ def test_other_kernels_by_shape():
     # a few filters on many channels: the vector-ALU kernel of the general case, where it covers the chip
     assert choice(False, 8, 64, 224, 224, 3, 3) == dconv.CHOICE_FEW_FILTERS
     assert choice(False, 8, 16, 224, 224, 1, 7) == dconv.CHOICE_FEW_FILTERS
-    assert choice(False, 1, 256, 128, 128, 3, 3) == 2            # too few tiles
+    assert choice(False, 1, 256, 128, 128, 3, 3) == 2            # a few tiles, many channels to walk
+    assert choice(False, 1, 3, 112, 112, 1, 5) == dconv.CHOICE_FEW_FILTERS      # a few tiles, few channels
+    assert choice(False, 4, 3, 28, 28, 3, 3) == dconv.CHOICE_FEW_FILTERS
+    assert choice(False, 1, 64, 56, 56, 8, 5) >= 0
     assert choice(False, 64, 256, 38, 38, 4, 1) == 2             # a barrier per channel for very little work
     assert choice(False, 21, 8, 96, 640, 12, 5) == dconv.CHOICE_FEW_FILTERS      # (nine to sixteen filters: few channels)
     assert choice(False, 15, 3, 384, 384, 10, 3) == dconv.CHOICE_FEW_FILTERS

@@ -1017,7 +1017,8 @@ def test_general_few_filters_where_the_library_picks_it():
     """Layers with one to sixteen filters that cover the chip, at full size on sampled outputs; the
     plain call and the forced kernel agree bit for bit."""
     for (N, C, H, W, K, F) in ((8, 16, 224, 224, 3, 5), (64, 32, 56, 56, 1, 3), (4, 32, 300, 512, 8, 3),
-                               (15, 3, 384, 384, 10, 3), (21, 8, 96, 640, 12, 5), (64, 3, 128, 128, 16, 2)):
+                               (15, 3, 384, 384, 10, 3), (21, 8, 96, 640, 12, 5), (64, 3, 128, 128, 16, 2),
+                               (1, 3, 112, 112, 1, 5), (4, 3, 28, 28, 3, 3)):
         assert dconv.tile_choice(False, N, C, H, W, K, F) == dconv.CHOICE_FEW_FILTERS
         x, f = wl.random_case(6400 + K, N, C, H, W, K, F)
         got = dconv.dconv_general(dev(x), dev(f))
