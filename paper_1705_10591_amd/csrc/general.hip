@@ -217,7 +217,11 @@ int shape_for(const Shape& s)
     const bool tiny = (int64_t)s.Ho * s.Wo < 100;
     // Up to 32 filters: the 32 x 256 tile, so that half of every filter block is not padding
     // (1x1 filters on tiny maps, where a 256-pixel tile reaches over several images: 64 x 128).
-    if (s.K <= 32) return (tiny && s.F == 1) ? 0 : 2;
+    // (and 1x1 filters on 64 channels or more in a launch of under a hundred wide tiles: the
+    // 64 x 128 tile's three workgroups per CU hide the barrier per chunk, which counts for more
+    // than the padded half block -- kernel times from replayed graphs, 8 x 64 x 28 x 28 with 32
+    // filters: 11.7 -> 8.8 us)
+    if (s.K <= 32) return (s.F == 1 && (tiny || (s.C >= 64 && wide_tiles < 100))) ? 0 : 2;
     // Filter counts whose last block of 64 is at most half full (96, 160, 224, 288): the 32 x 256
     // tile computes 25, 17, 12, 10 % fewer padded filters and is 20, 10, 5, 4 % faster from 3x3
     // on (and for the smaller filters with few channels); on tiny maps only for 96.
@@ -233,7 +237,9 @@ int shape_for(const Shape& s)
     // channels on, and from 64 on maps up to 64 wide (14 x 14 .. 224 x 224 maps, 32 to 512
     // channels, 64 to 512 filters); with fewer channels or on wider maps the large tile's
     // fewer, longer output runs win by up to 30 %.
-    if (s.F == 1) return (s.C >= 128 || (s.C >= 64 && s.Wo <= 64)) ? 0 : 1;
+    // (a launch of a few tiles: the 32 x 256 tile, twice the tiles, 10-25 % faster in kernel
+    // time on 7 x 7 .. 56 x 56 maps with 16 or 32 channels)
+    if (s.F == 1) return (s.C >= 128 || (s.C >= 64 && s.Wo <= 64)) ? 0 : tiles < 64 ? 2 : 1;
     // Tiny maps (under a hundred outputs per image): a 256-pixel tile reaches over several
     // images, each with its halo rows in the image block; the 128-pixel tile is 20-35 % faster
     // (7 x 7 outputs, 64 to 512 channels and filters, hundreds of images).

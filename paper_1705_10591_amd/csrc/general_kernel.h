@@ -860,8 +860,12 @@ int gen_try_launch(const float* in, const float* filt, float* out, const Shape& 
         for (int parts = 2; parts <= 32; ++parts) consider(parts * tiles);
         for (int k = 1; k <= 6; ++k) consider((int64_t)k * cus / 2);
         // (shared only for a tenth or more: the model knows nothing of the cost of a workgroup's
-        // passing from one tile to the next)
-        if (best < 0.9 * whole) { split = 1; U = tiles * nch; G = (int)best_g; }
+        // passing from one tile to the next; and only for three microseconds or more: with a
+        // few short chunks per tile the launch, the first loads and the write-back are most of
+        // the kernel's time and sharing adds to them -- kernel times from replayed graphs,
+        // 4 x 128 x 56 x 56 with 64 1x1 filters: 20.7 us shared, 13.2 us whole; where the model
+        // promises 4.5 us or more, sharing is 25-85 % faster)
+        if (best < 0.9 * whole && whole - best >= 3.0) { split = 1; U = tiles * nch; G = (int)best_g; }
         else { split = 0; U = tiles; G = (int)tiles; }
     }
 
