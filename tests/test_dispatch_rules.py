@@ -124,7 +124,7 @@ def test_other_kernels_by_shape():
     assert choice(False, 64, 256, 38, 38, 4, 1) == 2             # a barrier per channel for very little work
     assert choice(False, 21, 8, 96, 640, 12, 5) == dconv.CHOICE_FEW_FILTERS      # (nine to sixteen filters: few channels)
     assert choice(False, 15, 3, 384, 384, 10, 3) == dconv.CHOICE_FEW_FILTERS
-    assert choice(False, 8, 64, 224, 224, 16, 3) == 2            # sixteen filters on many channels
+    assert choice(False, 8, 256, 56, 56, 16, 3) == 2             # sixteen filters on many channels
     assert choice(False, 8, 64, 224, 224, 17, 3) == 2            # seventeen filters
 
 
