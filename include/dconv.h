@@ -67,10 +67,10 @@ enum {
                                  kernel.  dconv_general_v: the paper's
                                  Algorithm 2 with all filters in a thread's
                                  register tile, K <= 16 only; what AUTO picks for
-                                 such layers where the launch covers the chip
-                                 and a 32-filter matrix-core block would be
-                                 mostly padding (from nine filters on: layers of
-                                 few channels)                                   */
+                                 such layers where its estimated kernel time is
+                                 below the matrix-core kernel's, whose 32-filter
+                                 block would be mostly padding (few filters, or
+                                 up to sixteen on few channels)                  */
     DCONV_VARIANT_SPECIAL_CASE = 4,
                               /* dconv_general with C = 1 (any filter up to
                                  11x11) or C <= 4 (filters up to 5x5) only: the
